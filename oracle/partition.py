@@ -1,0 +1,226 @@
+"""Oracle: alpha-balanced greedy LPT partitioning (Algorithm 1, Sec. 3.2).
+
+Test infrastructure only (see the package docstring).  Plain Python: integer
+loads are Python ints, every real quantity is a Python float (IEEE fp64) and
+the operations are taken in the order the algorithm lists them, so that an
+independent implementation using the same order reproduces every decision
+bit for bit.  ``partition_alpha_exact`` replays the same algorithm in exact
+rationals and reports how close any decision came to a tie.
+
+Readings of points the paper leaves open (each is also listed in the design doc):
+
+* cuts are parameter indices inside the bucket (the domain of Phi_i in the
+  "Define" lines of Algorithm 1), not element offsets;
+* ranks are numbered 0..R-1 here (the paper counts from 1);
+* buckets of equal total load are visited in ascending original index
+  (a stable sort for the "Sort" line);
+* when two feasible cuts are equally close to the running target C the
+  smaller index wins ("arg min" line of Step (4));
+* a rank may receive an empty slice of a bucket (0 is a feasible cut).
+"""
+from __future__ import annotations
+
+from fractions import Fraction
+
+COST_NUMEL = 0      # W(p) = numel(p), the paper's default (Sec. 3.2)
+COST_NS_FLOPS = 1   # W(p) = FLOPs of the Newton-Schulz chain (App. D.5 ablation)
+
+
+def ns_flops(rows: int, cols: int, ns_steps: int = 5) -> int:
+    """FLOPs of ns_steps quintic Newton-Schulz steps on a rows x cols matrix.
+
+    With m = min(rows, cols) and n = max(rows, cols) one step is the Gram
+    product X X^T (2 m^2 n), the square A A (2 m^3) and the product B X
+    (2 m^2 n).  This is the "exact FLOPs" cost of App. D.5.
+    """
+    m, n = (rows, cols) if rows <= cols else (cols, rows)
+    return ns_steps * (4 * m * m * n + 2 * m * m * m)
+
+
+def param_cost(rows, cols, cost_kind: int = COST_NUMEL, ns_steps: int = 5):
+    """W(p) for every parameter, as Python ints."""
+    if cost_kind == COST_NUMEL:
+        return [int(r) * int(c) for r, c in zip(rows, cols)]
+    if cost_kind == COST_NS_FLOPS:
+        return [ns_flops(int(r), int(c), ns_steps) for r, c in zip(rows, cols)]
+    raise ValueError("unknown cost_kind %r" % (cost_kind,))
+
+
+def _check_inputs(n_params, bucket_off, n_ranks, alpha):
+    if n_ranks < 1:
+        raise ValueError("n_ranks must be >= 1")
+    if not (0.0 <= alpha <= 1.0):
+        raise ValueError("alpha must lie in [0, 1]")
+    if len(bucket_off) < 1 or bucket_off[0] != 0 or bucket_off[-1] != n_params:
+        raise ValueError("bucket_off must start at 0 and end at n_params")
+    for lo, hi in zip(bucket_off[:-1], bucket_off[1:]):
+        if hi < lo:
+            raise ValueError("bucket_off must be non-decreasing")
+
+
+def _algorithm1(cost, bucket_off, n_ranks, alpha, real, margin_log=None):
+    """Algorithm 1 with the real-number type given by ``real``.
+
+    ``real`` converts an int (or the float alpha) into the number type used
+    for mu, d, D, v, target and C: ``float`` for the fp64 oracle,
+    ``Fraction`` for the exact replay.
+    """
+    R = n_ranks
+    n_buckets = len(bucket_off) - 1
+    # "Define" lines: bucket totals W^i and cumulative loads Phi_i(u).
+    phi = []
+    for i in range(n_buckets):
+        acc = [0]
+        for p in range(bucket_off[i], bucket_off[i + 1]):
+            acc.append(acc[-1] + cost[p])
+        phi.append(acc)
+    w_bucket = [phi[i][-1] for i in range(n_buckets)]
+
+    load = [0] * R                                   # "Initialize" line
+    mu = real(sum(w_bucket)) / real(R)               # "Target" line
+    order = sorted(range(n_buckets), key=lambda i: (-w_bucket[i], i))  # "Sort"
+
+    one = real(1)
+    al = real(alpha)
+    cuts = [[0] * (R + 1) for _ in range(n_buckets)]
+    for k in order:
+        # Step (1): deficits in the load domain.
+        d = []
+        for r in range(R):
+            gap = mu - real(load[r])
+            d.append(gap if gap > 0 else real(0))
+        d_total = real(0)
+        for r in range(R):
+            d_total = d_total + d[r]
+        # Steps (2) and (3): basis vectors and the blended target.
+        v_even = one / real(R)
+        target = []
+        for r in range(R):
+            v_fill = d[r] / d_total if d_total > 0 else v_even
+            v_star = (one - al) * v_even + al * v_fill
+            target.append(real(w_bucket[k]) * v_star)
+        # Step (4): project the running target onto the atomic cuts.
+        s = cuts[k]
+        s[0] = 0
+        c_run = real(0)
+        for r in range(R - 1):
+            c_run = c_run + target[r]
+            gaps = [abs(real(phi[k][u]) - c_run) for u in range(len(phi[k]))]
+            best_u = 0
+            for u in range(1, len(gaps)):
+                if gaps[u] < gaps[best_u]:      # strict: the smaller u keeps a tie
+                    best_u = u
+            if margin_log is not None and len(gaps) > 1:
+                runner_up = min(g for u, g in enumerate(gaps) if u != best_u)
+                margin_log.append((runner_up - gaps[best_u], k, r + 1))
+            s[r + 1] = best_u
+            load[r] += phi[k][s[r + 1]] - phi[k][s[r]]
+        s[R] = len(phi[k]) - 1
+        load[R - 1] += phi[k][s[R]] - phi[k][s[R - 1]]
+    return cuts, load
+
+
+def _owners(cuts, bucket_off, n_ranks, n_params):
+    owner = [-1] * n_params
+    for i in range(len(bucket_off) - 1):
+        for r in range(n_ranks):
+            for u in range(cuts[i][r], cuts[i][r + 1]):
+                owner[bucket_off[i] + u] = r
+    return owner
+
+
+def partition_alpha(rows, cols, bucket_off, n_ranks, alpha,
+                    cost=None, cost_kind=COST_NUMEL):
+    """Algorithm 1 in fp64.  Returns (cuts, owner, load).
+
+    cuts[i][r] .. cuts[i][r+1] is the half-open range of parameter indices
+    (relative to bucket i) owned by rank r; owner[p] is the owning rank of
+    parameter p; load[r] is the final accumulated load L_r in cost units.
+    """
+    n_params = len(rows)
+    bucket_off = [int(x) for x in bucket_off]
+    _check_inputs(n_params, bucket_off, n_ranks, alpha)
+    if cost is None:
+        cost = param_cost(rows, cols, cost_kind)
+    cost = [int(c) for c in cost]
+    if any(c < 0 for c in cost):
+        raise ValueError("costs must be non-negative")
+    cuts, load = _algorithm1(cost, bucket_off, n_ranks, float(alpha), float)
+    owner = _owners(cuts, bucket_off, n_ranks, n_params)
+    return cuts, owner, load
+
+
+def partition_alpha_exact(rows, cols, bucket_off, n_ranks, alpha,
+                          cost=None, cost_kind=COST_NUMEL):
+    """The same algorithm in exact rationals.
+
+    Returns (cuts, owner, load, min_margin, n_ties): min_margin is the
+    smallest non-zero difference between the best and the second-best
+    |Phi(u) - C| over all decisions (None if there was no decision with two
+    candidates), n_ties the number of decisions with an exact tie.  alpha is
+    taken as the exact value of the fp64 number passed in.
+    """
+    n_params = len(rows)
+    bucket_off = [int(x) for x in bucket_off]
+    _check_inputs(n_params, bucket_off, n_ranks, alpha)
+    if cost is None:
+        cost = param_cost(rows, cols, cost_kind)
+    cost = [int(c) for c in cost]
+    log = []
+    cuts, load = _algorithm1(cost, bucket_off, n_ranks, float(alpha), Fraction, log)
+    owner = _owners(cuts, bucket_off, n_ranks, n_params)
+    nonzero = [m for m, _, _ in log if m != 0]
+    n_ties = sum(1 for m, _, _ in log if m == 0)
+    return cuts, owner, load, (min(nonzero) if nonzero else None), n_ties
+
+
+# --------------------------------------------------------------------------
+# Diagnostics: Eq. 2 (J_DP), Eq. 3 (J_Comm), Eq. 6 (R_LB), Eq. 1 (naive rule)
+# --------------------------------------------------------------------------
+
+def r_lb(values) -> float:
+    """Load-balance ratio max_r v_r / avg_r v_r (Eq. 6)."""
+    values = [float(v) for v in values]
+    avg = sum(values) / len(values)
+    return max(values) / avg if avg > 0 else 1.0
+
+
+def j_dp(load) -> float:
+    """Largest deviation of a rank's total load from the mean (Eq. 2)."""
+    mu = float(sum(load)) / len(load)
+    return max(abs(float(l) - mu) for l in load)
+
+
+def j_comm(cuts, numel, bucket_off) -> float:
+    """Sum over buckets and ranks of |S_{i,r} - |B_i|/R| in elements (Eq. 3)."""
+    total = 0.0
+    for i in range(len(bucket_off) - 1):
+        sizes = [int(numel[p]) for p in range(bucket_off[i], bucket_off[i + 1])]
+        pre = [0]
+        for s in sizes:
+            pre.append(pre[-1] + s)
+        R = len(cuts[i]) - 1
+        for r in range(R):
+            s_ir = pre[cuts[i][r + 1]] - pre[cuts[i][r]]
+            total += abs(s_ir - pre[-1] / R)
+    return total
+
+
+def rank_loads(owner, values, n_ranks):
+    """Sum of values[p] over the parameters each rank owns."""
+    out = [0] * n_ranks
+    for p, r in enumerate(owner):
+        out[r] += values[p]
+    return out
+
+
+def ownership_naive(numel, n_ranks):
+    """Atomic Ownership Rule (Eq. 1), 0-based: with stride S = |B|/R over the
+    whole flattened buffer, rank r owns p iff r*S <= Start_Index(p) < (r+1)*S.
+    Integer arithmetic: r = floor(start * R / |B|)."""
+    total = sum(int(x) for x in numel)
+    owner, start = [], 0
+    for x in numel:
+        owner.append(min(n_ranks - 1, (start * n_ranks) // total) if total > 0 else 0)
+        start += int(x)
+    return owner
