@@ -1,0 +1,179 @@
+/*
+ * canz - per-rank matrix-optimizer (Muon) step of Canzona, arxiv 2602.06079,
+ * for AMD MI355X (gfx950).  C ABI of libcanz.so.
+ *
+ * Three calls follow the paper's statement of the problem:
+ *   canz_partition_alpha   Algorithm 1 (Sec. 3.2): which rank owns which whole matrix.  CPU.
+ *   canz_microgroup_plan   batches one rank's same-shape matrices for one launch.        CPU.
+ *   canz_muon_step         Delta W = Muon_step(G, States) (Sec. 4.1 stage (2), Sec. 3.3
+ *                          stage (2)): momentum, Frobenius normalisation, k Newton-Schulz
+ *                          steps, scaled update - enqueued on a HIP stream.
+ *
+ * General rules
+ *   - Every function returns CANZ_OK (0) or a negative error code; nothing throws.
+ *     canz_last_error() gives a message for the calling thread's last failure.
+ *   - The library never allocates or frees device memory and never synchronises a
+ *     stream or the device.  Host arrays passed in are read during the call only.
+ *   - "host" / "device" in a comment says where a pointer must point.
+ *   - Ranks are numbered 0 .. n_ranks-1 (the paper counts from 1).
+ */
+#ifndef CANZ_H
+#define CANZ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  CANZ_OK = 0,
+  CANZ_EINVAL = -1,       /* null pointer, value out of range, inconsistent sizes   */
+  CANZ_ESHAPE = -2,       /* shape not supported by a kernel (alignment, tp split)  */
+  CANZ_EWORKSPACE = -3,   /* workspace missing, misaligned or too small             */
+  CANZ_EHIP = -4,         /* a HIP call or kernel launch failed                     */
+  CANZ_EUNSUPPORTED = -5  /* unknown enum value                                     */
+};
+
+enum { CANZ_COST_NUMEL = 0, CANZ_COST_NS_FLOPS = 1 };
+enum { CANZ_DT_F32 = 0, CANZ_DT_BF16 = 1 };
+enum { CANZ_SCALE_NONE = 0, CANZ_SCALE_ASPECT = 1, CANZ_SCALE_RMS = 2 };
+enum { CANZ_PREC_BF16 = 0, CANZ_PREC_F32 = 1 };
+enum { CANZ_OUT_PARAM = 0, CANZ_OUT_DELTA = 1 };
+
+/* Message for the last error on this thread (static storage, never NULL). */
+const char* canz_last_error(void);
+/* Library version string, e.g. "0.1.0". */
+const char* canz_version(void);
+
+/*
+ * canz_partition_alpha - alpha-balanced greedy LPT partitioning, Algorithm 1 (Sec. 3.2;
+ * walkthrough in App. C "Detailed Walkthrough of Load-Balancing Algorithms").
+ *
+ * The flat parameter list is cut into n_buckets ordered buckets; bucket i holds the
+ * parameters bucket_off[i] .. bucket_off[i+1]-1.  Buckets are visited by total load,
+ * heaviest first (equal loads: lower index first).  For each bucket the deficits
+ * d_r = max(0, mu - L_r) give v_fill = d / sum(d) (v_even if the sum is 0), the target is
+ * W^k * ((1-alpha) v_even + alpha v_fill), and the running sum of targets is projected
+ * onto the nearest parameter boundary (equal distance: the smaller index).
+ *
+ * All arguments are host pointers owned by the caller.
+ *   rows, cols   [n_mats]  matrix shapes (used when cost == NULL)
+ *   cost         [n_mats]  load W(p) >= 0 per parameter, or NULL to derive it from
+ *                          cost_kind: CANZ_COST_NUMEL rows*cols (the paper's default),
+ *                          CANZ_COST_NS_FLOPS 5*(4 m^2 n + 2 m^3), m = min, n = max
+ *   bucket_off   [n_buckets+1] non-decreasing, bucket_off[0] = 0, last = n_mats
+ *   alpha        blend factor in [0, 1]: 1 = fill deficits, 0 = even split per bucket
+ *   cut_out      [n_buckets*(n_ranks+1)] cut vectors s_i in the original bucket order:
+ *                rank r owns parameters cut[i][r] .. cut[i][r+1]-1 of bucket i
+ *                (indices relative to the bucket)
+ *   owner_out    [n_mats]  owning rank of each parameter
+ *   load_out     [n_ranks] final accumulated load L_r
+ * Real-valued steps run in IEEE fp64 in a fixed order (mu = total/R; deficits summed by
+ * ascending rank; v = (1-alpha)*(1/R) + alpha*(d/D); target = W^k * v; C += target), so
+ * results are reproducible bit for bit.  Total load must stay below 2^53.
+ * Errors: CANZ_EINVAL for null pointers, n_ranks < 1, alpha outside [0,1], malformed
+ * bucket_off, negative cost; CANZ_EUNSUPPORTED for an unknown cost_kind.
+ */
+int canz_partition_alpha(int64_t n_mats, const int64_t* rows, const int64_t* cols,
+                         const int64_t* cost, int32_t cost_kind,
+                         int64_t n_buckets, const int64_t* bucket_off,
+                         int32_t n_ranks, double alpha,
+                         int64_t* cut_out, int32_t* owner_out, int64_t* load_out);
+
+/*
+ * canz_microgroup_plan - group the matrices one rank owns into same-shape batches.
+ *
+ * The paper's micro-groups fuse tensors for one collective (Sec. 4, Algorithm 2); here a
+ * micro-group is the unit of one batched launch, so its members share (rows, cols, dtype).
+ * Classes are ordered by per-matrix element count, largest first, ties by smallest member
+ * id (the deterministic (W(p), ID_p) order of Algorithm 2, Phase 1); inside a class ids
+ * ascend and are cut into consecutive chunks of at most max_mats matrices and at most
+ * cmax_bytes bytes of bf16 matrix data (the role of C_max).
+ *
+ * Host pointers, caller-owned.
+ *   rows, cols, dtype, owner [n_mats]; rank selects owner[p] == rank
+ *   max_mats     0 = no cap;  cmax_bytes 0 = no cap
+ *   n_groups_out number of groups G
+ *   group_off_out [n_owned+1 capacity] offsets into member_out, G+1 entries written
+ *   member_out   [n_owned capacity] matrix ids, group after group
+ * Capacity n_mats+1 / n_mats always suffices.
+ * Errors: CANZ_EINVAL for null pointers or negative caps; CANZ_ESHAPE if one matrix alone
+ * exceeds cmax_bytes (Algorithm 3's "single item exceeds C_max").
+ */
+int canz_microgroup_plan(int64_t n_mats, const int64_t* rows, const int64_t* cols,
+                         const int32_t* dtype, const int32_t* owner, int32_t rank,
+                         int32_t max_mats, int64_t cmax_bytes,
+                         int64_t* n_groups_out, int64_t* group_off_out, int64_t* member_out);
+
+/*
+ * One micro-group for canz_muon_step: n_mats matrices of identical shape and dtypes.
+ * Every matrix is rows x cols, row-major, dense.  With tp > 1 the gradient (and, with
+ * CANZ_OUT_DELTA, the output) of each matrix is held as tp column fragments of shape
+ * rows x (cols/tp) in separate buffers (column-parallel split, App. B.2; gathered before
+ * and scattered after the computation, Sec. 4.1 stages (1) and (3)).
+ * The three pointer tables are HOST arrays of DEVICE pointers; they are read during the
+ * call and may be freed on return.  The device buffers must stay valid until the stream
+ * has finished the step.  Device pointers must be 16-byte aligned; cols/tp must be a
+ * multiple of 8.  grad, mom and out buffers must not overlap.
+ */
+typedef struct {
+  int64_t rows, cols;
+  int32_t n_mats;
+  int32_t tp;               /* 1 = whole matrices; >1 = column fragments (max 8)          */
+  int32_t grad_dtype;       /* CANZ_DT_F32 or CANZ_DT_BF16                                 */
+  int32_t out_dtype;        /* dtype of the out buffers                                    */
+  const void* const* grad;  /* [n_mats*tp] fragment f of matrix i at grad[i*tp+f]          */
+  void* const* mom;         /* [n_mats]    fp32 momentum, whole, updated in place          */
+  void* const* out;         /* CANZ_OUT_PARAM: [n_mats] whole parameters, updated in place
+                               CANZ_OUT_DELTA: [n_mats*tp] Delta W fragments, overwritten  */
+} canz_group;
+
+/*
+ * Hyper-parameters of the step.  Per matrix (Sec. 4.1 stage (2); App. B.3, Eq. 5):
+ *   M <- beta M + G;  U = M (nesterov: U = G + beta M)
+ *   X = U / (||U||_F + eps); the iteration runs on the wide orientation
+ *   ns_steps times: A = X X^T; B = b A + c A A; X <- a X + B X
+ *   O = X; scale = 1 | sqrt(max(1, rows/cols)) | 0.2 sqrt(max(rows, cols))
+ *   CANZ_OUT_PARAM: P <- P (1 - lr weight_decay) - lr scale O
+ *   CANZ_OUT_DELTA: Delta W = - lr scale O
+ */
+typedef struct {
+  float beta, lr, weight_decay, eps;
+  int32_t nesterov;
+  int32_t ns_steps;         /* >= 0 */
+  float a, b, c;            /* c = 0 gives the cubic iteration */
+  int32_t scale_mode;       /* CANZ_SCALE_* */
+  int32_t precision;        /* CANZ_PREC_BF16: bf16 MFMA, fp32 accumulate; CANZ_PREC_F32: fp32 */
+  int32_t out_mode;         /* CANZ_OUT_* */
+} canz_muon_hparams;
+
+/*
+ * canz_muon_workspace_bytes - device scratch needed by canz_muon_step for these groups
+ * (the maximum over groups; groups run one after another on the stream).
+ * g: host array [n_groups]; pointer tables inside may be NULL for this call.
+ */
+int canz_muon_workspace_bytes(const canz_group* g, int32_t n_groups,
+                              const canz_muon_hparams* hp, size_t* bytes_out);
+
+/*
+ * canz_muon_step - enqueue one optimizer step for the given micro-groups on hip_stream.
+ *   g               host array [n_groups]
+ *   workspace       device, 256-byte aligned, at least canz_muon_workspace_bytes() bytes,
+ *                   caller-owned; contents are scratch and need not be initialised
+ *   hip_stream      a hipStream_t (NULL = the null stream)
+ * Returns after enqueueing; completion follows stream order.  Results per matrix do not
+ * depend on which other matrices share the group or the call.
+ * Errors: CANZ_EINVAL (null pointers, n_mats < 0, tp outside 1..8, ns_steps < 0),
+ * CANZ_ESHAPE (cols not divisible by tp, fragment width not a multiple of 8),
+ * CANZ_EWORKSPACE, CANZ_EUNSUPPORTED (dtype / mode enums), CANZ_EHIP (launch failure;
+ * earlier groups of the call may already be enqueued).
+ */
+int canz_muon_step(const canz_group* g, int32_t n_groups, const canz_muon_hparams* hp,
+                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CANZ_H */

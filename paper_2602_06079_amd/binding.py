@@ -1,0 +1,198 @@
+"""ctypes binding of libcanz.so: argument marshalling only.
+
+The functions carry the names of the C ABI (include/canz.h).  Device buffers are
+passed as integer addresses (``tensor.data_ptr()``) or as objects that have a
+``data_ptr()`` method; the stream as an integer (``torch.cuda.current_stream().cuda_stream``).
+If the library has not been built the import of this module fails loudly - there is
+no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass, field
+from typing import List, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcanz.so")
+
+OK, EINVAL, ESHAPE, EWORKSPACE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+COST_NUMEL, COST_NS_FLOPS = 0, 1
+DT_F32, DT_BF16 = 0, 1
+SCALE_NONE, SCALE_ASPECT, SCALE_RMS = 0, 1, 2
+PREC_BF16, PREC_F32 = 0, 1
+OUT_PARAM, OUT_DELTA = 0, 1
+
+EXPORTS = ("canz_last_error", "canz_version", "canz_partition_alpha", "canz_microgroup_plan",
+           "canz_muon_workspace_bytes", "canz_muon_step")
+
+
+class CanzError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__("canz error %d: %s" % (code, message))
+        self.code = code
+
+
+class _Group(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("n_mats", C.c_int32), ("tp", C.c_int32),
+                ("grad_dtype", C.c_int32), ("out_dtype", C.c_int32),
+                ("grad", C.POINTER(C.c_void_p)), ("mom", C.POINTER(C.c_void_p)), ("out", C.POINTER(C.c_void_p))]
+
+
+class _Hparams(C.Structure):
+    _fields_ = [("beta", C.c_float), ("lr", C.c_float), ("weight_decay", C.c_float), ("eps", C.c_float),
+                ("nesterov", C.c_int32), ("ns_steps", C.c_int32),
+                ("a", C.c_float), ("b", C.c_float), ("c", C.c_float),
+                ("scale_mode", C.c_int32), ("precision", C.c_int32), ("out_mode", C.c_int32)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libcanz.so is missing at %s - build it with "
+                           "`python -m paper_2602_06079_amd.build` (there is no fallback)" % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    lib.canz_last_error.restype = C.c_char_p
+    lib.canz_version.restype = C.c_char_p
+    i64p, i32p = C.POINTER(C.c_int64), C.POINTER(C.c_int32)
+    lib.canz_partition_alpha.argtypes = [C.c_int64, i64p, i64p, i64p, C.c_int32, C.c_int64, i64p, C.c_int32,
+                                         C.c_double, i64p, i32p, i64p]
+    lib.canz_partition_alpha.restype = C.c_int
+    lib.canz_microgroup_plan.argtypes = [C.c_int64, i64p, i64p, i32p, i32p, C.c_int32, C.c_int32, C.c_int64,
+                                         i64p, i64p, i64p]
+    lib.canz_microgroup_plan.restype = C.c_int
+    lib.canz_muon_workspace_bytes.argtypes = [C.POINTER(_Group), C.c_int32, C.POINTER(_Hparams),
+                                              C.POINTER(C.c_size_t)]
+    lib.canz_muon_workspace_bytes.restype = C.c_int
+    lib.canz_muon_step.argtypes = [C.POINTER(_Group), C.c_int32, C.POINTER(_Hparams), C.c_void_p, C.c_size_t,
+                                   C.c_void_p]
+    lib.canz_muon_step.restype = C.c_int
+    return lib
+
+
+_lib = _load()
+
+
+def _check(rc: int):
+    if rc != OK:
+        raise CanzError(rc, _lib.canz_last_error().decode())
+
+
+def canz_version() -> str:
+    return _lib.canz_version().decode()
+
+
+def canz_last_error() -> str:
+    return _lib.canz_last_error().decode()
+
+
+def _i64(x):
+    return np.ascontiguousarray(x, dtype=np.int64)
+
+
+def _i32(x):
+    return np.ascontiguousarray(x, dtype=np.int32)
+
+
+def _p64(a):
+    return a.ctypes.data_as(C.POINTER(C.c_int64))
+
+
+def _p32(a):
+    return a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def canz_partition_alpha(rows, cols, bucket_off, n_ranks, alpha, cost=None, cost_kind=COST_NUMEL):
+    """Algorithm 1.  Returns (cuts [n_buckets][n_ranks+1], owner [n_mats], load [n_ranks]) as numpy arrays."""
+    rows, cols, bucket_off = _i64(rows), _i64(cols), _i64(bucket_off)
+    n_mats, n_buckets = rows.shape[0], bucket_off.shape[0] - 1
+    cost_a = None if cost is None else _i64(cost)
+    cuts = np.zeros((max(n_buckets, 0), max(int(n_ranks), 0) + 1), dtype=np.int64)
+    owner = np.full(n_mats, -1, dtype=np.int32)
+    load = np.zeros(max(int(n_ranks), 0), dtype=np.int64)
+    _check(_lib.canz_partition_alpha(n_mats, _p64(rows), _p64(cols), None if cost_a is None else _p64(cost_a),
+                                     int(cost_kind), n_buckets, _p64(bucket_off), int(n_ranks), float(alpha),
+                                     _p64(cuts), _p32(owner), _p64(load)))
+    return cuts, owner, load
+
+
+def canz_microgroup_plan(rows, cols, dtype, owner, rank, max_mats=8, cmax_bytes=0) -> List[List[int]]:
+    """Same-shape batches of the matrices ``rank`` owns; a list of id lists."""
+    rows, cols, dtype, owner = _i64(rows), _i64(cols), _i32(dtype), _i32(owner)
+    n = rows.shape[0]
+    n_groups = C.c_int64(0)
+    off = np.zeros(n + 1, dtype=np.int64)
+    member = np.zeros(max(n, 1), dtype=np.int64)
+    _check(_lib.canz_microgroup_plan(n, _p64(rows), _p64(cols), _p32(dtype), _p32(owner), int(rank), int(max_mats),
+                                     int(cmax_bytes), C.byref(n_groups), _p64(off), _p64(member)))
+    return [[int(x) for x in member[off[i]:off[i + 1]]] for i in range(n_groups.value)]
+
+
+@dataclass
+class Hparams:
+    beta: float = 0.95
+    lr: float = 0.02
+    weight_decay: float = 0.0
+    eps: float = 1e-7
+    nesterov: bool = False
+    ns_steps: int = 5
+    a: float = 3.4445
+    b: float = -4.7750
+    c: float = 2.0315
+    scale_mode: int = SCALE_RMS
+    precision: int = PREC_BF16
+    out_mode: int = OUT_PARAM
+
+    def _c(self) -> _Hparams:
+        return _Hparams(self.beta, self.lr, self.weight_decay, self.eps, int(bool(self.nesterov)), int(self.ns_steps),
+                        self.a, self.b, self.c, int(self.scale_mode), int(self.precision), int(self.out_mode))
+
+
+@dataclass
+class Group:
+    """One micro-group: device buffers given as addresses or objects with data_ptr()."""
+    rows: int
+    cols: int
+    grad: Sequence = field(default_factory=list)   # n_mats * tp
+    mom: Sequence = field(default_factory=list)    # n_mats
+    out: Sequence = field(default_factory=list)    # n_mats (params) or n_mats * tp (delta fragments)
+    tp: int = 1
+    grad_dtype: int = DT_BF16
+    out_dtype: int = DT_F32
+    n_mats: int = -1                               # -1: len(mom)
+
+
+def _addr(x) -> int:
+    return int(x.data_ptr()) if hasattr(x, "data_ptr") else int(x)
+
+
+def _marshal(groups: Sequence[Group]):
+    arr = (_Group * max(len(groups), 1))()
+    keep = []
+    for i, g in enumerate(groups):
+        n_mats = len(g.mom) if g.n_mats < 0 else g.n_mats
+        tabs = []
+        for seq in (g.grad, g.mom, g.out):
+            t = (C.c_void_p * max(len(seq), 1))(*[_addr(x) for x in seq])
+            keep.append(t)
+            tabs.append(C.cast(t, C.POINTER(C.c_void_p)) if len(seq) else None)
+        arr[i] = _Group(int(g.rows), int(g.cols), int(n_mats), int(g.tp), int(g.grad_dtype), int(g.out_dtype),
+                        tabs[0], tabs[1], tabs[2])
+    return arr, keep
+
+
+def canz_muon_workspace_bytes(groups: Sequence[Group], hp: Hparams) -> int:
+    arr, _keep = _marshal(groups)
+    out = C.c_size_t(0)
+    h = hp._c()
+    _check(_lib.canz_muon_workspace_bytes(arr, len(groups), C.byref(h), C.byref(out)))
+    return int(out.value)
+
+
+def canz_muon_step(groups: Sequence[Group], hp: Hparams, workspace, workspace_bytes: int, stream=0) -> None:
+    """Enqueue one optimizer step on ``stream`` (an integer hipStream_t)."""
+    arr, _keep = _marshal(groups)
+    h = hp._c()
+    _check(_lib.canz_muon_step(arr, len(groups), C.byref(h), C.c_void_p(_addr(workspace)), int(workspace_bytes),
+                               C.c_void_p(int(stream))))

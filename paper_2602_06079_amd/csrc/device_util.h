@@ -1,0 +1,60 @@
+// Small device-side helpers shared by the kernels: bf16 conversion, wave / block
+// reductions, and the store of one output element into the caller's buffers.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "canz.h"
+#include "kernels.h"
+
+namespace canz {
+
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+template <typename T>
+__device__ __forceinline__ T from_f32(float v);
+template <>
+__device__ __forceinline__ float from_f32<float>(float v) {
+  return v;
+}
+template <>
+__device__ __forceinline__ __bf16 from_f32<__bf16>(float v) {
+  return static_cast<__bf16>(v);  // round-to-nearest-even (v_cvt_pk_bf16_f32)
+}
+
+// Sum over the 64 lanes of a wavefront; every lane receives the total.
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// O (one element of the orthogonalised matrix, caller's orientation) -> caller's buffer.
+//   CANZ_OUT_PARAM: P <- P * decay + neg_lr_scale * O       (Sec. 3.3 stage (2))
+//   CANZ_OUT_DELTA: Delta W fragment <- neg_lr_scale * O     (Sec. 4.1 stage (3))
+__device__ __forceinline__ void store_out(const OutSpec& o, const Shape& s, int b, int row, int col, float ortho) {
+  const float delta = o.neg_lr_scale * ortho;
+  if (o.out_mode == CANZ_OUT_PARAM) {
+    const int64_t idx = static_cast<int64_t>(row) * s.cols + col;
+    if (o.out_dtype == CANZ_DT_F32) {
+      float* p = static_cast<float*>(o.out.p[b]);
+      p[idx] = p[idx] * o.decay + delta;
+    } else {
+      __bf16* p = static_cast<__bf16*>(o.out.p[b]);
+      p[idx] = static_cast<__bf16>(static_cast<float>(p[idx]) * o.decay + delta);
+    }
+  } else {
+    const int wf = static_cast<int>(s.wfrag);
+    const int f = col / wf;
+    const int64_t idx = static_cast<int64_t>(row) * wf + (col - f * wf);
+    if (o.out_dtype == CANZ_DT_F32) {
+      static_cast<float*>(o.out.p[b * s.tp + f])[idx] = delta;
+    } else {
+      static_cast<__bf16*>(o.out.p[b * s.tp + f])[idx] = static_cast<__bf16>(delta);
+    }
+  }
+}
+
+}  // namespace canz

@@ -1,0 +1,92 @@
+// Launchers of the device kernels behind canz_muon_step (internal, not part of the ABI).
+//
+// Working layout of one sub-batch of nb same-shape matrices (m = min(rows, cols),
+// n = max(rows, cols), mp / np = m / n rounded up to PAD):
+//   XW  [nb][mp][np]  the iterate X in its wide orientation, row-major
+//   XT  [nb][np][mp]  the same values transposed (two buffers, ping-pong)
+//   A,B [nb][mp][mp]  Gram matrix and the polynomial aI + bA + cAA
+// Padding rows / columns hold zeros; zeros stay zero under the iteration, so the GEMM
+// kernels run on the padded extents without bounds checks.  Both orientations are kept
+// because every product then contracts over a contiguous index of both operands
+// (C[i][j] = sum_k P[i][k] Q[j][k]), which is the operand form of the bf16 MFMA.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace canz {
+
+constexpr int PAD = 256;           // working extents are multiples of this
+constexpr int MAX_BATCH = 16;      // matrices per launch (larger groups are split)
+constexpr int MAX_TP = 8;
+constexpr int EW_TILE = 64;        // elementwise kernels work on 64 x 64 tiles
+
+// Pointer tables travel as kernel arguments, so nothing is copied to the device.
+struct PtrTable {
+  void* p[MAX_BATCH * MAX_TP];
+};
+
+struct Shape {
+  int64_t rows, cols;   // caller's matrix
+  int64_t m, n;         // min / max extent
+  int64_t mp, np;       // padded
+  int tall;             // rows > cols: the wide orientation is the transpose
+  int tp;               // column fragments of grad / delta
+  int64_t wfrag;        // cols / tp
+};
+
+// ---- elementwise -----------------------------------------------------------------
+// M <- beta M + G; U = M or G + beta M; U written (type T = bf16 or float) to XW and XT
+// (padding zero-filled); per-tile sums of U^2 to partial[b][tile].
+template <typename T>
+hipError_t launch_momentum(const Shape& s, int nb, const PtrTable& grad, int grad_dtype,
+                           const PtrTable& mom, float beta, int nesterov, T* xw, T* xt,
+                           float* partial, hipStream_t st);
+int momentum_tiles(const Shape& s);  // partial sums per matrix
+
+// scale[b] = 1 / (sqrt(sum partial[b][*]) + eps), scale2[b] = scale[b]^2
+hipError_t launch_norm_scale(int nb, int n_partial, const float* partial, float eps, float* scale,
+                             float* scale2, hipStream_t st);
+
+struct OutSpec {
+  PtrTable out;
+  int out_dtype;      // CANZ_DT_*
+  int out_mode;       // CANZ_OUT_*
+  float decay;        // 1 - lr * weight_decay
+  float neg_lr_scale; // -lr * scale
+};
+
+// ns_steps == 0: O = scale[b] * U taken from the orientation that matches the caller's.
+template <typename T>
+hipError_t launch_apply(const Shape& s, int nb, const T* x_straight, int64_t ld, int64_t batch_stride,
+                        const float* scale, const OutSpec& o, hipStream_t st);
+
+// ---- bf16 MFMA GEMMs -------------------------------------------------------------
+struct GemmDims {
+  int64_t M, N, K;          // multiples of PAD
+  int64_t ldp, ldq;         // row strides of P [M][K] and Q [N][K]
+  int64_t sp, sq;           // batch strides
+  int nb;
+};
+// A = scale2[b] * X X^T                      (P = Q = XW)
+hipError_t launch_gram_bf16(const GemmDims& d, const void* xw, void* a_out, const float* scale2, hipStream_t st);
+// B = ca I + cb A + cc A A                   (P = Q = A, symmetric)
+hipError_t launch_poly_bf16(const GemmDims& d, const void* a_in, void* b_out, float ca, float cb, float cc,
+                            hipStream_t st);
+// X' = scale[b] * B X: XW' [mp][np] straight and XT' [np][mp] transposed  (P = B, Q = XT)
+hipError_t launch_update_bf16(const GemmDims& d, const void* b_in, const void* xt_in, void* xw_out, void* xt_out,
+                              const float* scale, hipStream_t st);
+// last step: O = scale[b] * B X goes straight into the caller's buffers
+hipError_t launch_final_bf16(const GemmDims& d, const void* b_in, const void* xt_in, const float* scale,
+                             const Shape& s, const OutSpec& o, hipStream_t st);
+
+// ---- fp32 verification GEMMs (same contracts, float storage) ----------------------
+hipError_t launch_gram_f32(const GemmDims& d, const void* xw, void* a_out, const float* scale2, hipStream_t st);
+hipError_t launch_poly_f32(const GemmDims& d, const void* a_in, void* b_out, float ca, float cb, float cc,
+                           hipStream_t st);
+hipError_t launch_update_f32(const GemmDims& d, const void* b_in, const void* xt_in, void* xw_out, void* xt_out,
+                             const float* scale, hipStream_t st);
+hipError_t launch_final_f32(const GemmDims& d, const void* b_in, const void* xt_in, const float* scale,
+                            const Shape& s, const OutSpec& o, hipStream_t st);
+
+}  // namespace canz

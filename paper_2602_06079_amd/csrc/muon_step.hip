@@ -1,0 +1,221 @@
+// canz_muon_step / canz_muon_workspace_bytes: host side of the per-rank Muon step
+// (Delta W = Muon_step(G, States), Sec. 4.1 stage (2); zero-communication owner update,
+// Sec. 3.3 stage (2)).  Validates the groups, carves the caller's workspace and enqueues
+// the kernels of each micro-group on the caller's stream:
+//   momentum (+ TP gather, cast, norm partials) -> norm scale ->
+//   ns_steps x { Gram, polynomial, update }  with the last update writing the caller's
+//   buffers (+ TP scatter).  Nothing here allocates, copies to the device or synchronises.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+
+#include "canz.h"
+#include "canz_internal.h"
+#include "kernels.h"
+
+namespace canz {
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+inline int64_t pad_up(int64_t x) { return (x + PAD - 1) / PAD * PAD; }
+
+struct Carve {
+  size_t xw, xt0, xt1, a, b, partial, scale, scale2, total;
+};
+
+Shape make_shape(const canz_group& g) {
+  Shape s{};
+  s.rows = g.rows, s.cols = g.cols;
+  s.m = std::min(g.rows, g.cols), s.n = std::max(g.rows, g.cols);
+  s.mp = pad_up(s.m), s.np = pad_up(s.n);
+  s.tall = g.rows > g.cols;
+  s.tp = g.tp;
+  s.wfrag = g.cols / g.tp;
+  return s;
+}
+
+Carve carve(const Shape& s, int nb, int precision) {
+  const size_t esz = precision == CANZ_PREC_BF16 ? 2 : 4;
+  const size_t x_bytes = align_up(static_cast<size_t>(nb) * s.mp * s.np * esz);
+  const size_t a_bytes = align_up(static_cast<size_t>(nb) * s.mp * s.mp * esz);
+  Carve c{};
+  size_t off = 0;
+  c.xw = off, off += x_bytes;
+  c.xt0 = off, off += x_bytes;
+  c.xt1 = off, off += x_bytes;
+  c.a = off, off += a_bytes;
+  c.b = off, off += a_bytes;
+  c.partial = off, off += align_up(static_cast<size_t>(nb) * momentum_tiles(s) * sizeof(float));
+  c.scale = off, off += align_up(nb * sizeof(float));
+  c.scale2 = off, off += align_up(nb * sizeof(float));
+  c.total = off;
+  return c;
+}
+
+int check_hparams(const canz_muon_hparams* hp) {
+  if (!hp) return fail(CANZ_EINVAL, "null hparams");
+  if (hp->ns_steps < 0) return fail(CANZ_EINVAL, "ns_steps must be >= 0");
+  if (hp->scale_mode < CANZ_SCALE_NONE || hp->scale_mode > CANZ_SCALE_RMS)
+    return fail(CANZ_EUNSUPPORTED, "unknown scale_mode %d", hp->scale_mode);
+  if (hp->precision != CANZ_PREC_BF16 && hp->precision != CANZ_PREC_F32)
+    return fail(CANZ_EUNSUPPORTED, "unknown precision %d", hp->precision);
+  if (hp->out_mode != CANZ_OUT_PARAM && hp->out_mode != CANZ_OUT_DELTA)
+    return fail(CANZ_EUNSUPPORTED, "unknown out_mode %d", hp->out_mode);
+  return CANZ_OK;
+}
+
+int check_group(const canz_group& g, int idx, bool need_ptrs, int out_mode) {
+  if (g.n_mats < 0) return fail(CANZ_EINVAL, "group %d: n_mats < 0", idx);
+  if (g.rows < 1 || g.cols < 1) return fail(CANZ_EINVAL, "group %d: empty shape", idx);
+  if (g.rows > (int64_t(1) << 30) || g.cols > (int64_t(1) << 30))
+    return fail(CANZ_ESHAPE, "group %d: extent above 2^30", idx);
+  if (g.tp < 1 || g.tp > MAX_TP) return fail(CANZ_EINVAL, "group %d: tp must be in 1..%d", idx, MAX_TP);
+  if (g.cols % g.tp) return fail(CANZ_ESHAPE, "group %d: cols not divisible by tp", idx);
+  if (g.tp > 1 && (g.cols / g.tp) % 8) return fail(CANZ_ESHAPE, "group %d: fragment width not a multiple of 8", idx);
+  if (g.grad_dtype != CANZ_DT_F32 && g.grad_dtype != CANZ_DT_BF16)
+    return fail(CANZ_EUNSUPPORTED, "group %d: unknown grad_dtype", idx);
+  if (g.out_dtype != CANZ_DT_F32 && g.out_dtype != CANZ_DT_BF16)
+    return fail(CANZ_EUNSUPPORTED, "group %d: unknown out_dtype", idx);
+  if (!need_ptrs || g.n_mats == 0) return CANZ_OK;
+  if (!g.grad || !g.mom || !g.out) return fail(CANZ_EINVAL, "group %d: null pointer table", idx);
+  const int n_out = out_mode == CANZ_OUT_DELTA ? g.n_mats * g.tp : g.n_mats;
+  auto bad = [](const void* p) { return p == nullptr || (reinterpret_cast<uintptr_t>(p) & 15u) != 0; };
+  for (int i = 0; i < g.n_mats * g.tp; ++i)
+    if (bad(g.grad[i])) return fail(CANZ_EINVAL, "group %d: grad[%d] null or not 16-byte aligned", idx, i);
+  for (int i = 0; i < g.n_mats; ++i)
+    if (bad(g.mom[i])) return fail(CANZ_EINVAL, "group %d: mom[%d] null or not 16-byte aligned", idx, i);
+  for (int i = 0; i < n_out; ++i)
+    if (bad(g.out[i])) return fail(CANZ_EINVAL, "group %d: out[%d] null or not 16-byte aligned", idx, i);
+  return CANZ_OK;
+}
+
+double update_scale(const canz_group& g, int mode) {
+  if (mode == CANZ_SCALE_ASPECT) return std::sqrt(std::max(1.0, static_cast<double>(g.rows) / static_cast<double>(g.cols)));
+  if (mode == CANZ_SCALE_RMS) return 0.2 * std::sqrt(static_cast<double>(std::max(g.rows, g.cols)));
+  return 1.0;
+}
+
+#define CANZ_HIP(expr, what)                                                            \
+  do {                                                                                  \
+    hipError_t err__ = (expr);                                                          \
+    if (err__ != hipSuccess) return fail(CANZ_EHIP, "%s: %s", what, hipGetErrorString(err__)); \
+  } while (0)
+
+// One sub-batch (<= MAX_BATCH matrices of one group).
+template <typename T>
+int run_batch(const canz_group& g, int first, int nb, const canz_muon_hparams& hp, char* ws, hipStream_t st) {
+  const Shape s = make_shape(g);
+  const Carve c = carve(s, nb, hp.precision);
+  T* xw = reinterpret_cast<T*>(ws + c.xw);
+  T* xt[2] = {reinterpret_cast<T*>(ws + c.xt0), reinterpret_cast<T*>(ws + c.xt1)};
+  T* a = reinterpret_cast<T*>(ws + c.a);
+  T* bm = reinterpret_cast<T*>(ws + c.b);
+  float* partial = reinterpret_cast<float*>(ws + c.partial);
+  float* scale = reinterpret_cast<float*>(ws + c.scale);
+  float* scale2 = reinterpret_cast<float*>(ws + c.scale2);
+  constexpr bool is_bf16 = sizeof(T) == 2;
+
+  PtrTable grad{}, mom{};
+  OutSpec o{};
+  for (int i = 0; i < nb * g.tp; ++i) grad.p[i] = const_cast<void*>(g.grad[first * g.tp + i]);
+  for (int i = 0; i < nb; ++i) mom.p[i] = g.mom[first + i];
+  if (hp.out_mode == CANZ_OUT_DELTA)
+    for (int i = 0; i < nb * g.tp; ++i) o.out.p[i] = g.out[first * g.tp + i];
+  else
+    for (int i = 0; i < nb; ++i) o.out.p[i] = g.out[first + i];
+  o.out_dtype = g.out_dtype;
+  o.out_mode = hp.out_mode;
+  o.decay = static_cast<float>(1.0 - static_cast<double>(hp.lr) * static_cast<double>(hp.weight_decay));
+  o.neg_lr_scale = static_cast<float>(-static_cast<double>(hp.lr) * update_scale(g, hp.scale_mode));
+
+  CANZ_HIP(launch_momentum<T>(s, nb, grad, g.grad_dtype, mom, hp.beta, hp.nesterov, xw, xt[0], partial, st),
+           "momentum kernel");
+  CANZ_HIP(launch_norm_scale(nb, momentum_tiles(s), partial, hp.eps, scale, scale2, st), "norm kernel");
+
+  if (hp.ns_steps == 0) {
+    const T* straight = s.tall ? xt[0] : xw;
+    const int64_t ld = s.tall ? s.mp : s.np;
+    CANZ_HIP(launch_apply<T>(s, nb, straight, ld, s.mp * s.np, scale, o, st), "apply kernel");
+    return CANZ_OK;
+  }
+
+  GemmDims gram{s.mp, s.mp, s.np, s.np, s.np, s.mp * s.np, s.mp * s.np, nb};
+  GemmDims poly{s.mp, s.mp, s.mp, s.mp, s.mp, s.mp * s.mp, s.mp * s.mp, nb};
+  GemmDims upd{s.mp, s.np, s.mp, s.mp, s.mp, s.mp * s.mp, s.np * s.mp, nb};
+  int cur = 0;
+  for (int it = 0; it < hp.ns_steps; ++it) {
+    const float* sc1 = it == 0 ? scale : nullptr;
+    const float* sc2 = it == 0 ? scale2 : nullptr;
+    const bool last = it + 1 == hp.ns_steps;
+    if (is_bf16) {
+      CANZ_HIP(launch_gram_bf16(gram, xw, a, sc2, st), "gram kernel");
+      CANZ_HIP(launch_poly_bf16(poly, a, bm, hp.a, hp.b, hp.c, st), "poly kernel");
+      if (!last)
+        CANZ_HIP(launch_update_bf16(upd, bm, xt[cur], xw, xt[cur ^ 1], sc1, st), "update kernel");
+      else
+        CANZ_HIP(launch_final_bf16(upd, bm, xt[cur], sc1, s, o, st), "final kernel");
+    } else {
+      CANZ_HIP(launch_gram_f32(gram, xw, a, sc2, st), "gram kernel");
+      CANZ_HIP(launch_poly_f32(poly, a, bm, hp.a, hp.b, hp.c, st), "poly kernel");
+      if (!last)
+        CANZ_HIP(launch_update_f32(upd, bm, xt[cur], xw, xt[cur ^ 1], sc1, st), "update kernel");
+      else
+        CANZ_HIP(launch_final_f32(upd, bm, xt[cur], sc1, s, o, st), "final kernel");
+    }
+    cur ^= 1;
+  }
+  return CANZ_OK;
+}
+
+}  // namespace
+}  // namespace canz
+
+extern "C" int canz_muon_workspace_bytes(const canz_group* g, int32_t n_groups, const canz_muon_hparams* hp,
+                                         size_t* bytes_out) {
+  using namespace canz;
+  if (!bytes_out) return fail(CANZ_EINVAL, "null bytes_out");
+  if (n_groups < 0 || (n_groups > 0 && !g)) return fail(CANZ_EINVAL, "bad group array");
+  if (int rc = check_hparams(hp)) return rc;
+  size_t need = ALIGN;
+  for (int i = 0; i < n_groups; ++i) {
+    if (int rc = check_group(g[i], i, false, hp->out_mode)) return rc;
+    if (g[i].n_mats == 0) continue;
+    const int nb = std::min<int>(g[i].n_mats, MAX_BATCH);
+    need = std::max(need, carve(make_shape(g[i]), nb, hp->precision).total);
+  }
+  *bytes_out = need;
+  return CANZ_OK;
+}
+
+extern "C" int canz_muon_step(const canz_group* g, int32_t n_groups, const canz_muon_hparams* hp, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  using namespace canz;
+  if (n_groups < 0 || (n_groups > 0 && !g)) return fail(CANZ_EINVAL, "bad group array");
+  if (int rc = check_hparams(hp)) return rc;
+  size_t need = 0;
+  if (int rc = canz_muon_workspace_bytes(g, n_groups, hp, &need)) return rc;
+  for (int i = 0; i < n_groups; ++i)
+    if (int rc = check_group(g[i], i, true, hp->out_mode)) return rc;
+  bool any = false;
+  for (int i = 0; i < n_groups; ++i) any = any || g[i].n_mats > 0;
+  if (!any) return CANZ_OK;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (ALIGN - 1)))
+    return fail(CANZ_EWORKSPACE, "workspace null or not 256-byte aligned");
+  if (workspace_bytes < need)
+    return fail(CANZ_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  for (int i = 0; i < n_groups; ++i) {
+    for (int first = 0; first < g[i].n_mats; first += MAX_BATCH) {
+      const int nb = std::min<int>(MAX_BATCH, g[i].n_mats - first);
+      const int rc = hp->precision == CANZ_PREC_BF16 ? run_batch<__bf16>(g[i], first, nb, *hp, ws, st)
+                                                     : run_batch<float>(g[i], first, nb, *hp, ws, st);
+      if (rc) return rc;
+    }
+  }
+  return CANZ_OK;
+}

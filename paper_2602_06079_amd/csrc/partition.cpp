@@ -1,0 +1,116 @@
+// canz_partition_alpha: alpha-balanced greedy LPT partitioning (Algorithm 1, Sec. 3.2).
+//
+// Host code.  Loads are int64; mu, deficits, blend and running target are IEEE fp64 in
+// the operation order documented in canz.h.  Build with -ffp-contract=off so that no
+// multiply-add is fused: the decisions must be reproducible bit for bit.
+#include <algorithm>
+#include <cmath>
+#include <numeric>
+#include <vector>
+
+#include "canz.h"
+#include "canz_internal.h"
+
+namespace {
+
+int64_t ns_flops(int64_t rows, int64_t cols) {
+  const int64_t m = std::min(rows, cols), n = std::max(rows, cols);
+  return 5 * (4 * m * m * n + 2 * m * m * m);
+}
+
+}  // namespace
+
+extern "C" int canz_partition_alpha(int64_t n_mats, const int64_t* rows, const int64_t* cols,
+                                    const int64_t* cost, int32_t cost_kind, int64_t n_buckets,
+                                    const int64_t* bucket_off, int32_t n_ranks, double alpha,
+                                    int64_t* cut_out, int32_t* owner_out, int64_t* load_out) {
+  using canz::fail;
+  if (n_mats < 0 || n_buckets < 0) return fail(CANZ_EINVAL, "negative size");
+  if (!bucket_off || !cut_out || !owner_out || !load_out) return fail(CANZ_EINVAL, "null pointer");
+  if (!cost && (!rows || !cols) && n_mats > 0) return fail(CANZ_EINVAL, "need cost or rows/cols");
+  if (n_ranks < 1) return fail(CANZ_EINVAL, "n_ranks must be >= 1");
+  if (!(alpha >= 0.0 && alpha <= 1.0)) return fail(CANZ_EINVAL, "alpha must lie in [0,1]");
+  if (!cost && cost_kind != CANZ_COST_NUMEL && cost_kind != CANZ_COST_NS_FLOPS)
+    return fail(CANZ_EUNSUPPORTED, "unknown cost_kind %d", cost_kind);
+  if (bucket_off[0] != 0 || bucket_off[n_buckets] != n_mats)
+    return fail(CANZ_EINVAL, "bucket_off must run from 0 to n_mats");
+  for (int64_t i = 0; i < n_buckets; ++i)
+    if (bucket_off[i + 1] < bucket_off[i]) return fail(CANZ_EINVAL, "bucket_off must be non-decreasing");
+
+  // W(p)
+  std::vector<int64_t> w(n_mats);
+  for (int64_t p = 0; p < n_mats; ++p) {
+    if (cost) {
+      w[p] = cost[p];
+    } else {
+      if (rows[p] < 0 || cols[p] < 0) return fail(CANZ_EINVAL, "negative shape at %lld", (long long)p);
+      w[p] = cost_kind == CANZ_COST_NUMEL ? rows[p] * cols[p] : ns_flops(rows[p], cols[p]);
+    }
+    if (w[p] < 0) return fail(CANZ_EINVAL, "negative cost at %lld", (long long)p);
+  }
+
+  const int R = n_ranks;
+  // Phi_i(u): prefix sums per bucket, stored flat at bucket_off[i] + i + u.
+  std::vector<int64_t> phi(n_mats + n_buckets);
+  std::vector<int64_t> wk(n_buckets);
+  int64_t total = 0;
+  for (int64_t i = 0; i < n_buckets; ++i) {
+    int64_t* ph = phi.data() + bucket_off[i] + i;
+    ph[0] = 0;
+    const int64_t len = bucket_off[i + 1] - bucket_off[i];
+    for (int64_t u = 0; u < len; ++u) ph[u + 1] = ph[u] + w[bucket_off[i] + u];
+    wk[i] = ph[len];
+    total += wk[i];
+  }
+  if (total >= (int64_t(1) << 53)) return fail(CANZ_EINVAL, "total load exceeds 2^53");
+
+  std::vector<int64_t> order(n_buckets);
+  std::iota(order.begin(), order.end(), int64_t(0));
+  std::stable_sort(order.begin(), order.end(), [&](int64_t x, int64_t y) { return wk[x] > wk[y]; });
+
+  std::vector<int64_t> load(R, 0);
+  std::vector<double> d(R);
+  const double mu = static_cast<double>(total) / static_cast<double>(R);
+  const double v_even = 1.0 / static_cast<double>(R);
+
+  for (int64_t t = 0; t < n_buckets; ++t) {
+    const int64_t k = order[t];
+    const int64_t len = bucket_off[k + 1] - bucket_off[k];
+    const int64_t* ph = phi.data() + bucket_off[k] + k;
+    int64_t* s = cut_out + k * (int64_t(R) + 1);
+
+    double d_total = 0.0;
+    for (int r = 0; r < R; ++r) {
+      const double gap = mu - static_cast<double>(load[r]);
+      d[r] = gap > 0.0 ? gap : 0.0;
+    }
+    for (int r = 0; r < R; ++r) d_total = d_total + d[r];
+
+    s[0] = 0;
+    double c_run = 0.0;
+    for (int r = 0; r + 1 < R; ++r) {
+      const double v_fill = d_total > 0.0 ? d[r] / d_total : v_even;
+      const double v_star = (1.0 - alpha) * v_even + alpha * v_fill;
+      const double target = static_cast<double>(wk[k]) * v_star;
+      c_run = c_run + target;
+      int64_t best_u = 0;
+      double best_gap = std::fabs(static_cast<double>(ph[0]) - c_run);
+      for (int64_t u = 1; u <= len; ++u) {
+        const double gap = std::fabs(static_cast<double>(ph[u]) - c_run);
+        if (gap < best_gap) {
+          best_gap = gap;
+          best_u = u;
+        }
+      }
+      s[r + 1] = best_u;
+      load[r] += ph[s[r + 1]] - ph[s[r]];
+    }
+    s[R] = len;
+    load[R - 1] += ph[s[R]] - ph[s[R - 1]];
+
+    for (int r = 0; r < R; ++r)
+      for (int64_t u = s[r]; u < s[r + 1]; ++u) owner_out[bucket_off[k] + u] = r;
+  }
+  for (int r = 0; r < R; ++r) load_out[r] = load[r];
+  return CANZ_OK;
+}

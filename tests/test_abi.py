@@ -1,0 +1,75 @@
+"""The C-ABI library loads and exports every symbol include/canz.h declares; host-side
+validation of canz_muon_step (everything that is rejected before any device work)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "canz.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(canz_[a-z_]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported(canz):
+    names = _declared_functions()
+    assert set(names) == set(canz.EXPORTS)
+    lib = ctypes.CDLL(canz.LIB_PATH)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert canz.canz_version() == "0.1.0"
+
+
+def test_struct_layouts_match_header(canz):
+    # canz_group: 2 x int64, 4 x int32, 3 pointers; canz_muon_hparams: 12 four-byte fields
+    assert ctypes.sizeof(canz._Group) == 16 + 16 + 24
+    assert ctypes.sizeof(canz._Hparams) == 48
+
+
+def test_workspace_bytes_formula(canz):
+    hp = canz.Hparams()
+    g = canz.Group(rows=256, cols=512, n_mats=8)
+    # bf16: 3 X buffers of 8*256*512*2 B, A and B of 8*256*256*2 B, 8*(4*8) tile sums, two scale arrays
+    want = 3 * 8 * 256 * 512 * 2 + 2 * 8 * 256 * 256 * 2 + 8 * 32 * 4 + 256 + 256
+    assert canz.canz_muon_workspace_bytes([g], hp) == want
+    # ragged shapes are padded to multiples of 256; fp32 mode doubles the element size
+    g2 = canz.Group(rows=300, cols=77, n_mats=1)
+    hp32 = canz.Hparams(precision=canz.PREC_F32)
+    want2 = 3 * 256 * 512 * 4 + 2 * 256 * 256 * 4 + 256 + 256 + 256
+    assert canz.canz_muon_workspace_bytes([g2], hp32) == want2
+    # the maximum over groups, and batches above 16 matrices are split
+    g3 = canz.Group(rows=256, cols=512, n_mats=40)
+    want3 = 3 * 16 * 256 * 512 * 2 + 2 * 16 * 256 * 256 * 2 + 16 * 32 * 4 + 256 + 256
+    assert canz.canz_muon_workspace_bytes([g, g3], hp) == want3
+    assert canz.canz_muon_workspace_bytes([], hp) == 256
+
+
+def test_step_argument_errors_without_device(canz):
+    hp = canz.Hparams()
+    ok = dict(rows=256, cols=512, grad=[4096], mom=[8192], out=[12288])
+
+    def code(groups, hp_, ws=256 * 1024, ws_bytes=1 << 40):
+        with pytest.raises(canz.CanzError) as e:
+            canz.canz_muon_step(groups, hp_, ws, ws_bytes, 0)
+        return e.value.code
+
+    assert code([canz.Group(**{**ok, "grad": [4100]})], hp) == canz.EINVAL          # misaligned
+    assert code([canz.Group(**{**ok, "mom": [0]})], hp) == canz.EINVAL              # null
+    assert code([canz.Group(**{**ok, "tp": 9})], hp) == canz.EINVAL
+    assert code([canz.Group(**{**ok, "tp": 3})], hp) == canz.ESHAPE                 # 512 % 3
+    assert code([canz.Group(**{**ok, "cols": 36, "tp": 3, "grad": [4096] * 3})], hp) == canz.ESHAPE  # width 12
+    assert code([canz.Group(**{**ok, "grad_dtype": 7})], hp) == canz.EUNSUPPORTED
+    assert code([canz.Group(**ok)], canz.Hparams(ns_steps=-1)) == canz.EINVAL
+    assert code([canz.Group(**ok)], canz.Hparams(scale_mode=9)) == canz.EUNSUPPORTED
+    assert code([canz.Group(**ok)], canz.Hparams(precision=2)) == canz.EUNSUPPORTED
+    assert code([canz.Group(**ok)], hp, ws=0) == canz.EWORKSPACE
+    assert code([canz.Group(**ok)], hp, ws=4096 + 16) == canz.EWORKSPACE            # not 256-aligned
+    assert code([canz.Group(**ok)], hp, ws_bytes=1024) == canz.EWORKSPACE
+    assert "workspace too small" in canz.canz_last_error()
+    # nothing to do: no device work, no workspace needed
+    canz.canz_muon_step([], hp, 0, 0, 0)
+    canz.canz_muon_step([canz.Group(rows=4, cols=4, n_mats=0)], hp, 0, 0, 0)
