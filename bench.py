@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of one rank's Muon optimizer step (canz_muon_step) on one MI355X.
+
+A "step" is one pass of the whole hot path - momentum, normalisation, ns_steps
+Newton-Schulz iterations and the fused update - over the share of the matrix set that
+the alpha-balanced partitioner assigns to the chosen rank.  Inputs are seeded synthetic
+Qwen3-shaped gradients already resident in HBM when timing starts.  One JSON line is
+printed on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6     # 256 CUs x 4096 FLOP/clk/CU x 2.4 GHz, dense
+PEAK_HBM_GBS = 8000.0
+
+
+def log(msg):
+    sys.stderr.write("[bench] %s\n" % msg)
+    sys.stderr.flush()
+
+
+def pick_share(canz, W, cfg):
+    """Planner calls (timed) -> (set, rank, groups of matrix ids, diagnostics)."""
+    import numpy as np
+    s = W.matrix_set(cfg)
+    t0 = time.perf_counter()
+    cuts, owner, load = canz.canz_partition_alpha(s["rows"], s["cols"], s["bucket_off"], s["n_ranks"], s["alpha"])
+    rank = 0 if cfg in (1, 2, 5) else int(np.argmax(load))   # argmax: lowest rank among equals
+    groups = canz.canz_microgroup_plan(s["rows"], s["cols"], s["dtype"], owner, rank, max_mats=8)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    mean = float(load.sum()) / len(load)
+    diag = dict(rank=rank, n_ranks=s["n_ranks"], alpha=s["alpha"], r_lb_numel=float(load.max()) / mean if mean else 1.0,
+                planner_ms=plan_ms)
+    return s, rank, groups, diag
+
+
+def ns_flops(rows, cols, steps):
+    m, n = min(rows, cols), max(rows, cols)
+    return steps * (4 * m * m * n + 2 * m ** 3)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default 4: Qwen3-32B share)")
+    ap.add_argument("--precision", choices=["bf16", "f32"], default="bf16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py measures one rank's share on ONE GPU; this build has no multi-GPU path "
+                         "(--gpus %d refused).\n" % args.gpus)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2602_06079_amd import build as _build
+    if not os.path.exists(_build.OUT):
+        _build.build()
+    from paper_2602_06079_amd import binding as canz
+    from paper_2602_06079_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = args.config
+    s, rank, groups, diag = pick_share(canz, W, cfg)
+    tp = s["tp"]
+    n_share = sum(len(g) for g in groups)
+    log("config %d (%s): rank %d owns %d matrices in %d groups; planner %.2f ms" %
+        (cfg, s["name"], rank, n_share, len(groups), diag["planner_ms"]))
+
+    # ---- inputs, resident in HBM before timing
+    hp = canz.Hparams(precision=canz.PREC_BF16 if args.precision == "bf16" else canz.PREC_F32,
+                      out_mode=canz.OUT_DELTA if tp > 1 else canz.OUT_PARAM)
+    total_elems = sum(s["rows"][p] * s["cols"][p] for g in groups for p in g)
+    host_gen = total_elems <= 700_000_000
+    dgroups, keep, first_host = [], [], None
+    t0 = time.perf_counter()
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(W.SEED_BASE + cfg)
+    for g in groups:
+        rows, cols = s["rows"][g[0]], s["cols"][g[0]]
+        grads, moms, outs = [], [], []
+        for p in g:
+            if host_gen:
+                bits, dt = W.gen_grad(cfg, p, rows, cols)
+                if first_host is None:
+                    first_host = (p, bits)
+                frags = W.split_columns(bits, tp) if tp > 1 else [bits]
+                for f in frags:
+                    t = torch.from_numpy(f)
+                    grads.append((t.view(torch.bfloat16) if f.dtype == np.uint16 else t).cuda())
+            else:
+                for _ in range(tp):
+                    grads.append((torch.randn(rows, cols // tp, device="cuda", generator=gen) * s["grad_std"])
+                                 .to(torch.bfloat16 if s["grad_dtype"] == W.DT_BF16 else torch.float32))
+            moms.append(torch.zeros(rows, cols, device="cuda"))
+            if tp > 1:
+                outs += [torch.zeros(rows, cols // tp, device="cuda", dtype=torch.bfloat16) for _ in range(tp)]
+            else:
+                outs.append(torch.randn(rows, cols, device="cuda", generator=gen) * 0.02)
+        keep.append((grads, moms, outs))
+        dgroups.append(canz.Group(rows=rows, cols=cols, grad=grads, mom=moms, out=outs, tp=tp,
+                                  grad_dtype=s["grad_dtype"],
+                                  out_dtype=canz.DT_BF16 if tp > 1 else canz.DT_F32))
+    ws_bytes = canz.canz_muon_workspace_bytes(dgroups, hp)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    log("inputs ready in %.1f s (%s); %.2f G elements; workspace %.2f GB" %
+        (time.perf_counter() - t0, "host numpy" if host_gen else "device torch.randn", total_elems / 1e9,
+         ws_bytes / 1e9))
+
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        canz.canz_muon_step(dgroups, hp, ws, ws_bytes, stream)
+
+    for i in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    log("warm-up done")
+
+    launches_per_step = sum(((len(g) + 15) // 16) * (2 + 3 * hp.ns_steps) for g in groups)
+    canz.canz_profile_enable(launches_per_step * args.steps + 8)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    ev[0].record()
+    for i in range(args.steps):
+        step()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_start) * 1e3
+    prof = canz.canz_profile_collect()
+    canz.canz_profile_disable()
+    per_step = [ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]
+    ms_per_step = wall_ms / args.steps
+    log("timed %d steps: %.3f ms/step (events: median %.3f, min %.3f)" %
+        (args.steps, ms_per_step, float(np.median(per_step)), min(per_step)))
+
+    # ---- work accounting
+    flops_step = float(sum(ns_flops(s["rows"][p], s["cols"][p], hp.ns_steps) for g in groups for p in g))
+    tflops = flops_step / (ms_per_step * 1e-3) / 1e12
+    # algorithmic FLOPs per launch kind (per step), as the method writes them
+    kind_flops = dict(gram=0.0, poly=0.0, update=0.0, final=0.0)
+    for g in groups:
+        rows, cols = s["rows"][g[0]], s["cols"][g[0]]
+        m, n = min(rows, cols), max(rows, cols)
+        kind_flops["gram"] += 2.0 * m * m * n * len(g) * hp.ns_steps
+        kind_flops["poly"] += 2.0 * m ** 3 * len(g) * hp.ns_steps
+        kind_flops["update"] += 2.0 * m * m * n * len(g) * (hp.ns_steps - 1)
+        kind_flops["final"] += 2.0 * m * m * n * len(g)
+    kernels = {}
+    for k, (ms, n) in prof.items():
+        if n:
+            kernels[k] = dict(ms_per_step=ms / args.steps, launches_per_step=n / args.steps, avg_ms=ms / n)
+            if k in kind_flops:
+                kernels[k]["tflops"] = kind_flops[k] * args.steps / (ms * 1e-3) / 1e12
+    dom = max((k for k in kernels if k in kind_flops), key=lambda k: kernels[k]["ms_per_step"])
+    dom_flops_per_launch = kind_flops[dom] / kernels[dom]["launches_per_step"]
+    achieved = dom_flops_per_launch / (kernels[dom]["avg_ms"] * 1e-3) / 1e12
+    roofline = dict(bound="mfma", kernel="k_gemm_nt_bf16<%s>" % dom, achieved=achieved, peak=PEAK_BF16_TFLOPS,
+                    unit="TFLOP/s", frac=achieved / PEAK_BF16_TFLOPS, traffic=None,
+                    flops_per_launch=dom_flops_per_launch, avg_launch_ms=kernels[dom]["avg_ms"])
+    if "momentum" in kernels:
+        grad_b = 2 if s["grad_dtype"] == W.DT_BF16 else 4
+        esz = 2 if args.precision == "bf16" else 4
+        bytes_step = total_elems * (grad_b + 8 + 2 * esz)
+        kernels["momentum"]["gbs"] = bytes_step / (kernels["momentum"]["ms_per_step"] * 1e-3) / 1e9
+        kernels["momentum"]["frac_hbm_peak"] = kernels["momentum"]["gbs"] / PEAK_HBM_GBS
+
+    # ---- the oracle on the host cores, bounded sample
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import muon as OM
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [os.cpu_count()])
+        except Exception:
+            cores = os.cpu_count()
+        f = lambda v: float(np.float32(v))
+        g0 = groups[0]
+        rows, cols = s["rows"][g0[0]], s["cols"][g0[0]]
+        if first_host is not None and first_host[0] == g0[0]:
+            bits = first_host[1]
+        else:
+            bits = W.gen_grad(cfg, g0[0], rows, cols)[0]
+        g64 = OM.bf16_bits_to_f64(bits) if bits.dtype == np.uint16 else bits.astype(np.float64)
+        mom0 = np.zeros((rows, cols))
+        base = dict(beta=f(hp.beta), lr=f(hp.lr), eps=f(hp.eps), a=f(hp.a), b=f(hp.b), c=f(hp.c),
+                    scale_mode=hp.scale_mode)
+        t0 = time.perf_counter()
+        OM.muon_step(g64, mom0, OM.Hparams(ns_steps=0, **base), param=mom0)
+        t_ew = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        OM.muon_step(g64, mom0, OM.Hparams(ns_steps=1, **base), param=mom0)
+        t_one = time.perf_counter() - t0
+        t_iter = max(t_one - t_ew, 0.0)
+        f0 = ns_flops(rows, cols, 1)
+        est_s = 0.0
+        for g in groups:
+            r, c = s["rows"][g[0]], s["cols"][g[0]]
+            est_s += len(g) * (t_ew * (r * c) / (rows * cols) + hp.ns_steps * t_iter * ns_flops(r, c, 1) / f0)
+        cpu = dict(value=est_s * 1e3, unit="ms", cores=int(cores), kind="oracle",
+                   sample="fp64 oracle on matrix %d (%dx%d): elementwise part %.2f s + one of %d Newton-Schulz "
+                          "iterations %.2f s (%.0f GFLOP/s), scaled by FLOPs and elements to the %d-matrix share"
+                          % (g0[0], rows, cols, t_ew, hp.ns_steps, t_iter, f0 / max(t_iter, 1e-9) / 1e9, n_share))
+        log("oracle sample: %.2f s measured, share estimated at %.1f s on %d threads" % (t_ew + t_one, est_s, cores))
+
+    out = {
+        "metric": "optimizer_step_latency_ms", "value": ms_per_step, "unit": "ms",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": args.precision, "data": "synthetic",
+        "config": {"workload": "config %d %s: rank %d of %d (alpha=%.2g), %d matrices %s in %d micro-groups, "
+                               "%d Newton-Schulz steps" %
+                               (cfg, s["name"], rank, s["n_ranks"], s["alpha"], n_share,
+                                sorted({(s["rows"][p], s["cols"][p]) for g in groups for p in g}), len(groups),
+                                hp.ns_steps),
+                   "tp": tp, "elements": total_elems},
+        "tflops": tflops, "frac_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS, "ns_flops_per_step": flops_step,
+        "step_ms_events": {"median": float(np.median(per_step)), "min": float(min(per_step))},
+        "planner": diag, "kernels": kernels, "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -173,6 +173,33 @@ int canz_muon_workspace_bytes(const canz_group* g, int32_t n_groups,
 int canz_muon_step(const canz_group* g, int32_t n_groups, const canz_muon_hparams* hp,
                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Per-kernel timing of canz_muon_step, for benchmarks (the measurement protocol of
+ * App. C.1 reports the optimizer time; this splits it by kernel).  While enabled, every
+ * kernel launch of a step is bracketed by a pair of HIP events on the step's own stream.
+ * Process-wide state: use from one thread, with steps that do not overlap.
+ *   canz_profile_enable   creates (host-side) events for up to max_launches launches per
+ *                         collection period and starts recording; launches beyond that
+ *                         are not recorded.
+ *   canz_profile_collect  waits for the recorded events, adds elapsed milliseconds and
+ *                         launch counts per kernel kind into ms_out / launches_out
+ *                         (host arrays of CANZ_KERNEL_KINDS entries) and starts a new period.
+ *   canz_profile_disable  stops recording.
+ */
+enum {
+  CANZ_KERNEL_MOMENTUM = 0, /* momentum + gather + cast + norm partial sums */
+  CANZ_KERNEL_NORM = 1,     /* 1 / (||U|| + eps)                            */
+  CANZ_KERNEL_GRAM = 2,     /* A = X X^T                                    */
+  CANZ_KERNEL_POLY = 3,     /* B = a I + b A + c A A                        */
+  CANZ_KERNEL_UPDATE = 4,   /* X <- B X (both orientations)                 */
+  CANZ_KERNEL_FINAL = 5,    /* last B X fused with the parameter update     */
+  CANZ_KERNEL_APPLY = 6,    /* update without Newton-Schulz steps           */
+  CANZ_KERNEL_KINDS = 7
+};
+int canz_profile_enable(int32_t max_launches);
+int canz_profile_collect(double* ms_out, int64_t* launches_out);
+int canz_profile_disable(void);
+
 #ifdef __cplusplus
 }
 #endif

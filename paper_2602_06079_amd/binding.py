@@ -26,7 +26,9 @@ PREC_BF16, PREC_F32 = 0, 1
 OUT_PARAM, OUT_DELTA = 0, 1
 
 EXPORTS = ("canz_last_error", "canz_version", "canz_partition_alpha", "canz_microgroup_plan",
-           "canz_muon_workspace_bytes", "canz_muon_step")
+           "canz_muon_workspace_bytes", "canz_muon_step",
+           "canz_profile_enable", "canz_profile_collect", "canz_profile_disable")
+KERNEL_KINDS = ("momentum", "norm", "gram", "poly", "update", "final", "apply")
 
 
 class CanzError(RuntimeError):
@@ -52,6 +54,13 @@ def _load():
     if not os.path.exists(LIB_PATH):
         raise RuntimeError("libcanz.so is missing at %s - build it with "
                            "`python -m paper_2602_06079_amd.build` (there is no fallback)" % LIB_PATH)
+    # One process must use one HIP runtime.  PyTorch ships its own copy and supplies the
+    # device memory and streams here, so it is loaded first; libcanz.so then binds to the
+    # runtime that is already in the process (same soname) instead of a second one.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(LIB_PATH)
     lib.canz_last_error.restype = C.c_char_p
     lib.canz_version.restype = C.c_char_p
@@ -68,6 +77,12 @@ def _load():
     lib.canz_muon_step.argtypes = [C.POINTER(_Group), C.c_int32, C.POINTER(_Hparams), C.c_void_p, C.c_size_t,
                                    C.c_void_p]
     lib.canz_muon_step.restype = C.c_int
+    lib.canz_profile_enable.argtypes = [C.c_int32]
+    lib.canz_profile_enable.restype = C.c_int
+    lib.canz_profile_collect.argtypes = [C.POINTER(C.c_double), i64p]
+    lib.canz_profile_collect.restype = C.c_int
+    lib.canz_profile_disable.argtypes = []
+    lib.canz_profile_disable.restype = C.c_int
     return lib
 
 
@@ -196,3 +211,19 @@ def canz_muon_step(groups: Sequence[Group], hp: Hparams, workspace, workspace_by
     h = hp._c()
     _check(_lib.canz_muon_step(arr, len(groups), C.byref(h), C.c_void_p(_addr(workspace)), int(workspace_bytes),
                                C.c_void_p(int(stream))))
+
+
+def canz_profile_enable(max_launches: int) -> None:
+    _check(_lib.canz_profile_enable(int(max_launches)))
+
+
+def canz_profile_collect():
+    """Returns {kind: (milliseconds, launches)} for the period since the last collection."""
+    ms = (C.c_double * len(KERNEL_KINDS))()
+    n = (C.c_int64 * len(KERNEL_KINDS))()
+    _check(_lib.canz_profile_collect(ms, n))
+    return {k: (float(ms[i]), int(n[i])) for i, k in enumerate(KERNEL_KINDS)}
+
+
+def canz_profile_disable() -> None:
+    _check(_lib.canz_profile_disable())

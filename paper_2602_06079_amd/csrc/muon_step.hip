@@ -10,6 +10,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <vector>
 
 #include "canz.h"
 #include "canz_internal.h"
@@ -98,9 +99,32 @@ double update_scale(const canz_group& g, int mode) {
   return 1.0;
 }
 
-#define CANZ_HIP(expr, what)                                                            \
+// ---- optional per-kernel timing (canz_profile_*): a pool of event pairs recorded around
+// each launch on the step's own stream.  Process-wide state; not meant for concurrent steps.
+struct Profiler {
+  bool on = false;
+  std::vector<hipEvent_t> ev;   // 2 per launch
+  std::vector<int> kind;        // kind of each recorded launch
+  size_t used = 0;              // launches recorded
+};
+Profiler g_prof;
+
+inline void prof_mark(hipStream_t st, int kind, bool begin) {
+  if (!g_prof.on || g_prof.used * 2 + 1 >= g_prof.ev.size()) return;
+  if (begin) {
+    (void)hipEventRecord(g_prof.ev[g_prof.used * 2], st);
+  } else {
+    (void)hipEventRecord(g_prof.ev[g_prof.used * 2 + 1], st);
+    g_prof.kind[g_prof.used] = kind;
+    ++g_prof.used;
+  }
+}
+
+#define CANZ_HIP(kind, expr, what)                                                      \
   do {                                                                                  \
+    prof_mark(st, kind, true);                                                          \
     hipError_t err__ = (expr);                                                          \
+    prof_mark(st, kind, false);                                                         \
     if (err__ != hipSuccess) return fail(CANZ_EHIP, "%s: %s", what, hipGetErrorString(err__)); \
   } while (0)
 
@@ -131,14 +155,14 @@ int run_batch(const canz_group& g, int first, int nb, const canz_muon_hparams& h
   o.decay = static_cast<float>(1.0 - static_cast<double>(hp.lr) * static_cast<double>(hp.weight_decay));
   o.neg_lr_scale = static_cast<float>(-static_cast<double>(hp.lr) * update_scale(g, hp.scale_mode));
 
-  CANZ_HIP(launch_momentum<T>(s, nb, grad, g.grad_dtype, mom, hp.beta, hp.nesterov, xw, xt[0], partial, st),
+  CANZ_HIP(CANZ_KERNEL_MOMENTUM, launch_momentum<T>(s, nb, grad, g.grad_dtype, mom, hp.beta, hp.nesterov, xw, xt[0], partial, st),
            "momentum kernel");
-  CANZ_HIP(launch_norm_scale(nb, momentum_tiles(s), partial, hp.eps, scale, scale2, st), "norm kernel");
+  CANZ_HIP(CANZ_KERNEL_NORM, launch_norm_scale(nb, momentum_tiles(s), partial, hp.eps, scale, scale2, st), "norm kernel");
 
   if (hp.ns_steps == 0) {
     const T* straight = s.tall ? xt[0] : xw;
     const int64_t ld = s.tall ? s.mp : s.np;
-    CANZ_HIP(launch_apply<T>(s, nb, straight, ld, s.mp * s.np, scale, o, st), "apply kernel");
+    CANZ_HIP(CANZ_KERNEL_APPLY, launch_apply<T>(s, nb, straight, ld, s.mp * s.np, scale, o, st), "apply kernel");
     return CANZ_OK;
   }
 
@@ -151,19 +175,19 @@ int run_batch(const canz_group& g, int first, int nb, const canz_muon_hparams& h
     const float* sc2 = it == 0 ? scale2 : nullptr;
     const bool last = it + 1 == hp.ns_steps;
     if (is_bf16) {
-      CANZ_HIP(launch_gram_bf16(gram, xw, a, sc2, st), "gram kernel");
-      CANZ_HIP(launch_poly_bf16(poly, a, bm, hp.a, hp.b, hp.c, st), "poly kernel");
+      CANZ_HIP(CANZ_KERNEL_GRAM, launch_gram_bf16(gram, xw, a, sc2, st), "gram kernel");
+      CANZ_HIP(CANZ_KERNEL_POLY, launch_poly_bf16(poly, a, bm, hp.a, hp.b, hp.c, st), "poly kernel");
       if (!last)
-        CANZ_HIP(launch_update_bf16(upd, bm, xt[cur], xw, xt[cur ^ 1], sc1, st), "update kernel");
+        CANZ_HIP(CANZ_KERNEL_UPDATE, launch_update_bf16(upd, bm, xt[cur], xw, xt[cur ^ 1], sc1, st), "update kernel");
       else
-        CANZ_HIP(launch_final_bf16(upd, bm, xt[cur], sc1, s, o, st), "final kernel");
+        CANZ_HIP(CANZ_KERNEL_FINAL, launch_final_bf16(upd, bm, xt[cur], sc1, s, o, st), "final kernel");
     } else {
-      CANZ_HIP(launch_gram_f32(gram, xw, a, sc2, st), "gram kernel");
-      CANZ_HIP(launch_poly_f32(poly, a, bm, hp.a, hp.b, hp.c, st), "poly kernel");
+      CANZ_HIP(CANZ_KERNEL_GRAM, launch_gram_f32(gram, xw, a, sc2, st), "gram kernel");
+      CANZ_HIP(CANZ_KERNEL_POLY, launch_poly_f32(poly, a, bm, hp.a, hp.b, hp.c, st), "poly kernel");
       if (!last)
-        CANZ_HIP(launch_update_f32(upd, bm, xt[cur], xw, xt[cur ^ 1], sc1, st), "update kernel");
+        CANZ_HIP(CANZ_KERNEL_UPDATE, launch_update_f32(upd, bm, xt[cur], xw, xt[cur ^ 1], sc1, st), "update kernel");
       else
-        CANZ_HIP(launch_final_f32(upd, bm, xt[cur], sc1, s, o, st), "final kernel");
+        CANZ_HIP(CANZ_KERNEL_FINAL, launch_final_f32(upd, bm, xt[cur], sc1, s, o, st), "final kernel");
     }
     cur ^= 1;
   }
@@ -217,5 +241,42 @@ extern "C" int canz_muon_step(const canz_group* g, int32_t n_groups, const canz_
       if (rc) return rc;
     }
   }
+  return CANZ_OK;
+}
+
+extern "C" int canz_profile_enable(int32_t max_launches) {
+  using namespace canz;
+  if (max_launches < 1) return fail(CANZ_EINVAL, "max_launches must be >= 1");
+  while (g_prof.ev.size() < static_cast<size_t>(max_launches) * 2) {
+    hipEvent_t e;
+    hipError_t err = hipEventCreate(&e);
+    if (err != hipSuccess) return fail(CANZ_EHIP, "hipEventCreate: %s", hipGetErrorString(err));
+    g_prof.ev.push_back(e);
+  }
+  g_prof.kind.assign(g_prof.ev.size() / 2, 0);
+  g_prof.used = 0;
+  g_prof.on = true;
+  return CANZ_OK;
+}
+
+extern "C" int canz_profile_collect(double* ms_out, int64_t* launches_out) {
+  using namespace canz;
+  if (!ms_out || !launches_out) return fail(CANZ_EINVAL, "null output pointer");
+  for (int k = 0; k < CANZ_KERNEL_KINDS; ++k) ms_out[k] = 0.0, launches_out[k] = 0;
+  for (size_t i = 0; i < g_prof.used; ++i) {
+    hipError_t err = hipEventSynchronize(g_prof.ev[2 * i + 1]);
+    float ms = 0.f;
+    if (err == hipSuccess) err = hipEventElapsedTime(&ms, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]);
+    if (err != hipSuccess) return fail(CANZ_EHIP, "profile event: %s", hipGetErrorString(err));
+    ms_out[g_prof.kind[i]] += ms;
+    launches_out[g_prof.kind[i]] += 1;
+  }
+  g_prof.used = 0;
+  return CANZ_OK;
+}
+
+extern "C" int canz_profile_disable(void) {
+  canz::g_prof.on = false;
+  canz::g_prof.used = 0;
   return CANZ_OK;
 }
