@@ -57,4 +57,51 @@ __device__ __forceinline__ void store_out(const OutSpec& o, const Shape& s, int 
   }
 }
 
+
+// The same for the 16 accumulator values one lane holds of a 32 x 32 MFMA tile: rows
+// row0 + 8 * (r / 4) + (r % 4), r = 0..15, one column.  All old parameter values are
+// loaded before the first store, so the 16 read-modify-writes overlap instead of
+// running as a chain of dependent memory round trips.
+__device__ __forceinline__ void store_out_tile(const OutSpec& o, const Shape& s, int b, int row0, int col,
+                                               const float (&ortho)[16]) {
+  if (col >= s.cols) return;
+  const int rows = static_cast<int>(s.rows);
+  int ld = static_cast<int>(s.cols), c = col, tab = b;
+  if (o.out_mode == CANZ_OUT_DELTA) {
+    ld = static_cast<int>(s.wfrag);
+    const int f = col / ld;
+    c = col - f * ld;
+    tab = b * s.tp + f;
+  }
+  void* base = o.out.p[tab];
+  float val[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) val[r] = 0.f;
+  if (o.out_mode == CANZ_OUT_PARAM) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = row0 + 8 * (r >> 2) + (r & 3);
+      if (row < rows) {
+        const int64_t idx = static_cast<int64_t>(row) * ld + c;
+        val[r] = o.out_dtype == CANZ_DT_F32 ? static_cast<const float*>(base)[idx]
+                                            : static_cast<float>(static_cast<const __bf16*>(base)[idx]);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) val[r] *= o.decay;
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int row = row0 + 8 * (r >> 2) + (r & 3);
+    if (row < rows) {
+      const int64_t idx = static_cast<int64_t>(row) * ld + c;
+      const float v = val[r] + o.neg_lr_scale * ortho[r];
+      if (o.out_dtype == CANZ_DT_F32)
+        static_cast<float*>(base)[idx] = v;
+      else
+        static_cast<__bf16*>(base)[idx] = static_cast<__bf16>(v);
+    }
+  }
+}
+
 }  // namespace canz

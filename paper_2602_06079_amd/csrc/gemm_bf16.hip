@@ -5,11 +5,23 @@
 // consecutive k of row (l % 32), k-group (l / 32).
 //
 // Tiling: one 256-thread block (4 wavefronts, 2 x 2) owns a 256 x 256 tile of C; each
-// wavefront owns 128 x 128 = 4 x 4 MFMA tiles, i.e. 256 fp32 accumulators per lane.  K is
-// walked in steps of 64.  The 256 x 64 panels of P and Q are staged in LDS (32 KiB each)
-// with the 16-byte chunk index XOR-swizzled by (row >> 1) & 7 so that the 16 lanes served
-// per LDS cycle hit 16 different bank groups on both the b128 stores and the MFMA operand
-// loads.  The next panel is fetched into registers while the current one is multiplied.
+// wavefront owns 128 x 128 = 4 x 4 MFMA tiles, i.e. 256 fp32 accumulators per lane (one
+// wavefront per SIMD, 512 registers each).  K is walked in steps of 64.
+//
+// Operand staging: the 256 x 64 panels of P and Q go from global memory straight into LDS
+// (global_load_lds_dwordx4: every lane fetches 16 bytes, a wavefront fills 1 KiB = 8 panel
+// rows), into one of two 64 KiB stages.  Inside a panel row the 16-byte chunk index is
+// XOR-swizzled by (row >> 1) & 7 - applied on the global side, by choosing which chunk a
+// lane fetches - so that the ds_read_b128 operand loads of 16 consecutive rows hit 16
+// different bank groups.
+//
+// Pipeline per k-step (one barrier): the panels of step t+1 are in flight while step t is
+// multiplied; the MFMA operand fragments are double-buffered in registers, and the
+// barrier sits before the last quarter of the step so that the fetch of step t+2 and the
+// first fragments of step t+1 are issued under the remaining 16 MFMAs.
+//
+// Blocks are numbered so that the 32 blocks resident on one XCD (blockIdx % 8 selects the
+// XCD) form a 4 x 8 patch of tiles of one matrix and share panels in that XCD's L2.
 // Extents are multiples of 256 (zero padded by the producer), so there are no bounds
 // checks on the operand side; only the final epilogue clips to the caller's shape.
 #include "device_util.h"
@@ -19,18 +31,22 @@ namespace {
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int NTHREADS = 256;
-constexpr int CHUNKS = BK / 8;                 // 16-byte chunks per panel row
-constexpr int LD_PASSES = BM * CHUNKS / NTHREADS;  // 8 loads of 16 B per thread and panel
+constexpr int CHUNKS = BK / 8;   // 16-byte chunks per panel row
+constexpr int GROUP_M = 4;       // tile rows per raster band
+constexpr int N_XCD = 8;
 
 enum { EPI_GRAM = 0, EPI_POLY = 1, EPI_UPDATE = 2, EPI_FINAL = 3 };
 
 struct EpiArgs {
-  void* c;                 // GRAM/POLY: [nb][M][N] bf16; UPDATE: XW' [nb][M][N]
-  void* ct;                // UPDATE: XT' [nb][N][M]
+  void* c;                 // GRAM/POLY: [nb][M][N] bf16; UPDATE: straight output [nb][M][N]
+  void* ct;                // UPDATE: transposed output [nb][N][M]
   const void* aux;         // POLY: A [nb][M][N]
   const float* scale;      // per-matrix factor applied to the accumulator, or nullptr
   float ca, cb, cc;        // POLY coefficients
 };
+
+#define CANZ_LDS(p) ((__attribute__((address_space(3))) void*)(p))
+#define CANZ_GLB(p) ((const __attribute__((address_space(1))) void*)(p))
 
 __device__ __forceinline__ int swz(int row, int chunk) {
   return (row * CHUNKS + (chunk ^ ((row >> 1) & (CHUNKS - 1)))) * 8;  // element offset in the panel
@@ -40,41 +56,55 @@ template <int EPI>
 __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __bf16* __restrict__ P,
                                                             const __bf16* __restrict__ Q, EpiArgs e, Shape s,
                                                             OutSpec o) {
-  __shared__ __attribute__((aligned(16))) __bf16 sP[BM * BK];
-  __shared__ __attribute__((aligned(16))) __bf16 sQ[BN * BK];
+  // four separate arrays (not one carved buffer): the compiler then knows that a fetch into
+  // one stage does not alias the operand reads of the other and keeps them overlapped
+  __shared__ __attribute__((aligned(1024))) __bf16 sP0[BM * BK];
+  __shared__ __attribute__((aligned(1024))) __bf16 sQ0[BN * BK];
+  __shared__ __attribute__((aligned(1024))) __bf16 sP1[BM * BK];
+  __shared__ __attribute__((aligned(1024))) __bf16 sQ1[BN * BK];
 
+  // ---- block -> (matrix, tile): XCD-contiguous numbering, then 4-row raster bands
   const int tiles_n = static_cast<int>(d.N / BN);
   const int tiles_m = static_cast<int>(d.M / BM);
   const int per_batch = tiles_m * tiles_n;
-  const int bid = blockIdx.x;
-  const int b = bid / per_batch;
-  const int tix = bid - b * per_batch;
-  const int tm = tix / tiles_n, tn = tix - tm * tiles_n;
+  int logical;
+  {
+    const int nblocks = gridDim.x, bid = blockIdx.x;
+    const int per = nblocks / N_XCD, rem = nblocks % N_XCD;
+    const int xcd = bid % N_XCD, q = bid / N_XCD;
+    logical = xcd < rem ? xcd * (per + 1) + q : rem * (per + 1) + (xcd - rem) * per + q;
+  }
+  const int b = logical / per_batch;
+  const int tix = logical - b * per_batch;
+  int tm, tn;
+  {
+    const int band = tix / (GROUP_M * tiles_n);
+    const int in_band = tix - band * GROUP_M * tiles_n;
+    const int rows_here = min(GROUP_M, tiles_m - band * GROUP_M);
+    tn = in_band / rows_here;
+    tm = band * GROUP_M + (in_band - tn * rows_here);
+  }
 
   const int t = threadIdx.x;
-  const int lane = t & 63, wave = t >> 6;
+  const int lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wm = wave >> 1, wn = wave & 1;
 
   const __bf16* Pg = P + static_cast<int64_t>(b) * d.sp + static_cast<int64_t>(tm) * BM * d.ldp;
   const __bf16* Qg = Q + static_cast<int64_t>(b) * d.sq + static_cast<int64_t>(tn) * BN * d.ldq;
 
-  // global -> register staging: thread t fetches chunk (t % 8) of rows (t / 8) + 32 * pass
-  const int ld_row = t >> 3, ld_chunk = t & 7;
-  bf16x8 rp[LD_PASSES], rq[LD_PASSES];
-  auto fetch = [&](int64_t k0) {
+  // ---- global -> LDS: wavefront w fills rows w*8 + 32*g .. +7 (g = 0..7) of both panels;
+  //      lane l lands at row (l / 8), slot (l % 8) and therefore fetches chunk slot ^ swizzle.
+  const int r8 = lane >> 3, slot = lane & 7;
+  const int chunk = slot ^ (((wave & 1) << 2) | (r8 >> 1));
+  const __bf16* pl = Pg + static_cast<int64_t>(wave * 8 + r8) * d.ldp + chunk * 8;
+  const __bf16* ql = Qg + static_cast<int64_t>(wave * 8 + r8) * d.ldq + chunk * 8;
+  const int64_t p_step = 32 * d.ldp, q_step = 32 * d.ldq;
+  auto fetch = [&](__bf16* sP, __bf16* sQ, int64_t k0) {
 #pragma unroll
-    for (int p = 0; p < LD_PASSES; ++p) {
-      const int row = ld_row + 32 * p;
-      rp[p] = *reinterpret_cast<const bf16x8*>(Pg + static_cast<int64_t>(row) * d.ldp + k0 + ld_chunk * 8);
-      rq[p] = *reinterpret_cast<const bf16x8*>(Qg + static_cast<int64_t>(row) * d.ldq + k0 + ld_chunk * 8);
-    }
-  };
-  auto stash = [&]() {
-#pragma unroll
-    for (int p = 0; p < LD_PASSES; ++p) {
-      const int row = ld_row + 32 * p;
-      *reinterpret_cast<bf16x8*>(sP + swz(row, ld_chunk)) = rp[p];
-      *reinterpret_cast<bf16x8*>(sQ + swz(row, ld_chunk)) = rq[p];
+    for (int g = 0; g < 8; ++g) {
+      __builtin_amdgcn_global_load_lds(CANZ_GLB(pl + g * p_step + k0), CANZ_LDS(sP + (wave * 8 + g * 32) * BK), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(CANZ_GLB(ql + g * q_step + k0), CANZ_LDS(sQ + (wave * 8 + g * 32) * BK), 16, 0, 0);
     }
   };
 
@@ -87,33 +117,63 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int frag_row = lane & 31, frag_kg = lane >> 5;
-  const int nk = static_cast<int>(d.K / BK);
-  fetch(0);
-  stash();
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    if (kt + 1 < nk) fetch(static_cast<int64_t>(kt + 1) * BK);
+  bf16x8 fa[2][4], fb[2][4];
+  auto load_frags = [&](const __bf16* sP, const __bf16* sQ, int kk, int set) {
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 fa[4], fb[4];
+    for (int i = 0; i < 4; ++i)
+      fa[set][i] = *reinterpret_cast<const bf16x8*>(sP + swz(wm * 128 + i * 32 + frag_row, kk * 2 + frag_kg));
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        fa[i] = *reinterpret_cast<const bf16x8*>(sP + swz(wm * 128 + i * 32 + frag_row, kk * 2 + frag_kg));
+    for (int j = 0; j < 4; ++j)
+      fb[set][j] = *reinterpret_cast<const bf16x8*>(sQ + swz(wn * 128 + j * 32 + frag_row, kk * 2 + frag_kg));
+  };
+  // the 16 MFMAs of one quarter-step, rows [i0, i1) of the 4 x 4 arrangement
+  auto mma = [&](int set, int i0, int i1) {
+#pragma unroll
+    for (int i = i0; i < i1; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        fb[j] = *reinterpret_cast<const bf16x8*>(sQ + swz(wn * 128 + j * 32 + frag_row, kk * 2 + frag_kg));
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+  };
+
+  const int nk = static_cast<int>(d.K / BK);  // even: K is a multiple of 256
+  // Scheduling fences: the operand loads of the next quarter-step must be issued before
+  // the MFMAs of the current one (the compiler otherwise sinks them next to their use
+  // and exposes the LDS latency); the counters it inserts then become partial waits.
+#define CANZ_FENCE() __builtin_amdgcn_sched_barrier(0)
+  // one k-step on stage (cP, cQ); the other stage (nP, nQ) holds step kt + 1.  The fetch
+  // index is clamped instead of guarded (a branch here costs the compiler its knowledge of
+  // which stage is in flight); the last two steps refetch the final panel into stages
+  // nobody reads any more.
+  auto k_step = [&](__bf16* cP, __bf16* cQ, const __bf16* nP, const __bf16* nQ, int kt) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    for (int kk = 0; kk < 3; ++kk) {
+      mma(kk & 1, 0, 1);
+      CANZ_FENCE();
+      load_frags(cP, cQ, kk + 1, (kk + 1) & 1);  // lands under the 12 MFMAs that follow
+      CANZ_FENCE();
+      mma(kk & 1, 1, 4);
+      CANZ_FENCE();
     }
-    __syncthreads();
-    if (kt + 1 < nk) {
-      stash();
-      __syncthreads();
-    }
+    __syncthreads();  // step kt+1 has landed everywhere; nobody reads (cP, cQ) any more
+    mma(1, 0, 1);
+    CANZ_FENCE();
+    fetch(cP, cQ, static_cast<int64_t>(min(kt + 2, nk - 1)) * BK);
+    load_frags(nP, nQ, 0, 0);
+    CANZ_FENCE();
+    mma(1, 1, 4);
+    CANZ_FENCE();
+  };
+
+  fetch(sP0, sQ0, 0);
+  __syncthreads();
+  fetch(sP1, sQ1, BK);
+  load_frags(sP0, sQ0, 0, 0);
+  for (int kt = 0; kt < nk; kt += 2) {
+    k_step(sP0, sQ0, sP1, sQ1, kt);
+    k_step(sP1, sQ1, sP0, sQ0, kt + 1);
   }
+  __syncthreads();  // drains the clamped tail fetches before the block may retire
+#undef CANZ_FENCE
 
   // ---- epilogue.  Accumulator register r of lane l in MFMA tile (i, j) is element
   //      row = 8 * (r / 4) + 4 * (l / 32) + (r % 4),  col = l % 32   of that 32 x 32 tile.
@@ -125,6 +185,14 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int col = col_base + j * 32;
+      if (EPI == EPI_FINAL) {
+        // the host orders the operands so that (row, col) is the caller's orientation
+        float v[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) v[r] = acc[i][j][r] * sc;
+        store_out_tile(o, s, b, row_base + i * 32, col, v);
+        continue;
+      }
 #pragma unroll
       for (int rq4 = 0; rq4 < 4; ++rq4) {
         const int row0 = row_base + i * 32 + rq4 * 8;
@@ -138,12 +206,14 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
         } else if (EPI == EPI_POLY) {
           __bf16* C = static_cast<__bf16*>(e.c) + static_cast<int64_t>(b) * d.M * d.N;
           const __bf16* A = static_cast<const __bf16*>(e.aux) + static_cast<int64_t>(b) * d.M * d.N;
+          float av[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) av[q] = static_cast<float>(A[static_cast<int64_t>(row0 + q) * d.N + col]);
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            const int64_t idx = static_cast<int64_t>(row0 + q) * d.N + col;
-            float r = e.cb * static_cast<float>(A[idx]) + e.cc * v[q];
+            float r = e.cb * av[q] + e.cc * v[q];
             if (row0 + q == col) r += e.ca;
-            C[idx] = static_cast<__bf16>(r);
+            C[static_cast<int64_t>(row0 + q) * d.N + col] = static_cast<__bf16>(r);
           }
         } else if (EPI == EPI_UPDATE) {
           __bf16* C = static_cast<__bf16*>(e.c) + static_cast<int64_t>(b) * d.M * d.N;
@@ -155,14 +225,6 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
             C[static_cast<int64_t>(row0 + q) * d.N + col] = pk[q];
           }
           *reinterpret_cast<bf16x4*>(CT + static_cast<int64_t>(col) * d.M + row0) = pk;
-        } else {
-          // (row, col) index the wide orientation [m][n]; the caller's matrix is its transpose if tall
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int wr = row0 + q, wc = col;
-            const int orow = s.tall ? wc : wr, ocol = s.tall ? wr : wc;
-            if (orow < s.rows && ocol < s.cols) store_out(o, s, b, orow, ocol, v[q]);
-          }
         }
       }
     }
@@ -205,11 +267,11 @@ hipError_t launch_update_bf16(const GemmDims& d, const void* b_in, const void* x
   return launch<EPI_UPDATE>(d, b_in, xt_in, e, Shape{}, OutSpec{}, st);
 }
 
-hipError_t launch_final_bf16(const GemmDims& d, const void* b_in, const void* xt_in, const float* scale,
-                             const Shape& s, const OutSpec& o, hipStream_t st) {
+hipError_t launch_final_bf16(const GemmDims& d, const void* p, const void* q, const float* scale, const Shape& s,
+                             const OutSpec& o, hipStream_t st) {
   EpiArgs e{};
   e.scale = scale;
-  return launch<EPI_FINAL>(d, b_in, xt_in, e, s, o, st);
+  return launch<EPI_FINAL>(d, p, q, e, s, o, st);
 }
 
 }  // namespace canz

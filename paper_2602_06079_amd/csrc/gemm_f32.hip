@@ -103,6 +103,13 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_f32(GemmDims d, const floa
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int col = col_base + j * 32;
+      if (EPI == EPI_FINAL) {
+        float v[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) v[r] = tot[i][j][r] * sc;
+        store_out_tile(o, s, b, row_base + i * 32, col, v);
+        continue;
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = row_base + i * 32 + (r >> 2) * 8 + (r & 3);
@@ -117,9 +124,6 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_f32(GemmDims d, const floa
         } else if (EPI == EPI_UPDATE) {
           static_cast<float*>(e.c)[idx] = v;
           static_cast<float*>(e.ct)[cb + static_cast<int64_t>(col) * d.M + row] = v;
-        } else {
-          const int orow = s.tall ? col : row, ocol = s.tall ? row : col;
-          if (orow < s.rows && ocol < s.cols) store_out(o, s, b, orow, ocol, v);
         }
       }
     }
@@ -162,11 +166,11 @@ hipError_t launch_update_f32(const GemmDims& d, const void* b_in, const void* xt
   return launch<EPI_UPDATE>(d, b_in, xt_in, e, Shape{}, OutSpec{}, st);
 }
 
-hipError_t launch_final_f32(const GemmDims& d, const void* b_in, const void* xt_in, const float* scale, const Shape& s,
+hipError_t launch_final_f32(const GemmDims& d, const void* p, const void* q, const float* scale, const Shape& s,
                             const OutSpec& o, hipStream_t st) {
   EpiArgs e{};
   e.scale = scale;
-  return launch<EPI_FINAL>(d, b_in, xt_in, e, s, o, st);
+  return launch<EPI_FINAL>(d, p, q, e, s, o, st);
 }
 
 }  // namespace canz

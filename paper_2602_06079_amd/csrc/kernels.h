@@ -76,8 +76,10 @@ hipError_t launch_poly_bf16(const GemmDims& d, const void* a_in, void* b_out, fl
 // X' = scale[b] * B X: XW' [mp][np] straight and XT' [np][mp] transposed  (P = B, Q = XT)
 hipError_t launch_update_bf16(const GemmDims& d, const void* b_in, const void* xt_in, void* xw_out, void* xt_out,
                               const float* scale, hipStream_t st);
-// last step: O = scale[b] * B X goes straight into the caller's buffers
-hipError_t launch_final_bf16(const GemmDims& d, const void* b_in, const void* xt_in, const float* scale,
+// last step: O = scale[b] * P Q^T goes straight into the caller's buffers; the caller of
+// this launcher orders the operands so that C is in the matrix's own orientation:
+// wide matrix: P = B, Q = XT (C = B X);  tall matrix: P = XT, Q = B (C = X^T B = (B X)^T)
+hipError_t launch_final_bf16(const GemmDims& d, const void* p, const void* q, const float* scale,
                              const Shape& s, const OutSpec& o, hipStream_t st);
 
 // ---- fp32 verification GEMMs (same contracts, float storage) ----------------------
@@ -86,7 +88,7 @@ hipError_t launch_poly_f32(const GemmDims& d, const void* a_in, void* b_out, flo
                            hipStream_t st);
 hipError_t launch_update_f32(const GemmDims& d, const void* b_in, const void* xt_in, void* xw_out, void* xt_out,
                              const float* scale, hipStream_t st);
-hipError_t launch_final_f32(const GemmDims& d, const void* b_in, const void* xt_in, const float* scale,
+hipError_t launch_final_f32(const GemmDims& d, const void* p, const void* q, const float* scale,
                             const Shape& s, const OutSpec& o, hipStream_t st);
 
 }  // namespace canz

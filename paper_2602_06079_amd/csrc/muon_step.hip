@@ -169,6 +169,8 @@ int run_batch(const canz_group& g, int first, int nb, const canz_muon_hparams& h
   GemmDims gram{s.mp, s.mp, s.np, s.np, s.np, s.mp * s.np, s.mp * s.np, nb};
   GemmDims poly{s.mp, s.mp, s.mp, s.mp, s.mp, s.mp * s.mp, s.mp * s.mp, nb};
   GemmDims upd{s.mp, s.np, s.mp, s.mp, s.mp, s.mp * s.mp, s.np * s.mp, nb};
+  // last product in the caller's orientation: for a tall matrix the roles of B and XT swap
+  GemmDims fin = s.tall ? GemmDims{s.np, s.mp, s.mp, s.mp, s.mp, s.np * s.mp, s.mp * s.mp, nb} : upd;
   int cur = 0;
   for (int it = 0; it < hp.ns_steps; ++it) {
     const float* sc1 = it == 0 ? scale : nullptr;
@@ -180,14 +182,14 @@ int run_batch(const canz_group& g, int first, int nb, const canz_muon_hparams& h
       if (!last)
         CANZ_HIP(CANZ_KERNEL_UPDATE, launch_update_bf16(upd, bm, xt[cur], xw, xt[cur ^ 1], sc1, st), "update kernel");
       else
-        CANZ_HIP(CANZ_KERNEL_FINAL, launch_final_bf16(upd, bm, xt[cur], sc1, s, o, st), "final kernel");
+        CANZ_HIP(CANZ_KERNEL_FINAL, launch_final_bf16(fin, s.tall ? (const void*)xt[cur] : (const void*)bm, s.tall ? (const void*)bm : (const void*)xt[cur], sc1, s, o, st), "final kernel");
     } else {
       CANZ_HIP(CANZ_KERNEL_GRAM, launch_gram_f32(gram, xw, a, sc2, st), "gram kernel");
       CANZ_HIP(CANZ_KERNEL_POLY, launch_poly_f32(poly, a, bm, hp.a, hp.b, hp.c, st), "poly kernel");
       if (!last)
         CANZ_HIP(CANZ_KERNEL_UPDATE, launch_update_f32(upd, bm, xt[cur], xw, xt[cur ^ 1], sc1, st), "update kernel");
       else
-        CANZ_HIP(CANZ_KERNEL_FINAL, launch_final_f32(upd, bm, xt[cur], sc1, s, o, st), "final kernel");
+        CANZ_HIP(CANZ_KERNEL_FINAL, launch_final_f32(fin, s.tall ? (const void*)xt[cur] : (const void*)bm, s.tall ? (const void*)bm : (const void*)xt[cur], sc1, s, o, st), "final kernel");
     }
     cur ^= 1;
   }
