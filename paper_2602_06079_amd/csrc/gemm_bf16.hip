@@ -100,12 +100,17 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
   const __bf16* pl = Pg + static_cast<int64_t>(wave * 8 + r8) * d.ldp + chunk * 8;
   const __bf16* ql = Qg + static_cast<int64_t>(wave * 8 + r8) * d.ldq + chunk * 8;
   const int64_t p_step = 32 * d.ldp, q_step = 32 * d.ldq;
+  // one of the 16 direct loads of a stage: idx 0..7 -> P rows, 8..15 -> Q rows
+  auto fetch_one = [&](__bf16* sP, __bf16* sQ, int64_t k0, int idx) {
+    const int g = idx & 7;
+    if (idx < 8)
+      __builtin_amdgcn_global_load_lds(CANZ_GLB(pl + g * p_step + k0), CANZ_LDS(sP + (wave * 8 + g * 32) * BK), 16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds(CANZ_GLB(ql + g * q_step + k0), CANZ_LDS(sQ + (wave * 8 + g * 32) * BK), 16, 0, 0);
+  };
   auto fetch = [&](__bf16* sP, __bf16* sQ, int64_t k0) {
 #pragma unroll
-    for (int g = 0; g < 8; ++g) {
-      __builtin_amdgcn_global_load_lds(CANZ_GLB(pl + g * p_step + k0), CANZ_LDS(sP + (wave * 8 + g * 32) * BK), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(CANZ_GLB(ql + g * q_step + k0), CANZ_LDS(sQ + (wave * 8 + g * 32) * BK), 16, 0, 0);
-    }
+    for (int idx = 0; idx < 16; ++idx) fetch_one(sP, sQ, k0, idx);
   };
 
   f32x16 acc[4][4];
@@ -116,29 +121,30 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // MFMA operand fragments, double-buffered in registers: idx 0..3 -> rows of P, 4..7 -> rows of Q
   const int frag_row = lane & 31, frag_kg = lane >> 5;
   bf16x8 fa[2][4], fb[2][4];
+  auto frag_one = [&](const __bf16* sP, const __bf16* sQ, int kk, int set, int idx) {
+    if (idx < 4)
+      fa[set][idx] = *reinterpret_cast<const bf16x8*>(sP + swz(wm * 128 + idx * 32 + frag_row, kk * 2 + frag_kg));
+    else
+      fb[set][idx - 4] =
+          *reinterpret_cast<const bf16x8*>(sQ + swz(wn * 128 + (idx - 4) * 32 + frag_row, kk * 2 + frag_kg));
+  };
   auto load_frags = [&](const __bf16* sP, const __bf16* sQ, int kk, int set) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      fa[set][i] = *reinterpret_cast<const bf16x8*>(sP + swz(wm * 128 + i * 32 + frag_row, kk * 2 + frag_kg));
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      fb[set][j] = *reinterpret_cast<const bf16x8*>(sQ + swz(wn * 128 + j * 32 + frag_row, kk * 2 + frag_kg));
+    for (int idx = 0; idx < 8; ++idx) frag_one(sP, sQ, kk, set, idx);
   };
-  // the 16 MFMAs of one quarter-step, rows [i0, i1) of the 4 x 4 arrangement
-  auto mma = [&](int set, int i0, int i1) {
-#pragma unroll
-    for (int i = i0; i < i1; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+  auto mma_one = [&](int set, int idx) {
+    const int i = idx >> 2, j = idx & 3;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
   };
 
   const int nk = static_cast<int>(d.K / BK);  // even: K is a multiple of 256
-  // Scheduling fences: the operand loads of the next quarter-step must be issued before
-  // the MFMAs of the current one (the compiler otherwise sinks them next to their use
-  // and exposes the LDS latency); the counters it inserts then become partial waits.
+  // The issue order below is pinned with scheduling fences.  A wavefront issues in order and
+  // an MFMA occupies the matrix pipe for 32 cycles, so every other instruction is placed in
+  // the shadow of one MFMA: one LDS operand load or one direct global->LDS load per MFMA.
+  // Left to itself the compiler clusters the loads and the matrix pipe drains meanwhile.
 #define CANZ_FENCE() __builtin_amdgcn_sched_barrier(0)
   // one k-step on stage (cP, cQ); the other stage (nP, nQ) holds step kt + 1.  The fetch
   // index is clamped instead of guarded (a branch here costs the compiler its knowledge of
@@ -147,21 +153,29 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
   auto k_step = [&](__bf16* cP, __bf16* cQ, const __bf16* nP, const __bf16* nQ, int kt) {
 #pragma unroll
     for (int kk = 0; kk < 3; ++kk) {
-      mma(kk & 1, 0, 1);
-      CANZ_FENCE();
-      load_frags(cP, cQ, kk + 1, (kk + 1) & 1);  // lands under the 12 MFMAs that follow
-      CANZ_FENCE();
-      mma(kk & 1, 1, 4);
-      CANZ_FENCE();
+#pragma unroll
+      for (int idx = 0; idx < 16; ++idx) {
+        mma_one(kk & 1, idx);
+        CANZ_FENCE();
+        if (idx < 8) {
+          frag_one(cP, cQ, kk + 1, (kk + 1) & 1, idx);  // lands under the 8 MFMAs that follow
+          CANZ_FENCE();
+        }
+      }
     }
     __syncthreads();  // step kt+1 has landed everywhere; nobody reads (cP, cQ) any more
-    mma(1, 0, 1);
-    CANZ_FENCE();
-    fetch(cP, cQ, static_cast<int64_t>(min(kt + 2, nk - 1)) * BK);
-    load_frags(nP, nQ, 0, 0);
-    CANZ_FENCE();
-    mma(1, 1, 4);
-    CANZ_FENCE();
+    const int64_t k2 = static_cast<int64_t>(min(kt + 2, nk - 1)) * BK;
+#pragma unroll
+    for (int idx = 0; idx < 16; ++idx) {
+      mma_one(1, idx);
+      CANZ_FENCE();
+      fetch_one(cP, cQ, k2, idx);
+      CANZ_FENCE();
+      if (idx < 8) {
+        frag_one(nP, nQ, 0, 0, idx);
+        CANZ_FENCE();
+      }
+    }
   };
 
   fetch(sP0, sQ0, 0);
