@@ -104,4 +104,36 @@ __device__ __forceinline__ void store_out_tile(const OutSpec& o, const Shape& s,
   }
 }
 
+
+// Four consecutive columns at once (row length and col are multiples of 4, so the four
+// elements are 16-byte aligned in fp32 buffers and lie in one TP fragment).
+__device__ __forceinline__ f32x4 load_param4(const OutSpec& o, const Shape& s, int b, int row, int col) {
+  const int64_t idx = static_cast<int64_t>(row) * s.cols + col;
+  if (o.out_dtype == CANZ_DT_F32) return *reinterpret_cast<const f32x4*>(static_cast<const float*>(o.out.p[b]) + idx);
+  const bf16x4 v = *reinterpret_cast<const bf16x4*>(static_cast<const __bf16*>(o.out.p[b]) + idx);
+  f32x4 r;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) r[e] = static_cast<float>(v[e]);
+  return r;
+}
+
+__device__ __forceinline__ void store_out4(const OutSpec& o, const Shape& s, int b, int row, int col, f32x4 val) {
+  int ld = static_cast<int>(s.cols), c = col, tab = b;
+  if (o.out_mode == CANZ_OUT_DELTA) {
+    ld = static_cast<int>(s.wfrag);
+    const int f = col / ld;
+    c = col - f * ld;
+    tab = b * s.tp + f;
+  }
+  const int64_t idx = static_cast<int64_t>(row) * ld + c;
+  if (o.out_dtype == CANZ_DT_F32) {
+    *reinterpret_cast<f32x4*>(static_cast<float*>(o.out.p[tab]) + idx) = val;
+  } else {
+    bf16x4 v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = static_cast<__bf16>(val[e]);
+    *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(o.out.p[tab]) + idx) = v;
+  }
+}
+
 }  // namespace canz

@@ -4,6 +4,7 @@
 // These passes are HBM-bound: every global access is a 16-byte vector per lane on
 // contiguous rows, the transpose goes through LDS, the reduction through wave shuffles.
 #include "device_util.h"
+#include "panel_layout.h"
 
 namespace canz {
 namespace {
@@ -107,7 +108,7 @@ __global__ __launch_bounds__(NTHREADS) void k_momentum(Shape s, PtrTable grad, i
       o.v[e] = from_f32<T>(u[e]);
       tile[rl][cv + e] = u[e];
     }
-    *reinterpret_cast<Vec8<T>*>(straight + static_cast<int64_t>(row) * pc + col) = o;
+    *reinterpret_cast<Vec8<T>*>(straight + WorkLayout<T>::chunk_off(row, col, pc)) = o;
   }
   __syncthreads();
 #pragma unroll
@@ -116,7 +117,7 @@ __global__ __launch_bounds__(NTHREADS) void k_momentum(Shape s, PtrTable grad, i
     Vec8<T> o;
 #pragma unroll
     for (int e = 0; e < 8; ++e) o.v[e] = from_f32<T>(tile[cv + e][cl]);
-    *reinterpret_cast<Vec8<T>*>(transposed + static_cast<int64_t>(c0 + cl) * pr + r0 + cv) = o;
+    *reinterpret_cast<Vec8<T>*>(transposed + WorkLayout<T>::chunk_off(c0 + cl, r0 + cv, pr)) = o;
   }
   // sum of squares of this tile, fixed order: lanes -> waves -> thread 0
   ss = wave_sum(ss);
@@ -150,17 +151,16 @@ __global__ __launch_bounds__(NTHREADS) void k_norm_scale(int n_partial, const fl
   }
 }
 
-// ns_steps == 0: O = scale * U.
+// ns_steps == 0: O = scale * U, read back from the working copy in the caller's orientation.
 template <typename T>
 __global__ __launch_bounds__(NTHREADS) void k_apply(Shape s, const T* __restrict__ x, int64_t ld, int64_t batch_stride,
                                                      const float* __restrict__ scale, OutSpec o) {
   const int b = blockIdx.z;
   const float sc = scale[b];
-  for (int row = blockIdx.y; row < s.rows; row += gridDim.y) {
-    const T* xr = x + static_cast<int64_t>(b) * batch_stride + static_cast<int64_t>(row) * ld;
+  const T* xb = x + static_cast<int64_t>(b) * batch_stride;
+  for (int row = blockIdx.y; row < s.rows; row += gridDim.y)
     for (int col = blockIdx.x * NTHREADS + threadIdx.x; col < s.cols; col += gridDim.x * NTHREADS)
-      store_out(o, s, b, row, col, sc * static_cast<float>(xr[col]));
-  }
+      store_out(o, s, b, row, col, sc * static_cast<float>(xb[WorkLayout<T>::chunk_off(row, col & ~7, ld) + (col & 7)]));
 }
 
 }  // namespace

@@ -2,29 +2,37 @@
 //   C[b][i][j] = sum_k P[b][i][k] * Q[b][j][k]        fp32 accumulate
 // Both operands are contiguous along k (see kernels.h for why both orientations of X are
 // kept), which is the lane layout v_mfma_f32_32x32x16_bf16 wants: lane l supplies 8
-// consecutive k of row (l % 32), k-group (l / 32).
+// consecutive k of row (l % 32), k-group (l / 32).  Operands and bf16 results live in the
+// panel layout of panel_layout.h.
 //
 // Tiling: one 256-thread block (4 wavefronts, 2 x 2) owns a 256 x 256 tile of C; each
 // wavefront owns 128 x 128 = 4 x 4 MFMA tiles, i.e. 256 fp32 accumulators per lane (one
 // wavefront per SIMD, 512 registers each).  K is walked in steps of 64.
 //
-// Operand staging: the 256 x 64 panels of P and Q go from global memory straight into LDS
-// (global_load_lds_dwordx4: every lane fetches 16 bytes, a wavefront fills 1 KiB = 8 panel
-// rows), into one of two 64 KiB stages.  Inside a panel row the 16-byte chunk index is
-// XOR-swizzled by (row >> 1) & 7 - applied on the global side, by choosing which chunk a
-// lane fetches - so that the ds_read_b128 operand loads of 16 consecutive rows hit 16
-// different bank groups.
+// Operand staging: a 256 x 64 panel is 32 KiB of contiguous memory that already has the
+// bank-conflict-free LDS arrangement, so it goes from global memory straight into LDS as
+// a linear copy (global_load_lds_dwordx4: a wavefront moves 1 KiB per instruction), into
+// one of two 64 KiB stages.
 //
 // Pipeline per k-step (one barrier): the panels of step t+1 are in flight while step t is
 // multiplied; the MFMA operand fragments are double-buffered in registers, and the
 // barrier sits before the last quarter of the step so that the fetch of step t+2 and the
-// first fragments of step t+1 are issued under the remaining 16 MFMAs.
+// first fragments of step t+1 are issued under the remaining 16 MFMAs.  The kernel is
+// bound as much by moving 64 KiB per step from L2 into LDS as by the matrix pipe, so the
+// loads are spread out: one LDS or global instruction in the shadow of each MFMA.
+//
+// Epilogue: the accumulators are re-arranged through LDS (free after the last step) into
+// panel-layout images, one per wavefront, and leave as linear 16-byte-per-lane stores; the
+// last product of the chain instead stages fp32 rows and applies the parameter update
+// with 16-byte accesses on the caller's row-major buffers.
 //
 // Blocks are numbered so that the 32 blocks resident on one XCD (blockIdx % 8 selects the
 // XCD) form a 4 x 8 patch of tiles of one matrix and share panels in that XCD's L2.
-// Extents are multiples of 256 (zero padded by the producer), so there are no bounds
-// checks on the operand side; only the final epilogue clips to the caller's shape.
+// Symmetric products (Gram, polynomial) run only the tiles on or above the diagonal and
+// write the mirror image as well.  Extents are multiples of 256 (zero padded by the
+// producer), so only the final epilogue clips to the caller's shape.
 #include "device_util.h"
+#include "panel_layout.h"
 
 namespace canz {
 namespace {
@@ -34,22 +42,31 @@ constexpr int NTHREADS = 256;
 constexpr int CHUNKS = BK / 8;   // 16-byte chunks per panel row
 constexpr int GROUP_M = 4;       // tile rows per raster band
 constexpr int N_XCD = 8;
+static_assert(BM == PANEL_ROWS && BK == PANEL_K, "tile = panel");
 
 enum { EPI_GRAM = 0, EPI_POLY = 1, EPI_UPDATE = 2, EPI_FINAL = 3 };
 
 struct EpiArgs {
-  void* c;                 // GRAM/POLY: [nb][M][N] bf16; UPDATE: straight output [nb][M][N]
-  void* ct;                // UPDATE: transposed output [nb][N][M]
-  const void* aux;         // POLY: A [nb][M][N]
+  void* c;                 // GRAM/POLY: [nb][M][N] panels; UPDATE: straight output [nb][M][N] panels
+  void* ct;                // UPDATE: transposed output [nb][N][M] panels
+  const void* aux;         // POLY: A [nb][M][N] panels
   const float* scale;      // per-matrix factor applied to the accumulator, or nullptr
   float ca, cb, cc;        // POLY coefficients
 };
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 #define CANZ_LDS(p) ((__attribute__((address_space(3))) void*)(p))
 #define CANZ_GLB(p) ((const __attribute__((address_space(1))) void*)(p))
 
 __device__ __forceinline__ int swz(int row, int chunk) {
   return (row * CHUNKS + (chunk ^ ((row >> 1) & (CHUNKS - 1)))) * 8;  // element offset in the panel
+}
+
+// value of the neighbouring lane (lane ^ 1), through the DPP quad permute [1, 0, 3, 2]
+__device__ __forceinline__ float lane_xor1(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));
 }
 
 template <int EPI>
@@ -66,7 +83,7 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
   // ---- block -> (matrix, tile): XCD-contiguous numbering, then 4-row raster bands
   const int tiles_n = static_cast<int>(d.N / BN);
   const int tiles_m = static_cast<int>(d.M / BM);
-  const int per_batch = tiles_m * tiles_n;
+  const int per_batch = (EPI == EPI_GRAM || EPI == EPI_POLY) ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
   int logical;
   {
     const int nblocks = gridDim.x, bid = blockIdx.x;
@@ -77,7 +94,33 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
   const int b = logical / per_batch;
   const int tix = logical - b * per_batch;
   int tm, tn;
-  {
+  if (EPI == EPI_GRAM || EPI == EPI_POLY) {
+    // symmetric output: only tiles with tn >= tm exist (per_batch = nt (nt + 1) / 2); the
+    // epilogue writes each off-diagonal tile twice, straight and mirrored.  Same banding:
+    // inside a band of 4 tile rows starting at r0 the columns r0, r0+1, ... are walked one
+    // after the other, column c holding the rows r0 .. min(r0 + 3, c).
+    int rem = tix, band = 0;
+    for (;;) {
+      const int rows = min(GROUP_M, tiles_m - band * GROUP_M), cols = tiles_m - band * GROUP_M;
+      const int cnt = rows * cols - rows * (rows - 1) / 2;
+      if (rem < cnt) break;
+      rem -= cnt;
+      ++band;
+    }
+    const int r0 = band * GROUP_M;
+    const int rows = min(GROUP_M, tiles_m - r0);
+    const int tri = rows * (rows + 1) / 2;
+    if (rem < tri) {
+      int c = 0;
+      while (rem >= c + 1) rem -= c + 1, ++c;
+      tn = r0 + c;
+      tm = r0 + rem;
+    } else {
+      rem -= tri;
+      tn = r0 + rows + rem / rows;
+      tm = r0 + rem % rows;
+    }
+  } else {
     const int band = tix / (GROUP_M * tiles_n);
     const int in_band = tix - band * GROUP_M * tiles_n;
     const int rows_here = min(GROUP_M, tiles_m - band * GROUP_M);
@@ -90,27 +133,22 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wm = wave >> 1, wn = wave & 1;
 
-  const __bf16* Pg = P + static_cast<int64_t>(b) * d.sp + static_cast<int64_t>(tm) * BM * d.ldp;
-  const __bf16* Qg = Q + static_cast<int64_t>(b) * d.sq + static_cast<int64_t>(tn) * BN * d.ldq;
-
-  // ---- global -> LDS: wavefront w fills rows w*8 + 32*g .. +7 (g = 0..7) of both panels;
-  //      lane l lands at row (l / 8), slot (l % 8) and therefore fetches chunk slot ^ swizzle.
-  const int r8 = lane >> 3, slot = lane & 7;
-  const int chunk = slot ^ (((wave & 1) << 2) | (r8 >> 1));
-  const __bf16* pl = Pg + static_cast<int64_t>(wave * 8 + r8) * d.ldp + chunk * 8;
-  const __bf16* ql = Qg + static_cast<int64_t>(wave * 8 + r8) * d.ldq + chunk * 8;
-  const int64_t p_step = 32 * d.ldp, q_step = 32 * d.ldq;
-  // one of the 16 direct loads of a stage: idx 0..7 -> P rows, 8..15 -> Q rows
-  auto fetch_one = [&](__bf16* sP, __bf16* sQ, int64_t k0, int idx) {
+  // ---- global -> LDS: panel (tile row, k-step) is 32 KiB contiguous; wavefront w copies the
+  //      1 KiB pieces w, w+4, ..., w+28 of both panels, lane l the 16 bytes at l * 16.
+  const int64_t nkb = d.K / BK;
+  const __bf16* pl = P + static_cast<int64_t>(b) * d.sp + static_cast<int64_t>(tm) * nkb * PANEL_ELEMS + wave * 512 + lane * 8;
+  const __bf16* ql = Q + static_cast<int64_t>(b) * d.sq + static_cast<int64_t>(tn) * nkb * PANEL_ELEMS + wave * 512 + lane * 8;
+  // one of the 16 direct loads of a stage: idx 0..7 -> P pieces, 8..15 -> Q pieces
+  auto fetch_one = [&](__bf16* sP, __bf16* sQ, int64_t kt, int idx) {
     const int g = idx & 7;
     if (idx < 8)
-      __builtin_amdgcn_global_load_lds(CANZ_GLB(pl + g * p_step + k0), CANZ_LDS(sP + (wave * 8 + g * 32) * BK), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(CANZ_GLB(pl + kt * PANEL_ELEMS + g * 2048), CANZ_LDS(sP + wave * 512 + g * 2048), 16, 0, 0);
     else
-      __builtin_amdgcn_global_load_lds(CANZ_GLB(ql + g * q_step + k0), CANZ_LDS(sQ + (wave * 8 + g * 32) * BK), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(CANZ_GLB(ql + kt * PANEL_ELEMS + g * 2048), CANZ_LDS(sQ + wave * 512 + g * 2048), 16, 0, 0);
   };
-  auto fetch = [&](__bf16* sP, __bf16* sQ, int64_t k0) {
+  auto fetch = [&](__bf16* sP, __bf16* sQ, int64_t kt) {
 #pragma unroll
-    for (int idx = 0; idx < 16; ++idx) fetch_one(sP, sQ, k0, idx);
+    for (int idx = 0; idx < 16; ++idx) fetch_one(sP, sQ, kt, idx);
   };
 
   f32x16 acc[4][4];
@@ -140,7 +178,7 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
   };
 
-  const int nk = static_cast<int>(d.K / BK);  // even: K is a multiple of 256
+  const int nk = static_cast<int>(nkb);  // even: K is a multiple of 256
   // The issue order below is pinned with scheduling fences.  A wavefront issues in order and
   // an MFMA occupies the matrix pipe for 32 cycles, so every other instruction is placed in
   // the shadow of one MFMA: one LDS operand load or one direct global->LDS load per MFMA.
@@ -164,7 +202,7 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
       }
     }
     __syncthreads();  // step kt+1 has landed everywhere; nobody reads (cP, cQ) any more
-    const int64_t k2 = static_cast<int64_t>(min(kt + 2, nk - 1)) * BK;
+    const int64_t k2 = min(kt + 2, nk - 1);
 #pragma unroll
     for (int idx = 0; idx < 16; ++idx) {
       mma_one(1, idx);
@@ -180,67 +218,169 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
 
   fetch(sP0, sQ0, 0);
   __syncthreads();
-  fetch(sP1, sQ1, BK);
+  fetch(sP1, sQ1, 1);
   load_frags(sP0, sQ0, 0, 0);
   for (int kt = 0; kt < nk; kt += 2) {
     k_step(sP0, sQ0, sP1, sQ1, kt);
     k_step(sP1, sQ1, sP0, sQ0, kt + 1);
   }
-  __syncthreads();  // drains the clamped tail fetches before the block may retire
+  __syncthreads();  // the clamped tail fetches have drained; LDS is free for the epilogue
 #undef CANZ_FENCE
 
-  // ---- epilogue.  Accumulator register r of lane l in MFMA tile (i, j) is element
-  //      row = 8 * (r / 4) + 4 * (l / 32) + (r % 4),  col = l % 32   of that 32 x 32 tile.
-  const float sc = e.scale ? e.scale[b] : 1.f;
-  const int row_base = tm * BM + wm * 128 + 4 * (lane >> 5);
-  const int col_base = tn * BN + wn * 128 + (lane & 31);
+  // ---- epilogue.  Accumulator register r of lane l in MFMA tile (it, jt) is element
+  //      row = 32 it + 8 (r / 4) + 4 (l / 32) + (r % 4),  col = 32 jt + (l % 32)
+  //      of the wavefront's 128 x 128 part.  Each wavefront stages through its own 32 KiB.
+  __bf16* stage = wave == 0 ? sP0 : wave == 1 ? sQ0 : wave == 2 ? sP1 : sQ1;
+  const int lj = lane & 31, lh = lane >> 5;
+
+  // scale (first iteration: folded normalisation), or the polynomial in A for EPI_POLY
+  if (EPI == EPI_POLY) {
+    const __bf16* A = static_cast<const __bf16*>(e.aux) + static_cast<int64_t>(b) * d.M * d.N;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+    for (int it = 0; it < 4; ++it)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int col = col_base + j * 32;
-      if (EPI == EPI_FINAL) {
-        // the host orders the operands so that (row, col) is the caller's orientation
-        float v[16];
+      for (int jt = 0; jt < 4; ++jt) {
+        const int col = tn * BN + wn * 128 + jt * 32 + lj;
+        const int row0 = tm * BM + wm * 128 + it * 32 + 4 * lh;
+        float av[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) v[r] = acc[i][j][r] * sc;
-        store_out_tile(o, s, b, row_base + i * 32, col, v);
-        continue;
-      }
+        for (int r = 0; r < 16; ++r)
+          av[r] = static_cast<float>(A[panel_chunk_off(row0 + 8 * (r >> 2) + (r & 3), col & ~7, d.N) + (col & 7)]);
 #pragma unroll
-      for (int rq4 = 0; rq4 < 4; ++rq4) {
-        const int row0 = row_base + i * 32 + rq4 * 8;
-        float v[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = acc[i][j][rq4 * 4 + q] * sc;
-        if (EPI == EPI_GRAM) {
-          __bf16* C = static_cast<__bf16*>(e.c) + static_cast<int64_t>(b) * d.M * d.N;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) C[static_cast<int64_t>(row0 + q) * d.N + col] = static_cast<__bf16>(v[q]);
-        } else if (EPI == EPI_POLY) {
-          __bf16* C = static_cast<__bf16*>(e.c) + static_cast<int64_t>(b) * d.M * d.N;
-          const __bf16* A = static_cast<const __bf16*>(e.aux) + static_cast<int64_t>(b) * d.M * d.N;
-          float av[4];
-#pragma unroll
-          for (int q = 0; q < 4; ++q) av[q] = static_cast<float>(A[static_cast<int64_t>(row0 + q) * d.N + col]);
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            float r = e.cb * av[q] + e.cc * v[q];
-            if (row0 + q == col) r += e.ca;
-            C[static_cast<int64_t>(row0 + q) * d.N + col] = static_cast<__bf16>(r);
-          }
-        } else if (EPI == EPI_UPDATE) {
-          __bf16* C = static_cast<__bf16*>(e.c) + static_cast<int64_t>(b) * d.M * d.N;
-          __bf16* CT = static_cast<__bf16*>(e.ct) + static_cast<int64_t>(b) * d.M * d.N;
-          bf16x4 pk;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            pk[q] = static_cast<__bf16>(v[q]);
-            C[static_cast<int64_t>(row0 + q) * d.N + col] = pk[q];
-          }
-          *reinterpret_cast<bf16x4*>(CT + static_cast<int64_t>(col) * d.M + row0) = pk;
+        for (int r = 0; r < 16; ++r) {
+          float v = e.cb * av[r] + e.cc * acc[it][jt][r];
+          if (row0 + 8 * (r >> 2) + (r & 3) == col) v += e.ca;
+          acc[it][jt][r] = v;
         }
       }
+  } else if (e.scale) {
+    const float sc = e.scale[b];
+#pragma unroll
+    for (int it = 0; it < 4; ++it)
+#pragma unroll
+      for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[it][jt][r] *= sc;
+  }
+
+  // the wavefront's part of an output tile in panel layout: two pieces of 16 KiB (the two
+  // 64-wide k-blocks it covers), 128 rows each; LDS image == memory image
+  auto flush_stage = [&](__bf16* out, int64_t row_block, int64_t kc, int64_t kblock0, int half_rows) {
+    // out: matrix base; the wavefront's rows start at row_block * 256 + half_rows * 128
+#pragma unroll
+    for (int kb2 = 0; kb2 < 2; ++kb2) {
+      __bf16* dst = out + (row_block * (kc >> 6) + kblock0 + kb2) * PANEL_ELEMS + half_rows * 128 * PANEL_K;
+#pragma unroll
+      for (int x = 0; x < 16; ++x) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(stage + kb2 * 8192 + (x * 64 + lane) * 8);
+        *reinterpret_cast<u32x4*>(dst + (x * 64 + lane) * 8) = v;
+      }
+    }
+  };
+
+  if (EPI != EPI_FINAL) {
+    // ---- straight image: element (i, j) of C is (row i, k = j) of the result's panels.
+    // A 16-byte chunk is 8 consecutive j of one row, i.e. one value from each of 8 lanes:
+    // neighbouring lanes swap one value so that every lane writes two packed bf16.
+    __bf16* C = static_cast<__bf16*>(e.c) + static_cast<int64_t>(b) * d.M * d.N;
+#pragma unroll
+    for (int it = 0; it < 4; ++it)
+#pragma unroll
+      for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+        for (int rp = 0; rp < 8; ++rp) {  // register pairs (2 rp, 2 rp + 1): rows differ by one
+          const float own0 = acc[it][jt][2 * rp], own1 = acc[it][jt][2 * rp + 1];
+          const float got = lane_xor1((lane & 1) ? own0 : own1);
+          bf16x2 pk;
+          pk[0] = static_cast<__bf16>((lane & 1) ? got : own0);
+          pk[1] = static_cast<__bf16>((lane & 1) ? own1 : got);
+          const int row_l = it * 32 + 8 * (rp >> 1) + 4 * lh + 2 * (rp & 1) + (lane & 1);
+          const int chunk = 4 * (jt & 1) + (lj >> 3);
+          const int off = (jt >> 1) * 8192 + row_l * 64 + ((chunk ^ ((row_l >> 1) & 7)) << 3) + (lj & 6);
+          *reinterpret_cast<bf16x2*>(stage + off) = pk;
+        }
+    flush_stage(C, tm, d.N, 4 * tn + 2 * wn, wm);
+
+    // ---- transposed image: element (i, j) is (row j, k = i) of CT (UPDATE) or of the mirror
+    // tile of C (symmetric products).  A lane's 4 consecutive rows are half a chunk.
+    const bool mirror = (EPI == EPI_GRAM || EPI == EPI_POLY);
+    if (!mirror || tm != tn) {
+      __bf16* CT = mirror ? C : static_cast<__bf16*>(e.ct) + static_cast<int64_t>(b) * d.M * d.N;
+#pragma unroll
+      for (int it = 0; it < 4; ++it)
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            bf16x4 pk;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) pk[q] = static_cast<__bf16>(acc[it][jt][4 * g + q]);
+            const int row_l = jt * 32 + lj;
+            const int chunk = 4 * (it & 1) + g;
+            const int off = (it >> 1) * 8192 + row_l * 64 + ((chunk ^ ((row_l >> 1) & 7)) << 3) + 4 * lh;
+            *reinterpret_cast<bf16x4*>(stage + off) = pk;
+          }
+      flush_stage(CT, tn, d.M, 4 * tm + 2 * wm, wn);
+    }
+  } else {
+    // ---- last product: O in the caller's orientation (the host orders the operands so).
+    const int ld = static_cast<int>(o.out_mode == CANZ_OUT_DELTA ? s.wfrag : s.cols);
+    if ((ld & 3) == 0) {
+      // fp32 rows through LDS, 64 rows x 128 columns at a time; the column index is XOR-ed
+      // with 32 on rows whose bit 2 is set so that the two half-waves hit different banks
+      float* sf = reinterpret_cast<float*>(stage);
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+#pragma unroll
+        for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+          for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int row_l = i2 * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+              sf[row_l * 128 + ((jt * 32 + lj) ^ (lh << 5))] = acc[half * 2 + i2][jt][r];
+            }
+        const int row_base = tm * BM + wm * 128 + half * 64;
+        const int col_base = tn * BN + wn * 128;
+#pragma unroll
+        for (int x4 = 0; x4 < 8; ++x4) {  // 4 row-chunks at a time: loads of old values first
+          f32x4 v[4], old[4];
+          int row[4], col[4];
+          bool live[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int idx = (x4 * 4 + u) * 64 + lane;
+            const int row_l = idx >> 5, c4 = (idx & 31) * 4;
+            v[u] = *reinterpret_cast<const f32x4*>(sf + row_l * 128 + (c4 ^ (((row_l >> 2) & 1) << 5)));
+            row[u] = row_base + row_l;
+            col[u] = col_base + c4;
+            live[u] = row[u] < s.rows && col[u] < s.cols;
+          }
+          if (o.out_mode == CANZ_OUT_PARAM) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+              if (live[u]) old[u] = load_param4(o, s, b, row[u], col[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+              if (live[u]) store_out4(o, s, b, row[u], col[u], old[u] * o.decay + o.neg_lr_scale * v[u]);
+          } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+              if (live[u]) store_out4(o, s, b, row[u], col[u], o.neg_lr_scale * v[u]);
+          }
+        }
+      }
+    } else {
+      // unaligned row length: element-wise stores straight from the accumulators
+#pragma unroll
+      for (int it = 0; it < 4; ++it)
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) {
+          float v[16];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) v[r] = acc[it][jt][r];
+          store_out_tile(o, s, b, tm * BM + wm * 128 + it * 32 + 4 * lh, tn * BN + wn * 128 + jt * 32 + lj, v);
+        }
     }
   }
 }
@@ -248,7 +388,8 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
 template <int EPI>
 hipError_t launch(const GemmDims& d, const void* P, const void* Q, const EpiArgs& e, const Shape& s, const OutSpec& o,
                   hipStream_t st) {
-  const int64_t blocks = (d.M / BM) * (d.N / BN) * d.nb;
+  const int64_t tm = d.M / BM, tn = d.N / BN;
+  const int64_t blocks = ((EPI == EPI_GRAM || EPI == EPI_POLY) ? tm * (tm + 1) / 2 : tm * tn) * d.nb;
   hipLaunchKernelGGL((k_gemm_nt_bf16<EPI>), dim3(static_cast<unsigned>(blocks)), dim3(NTHREADS), 0, st, d,
                      static_cast<const __bf16*>(P), static_cast<const __bf16*>(Q), e, s, o);
   return hipGetLastError();
