@@ -151,27 +151,47 @@ def main():
     # ---- work accounting
     flops_step = float(sum(ns_flops(s["rows"][p], s["cols"][p], hp.ns_steps) for g in groups for p in g))
     tflops = flops_step / (ms_per_step * 1e-3) / 1e12
-    # algorithmic FLOPs per launch kind (per step), as the method writes them
+    # FLOPs per launch kind and step: "algorithmic" as the method writes them (2 m^2 n for the
+    # Gram and update products, 2 m^3 for the square); "issued" = what the MFMA units execute:
+    # padded extents, and only the tiles on or above the diagonal for the symmetric products.
+    def pad(x):
+        return (x + 255) // 256 * 256
+
     kind_flops = dict(gram=0.0, poly=0.0, update=0.0, final=0.0)
+    kind_issued = dict(gram=0.0, poly=0.0, update=0.0, final=0.0)
+    bf16 = args.precision == "bf16"
     for g in groups:
         rows, cols = s["rows"][g[0]], s["cols"][g[0]]
         m, n = min(rows, cols), max(rows, cols)
+        mp, np_ = pad(m), pad(n)
+        tri = (mp // 256) * (mp // 256 + 1) // 2 * 65536 if bf16 else mp * mp
         kind_flops["gram"] += 2.0 * m * m * n * len(g) * hp.ns_steps
         kind_flops["poly"] += 2.0 * m ** 3 * len(g) * hp.ns_steps
         kind_flops["update"] += 2.0 * m * m * n * len(g) * (hp.ns_steps - 1)
         kind_flops["final"] += 2.0 * m * m * n * len(g)
+        kind_issued["gram"] += 2.0 * tri * np_ * len(g) * hp.ns_steps
+        kind_issued["poly"] += 2.0 * tri * mp * len(g) * hp.ns_steps
+        kind_issued["update"] += 2.0 * mp * mp * np_ * len(g) * (hp.ns_steps - 1)
+        kind_issued["final"] += 2.0 * mp * mp * np_ * len(g)
+    issued_step = sum(kind_issued.values())
     kernels = {}
     for k, (ms, n) in prof.items():
         if n:
             kernels[k] = dict(ms_per_step=ms / args.steps, launches_per_step=n / args.steps, avg_ms=ms / n)
             if k in kind_flops:
-                kernels[k]["tflops"] = kind_flops[k] * args.steps / (ms * 1e-3) / 1e12
+                kernels[k]["tflops_algorithmic"] = kind_flops[k] * args.steps / (ms * 1e-3) / 1e12
+                kernels[k]["tflops_issued"] = kind_issued[k] * args.steps / (ms * 1e-3) / 1e12
     dom = max((k for k in kernels if k in kind_flops), key=lambda k: kernels[k]["ms_per_step"])
     dom_flops_per_launch = kind_flops[dom] / kernels[dom]["launches_per_step"]
+    dom_issued_per_launch = kind_issued[dom] / kernels[dom]["launches_per_step"]
     achieved = dom_flops_per_launch / (kernels[dom]["avg_ms"] * 1e-3) / 1e12
-    roofline = dict(bound="mfma", kernel="k_gemm_nt_bf16<%s>" % dom, achieved=achieved, peak=PEAK_BF16_TFLOPS,
-                    unit="TFLOP/s", frac=achieved / PEAK_BF16_TFLOPS, traffic=None,
-                    flops_per_launch=dom_flops_per_launch, avg_launch_ms=kernels[dom]["avg_ms"])
+    achieved_issued = dom_issued_per_launch / (kernels[dom]["avg_ms"] * 1e-3) / 1e12
+    peak = PEAK_BF16_TFLOPS if bf16 else 157.3
+    roofline = dict(bound="mfma", kernel="k_gemm_nt_%s<%s>" % (args.precision, dom), achieved=achieved, peak=peak,
+                    unit="TFLOP/s", frac=achieved / peak, traffic=None,
+                    achieved_issued=achieved_issued, frac_issued=achieved_issued / peak,
+                    flops_per_launch=dom_flops_per_launch, issued_flops_per_launch=dom_issued_per_launch,
+                    avg_launch_ms=kernels[dom]["avg_ms"])
     if "momentum" in kernels:
         grad_b = 2 if s["grad_dtype"] == W.DT_BF16 else 4
         esz = 2 if args.precision == "bf16" else 4
@@ -228,7 +248,10 @@ def main():
                                 sorted({(s["rows"][p], s["cols"][p]) for g in groups for p in g}), len(groups),
                                 hp.ns_steps),
                    "tp": tp, "elements": total_elems},
-        "tflops": tflops, "frac_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS, "ns_flops_per_step": flops_step,
+        "tflops_algorithmic": tflops, "ns_flops_per_step": flops_step,
+        "tflops_issued": issued_step / (ms_per_step * 1e-3) / 1e12, "issued_flops_per_step": issued_step,
+        "frac_mfma_peak_issued": issued_step / (ms_per_step * 1e-3) / 1e12 / peak,
+        "frac_mfma_peak_algorithmic": tflops / peak,
         "step_ms_events": {"median": float(np.median(per_step)), "min": float(min(per_step))},
         "planner": diag, "kernels": kernels, "roofline": roofline, "cpu_baseline": cpu,
     }

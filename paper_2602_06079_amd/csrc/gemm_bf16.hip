@@ -26,11 +26,15 @@
 // last product of the chain instead stages fp32 rows and applies the parameter update
 // with 16-byte accesses on the caller's row-major buffers.
 //
-// Blocks are numbered so that the 32 blocks resident on one XCD (blockIdx % 8 selects the
-// XCD) form a 4 x 8 patch of tiles of one matrix and share panels in that XCD's L2.
+// Blocks are persistent (one per CU) and loop over tiles, so the stores of one tile's
+// epilogue drain while the next tile is multiplied.  In every round the 32 blocks of one XCD
+// (blockIdx % 8 selects the XCD) form a 4 x 8 patch of tiles of one matrix and share panels
+// in that XCD's L2.
 // Symmetric products (Gram, polynomial) run only the tiles on or above the diagonal and
 // write the mirror image as well.  Extents are multiples of 256 (zero padded by the
 // producer), so only the final epilogue clips to the caller's shape.
+#include <type_traits>
+
 #include "device_util.h"
 #include "panel_layout.h"
 
@@ -80,24 +84,38 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
   __shared__ __attribute__((aligned(1024))) __bf16 sP1[BM * BK];
   __shared__ __attribute__((aligned(1024))) __bf16 sQ1[BN * BK];
 
-  // ---- block -> (matrix, tile): XCD-contiguous numbering, then 4-row raster bands
+  // ---- persistent blocks: the grid is one block per CU (or fewer); block `bid` works on the
+  //      logical tiles round * gridDim + slot(bid).  slot() makes the 32 blocks of one XCD
+  //      (blockIdx % 8 selects the XCD) neighbours, so that in every round they form a 4 x 8
+  //      patch of tiles of one matrix and share panels in that XCD's L2.
   const int tiles_n = static_cast<int>(d.N / BN);
   const int tiles_m = static_cast<int>(d.M / BM);
   const int per_batch = (EPI == EPI_GRAM || EPI == EPI_POLY) ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
-  int logical;
+  const int total_tiles = per_batch * d.nb;
+  int slot;
   {
     const int nblocks = gridDim.x, bid = blockIdx.x;
     const int per = nblocks / N_XCD, rem = nblocks % N_XCD;
     const int xcd = bid % N_XCD, q = bid / N_XCD;
-    logical = xcd < rem ? xcd * (per + 1) + q : rem * (per + 1) + (xcd - rem) * per + q;
+    slot = xcd < rem ? xcd * (per + 1) + q : rem * (per + 1) + (xcd - rem) * per + q;
   }
+
+  const int t = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+
+  for (int logical = slot; logical < total_tiles; logical += gridDim.x) {
+  // The lane id is made opaque once per tile: otherwise every lane-dependent address of the
+  // loop body (hundreds of them) is hoisted out of the tile loop and kept alive in scratch.
+  int lane = t & 63;
+  asm volatile("" : "+v"(lane));
   const int b = logical / per_batch;
   const int tix = logical - b * per_batch;
   int tm, tn;
   if (EPI == EPI_GRAM || EPI == EPI_POLY) {
     // symmetric output: only tiles with tn >= tm exist (per_batch = nt (nt + 1) / 2); the
-    // epilogue writes each off-diagonal tile twice, straight and mirrored.  Same banding:
-    // inside a band of 4 tile rows starting at r0 the columns r0, r0+1, ... are walked one
+    // epilogue writes each off-diagonal tile twice, straight and mirrored.  Raster: bands of
+    // 4 tile rows; inside the band starting at r0 the columns r0, r0+1, ... are walked one
     // after the other, column c holding the rows r0 .. min(r0 + 3, c).
     int rem = tix, band = 0;
     for (;;) {
@@ -121,17 +139,13 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
       tm = r0 + rem % rows;
     }
   } else {
+    // bands of 4 tile rows, walked column by column
     const int band = tix / (GROUP_M * tiles_n);
     const int in_band = tix - band * GROUP_M * tiles_n;
     const int rows_here = min(GROUP_M, tiles_m - band * GROUP_M);
     tn = in_band / rows_here;
     tm = band * GROUP_M + (in_band - tn * rows_here);
   }
-
-  const int t = threadIdx.x;
-  const int lane = t & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
 
   // ---- global -> LDS: panel (tile row, k-step) is 32 KiB contiguous; wavefront w copies the
   //      1 KiB pieces w, w+4, ..., w+28 of both panels, lane l the 16 bytes at l * 16.
@@ -283,6 +297,14 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
     // A 16-byte chunk is 8 consecutive j of one row, i.e. one value from each of 8 lanes:
     // neighbouring lanes swap one value so that every lane writes two packed bf16.
     __bf16* C = static_cast<__bf16*>(e.c) + static_cast<int64_t>(b) * d.M * d.N;
+    // Staging offset = (lane-only base) + (compile-time part), so that the compiler keeps two
+    // address registers instead of one per store.  With row_l = 32 it + 8 g + 2 p + 4 lh + odd
+    // (rp = 2 g + p) the swizzle term (row_l >> 1) & 7 is 4 (g & 1) | 2 lh | p, and the chunk
+    // 4 (jt & 1) + (lj >> 3); bit 2 of their XOR is compile-time, bits 0-1 are lane bits ^ p.
+    int s_base[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+      s_base[p] = (4 * lh + (lane & 1)) * 64 + ((((lj >> 3) ^ (2 * lh + p)) & 3) << 3) + (lj & 6);
 #pragma unroll
     for (int it = 0; it < 4; ++it)
 #pragma unroll
@@ -294,10 +316,9 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
           bf16x2 pk;
           pk[0] = static_cast<__bf16>((lane & 1) ? got : own0);
           pk[1] = static_cast<__bf16>((lane & 1) ? own1 : got);
-          const int row_l = it * 32 + 8 * (rp >> 1) + 4 * lh + 2 * (rp & 1) + (lane & 1);
-          const int chunk = 4 * (jt & 1) + (lj >> 3);
-          const int off = (jt >> 1) * 8192 + row_l * 64 + ((chunk ^ ((row_l >> 1) & 7)) << 3) + (lj & 6);
-          *reinterpret_cast<bf16x2*>(stage + off) = pk;
+          const int g = rp >> 1, p = rp & 1;
+          const int fixed = (jt >> 1) * 8192 + (it * 32 + 8 * g + 2 * p) * 64 + ((((jt & 1) ^ (g & 1)) << 2) << 3);
+          *reinterpret_cast<bf16x2*>(stage + fixed + s_base[p]) = pk;
         }
     flush_stage(C, tm, d.N, 4 * tn + 2 * wn, wm);
 
@@ -306,6 +327,10 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
     const bool mirror = (EPI == EPI_GRAM || EPI == EPI_POLY);
     if (!mirror || tm != tn) {
       __bf16* CT = mirror ? C : static_cast<__bf16*>(e.ct) + static_cast<int64_t>(b) * d.M * d.N;
+      // row_l = 32 jt + lj, chunk = 4 (it & 1) + g: one lane base per chunk value, rest immediate
+      int t_base[8];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) t_base[c] = lj * 64 + ((c ^ ((lj >> 1) & 7)) << 3) + 4 * lh;
 #pragma unroll
       for (int it = 0; it < 4; ++it)
 #pragma unroll
@@ -315,10 +340,7 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
             bf16x4 pk;
 #pragma unroll
             for (int q = 0; q < 4; ++q) pk[q] = static_cast<__bf16>(acc[it][jt][4 * g + q]);
-            const int row_l = jt * 32 + lj;
-            const int chunk = 4 * (it & 1) + g;
-            const int off = (it >> 1) * 8192 + row_l * 64 + ((chunk ^ ((row_l >> 1) & 7)) << 3) + 4 * lh;
-            *reinterpret_cast<bf16x4*>(stage + off) = pk;
+            *reinterpret_cast<bf16x4*>(stage + (it >> 1) * 8192 + jt * 32 * 64 + t_base[4 * (it & 1) + g]) = pk;
           }
       flush_stage(CT, tn, d.M, 4 * tm + 2 * wm, wn);
     }
@@ -327,48 +349,94 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
     const int ld = static_cast<int>(o.out_mode == CANZ_OUT_DELTA ? s.wfrag : s.cols);
     if ((ld & 3) == 0) {
       // fp32 rows through LDS, 64 rows x 128 columns at a time; the column index is XOR-ed
-      // with 32 on rows whose bit 2 is set so that the two half-waves hit different banks
-      float* sf = reinterpret_cast<float*>(stage);
+      // with 32 on rows whose bit 2 is set so that the two half-waves hit different banks.
+      // One instantiation per (output mode, output dtype): the branches stay outside the
+      // unrolled code.
+      auto run = [&](auto mode_tag, auto dtype_tag) {
+        constexpr int MODE = decltype(mode_tag)::value, DTYPE = decltype(dtype_tag)::value;
+        float* sf = reinterpret_cast<float*>(stage);
+        int f_base[2], r_base[2];
 #pragma unroll
-      for (int half = 0; half < 2; ++half) {
+        for (int p = 0; p < 2; ++p) {
+          f_base[p] = 4 * lh * 128 + lj + 32 * (p ^ lh);
+          r_base[p] = lh * 128 + ((lj * 4) ^ (p << 5));
+        }
+        // per-lane element offset of (row 0 of the wavefront's part, its 4 columns) in the
+        // caller's buffer, and the buffer itself (TP: the fragment that holds these columns)
+        const int col = tn * BN + wn * 128 + lj * 4;
+        const bool col_ok = col < s.cols;
+        int c_in = col, tab = b;
+        if (MODE == CANZ_OUT_DELTA) {
+          const int f = col_ok ? col / ld : 0;
+          c_in = col - f * ld;
+          tab = b * s.tp + f;
+        }
+        char* base = static_cast<char*>(o.out.p[col_ok ? tab : b * (MODE == CANZ_OUT_DELTA ? s.tp : 1)]);
+        constexpr int ESZ = DTYPE == CANZ_DT_F32 ? 4 : 2;
 #pragma unroll
-        for (int i2 = 0; i2 < 2; ++i2)
+        for (int half = 0; half < 2; ++half) {
 #pragma unroll
-          for (int jt = 0; jt < 4; ++jt)
+          for (int i2 = 0; i2 < 2; ++i2)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int row_l = i2 * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-              sf[row_l * 128 + ((jt * 32 + lj) ^ (lh << 5))] = acc[half * 2 + i2][jt][r];
+            for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                // (32 jt + lj) ^ (32 lh) = lj + 32 (jt ^ lh): lane base per parity of jt
+                const int fixed = (i2 * 32 + 8 * (r >> 2) + (r & 3)) * 128 + (jt & ~1) * 32;
+                sf[fixed + f_base[jt & 1]] = acc[half * 2 + i2][jt][r];
+              }
+          const int row_base = tm * BM + wm * 128 + half * 64 + lh;
+#pragma unroll
+          for (int x4 = 0; x4 < 8; ++x4) {  // 4 rows at a time: loads of old values first
+            f32x4 v[4], old[4];
+            char* ptr[4];
+            bool live[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              // lane reads 4 columns of row 2 (4 x4 + u) + lh; bit 2 of that row is bit 1 of u
+              v[u] = *reinterpret_cast<const f32x4*>(sf + 2 * (x4 * 4 + u) * 128 + r_base[(u >> 1) & 1]);
+              const int row = row_base + 2 * (x4 * 4 + u);
+              live[u] = col_ok && row < s.rows;
+              ptr[u] = base + (static_cast<int64_t>(row) * ld + c_in) * ESZ;
             }
-        const int row_base = tm * BM + wm * 128 + half * 64;
-        const int col_base = tn * BN + wn * 128;
+            if (MODE == CANZ_OUT_PARAM) {
 #pragma unroll
-        for (int x4 = 0; x4 < 8; ++x4) {  // 4 row-chunks at a time: loads of old values first
-          f32x4 v[4], old[4];
-          int row[4], col[4];
-          bool live[4];
+              for (int u = 0; u < 4; ++u) {
+                if (!live[u]) continue;
+                if (DTYPE == CANZ_DT_F32) {
+                  old[u] = *reinterpret_cast<const f32x4*>(ptr[u]);
+                } else {
+                  const bf16x4 ob = *reinterpret_cast<const bf16x4*>(ptr[u]);
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const int idx = (x4 * 4 + u) * 64 + lane;
-            const int row_l = idx >> 5, c4 = (idx & 31) * 4;
-            v[u] = *reinterpret_cast<const f32x4*>(sf + row_l * 128 + (c4 ^ (((row_l >> 2) & 1) << 5)));
-            row[u] = row_base + row_l;
-            col[u] = col_base + c4;
-            live[u] = row[u] < s.rows && col[u] < s.cols;
-          }
-          if (o.out_mode == CANZ_OUT_PARAM) {
+                  for (int q = 0; q < 4; ++q) old[u][q] = static_cast<float>(ob[q]);
+                }
+              }
+            }
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-              if (live[u]) old[u] = load_param4(o, s, b, row[u], col[u]);
+            for (int u = 0; u < 4; ++u) {
+              if (!live[u]) continue;
+              f32x4 res = o.neg_lr_scale * v[u];
+              if (MODE == CANZ_OUT_PARAM) res = old[u] * o.decay + res;
+              if (DTYPE == CANZ_DT_F32) {
+                *reinterpret_cast<f32x4*>(ptr[u]) = res;
+              } else {
+                bf16x4 rb;
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-              if (live[u]) store_out4(o, s, b, row[u], col[u], old[u] * o.decay + o.neg_lr_scale * v[u]);
-          } else {
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-              if (live[u]) store_out4(o, s, b, row[u], col[u], o.neg_lr_scale * v[u]);
+                for (int q = 0; q < 4; ++q) rb[q] = static_cast<__bf16>(res[q]);
+                *reinterpret_cast<bf16x4*>(ptr[u]) = rb;
+              }
+            }
           }
         }
+      };
+      using P_ = std::integral_constant<int, CANZ_OUT_PARAM>;
+      using D_ = std::integral_constant<int, CANZ_OUT_DELTA>;
+      using F_ = std::integral_constant<int, CANZ_DT_F32>;
+      using B_ = std::integral_constant<int, CANZ_DT_BF16>;
+      if (o.out_mode == CANZ_OUT_PARAM) {
+        if (o.out_dtype == CANZ_DT_F32) run(P_{}, F_{}); else run(P_{}, B_{});
+      } else {
+        if (o.out_dtype == CANZ_DT_F32) run(D_{}, F_{}); else run(D_{}, B_{});
       }
     } else {
       // unaligned row length: element-wise stores straight from the accumulators
@@ -383,13 +451,31 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
         }
     }
   }
+  // the next tile's loads overwrite every wavefront's staging area: wait for all of them.
+  // The global stores issued above keep draining while the next tile is multiplied.
+  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0) only
+  __builtin_amdgcn_s_barrier();
+  }  // persistent tile loop
+}
+
+int cu_count() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
 }
 
 template <int EPI>
 hipError_t launch(const GemmDims& d, const void* P, const void* Q, const EpiArgs& e, const Shape& s, const OutSpec& o,
                   hipStream_t st) {
   const int64_t tm = d.M / BM, tn = d.N / BN;
-  const int64_t blocks = ((EPI == EPI_GRAM || EPI == EPI_POLY) ? tm * (tm + 1) / 2 : tm * tn) * d.nb;
+  const int64_t tiles = ((EPI == EPI_GRAM || EPI == EPI_POLY) ? tm * (tm + 1) / 2 : tm * tn) * d.nb;
+  const int64_t blocks = tiles < cu_count() ? tiles : cu_count();
   hipLaunchKernelGGL((k_gemm_nt_bf16<EPI>), dim3(static_cast<unsigned>(blocks)), dim3(NTHREADS), 0, st, d,
                      static_cast<const __bf16*>(P), static_cast<const __bf16*>(Q), e, s, o);
   return hipGetLastError();
