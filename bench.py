@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default 4: Qwen3-32B share)")
     ap.add_argument("--precision", choices=["bf16", "f32"], default="bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy before the warm-up: under `rocprofv3 --pmc FETCH_SIZE` / "
+                         "`WRITE_SIZE` its known traffic gives the scale of the counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py measures one rank's share on ONE GPU; this build has no multi-GPU path "
@@ -125,6 +128,13 @@ def main():
     def step():
         canz.canz_muon_step(dgroups, hp, ws, ws_bytes, stream)
 
+    if args.calibration_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                                                    # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(args.warmup):
         step()
     torch.cuda.synchronize()
