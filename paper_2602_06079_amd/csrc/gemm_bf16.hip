@@ -7,19 +7,23 @@
 //
 // Tiling: one 256-thread block (4 wavefronts, 2 x 2) owns a 256 x 256 tile of C; each
 // wavefront owns 128 x 128 = 4 x 4 MFMA tiles, i.e. 256 fp32 accumulators per lane (one
-// wavefront per SIMD, 512 registers each).  K is walked in steps of 64.
+// wavefront per SIMD, 512 registers each).  K is walked in steps of 32.
 //
-// Operand staging: a 256 x 64 panel is 32 KiB of contiguous memory that already has the
+// Operand staging: a 256 x 32 panel is 16 KiB of contiguous memory that already has the
 // bank-conflict-free LDS arrangement, so it goes from global memory straight into LDS as
 // a linear copy (global_load_lds_dwordx4: a wavefront moves 1 KiB per instruction), into
-// one of two 64 KiB stages.
+// one of four 32 KiB stages (P panel + Q panel).
 //
-// Pipeline per k-step (one barrier): the panels of step t+1 are in flight while step t is
-// multiplied; the MFMA operand fragments are double-buffered in registers, and the
-// barrier sits before the last quarter of the step so that the fetch of step t+2 and the
-// first fragments of step t+1 are issued under the remaining 16 MFMAs.  The kernel is
-// bound as much by moving 64 KiB per step from L2 into LDS as by the matrix pipe, so the
-// loads are spread out: one LDS or global instruction in the shadow of each MFMA.
+// Pipeline: moving 32 KiB per k-step from L2 into LDS takes about as long as the 32 MFMAs
+// of the step, and a fetch needs more than a microsecond to land, so the ring is four
+// stages deep: while step t is multiplied, steps t+1 .. t+3 are resident or in flight and
+// step t+4 is being requested.  The MFMA operand fragments are double-buffered in
+// registers.  A wavefront issues in order and an MFMA keeps the matrix pipe busy for 32
+// cycles, so every other instruction is placed in the shadow of one MFMA: one LDS operand
+// load after each of the first 8 MFMAs of a half-step, one direct load after every
+// fourth.  One barrier per k-step, between its two half-steps: before it each wavefront
+// waits for its own share of step t+1 (s_waitcnt vmcnt(16): the 16 younger loads of steps
+// t+2 and t+3 may stay in flight); after it stage t is free for step t+4.
 //
 // Epilogue: the accumulators are re-arranged through LDS (free after the last step) into
 // panel-layout images, one per wavefront, and leave as linear 16-byte-per-lane stores; the
@@ -41,7 +45,7 @@
 namespace canz {
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int BM = 256, BN = 256, BK = 32;
 constexpr int NTHREADS = 256;
 constexpr int CHUNKS = BK / 8;   // 16-byte chunks per panel row
 constexpr int GROUP_M = 4;       // tile rows per raster band
@@ -65,7 +69,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 #define CANZ_GLB(p) ((const __attribute__((address_space(1))) void*)(p))
 
 __device__ __forceinline__ int swz(int row, int chunk) {
-  return (row * CHUNKS + (chunk ^ ((row >> 1) & (CHUNKS - 1)))) * 8;  // element offset in the panel
+  return (row * CHUNKS + (chunk ^ ((row >> 2) & (CHUNKS - 1)))) * 8;  // element offset in the panel
 }
 
 // value of the neighbouring lane (lane ^ 1), through the DPP quad permute [1, 0, 3, 2]
@@ -77,12 +81,14 @@ template <int EPI>
 __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __bf16* __restrict__ P,
                                                             const __bf16* __restrict__ Q, EpiArgs e, Shape s,
                                                             OutSpec o) {
-  // four separate arrays (not one carved buffer): the compiler then knows that a fetch into
-  // one stage does not alias the operand reads of the other and keeps them overlapped
-  __shared__ __attribute__((aligned(1024))) __bf16 sP0[BM * BK];
-  __shared__ __attribute__((aligned(1024))) __bf16 sQ0[BN * BK];
-  __shared__ __attribute__((aligned(1024))) __bf16 sP1[BM * BK];
-  __shared__ __attribute__((aligned(1024))) __bf16 sQ1[BN * BK];
+  // one array per stage (not one carved buffer): the compiler then knows that a fetch into
+  // one stage does not alias the operand reads of another and keeps them overlapped.
+  // Elements [0, 8192) hold the P panel, [8192, 16384) the Q panel.
+  constexpr int QOFF = BM * BK;
+  __shared__ __attribute__((aligned(1024))) __bf16 st0[(BM + BN) * BK];
+  __shared__ __attribute__((aligned(1024))) __bf16 st1[(BM + BN) * BK];
+  __shared__ __attribute__((aligned(1024))) __bf16 st2[(BM + BN) * BK];
+  __shared__ __attribute__((aligned(1024))) __bf16 st3[(BM + BN) * BK];
 
   // ---- persistent blocks: the grid is one block per CU (or fewer); block `bid` works on the
   //      logical tiles round * gridDim + slot(bid).  slot() makes the 32 blocks of one XCD
@@ -147,22 +153,22 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
     tm = band * GROUP_M + (in_band - tn * rows_here);
   }
 
-  // ---- global -> LDS: panel (tile row, k-step) is 32 KiB contiguous; wavefront w copies the
-  //      1 KiB pieces w, w+4, ..., w+28 of both panels, lane l the 16 bytes at l * 16.
+  // ---- global -> LDS: panel (tile row, k-step) is 16 KiB contiguous; wavefront w copies the
+  //      1 KiB pieces w, w+4, w+8, w+12 of both panels, lane l the 16 bytes at l * 16.
   const int64_t nkb = d.K / BK;
   const __bf16* pl = P + static_cast<int64_t>(b) * d.sp + static_cast<int64_t>(tm) * nkb * PANEL_ELEMS + wave * 512 + lane * 8;
   const __bf16* ql = Q + static_cast<int64_t>(b) * d.sq + static_cast<int64_t>(tn) * nkb * PANEL_ELEMS + wave * 512 + lane * 8;
-  // one of the 16 direct loads of a stage: idx 0..7 -> P pieces, 8..15 -> Q pieces
-  auto fetch_one = [&](__bf16* sP, __bf16* sQ, int64_t kt, int idx) {
-    const int g = idx & 7;
-    if (idx < 8)
-      __builtin_amdgcn_global_load_lds(CANZ_GLB(pl + kt * PANEL_ELEMS + g * 2048), CANZ_LDS(sP + wave * 512 + g * 2048), 16, 0, 0);
+  // one of the 8 direct loads of a stage: idx 0..3 -> P pieces, 4..7 -> Q pieces
+  auto fetch_one = [&](__bf16* st, int64_t kt, int idx) {
+    const int g = idx & 3;
+    if (idx < 4)
+      __builtin_amdgcn_global_load_lds(CANZ_GLB(pl + kt * PANEL_ELEMS + g * 2048), CANZ_LDS(st + wave * 512 + g * 2048), 16, 0, 0);
     else
-      __builtin_amdgcn_global_load_lds(CANZ_GLB(ql + kt * PANEL_ELEMS + g * 2048), CANZ_LDS(sQ + wave * 512 + g * 2048), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(CANZ_GLB(ql + kt * PANEL_ELEMS + g * 2048), CANZ_LDS(st + QOFF + wave * 512 + g * 2048), 16, 0, 0);
   };
-  auto fetch = [&](__bf16* sP, __bf16* sQ, int64_t kt) {
+  auto fetch = [&](__bf16* st, int64_t kt) {
 #pragma unroll
-    for (int idx = 0; idx < 16; ++idx) fetch_one(sP, sQ, kt, idx);
+    for (int idx = 0; idx < 8; ++idx) fetch_one(st, kt, idx);
   };
 
   f32x16 acc[4][4];
@@ -176,67 +182,75 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
   // MFMA operand fragments, double-buffered in registers: idx 0..3 -> rows of P, 4..7 -> rows of Q
   const int frag_row = lane & 31, frag_kg = lane >> 5;
   bf16x8 fa[2][4], fb[2][4];
-  auto frag_one = [&](const __bf16* sP, const __bf16* sQ, int kk, int set, int idx) {
+  auto frag_one = [&](const __bf16* st, int kk, int set, int idx) {
     if (idx < 4)
-      fa[set][idx] = *reinterpret_cast<const bf16x8*>(sP + swz(wm * 128 + idx * 32 + frag_row, kk * 2 + frag_kg));
+      fa[set][idx] = *reinterpret_cast<const bf16x8*>(st + swz(wm * 128 + idx * 32 + frag_row, kk * 2 + frag_kg));
     else
       fb[set][idx - 4] =
-          *reinterpret_cast<const bf16x8*>(sQ + swz(wn * 128 + (idx - 4) * 32 + frag_row, kk * 2 + frag_kg));
-  };
-  auto load_frags = [&](const __bf16* sP, const __bf16* sQ, int kk, int set) {
-#pragma unroll
-    for (int idx = 0; idx < 8; ++idx) frag_one(sP, sQ, kk, set, idx);
+          *reinterpret_cast<const bf16x8*>(st + QOFF + swz(wn * 128 + (idx - 4) * 32 + frag_row, kk * 2 + frag_kg));
   };
   auto mma_one = [&](int set, int idx) {
     const int i = idx >> 2, j = idx & 3;
     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
   };
 
-  const int nk = static_cast<int>(nkb);  // even: K is a multiple of 256
-  // The issue order below is pinned with scheduling fences.  A wavefront issues in order and
-  // an MFMA occupies the matrix pipe for 32 cycles, so every other instruction is placed in
-  // the shadow of one MFMA: one LDS operand load or one direct global->LDS load per MFMA.
-  // Left to itself the compiler clusters the loads and the matrix pipe drains meanwhile.
+  const int nk = static_cast<int>(nkb);  // multiple of 8: K is a multiple of 256
+  // The issue order below is pinned with scheduling fences (left to itself the compiler
+  // clusters the loads and the matrix pipe drains meanwhile).
 #define CANZ_FENCE() __builtin_amdgcn_sched_barrier(0)
-  // one k-step on stage (cP, cQ); the other stage (nP, nQ) holds step kt + 1.  The fetch
-  // index is clamped instead of guarded (a branch here costs the compiler its knowledge of
-  // which stage is in flight); the last two steps refetch the final panel into stages
-  // nobody reads any more.
-  auto k_step = [&](__bf16* cP, __bf16* cQ, const __bf16* nP, const __bf16* nQ, int kt) {
+  // One k-step on stage `cur`; `nxt` holds step kt+1, `prv` (free since the barrier of the
+  // previous step) receives the second half of step kt+3, `cur` after this step's barrier
+  // the first half of step kt+4.  Fetch indices are clamped instead of guarded (a branch
+  // here costs the compiler its knowledge of which stage is in flight, and the number of
+  // loads in flight must not depend on kt); the clamped refetches land in stages nobody
+  // reads any more.
+  auto k_step = [&](__bf16* cur, const __bf16* nxt, __bf16* prv, int kt) {
+    const int64_t k3 = min(kt + 3, nk - 1), k4 = min(kt + 4, nk - 1);
 #pragma unroll
-    for (int kk = 0; kk < 3; ++kk) {
-#pragma unroll
-      for (int idx = 0; idx < 16; ++idx) {
-        mma_one(kk & 1, idx);
+    for (int idx = 0; idx < 16; ++idx) {
+      mma_one(0, idx);
+      CANZ_FENCE();
+      if (idx < 8) {
+        frag_one(cur, 1, 1, idx);  // second half-step's operands, land under the next 8 MFMAs
         CANZ_FENCE();
-        if (idx < 8) {
-          frag_one(cP, cQ, kk + 1, (kk + 1) & 1, idx);  // lands under the 8 MFMAs that follow
-          CANZ_FENCE();
-        }
+      }
+      if ((idx & 3) == 2) {
+        fetch_one(prv, k3, 4 + (idx >> 2));  // Q panel of step kt+3
+        CANZ_FENCE();
       }
     }
-    __syncthreads();  // step kt+1 has landed everywhere; nobody reads (cP, cQ) any more
-    const int64_t k2 = min(kt + 2, nk - 1);
+    // own share of step kt+1 has landed (16 younger loads may be in flight); this wavefront's
+    // reads of `cur` are complete.  simm16 = vmcnt[3:0] | expcnt 7 << 4 | lgkmcnt << 8 | vmcnt[5:4] << 14
+    __builtin_amdgcn_s_waitcnt(0x4070);  // vmcnt(16) lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    CANZ_FENCE();
 #pragma unroll
     for (int idx = 0; idx < 16; ++idx) {
       mma_one(1, idx);
       CANZ_FENCE();
-      fetch_one(cP, cQ, k2, idx);
-      CANZ_FENCE();
       if (idx < 8) {
-        frag_one(nP, nQ, 0, 0, idx);
+        frag_one(nxt, 0, 0, idx);  // first operands of step kt+1
+        CANZ_FENCE();
+      }
+      if ((idx & 3) == 2) {
+        fetch_one(cur, k4, idx >> 2);  // P panel of step kt+4
         CANZ_FENCE();
       }
     }
   };
 
-  fetch(sP0, sQ0, 0);
+  fetch(st0, 0);
+  fetch(st1, 1);
+  fetch(st2, 2);
+  fetch(st3, 3);
   __syncthreads();
-  fetch(sP1, sQ1, 1);
-  load_frags(sP0, sQ0, 0, 0);
-  for (int kt = 0; kt < nk; kt += 2) {
-    k_step(sP0, sQ0, sP1, sQ1, kt);
-    k_step(sP1, sQ1, sP0, sQ0, kt + 1);
+#pragma unroll
+  for (int idx = 0; idx < 8; ++idx) frag_one(st0, 0, 0, idx);
+  for (int kt = 0; kt < nk; kt += 4) {
+    k_step(st0, st1, st3, kt);
+    k_step(st1, st2, st0, kt + 1);
+    k_step(st2, st3, st1, kt + 2);
+    k_step(st3, st0, st2, kt + 3);
   }
   __syncthreads();  // the clamped tail fetches have drained; LDS is free for the epilogue
 #undef CANZ_FENCE
@@ -244,7 +258,7 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
   // ---- epilogue.  Accumulator register r of lane l in MFMA tile (it, jt) is element
   //      row = 32 it + 8 (r / 4) + 4 (l / 32) + (r % 4),  col = 32 jt + (l % 32)
   //      of the wavefront's 128 x 128 part.  Each wavefront stages through its own 32 KiB.
-  __bf16* stage = wave == 0 ? sP0 : wave == 1 ? sQ0 : wave == 2 ? sP1 : sQ1;
+  __bf16* stage = wave == 0 ? st0 : wave == 1 ? st1 : wave == 2 ? st2 : st3;
   const int lj = lane & 31, lh = lane >> 5;
 
   // scale (first iteration: folded normalisation), or the polynomial in A for EPI_POLY
@@ -277,16 +291,16 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
         for (int r = 0; r < 16; ++r) acc[it][jt][r] *= sc;
   }
 
-  // the wavefront's part of an output tile in panel layout: two pieces of 16 KiB (the two
-  // 64-wide k-blocks it covers), 128 rows each; LDS image == memory image
+  // the wavefront's part of an output tile in panel layout: four pieces of 8 KiB (the four
+  // 32-wide k-blocks it covers), 128 rows each; LDS image == memory image
   auto flush_stage = [&](__bf16* out, int64_t row_block, int64_t kc, int64_t kblock0, int half_rows) {
     // out: matrix base; the wavefront's rows start at row_block * 256 + half_rows * 128
 #pragma unroll
-    for (int kb2 = 0; kb2 < 2; ++kb2) {
-      __bf16* dst = out + (row_block * (kc >> 6) + kblock0 + kb2) * PANEL_ELEMS + half_rows * 128 * PANEL_K;
+    for (int kb = 0; kb < 4; ++kb) {
+      __bf16* dst = out + (row_block * (kc >> 5) + kblock0 + kb) * PANEL_ELEMS + half_rows * 128 * PANEL_K;
 #pragma unroll
-      for (int x = 0; x < 16; ++x) {
-        const u32x4 v = *reinterpret_cast<const u32x4*>(stage + kb2 * 8192 + (x * 64 + lane) * 8);
+      for (int x = 0; x < 8; ++x) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(stage + kb * 4096 + (x * 64 + lane) * 8);
         *reinterpret_cast<u32x4*>(dst + (x * 64 + lane) * 8) = v;
       }
     }
@@ -298,13 +312,14 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
     // neighbouring lanes swap one value so that every lane writes two packed bf16.
     __bf16* C = static_cast<__bf16*>(e.c) + static_cast<int64_t>(b) * d.M * d.N;
     // Staging offset = (lane-only base) + (compile-time part), so that the compiler keeps two
-    // address registers instead of one per store.  With row_l = 32 it + 8 g + 2 p + 4 lh + odd
-    // (rp = 2 g + p) the swizzle term (row_l >> 1) & 7 is 4 (g & 1) | 2 lh | p, and the chunk
-    // 4 (jt & 1) + (lj >> 3); bit 2 of their XOR is compile-time, bits 0-1 are lane bits ^ p.
+    // address registers instead of one per store.  Element (row_l, col_l) of the wavefront's
+    // part, row_l = 32 it + 8 g + 2 p + 4 lh + odd (rp = 2 g + p), col_l = 32 jt + lj, lies in
+    // k-block jt at row_l * 32 + ((chunk ^ swizzle) << 3) with chunk = lj >> 3 and
+    // swizzle = (row_l >> 2) & 3 = 2 (g & 1) + lh: lane bits except for g & 1.
     int s_base[2];
 #pragma unroll
-    for (int p = 0; p < 2; ++p)
-      s_base[p] = (4 * lh + (lane & 1)) * 64 + ((((lj >> 3) ^ (2 * lh + p)) & 3) << 3) + (lj & 6);
+    for (int g1 = 0; g1 < 2; ++g1)
+      s_base[g1] = (4 * lh + (lane & 1)) * 32 + ((((lj >> 3) ^ (2 * g1 + lh)) & 3) << 3) + (lj & 6);
 #pragma unroll
     for (int it = 0; it < 4; ++it)
 #pragma unroll
@@ -317,20 +332,21 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
           pk[0] = static_cast<__bf16>((lane & 1) ? got : own0);
           pk[1] = static_cast<__bf16>((lane & 1) ? own1 : got);
           const int g = rp >> 1, p = rp & 1;
-          const int fixed = (jt >> 1) * 8192 + (it * 32 + 8 * g + 2 * p) * 64 + ((((jt & 1) ^ (g & 1)) << 2) << 3);
-          *reinterpret_cast<bf16x2*>(stage + fixed + s_base[p]) = pk;
+          const int fixed = jt * 4096 + (it * 32 + 8 * g + 2 * p) * 32;
+          *reinterpret_cast<bf16x2*>(stage + fixed + s_base[g & 1]) = pk;
         }
-    flush_stage(C, tm, d.N, 4 * tn + 2 * wn, wm);
+    flush_stage(C, tm, d.N, 8 * tn + 4 * wn, wm);
 
     // ---- transposed image: element (i, j) is (row j, k = i) of CT (UPDATE) or of the mirror
     // tile of C (symmetric products).  A lane's 4 consecutive rows are half a chunk.
     const bool mirror = (EPI == EPI_GRAM || EPI == EPI_POLY);
     if (!mirror || tm != tn) {
       __bf16* CT = mirror ? C : static_cast<__bf16*>(e.ct) + static_cast<int64_t>(b) * d.M * d.N;
-      // row_l = 32 jt + lj, chunk = 4 (it & 1) + g: one lane base per chunk value, rest immediate
-      int t_base[8];
+      // element (i_l, j_l) goes to row j_l = 32 jt + lj, k = i_l = 32 it + 8 g + 4 lh + q:
+      // k-block it, chunk g, swizzle (lj >> 2) & 3: one lane base per g, the rest immediate
+      int t_base[4];
 #pragma unroll
-      for (int c = 0; c < 8; ++c) t_base[c] = lj * 64 + ((c ^ ((lj >> 1) & 7)) << 3) + 4 * lh;
+      for (int g = 0; g < 4; ++g) t_base[g] = lj * 32 + ((g ^ ((lj >> 2) & 3)) << 3) + 4 * lh;
 #pragma unroll
       for (int it = 0; it < 4; ++it)
 #pragma unroll
@@ -340,9 +356,9 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
             bf16x4 pk;
 #pragma unroll
             for (int q = 0; q < 4; ++q) pk[q] = static_cast<__bf16>(acc[it][jt][4 * g + q]);
-            *reinterpret_cast<bf16x4*>(stage + (it >> 1) * 8192 + jt * 32 * 64 + t_base[4 * (it & 1) + g]) = pk;
+            *reinterpret_cast<bf16x4*>(stage + it * 4096 + jt * 32 * 32 + t_base[g]) = pk;
           }
-      flush_stage(CT, tn, d.M, 4 * tm + 2 * wm, wn);
+      flush_stage(CT, tn, d.M, 8 * tm + 4 * wm, wn);
     }
   } else {
     // ---- last product: O in the caller's orientation (the host orders the operands so).
