@@ -37,6 +37,7 @@
 // Symmetric products (Gram, polynomial) run only the tiles on or above the diagonal and
 // write the mirror image as well.  Extents are multiples of 256 (zero padded by the
 // producer), so only the final epilogue clips to the caller's shape.
+#include <algorithm>
 #include <type_traits>
 
 #include "device_util.h"
@@ -60,6 +61,10 @@ struct EpiArgs {
   const void* aux;         // POLY: A [nb][M][N] panels
   const float* scale;      // per-matrix factor applied to the accumulator, or nullptr
   float ca, cb, cc;        // POLY coefficients
+  // schedule of the persistent blocks (see launch()): full rounds of whole tiles, then the
+  // `left` remaining tiles, each cut into `splits` k-slices that different blocks compute
+  int full_rounds, left, splits, main_grid;
+  float* partial;          // [gridDim][256 regs][256 threads] fp32 accumulators of the k-slices
 };
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -77,47 +82,12 @@ __device__ __forceinline__ float lane_xor1(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));
 }
 
+// logical tile index -> (matrix b, tile row tm, tile column tn)
 template <int EPI>
-__global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __bf16* __restrict__ P,
-                                                            const __bf16* __restrict__ Q, EpiArgs e, Shape s,
-                                                            OutSpec o) {
-  // one array per stage (not one carved buffer): the compiler then knows that a fetch into
-  // one stage does not alias the operand reads of another and keeps them overlapped.
-  // Elements [0, 8192) hold the P panel, [8192, 16384) the Q panel.
-  constexpr int QOFF = BM * BK;
-  __shared__ __attribute__((aligned(1024))) __bf16 st0[(BM + BN) * BK];
-  __shared__ __attribute__((aligned(1024))) __bf16 st1[(BM + BN) * BK];
-  __shared__ __attribute__((aligned(1024))) __bf16 st2[(BM + BN) * BK];
-  __shared__ __attribute__((aligned(1024))) __bf16 st3[(BM + BN) * BK];
-
-  // ---- persistent blocks: the grid is one block per CU (or fewer); block `bid` works on the
-  //      logical tiles round * gridDim + slot(bid).  slot() makes the 32 blocks of one XCD
-  //      (blockIdx % 8 selects the XCD) neighbours, so that in every round they form a 4 x 8
-  //      patch of tiles of one matrix and share panels in that XCD's L2.
-  const int tiles_n = static_cast<int>(d.N / BN);
-  const int tiles_m = static_cast<int>(d.M / BM);
-  const int per_batch = (EPI == EPI_GRAM || EPI == EPI_POLY) ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
-  const int total_tiles = per_batch * d.nb;
-  int slot;
-  {
-    const int nblocks = gridDim.x, bid = blockIdx.x;
-    const int per = nblocks / N_XCD, rem = nblocks % N_XCD;
-    const int xcd = bid % N_XCD, q = bid / N_XCD;
-    slot = xcd < rem ? xcd * (per + 1) + q : rem * (per + 1) + (xcd - rem) * per + q;
-  }
-
-  const int t = threadIdx.x;
-  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
-
-  for (int logical = slot; logical < total_tiles; logical += gridDim.x) {
-  // The lane id is made opaque once per tile: otherwise every lane-dependent address of the
-  // loop body (hundreds of them) is hoisted out of the tile loop and kept alive in scratch.
-  int lane = t & 63;
-  asm volatile("" : "+v"(lane));
-  const int b = logical / per_batch;
+__device__ __forceinline__ void decode_tile(int logical, int tiles_m, int tiles_n, int per_batch, int& b, int& tm,
+                                            int& tn) {
+  b = logical / per_batch;
   const int tix = logical - b * per_batch;
-  int tm, tn;
   if (EPI == EPI_GRAM || EPI == EPI_POLY) {
     // symmetric output: only tiles with tn >= tm exist (per_batch = nt (nt + 1) / 2); the
     // epilogue writes each off-diagonal tile twice, straight and mirrored.  Raster: bands of
@@ -153,112 +123,18 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
     tm = band * GROUP_M + (in_band - tn * rows_here);
   }
 
-  // ---- global -> LDS: panel (tile row, k-step) is 16 KiB contiguous; wavefront w copies the
-  //      1 KiB pieces w, w+4, w+8, w+12 of both panels, lane l the 16 bytes at l * 16.
-  const int64_t nkb = d.K / BK;
-  const __bf16* pl = P + static_cast<int64_t>(b) * d.sp + static_cast<int64_t>(tm) * nkb * PANEL_ELEMS + wave * 512 + lane * 8;
-  const __bf16* ql = Q + static_cast<int64_t>(b) * d.sq + static_cast<int64_t>(tn) * nkb * PANEL_ELEMS + wave * 512 + lane * 8;
-  // one of the 8 direct loads of a stage: idx 0..3 -> P pieces, 4..7 -> Q pieces
-  auto fetch_one = [&](__bf16* st, int64_t kt, int idx) {
-    const int g = idx & 3;
-    if (idx < 4)
-      __builtin_amdgcn_global_load_lds(CANZ_GLB(pl + kt * PANEL_ELEMS + g * 2048), CANZ_LDS(st + wave * 512 + g * 2048), 16, 0, 0);
-    else
-      __builtin_amdgcn_global_load_lds(CANZ_GLB(ql + kt * PANEL_ELEMS + g * 2048), CANZ_LDS(st + QOFF + wave * 512 + g * 2048), 16, 0, 0);
-  };
-  auto fetch = [&](__bf16* st, int64_t kt) {
-#pragma unroll
-    for (int idx = 0; idx < 8; ++idx) fetch_one(st, kt, idx);
-  };
+}
 
-  f32x16 acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  // MFMA operand fragments, double-buffered in registers: idx 0..3 -> rows of P, 4..7 -> rows of Q
-  const int frag_row = lane & 31, frag_kg = lane >> 5;
-  bf16x8 fa[2][4], fb[2][4];
-  auto frag_one = [&](const __bf16* st, int kk, int set, int idx) {
-    if (idx < 4)
-      fa[set][idx] = *reinterpret_cast<const bf16x8*>(st + swz(wm * 128 + idx * 32 + frag_row, kk * 2 + frag_kg));
-    else
-      fb[set][idx - 4] =
-          *reinterpret_cast<const bf16x8*>(st + QOFF + swz(wn * 128 + (idx - 4) * 32 + frag_row, kk * 2 + frag_kg));
-  };
-  auto mma_one = [&](int set, int idx) {
-    const int i = idx >> 2, j = idx & 3;
-    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
-  };
-
-  const int nk = static_cast<int>(nkb);  // multiple of 8: K is a multiple of 256
-  // The issue order below is pinned with scheduling fences (left to itself the compiler
-  // clusters the loads and the matrix pipe drains meanwhile).
-#define CANZ_FENCE() __builtin_amdgcn_sched_barrier(0)
-  // One k-step on stage `cur`; `nxt` holds step kt+1, `prv` (free since the barrier of the
-  // previous step) receives the second half of step kt+3, `cur` after this step's barrier
-  // the first half of step kt+4.  Fetch indices are clamped instead of guarded (a branch
-  // here costs the compiler its knowledge of which stage is in flight, and the number of
-  // loads in flight must not depend on kt); the clamped refetches land in stages nobody
-  // reads any more.
-  auto k_step = [&](__bf16* cur, const __bf16* nxt, __bf16* prv, int kt) {
-    const int64_t k3 = min(kt + 3, nk - 1), k4 = min(kt + 4, nk - 1);
-#pragma unroll
-    for (int idx = 0; idx < 16; ++idx) {
-      mma_one(0, idx);
-      CANZ_FENCE();
-      if (idx < 8) {
-        frag_one(cur, 1, 1, idx);  // second half-step's operands, land under the next 8 MFMAs
-        CANZ_FENCE();
-      }
-      if ((idx & 3) == 2) {
-        fetch_one(prv, k3, 4 + (idx >> 2));  // Q panel of step kt+3
-        CANZ_FENCE();
-      }
-    }
-    // own share of step kt+1 has landed (16 younger loads may be in flight); this wavefront's
-    // reads of `cur` are complete.  simm16 = vmcnt[3:0] | expcnt 7 << 4 | lgkmcnt << 8 | vmcnt[5:4] << 14
-    __builtin_amdgcn_s_waitcnt(0x4070);  // vmcnt(16) lgkmcnt(0)
-    __builtin_amdgcn_s_barrier();
-    CANZ_FENCE();
-#pragma unroll
-    for (int idx = 0; idx < 16; ++idx) {
-      mma_one(1, idx);
-      CANZ_FENCE();
-      if (idx < 8) {
-        frag_one(nxt, 0, 0, idx);  // first operands of step kt+1
-        CANZ_FENCE();
-      }
-      if ((idx & 3) == 2) {
-        fetch_one(cur, k4, idx >> 2);  // P panel of step kt+4
-        CANZ_FENCE();
-      }
-    }
-  };
-
-  fetch(st0, 0);
-  fetch(st1, 1);
-  fetch(st2, 2);
-  fetch(st3, 3);
-  __syncthreads();
-#pragma unroll
-  for (int idx = 0; idx < 8; ++idx) frag_one(st0, 0, 0, idx);
-  for (int kt = 0; kt < nk; kt += 4) {
-    k_step(st0, st1, st3, kt);
-    k_step(st1, st2, st0, kt + 1);
-    k_step(st2, st3, st1, kt + 2);
-    k_step(st3, st0, st2, kt + 3);
-  }
-  __syncthreads();  // the clamped tail fetches have drained; LDS is free for the epilogue
-#undef CANZ_FENCE
-
+// Epilogue of one 256 x 256 tile held in the accumulators of the block's four wavefronts
+// (shared by the GEMM kernel and by the kernel that finishes k-split tiles).
+// `stage`: this wavefront's private 32 KiB of LDS.
+template <int EPI>
+__device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[4][4], __bf16* stage, int lane, int wm, int wn, int b,
+                                              int tm, int tn, const GemmDims& d, const EpiArgs& e, const Shape& s,
+                                              const OutSpec& o) {
   // ---- epilogue.  Accumulator register r of lane l in MFMA tile (it, jt) is element
   //      row = 32 it + 8 (r / 4) + 4 (l / 32) + (r % 4),  col = 32 jt + (l % 32)
   //      of the wavefront's 128 x 128 part.  Each wavefront stages through its own 32 KiB.
-  __bf16* stage = wave == 0 ? st0 : wave == 1 ? st1 : wave == 2 ? st2 : st3;
   const int lj = lane & 31, lh = lane >> 5;
 
   // scale (first iteration: folded normalisation), or the polynomial in A for EPI_POLY
@@ -467,11 +343,228 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
         }
     }
   }
+}
+
+template <int EPI, bool SPLIT>
+__global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __bf16* __restrict__ P,
+                                                            const __bf16* __restrict__ Q, EpiArgs e, Shape s,
+                                                            OutSpec o) {
+  // one array per stage (not one carved buffer): the compiler then knows that a fetch into
+  // one stage does not alias the operand reads of another and keeps them overlapped.
+  // Elements [0, 8192) hold the P panel, [8192, 16384) the Q panel.
+  constexpr int QOFF = BM * BK;
+  __shared__ __attribute__((aligned(1024))) __bf16 st0[(BM + BN) * BK];
+  __shared__ __attribute__((aligned(1024))) __bf16 st1[(BM + BN) * BK];
+  __shared__ __attribute__((aligned(1024))) __bf16 st2[(BM + BN) * BK];
+  __shared__ __attribute__((aligned(1024))) __bf16 st3[(BM + BN) * BK];
+
+  // ---- persistent blocks: the grid is one block per CU (or fewer); block `bid` works on the
+  //      logical tiles round * gridDim + slot(bid).  slot() makes the 32 blocks of one XCD
+  //      (blockIdx % 8 selects the XCD) neighbours, so that in every round they form a 4 x 8
+  //      patch of tiles of one matrix and share panels in that XCD's L2.
+  const int tiles_n = static_cast<int>(d.N / BN);
+  const int tiles_m = static_cast<int>(d.M / BM);
+  const int per_batch = (EPI == EPI_GRAM || EPI == EPI_POLY) ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
+  int slot;
+  {
+    const int nblocks = gridDim.x, bid = blockIdx.x;
+    const int per = nblocks / N_XCD, rem = nblocks % N_XCD;
+    const int xcd = bid % N_XCD, q = bid / N_XCD;
+    slot = xcd < rem ? xcd * (per + 1) + q : rem * (per + 1) + (xcd - rem) * per + q;
+  }
+
+  const int t = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+
+  const int nk_all = static_cast<int>(d.K / BK);  // multiple of 8: K is a multiple of 256
+  for (int work = 0;; ++work) {
+  // ---- what to do in this round: a whole tile, or one k-slice of a left-over tile.  When
+  //      the tiles do not fill the last round, each left-over tile is cut along k so that the
+  //      whole chip shares them (second launch); the slices' accumulators are parked in global
+  //      memory and k_split_finish adds them up and runs the epilogue.
+  // SPLIT = false: persistent blocks over whole tiles (the full rounds, plus the left-over
+  // tiles if they are not split).  SPLIT = true: a second launch in which every block
+  // computes one k-slice of one left-over tile and parks its accumulators.
+  int logical, k_begin = 0, nk = nk_all;
+  if (!SPLIT) {
+    const int rounds = e.full_rounds + (e.splits == 1 && slot < e.left ? 1 : 0);
+    if (work >= rounds) break;
+    logical = work * e.main_grid + slot;
+  } else {
+    if (work > 0) break;
+    const int l = slot / e.splits, sl = slot - l * e.splits;
+    logical = e.full_rounds * e.main_grid + l;
+    const int groups = nk_all / 4, base = groups / e.splits, extra = groups % e.splits;
+    k_begin = 4 * (sl * base + min(sl, extra));
+    nk = 4 * (base + (sl < extra ? 1 : 0));
+  }
+  // The lane id is made opaque once per tile: otherwise every lane-dependent address of the
+  // loop body (hundreds of them) is hoisted out of the tile loop and kept alive in scratch.
+  int lane = t & 63;
+  asm volatile("" : "+v"(lane));
+  int b, tm, tn;
+  decode_tile<EPI>(logical, tiles_m, tiles_n, per_batch, b, tm, tn);
+
+  // ---- global -> LDS: panel (tile row, k-step) is 16 KiB contiguous; wavefront w copies the
+  //      1 KiB pieces w, w+4, w+8, w+12 of both panels, lane l the 16 bytes at l * 16.
+  const int64_t nkb = d.K / BK;
+  const __bf16* pl = P + static_cast<int64_t>(b) * d.sp + (static_cast<int64_t>(tm) * nkb + k_begin) * PANEL_ELEMS + wave * 512 + lane * 8;
+  const __bf16* ql = Q + static_cast<int64_t>(b) * d.sq + (static_cast<int64_t>(tn) * nkb + k_begin) * PANEL_ELEMS + wave * 512 + lane * 8;
+  // one of the 8 direct loads of a stage: idx 0..3 -> P pieces, 4..7 -> Q pieces
+  auto fetch_one = [&](__bf16* st, int64_t kt, int idx) {
+    const int g = idx & 3;
+    if (idx < 4)
+      __builtin_amdgcn_global_load_lds(CANZ_GLB(pl + kt * PANEL_ELEMS + g * 2048), CANZ_LDS(st + wave * 512 + g * 2048), 16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds(CANZ_GLB(ql + kt * PANEL_ELEMS + g * 2048), CANZ_LDS(st + QOFF + wave * 512 + g * 2048), 16, 0, 0);
+  };
+  auto fetch = [&](__bf16* st, int64_t kt) {
+#pragma unroll
+    for (int idx = 0; idx < 8; ++idx) fetch_one(st, kt, idx);
+  };
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // MFMA operand fragments, double-buffered in registers: idx 0..3 -> rows of P, 4..7 -> rows of Q
+  const int frag_row = lane & 31, frag_kg = lane >> 5;
+  bf16x8 fa[2][4], fb[2][4];
+  auto frag_one = [&](const __bf16* st, int kk, int set, int idx) {
+    if (idx < 4)
+      fa[set][idx] = *reinterpret_cast<const bf16x8*>(st + swz(wm * 128 + idx * 32 + frag_row, kk * 2 + frag_kg));
+    else
+      fb[set][idx - 4] =
+          *reinterpret_cast<const bf16x8*>(st + QOFF + swz(wn * 128 + (idx - 4) * 32 + frag_row, kk * 2 + frag_kg));
+  };
+  auto mma_one = [&](int set, int idx) {
+    const int i = idx >> 2, j = idx & 3;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+  };
+
+  // The issue order below is pinned with scheduling fences (left to itself the compiler
+  // clusters the loads and the matrix pipe drains meanwhile).
+#define CANZ_FENCE() __builtin_amdgcn_sched_barrier(0)
+  // One k-step on stage `cur`; `nxt` holds step kt+1, `prv` (free since the barrier of the
+  // previous step) receives the second half of step kt+3, `cur` after this step's barrier
+  // the first half of step kt+4.  Fetch indices are clamped instead of guarded (a branch
+  // here costs the compiler its knowledge of which stage is in flight, and the number of
+  // loads in flight must not depend on kt); the clamped refetches land in stages nobody
+  // reads any more.
+  auto k_step = [&](__bf16* cur, const __bf16* nxt, __bf16* prv, int kt) {
+    const int64_t k3 = min(kt + 3, nk - 1), k4 = min(kt + 4, nk - 1);
+#pragma unroll
+    for (int idx = 0; idx < 16; ++idx) {
+      mma_one(0, idx);
+      CANZ_FENCE();
+      if (idx < 8) {
+        frag_one(cur, 1, 1, idx);  // second half-step's operands, land under the next 8 MFMAs
+        CANZ_FENCE();
+      }
+      if ((idx & 3) == 2) {
+        fetch_one(prv, k3, 4 + (idx >> 2));  // Q panel of step kt+3
+        CANZ_FENCE();
+      }
+    }
+    // own share of step kt+1 has landed (16 younger loads may be in flight); this wavefront's
+    // reads of `cur` are complete.  simm16 = vmcnt[3:0] | expcnt 7 << 4 | lgkmcnt << 8 | vmcnt[5:4] << 14
+    __builtin_amdgcn_s_waitcnt(0x4070);  // vmcnt(16) lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    CANZ_FENCE();
+#pragma unroll
+    for (int idx = 0; idx < 16; ++idx) {
+      mma_one(1, idx);
+      CANZ_FENCE();
+      if (idx < 8) {
+        frag_one(nxt, 0, 0, idx);  // first operands of step kt+1
+        CANZ_FENCE();
+      }
+      if ((idx & 3) == 2) {
+        fetch_one(cur, k4, idx >> 2);  // P panel of step kt+4
+        CANZ_FENCE();
+      }
+    }
+  };
+
+  fetch(st0, 0);
+  fetch(st1, 1);
+  fetch(st2, 2);
+  fetch(st3, 3);
+  __syncthreads();
+#pragma unroll
+  for (int idx = 0; idx < 8; ++idx) frag_one(st0, 0, 0, idx);
+  for (int kt = 0; kt < nk; kt += 4) {
+    k_step(st0, st1, st3, kt);
+    k_step(st1, st2, st0, kt + 1);
+    k_step(st2, st3, st1, kt + 2);
+    k_step(st3, st0, st2, kt + 3);
+  }
+  __syncthreads();  // the clamped tail fetches have drained; LDS is free for the epilogue
+#undef CANZ_FENCE
+
+  if (SPLIT) {
+    // k-slice: park the accumulators (register r of thread t at [r][t]: coalesced stores);
+    // k_split_finish adds the slices of each tile up and runs its epilogue.
+    float* mine = e.partial + static_cast<int64_t>(slot) * (256 * NTHREADS) + t;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mine[((i * 4 + j) * 16 + r) * NTHREADS] = acc[i][j][r];
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    break;
+  }
+
+  {
+    __bf16* stage = wave == 0 ? st0 : wave == 1 ? st1 : wave == 2 ? st2 : st3;
+    tile_epilogue<EPI>(acc, stage, lane, wm, wn, b, tm, tn, d, e, s, o);
+  }
+
   // the next tile's loads overwrite every wavefront's staging area: wait for all of them.
   // The global stores issued above keep draining while the next tile is multiplied.
   __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0) only
   __builtin_amdgcn_s_barrier();
-  }  // persistent tile loop
+  }  // persistent work loop
+}
+
+// Finishes the tiles whose k range was split: one block per tile adds the parked slices
+// (always in slice order, so the sum does not depend on timing) and runs the epilogue.
+template <int EPI>
+__global__ __launch_bounds__(NTHREADS) void k_split_finish(GemmDims d, EpiArgs e, Shape s, OutSpec o) {
+  __shared__ __attribute__((aligned(1024))) __bf16 stg[4][(BM + BN) * BK];
+  const int tiles_n = static_cast<int>(d.N / BN);
+  const int tiles_m = static_cast<int>(d.M / BM);
+  const int per_batch = (EPI == EPI_GRAM || EPI == EPI_POLY) ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
+  const int l = blockIdx.x;
+  int b, tm, tn;
+  decode_tile<EPI>(e.full_rounds * e.main_grid + l, tiles_m, tiles_n, per_batch, b, tm, tn);
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const float* first = e.partial + static_cast<int64_t>(l) * e.splits * (256 * NTHREADS) + t;
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      f32x16 sum;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum[r] = 0.f;
+      for (int sl = 0; sl < e.splits; ++sl) {
+        const float* p = first + static_cast<int64_t>(sl) * (256 * NTHREADS) + (i * 4 + j) * 16 * NTHREADS;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum[r] += p[r * NTHREADS];
+      }
+      acc[i][j] = sum;
+    }
+  tile_epilogue<EPI>(acc, stg[wave], lane, wave >> 1, wave & 1, b, tm, tn, d, e, s, o);
 }
 
 int cu_count() {
@@ -487,48 +580,73 @@ int cu_count() {
 }
 
 template <int EPI>
-hipError_t launch(const GemmDims& d, const void* P, const void* Q, const EpiArgs& e, const Shape& s, const OutSpec& o,
-                  hipStream_t st) {
+hipError_t launch(const GemmDims& d, const void* P, const void* Q, EpiArgs e, const SplitWs& w, const Shape& s,
+                  const OutSpec& o, hipStream_t st) {
   const int64_t tm = d.M / BM, tn = d.N / BN;
   const int64_t tiles = ((EPI == EPI_GRAM || EPI == EPI_POLY) ? tm * (tm + 1) / 2 : tm * tn) * d.nb;
-  const int64_t blocks = tiles < cu_count() ? tiles : cu_count();
-  hipLaunchKernelGGL((k_gemm_nt_bf16<EPI>), dim3(static_cast<unsigned>(blocks)), dim3(NTHREADS), 0, st, d,
-                     static_cast<const __bf16*>(P), static_cast<const __bf16*>(Q), e, s, o);
+  const int64_t cus = cu_count();
+  // full rounds of one tile per block, then the left-over tiles cut into k-slices (each at
+  // least 8 k-steps long) so that they occupy as many blocks as fit
+  e.full_rounds = static_cast<int>(tiles / cus);
+  e.left = static_cast<int>(tiles % cus);
+  e.splits = 1;
+  if (e.left > 0 && w.partial) {
+    const int64_t by_blocks = std::min<int64_t>(cus, w.max_blocks) / e.left;
+    const int64_t by_k = (d.K / BK) / 8;
+    const int64_t sp = std::max<int64_t>(1, std::min<int64_t>({by_blocks, by_k, 8}));
+    // Splitting costs two more launches plus parking and re-reading the accumulators, about
+    // 0.2 ms all told; a k-step takes about 0.65 us.  Split only where the part of a tile
+    // time it saves, (1 - 1/sp) * k-steps, is clearly longer than that.
+    if (sp > 1 && (d.K / BK) * (sp - 1) / sp >= 400) e.splits = static_cast<int>(sp);
+  }
+  e.partial = w.partial;
+  // whole tiles: one persistent block per CU (fewer if there are fewer tiles)
+  const int64_t whole = e.splits > 1 ? e.full_rounds * cus : tiles;
+  e.main_grid = static_cast<int>(std::min<int64_t>(cus, std::max<int64_t>(whole, 1)));
+  if (whole > 0)
+    hipLaunchKernelGGL((k_gemm_nt_bf16<EPI, false>), dim3(static_cast<unsigned>(e.main_grid)), dim3(NTHREADS), 0, st, d,
+                       static_cast<const __bf16*>(P), static_cast<const __bf16*>(Q), e, s, o);
+  if (e.splits > 1) {
+    hipLaunchKernelGGL((k_gemm_nt_bf16<EPI, true>), dim3(static_cast<unsigned>(e.left * e.splits)), dim3(NTHREADS), 0,
+                       st, d, static_cast<const __bf16*>(P), static_cast<const __bf16*>(Q), e, s, o);
+    hipLaunchKernelGGL((k_split_finish<EPI>), dim3(static_cast<unsigned>(e.left)), dim3(NTHREADS), 0, st, d, e, s, o);
+  }
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_gram_bf16(const GemmDims& d, const void* xw, void* a_out, const float* scale2, hipStream_t st) {
+hipError_t launch_gram_bf16(const GemmDims& d, const void* xw, void* a_out, const float* scale2, const SplitWs& w,
+                            hipStream_t st) {
   EpiArgs e{};
   e.c = a_out;
   e.scale = scale2;
-  return launch<EPI_GRAM>(d, xw, xw, e, Shape{}, OutSpec{}, st);
+  return launch<EPI_GRAM>(d, xw, xw, e, w, Shape{}, OutSpec{}, st);
 }
 
 hipError_t launch_poly_bf16(const GemmDims& d, const void* a_in, void* b_out, float ca, float cb, float cc,
-                            hipStream_t st) {
+                            const SplitWs& w, hipStream_t st) {
   EpiArgs e{};
   e.c = b_out;
   e.aux = a_in;
   e.ca = ca, e.cb = cb, e.cc = cc;
-  return launch<EPI_POLY>(d, a_in, a_in, e, Shape{}, OutSpec{}, st);
+  return launch<EPI_POLY>(d, a_in, a_in, e, w, Shape{}, OutSpec{}, st);
 }
 
 hipError_t launch_update_bf16(const GemmDims& d, const void* b_in, const void* xt_in, void* xw_out, void* xt_out,
-                              const float* scale, hipStream_t st) {
+                              const float* scale, const SplitWs& w, hipStream_t st) {
   EpiArgs e{};
   e.c = xw_out;
   e.ct = xt_out;
   e.scale = scale;
-  return launch<EPI_UPDATE>(d, b_in, xt_in, e, Shape{}, OutSpec{}, st);
+  return launch<EPI_UPDATE>(d, b_in, xt_in, e, w, Shape{}, OutSpec{}, st);
 }
 
-hipError_t launch_final_bf16(const GemmDims& d, const void* p, const void* q, const float* scale, const Shape& s,
-                             const OutSpec& o, hipStream_t st) {
+hipError_t launch_final_bf16(const GemmDims& d, const void* p, const void* q, const float* scale, const SplitWs& w,
+                             const Shape& s, const OutSpec& o, hipStream_t st) {
   EpiArgs e{};
   e.scale = scale;
-  return launch<EPI_FINAL>(d, p, q, e, s, o, st);
+  return launch<EPI_FINAL>(d, p, q, e, w, s, o, st);
 }
 
 }  // namespace canz

@@ -44,9 +44,10 @@ hipError_t launch_momentum(const Shape& s, int nb, const PtrTable& grad, int gra
                            float* partial, hipStream_t st);
 int momentum_tiles(const Shape& s);  // partial sums per matrix
 
-// scale[b] = 1 / (sqrt(sum partial[b][*]) + eps), scale2[b] = scale[b]^2
+// scale[b] = 1 / (sqrt(sum partial[b][*]) + eps), scale2[b] = scale[b]^2; also zeroes the
+// n_counters arrival counters used by the GEMMs' k-split
 hipError_t launch_norm_scale(int nb, int n_partial, const float* partial, float eps, float* scale,
-                             float* scale2, hipStream_t st);
+                             float* scale2, int* counters, int n_counters, hipStream_t st);
 
 struct OutSpec {
   PtrTable out;
@@ -68,18 +69,28 @@ struct GemmDims {
   int64_t sp, sq;           // batch strides
   int nb;
 };
+// Scratch for the k-split of left-over tiles: fp32 accumulators of up to max_blocks blocks
+// (256 KiB each) and one arrival counter per left-over tile (zero between launches).
+struct SplitWs {
+  float* partial;
+  int* counter;
+  int max_blocks;
+};
+constexpr int SPLIT_MAX_BLOCKS = 256;                       // CU count of MI355X; fewer blocks split on a smaller part
+constexpr size_t SPLIT_BLOCK_BYTES = 256 * 256 * sizeof(float);
 // A = scale2[b] * X X^T                      (P = Q = XW)
-hipError_t launch_gram_bf16(const GemmDims& d, const void* xw, void* a_out, const float* scale2, hipStream_t st);
+hipError_t launch_gram_bf16(const GemmDims& d, const void* xw, void* a_out, const float* scale2, const SplitWs& w,
+                            hipStream_t st);
 // B = ca I + cb A + cc A A                   (P = Q = A, symmetric)
 hipError_t launch_poly_bf16(const GemmDims& d, const void* a_in, void* b_out, float ca, float cb, float cc,
-                            hipStream_t st);
+                            const SplitWs& w, hipStream_t st);
 // X' = scale[b] * B X: XW' [mp][np] straight and XT' [np][mp] transposed  (P = B, Q = XT)
 hipError_t launch_update_bf16(const GemmDims& d, const void* b_in, const void* xt_in, void* xw_out, void* xt_out,
-                              const float* scale, hipStream_t st);
+                              const float* scale, const SplitWs& w, hipStream_t st);
 // last step: O = scale[b] * P Q^T goes straight into the caller's buffers; the caller of
 // this launcher orders the operands so that C is in the matrix's own orientation:
 // wide matrix: P = B, Q = XT (C = B X);  tall matrix: P = XT, Q = B (C = X^T B = (B X)^T)
-hipError_t launch_final_bf16(const GemmDims& d, const void* p, const void* q, const float* scale,
+hipError_t launch_final_bf16(const GemmDims& d, const void* p, const void* q, const float* scale, const SplitWs& w,
                              const Shape& s, const OutSpec& o, hipStream_t st);
 
 // ---- fp32 verification GEMMs (same contracts, float storage) ----------------------

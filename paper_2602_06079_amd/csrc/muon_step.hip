@@ -24,7 +24,7 @@ inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 inline int64_t pad_up(int64_t x) { return (x + PAD - 1) / PAD * PAD; }
 
 struct Carve {
-  size_t xw, xt0, xt1, a, b, partial, scale, scale2, total;
+  size_t xw, xt0, xt1, a, b, partial, scale, scale2, split_partial, split_counter, total;
 };
 
 Shape make_shape(const canz_group& g) {
@@ -52,6 +52,9 @@ Carve carve(const Shape& s, int nb, int precision) {
   c.partial = off, off += align_up(static_cast<size_t>(nb) * momentum_tiles(s) * sizeof(float));
   c.scale = off, off += align_up(nb * sizeof(float));
   c.scale2 = off, off += align_up(nb * sizeof(float));
+  c.split_counter = off, off += align_up(SPLIT_MAX_BLOCKS * sizeof(int));
+  c.split_partial = off;
+  if (precision == CANZ_PREC_BF16) off += align_up(SPLIT_MAX_BLOCKS * SPLIT_BLOCK_BYTES);
   c.total = off;
   return c;
 }
@@ -140,6 +143,8 @@ int run_batch(const canz_group& g, int first, int nb, const canz_muon_hparams& h
   float* partial = reinterpret_cast<float*>(ws + c.partial);
   float* scale = reinterpret_cast<float*>(ws + c.scale);
   float* scale2 = reinterpret_cast<float*>(ws + c.scale2);
+  int* counters = reinterpret_cast<int*>(ws + c.split_counter);
+  const SplitWs split{reinterpret_cast<float*>(ws + c.split_partial), counters, SPLIT_MAX_BLOCKS};
   constexpr bool is_bf16 = sizeof(T) == 2;
 
   PtrTable grad{}, mom{};
@@ -157,7 +162,7 @@ int run_batch(const canz_group& g, int first, int nb, const canz_muon_hparams& h
 
   CANZ_HIP(CANZ_KERNEL_MOMENTUM, launch_momentum<T>(s, nb, grad, g.grad_dtype, mom, hp.beta, hp.nesterov, xw, xt[0], partial, st),
            "momentum kernel");
-  CANZ_HIP(CANZ_KERNEL_NORM, launch_norm_scale(nb, momentum_tiles(s), partial, hp.eps, scale, scale2, st), "norm kernel");
+  CANZ_HIP(CANZ_KERNEL_NORM, launch_norm_scale(nb, momentum_tiles(s), partial, hp.eps, scale, scale2, counters, SPLIT_MAX_BLOCKS, st), "norm kernel");
 
   if (hp.ns_steps == 0) {
     const T* straight = s.tall ? xt[0] : xw;
@@ -177,12 +182,12 @@ int run_batch(const canz_group& g, int first, int nb, const canz_muon_hparams& h
     const float* sc2 = it == 0 ? scale2 : nullptr;
     const bool last = it + 1 == hp.ns_steps;
     if (is_bf16) {
-      CANZ_HIP(CANZ_KERNEL_GRAM, launch_gram_bf16(gram, xw, a, sc2, st), "gram kernel");
-      CANZ_HIP(CANZ_KERNEL_POLY, launch_poly_bf16(poly, a, bm, hp.a, hp.b, hp.c, st), "poly kernel");
+      CANZ_HIP(CANZ_KERNEL_GRAM, launch_gram_bf16(gram, xw, a, sc2, split, st), "gram kernel");
+      CANZ_HIP(CANZ_KERNEL_POLY, launch_poly_bf16(poly, a, bm, hp.a, hp.b, hp.c, split, st), "poly kernel");
       if (!last)
-        CANZ_HIP(CANZ_KERNEL_UPDATE, launch_update_bf16(upd, bm, xt[cur], xw, xt[cur ^ 1], sc1, st), "update kernel");
+        CANZ_HIP(CANZ_KERNEL_UPDATE, launch_update_bf16(upd, bm, xt[cur], xw, xt[cur ^ 1], sc1, split, st), "update kernel");
       else
-        CANZ_HIP(CANZ_KERNEL_FINAL, launch_final_bf16(fin, s.tall ? (const void*)xt[cur] : (const void*)bm, s.tall ? (const void*)bm : (const void*)xt[cur], sc1, s, o, st), "final kernel");
+        CANZ_HIP(CANZ_KERNEL_FINAL, launch_final_bf16(fin, s.tall ? (const void*)xt[cur] : (const void*)bm, s.tall ? (const void*)bm : (const void*)xt[cur], sc1, split, s, o, st), "final kernel");
     } else {
       CANZ_HIP(CANZ_KERNEL_GRAM, launch_gram_f32(gram, xw, a, sc2, st), "gram kernel");
       CANZ_HIP(CANZ_KERNEL_POLY, launch_poly_f32(poly, a, bm, hp.a, hp.b, hp.c, st), "poly kernel");
