@@ -131,9 +131,36 @@ inline void prof_mark(hipStream_t st, int kind, bool begin) {
     if (err__ != hipSuccess) return fail(CANZ_EHIP, "%s: %s", what, hipGetErrorString(err__)); \
   } while (0)
 
-// One sub-batch (<= MAX_BATCH matrices of one group).
+// Launch batches: consecutive matrices of the call that share shape and dtypes are batched
+// together, up to MAX_BATCH per launch, across micro-group boundaries (a matrix's result
+// does not depend on its batch, and small matrices need the larger batch to fill the chip).
+bool same_kind(const canz_group& a, const canz_group& b) {
+  return a.rows == b.rows && a.cols == b.cols && a.tp == b.tp && a.grad_dtype == b.grad_dtype &&
+         a.out_dtype == b.out_dtype;
+}
+
+// calls fn(proto group, first group index, first matrix in it, count) for every launch batch
+template <typename F>
+int for_each_batch(const canz_group* g, int n_groups, F&& fn) {
+  int proto = -1, count = 0, start_group = 0, start_mat = 0;
+  for (int i = 0; i < n_groups; ++i) {
+    for (int m = 0; m < g[i].n_mats; ++m) {
+      if (count > 0 && (count == MAX_BATCH || !same_kind(g[proto], g[i]))) {
+        if (int rc = fn(g[proto], start_group, start_mat, count)) return rc;
+        count = 0;
+      }
+      if (count == 0) proto = i, start_group = i, start_mat = m;
+      ++count;
+    }
+  }
+  if (count > 0) return fn(g[proto], start_group, start_mat, count);
+  return CANZ_OK;
+}
+
+// One launch batch (<= MAX_BATCH same-kind matrices).
 template <typename T>
-int run_batch(const canz_group& g, int first, int nb, const canz_muon_hparams& hp, char* ws, hipStream_t st) {
+int run_batch(const canz_group& g, const void* const* g_grad, void* const* g_mom, void* const* g_out, int nb,
+              const canz_muon_hparams& hp, char* ws, hipStream_t st) {
   const Shape s = make_shape(g);
   const Carve c = carve(s, nb, hp.precision);
   T* xw = reinterpret_cast<T*>(ws + c.xw);
@@ -149,12 +176,10 @@ int run_batch(const canz_group& g, int first, int nb, const canz_muon_hparams& h
 
   PtrTable grad{}, mom{};
   OutSpec o{};
-  for (int i = 0; i < nb * g.tp; ++i) grad.p[i] = const_cast<void*>(g.grad[first * g.tp + i]);
-  for (int i = 0; i < nb; ++i) mom.p[i] = g.mom[first + i];
-  if (hp.out_mode == CANZ_OUT_DELTA)
-    for (int i = 0; i < nb * g.tp; ++i) o.out.p[i] = g.out[first * g.tp + i];
-  else
-    for (int i = 0; i < nb; ++i) o.out.p[i] = g.out[first + i];
+  const int n_out = hp.out_mode == CANZ_OUT_DELTA ? nb * g.tp : nb;
+  for (int i = 0; i < nb * g.tp; ++i) grad.p[i] = const_cast<void*>(g_grad[i]);
+  for (int i = 0; i < nb; ++i) mom.p[i] = g_mom[i];
+  for (int i = 0; i < n_out; ++i) o.out.p[i] = g_out[i];
   o.out_dtype = g.out_dtype;
   o.out_mode = hp.out_mode;
   o.decay = static_cast<float>(1.0 - static_cast<double>(hp.lr) * static_cast<double>(hp.weight_decay));
@@ -211,12 +236,12 @@ extern "C" int canz_muon_workspace_bytes(const canz_group* g, int32_t n_groups, 
   if (n_groups < 0 || (n_groups > 0 && !g)) return fail(CANZ_EINVAL, "bad group array");
   if (int rc = check_hparams(hp)) return rc;
   size_t need = ALIGN;
-  for (int i = 0; i < n_groups; ++i) {
+  for (int i = 0; i < n_groups; ++i)
     if (int rc = check_group(g[i], i, false, hp->out_mode)) return rc;
-    if (g[i].n_mats == 0) continue;
-    const int nb = std::min<int>(g[i].n_mats, MAX_BATCH);
-    need = std::max(need, carve(make_shape(g[i]), nb, hp->precision).total);
-  }
+  for_each_batch(g, n_groups, [&](const canz_group& proto, int, int, int count) {
+    need = std::max(need, carve(make_shape(proto), count, hp->precision).total);
+    return CANZ_OK;
+  });
   *bytes_out = need;
   return CANZ_OK;
 }
@@ -240,15 +265,25 @@ extern "C" int canz_muon_step(const canz_group* g, int32_t n_groups, const canz_
 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
-  for (int i = 0; i < n_groups; ++i) {
-    for (int first = 0; first < g[i].n_mats; first += MAX_BATCH) {
-      const int nb = std::min<int>(MAX_BATCH, g[i].n_mats - first);
-      const int rc = hp->precision == CANZ_PREC_BF16 ? run_batch<__bf16>(g[i], first, nb, *hp, ws, st)
-                                                     : run_batch<float>(g[i], first, nb, *hp, ws, st);
-      if (rc) return rc;
+  std::vector<const void*> grad;
+  std::vector<void*> mom, out;
+  return for_each_batch(g, n_groups, [&](const canz_group& proto, int gi, int mi, int count) {
+    // gather the batch's pointers (it may continue into the following groups)
+    grad.clear(), mom.clear(), out.clear();
+    const int per_out = hp->out_mode == CANZ_OUT_DELTA ? proto.tp : 1;
+    for (int left = count; left > 0; ++gi, mi = 0) {
+      const int take = std::min(left, g[gi].n_mats - mi);
+      for (int m = mi; m < mi + take; ++m) {
+        for (int f = 0; f < proto.tp; ++f) grad.push_back(g[gi].grad[m * proto.tp + f]);
+        mom.push_back(g[gi].mom[m]);
+        for (int f = 0; f < per_out; ++f) out.push_back(g[gi].out[m * per_out + f]);
+      }
+      left -= take;
     }
-  }
-  return CANZ_OK;
+    return hp->precision == CANZ_PREC_BF16
+               ? run_batch<__bf16>(proto, grad.data(), mom.data(), out.data(), count, *hp, ws, st)
+               : run_batch<float>(proto, grad.data(), mom.data(), out.data(), count, *hp, ws, st);
+  });
 }
 
 extern "C" int canz_profile_enable(int32_t max_launches) {
