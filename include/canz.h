@@ -108,6 +108,33 @@ int canz_microgroup_plan(int64_t n_mats, const int64_t* rows, const int64_t* col
                          int64_t* n_groups_out, int64_t* group_off_out, int64_t* member_out);
 
 /*
+ * canz_tp_schedule - micro-group construction with greedy rollback for tensor-parallel
+ * fragments (Algorithm 2, Sec. 4.2; Algorithms 3 and 4 in App. C): which tensors are fused
+ * into one gather/scatter round and which host rank computes each of them.
+ *
+ * Tensors are taken in LPT order (cost descending, equal costs by ascending id).  A group
+ * grows one tensor at a time; after each addition it is scheduled onto the n_ranks host
+ * ranks with the LPT rule on a min-heap of (load, rank) pairs (smallest load first, lower
+ * rank among equals); if the largest rank load would exceed cmax, the addition is rolled
+ * back, the group is final and the tensor opens the next group.
+ *
+ * Host pointers, caller-owned.
+ *   cost          [n_mats] W(p) >= 0 (the paper uses numel)
+ *   cmax          capacity C_max of one group, in cost units, per host rank
+ *   n_groups_out  number of groups G
+ *   group_off_out [n_mats+1] offsets into member_out / host_rank_out, G+1 entries written
+ *   member_out    [n_mats] tensor ids, group after group, in the order the solver assigns
+ *                 them (descending cost)
+ *   host_rank_out [n_mats] host rank of member_out[i]
+ *   group_load_out[n_mats] largest rank load L_max of each group, G entries written
+ * Errors: CANZ_EINVAL for null pointers, n_ranks < 1, negative cost or capacity;
+ * CANZ_ESHAPE if one tensor alone exceeds cmax (Algorithm 3's error case).
+ */
+int canz_tp_schedule(int64_t n_mats, const int64_t* cost, int32_t n_ranks, int64_t cmax,
+                     int64_t* n_groups_out, int64_t* group_off_out, int64_t* member_out,
+                     int32_t* host_rank_out, int64_t* group_load_out);
+
+/*
  * One micro-group for canz_muon_step: n_mats matrices of identical shape and dtypes.
  * Every matrix is rows x cols, row-major, dense.  With tp > 1 the gradient (and, with
  * CANZ_OUT_DELTA, the output) of each matrix is held as tp column fragments of shape

@@ -14,6 +14,8 @@ partition   Algorithm 1 (alpha-balanced greedy LPT partitioning, Sec. 3.2 and
 microgroup  Same-shape batching of one rank's matrices (the deterministic
             (cost, id) ordering of Algorithm 2, Phase 1, applied to shape
             classes, with a capacity cap in the spirit of C_max).
+tp_schedule TP micro-group construction with greedy rollback and the min-heap LPT solver
+            (Algorithm 2; Algorithms 3 and 4 in App. C).
 muon        The Muon operator named in Sec. 4.1 / App. B.3: momentum,
             Frobenius normalisation, k Newton-Schulz steps, scaled update;
             TP column-fragment gather/scatter of Sec. 4.1 stages (1) and (3).

@@ -25,7 +25,7 @@ SCALE_NONE, SCALE_ASPECT, SCALE_RMS = 0, 1, 2
 PREC_BF16, PREC_F32 = 0, 1
 OUT_PARAM, OUT_DELTA = 0, 1
 
-EXPORTS = ("canz_last_error", "canz_version", "canz_partition_alpha", "canz_microgroup_plan",
+EXPORTS = ("canz_last_error", "canz_version", "canz_partition_alpha", "canz_microgroup_plan", "canz_tp_schedule",
            "canz_muon_workspace_bytes", "canz_muon_step",
            "canz_profile_enable", "canz_profile_collect", "canz_profile_disable")
 KERNEL_KINDS = ("momentum", "norm", "gram", "poly", "update", "final", "apply")
@@ -71,6 +71,8 @@ def _load():
     lib.canz_microgroup_plan.argtypes = [C.c_int64, i64p, i64p, i32p, i32p, C.c_int32, C.c_int32, C.c_int64,
                                          i64p, i64p, i64p]
     lib.canz_microgroup_plan.restype = C.c_int
+    lib.canz_tp_schedule.argtypes = [C.c_int64, i64p, C.c_int32, C.c_int64, i64p, i64p, i64p, i32p, i64p]
+    lib.canz_tp_schedule.restype = C.c_int
     lib.canz_muon_workspace_bytes.argtypes = [C.POINTER(_Group), C.c_int32, C.POINTER(_Hparams),
                                               C.POINTER(C.c_size_t)]
     lib.canz_muon_workspace_bytes.restype = C.c_int
@@ -142,6 +144,22 @@ def canz_microgroup_plan(rows, cols, dtype, owner, rank, max_mats=8, cmax_bytes=
     _check(_lib.canz_microgroup_plan(n, _p64(rows), _p64(cols), _p32(dtype), _p32(owner), int(rank), int(max_mats),
                                      int(cmax_bytes), C.byref(n_groups), _p64(off), _p64(member)))
     return [[int(x) for x in member[off[i]:off[i + 1]]] for i in range(n_groups.value)]
+
+
+def canz_tp_schedule(cost, n_ranks, cmax):
+    """Algorithm 2/3/4.  Returns (groups, loads): groups is a list of lists of
+    (tensor id, host rank) in assignment order, loads the largest rank load of each group."""
+    cost = _i64(cost)
+    n = cost.shape[0]
+    n_groups = C.c_int64(0)
+    off = np.zeros(n + 1, dtype=np.int64)
+    member = np.zeros(max(n, 1), dtype=np.int64)
+    host = np.zeros(max(n, 1), dtype=np.int32)
+    load = np.zeros(max(n, 1), dtype=np.int64)
+    _check(_lib.canz_tp_schedule(n, _p64(cost), int(n_ranks), int(cmax), C.byref(n_groups), _p64(off), _p64(member),
+                                 _p32(host), _p64(load)))
+    groups = [[(int(member[i]), int(host[i])) for i in range(off[k], off[k + 1])] for k in range(n_groups.value)]
+    return groups, [int(x) for x in load[:n_groups.value]]
 
 
 @dataclass

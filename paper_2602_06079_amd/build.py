@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 OUT = os.path.join(HERE, "libcanz.so")
 
-HOST_SOURCES = ["error.cpp", "partition.cpp", "microgroup.cpp"]
+HOST_SOURCES = ["error.cpp", "partition.cpp", "microgroup.cpp", "tp_schedule.cpp"]
 HIP_SOURCES = ["muon_step.hip", "elementwise.hip", "gemm_bf16.hip", "gemm_f32.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

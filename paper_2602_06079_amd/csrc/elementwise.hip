@@ -47,58 +47,74 @@ __global__ __launch_bounds__(NTHREADS) void k_momentum(Shape s, PtrTable grad, i
   const int t = threadIdx.x;
   const int cv = (t & 7) * 8;
   float ss = 0.f;
+  // Phase 1: every load of both half-tiles is issued before the first store (the momentum
+  // store of one half must not hold back the loads of the other: the buffers come from
+  // pointer tables and may alias as far as the compiler knows).
+  float g[2][8], mo[2][8];
+  bool live[2];
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const int row = r0 + (t >> 3) + half * 32, col = c0 + cv;
+    live[half] = row < rows && col < cols;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) g[half][e] = 0.f, mo[half][e] = 0.f;
+    if (!live[half]) continue;
+    if (VEC) {
+      // cols and wfrag are multiples of 8 here: the vector lies in one fragment
+      const int f = col / wf;
+      const int64_t gi = static_cast<int64_t>(row) * wf + (col - f * wf);
+      if (grad_dtype == CANZ_DT_BF16) {
+        const bf16x8 gv = *reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(grad.p[b * s.tp + f]) + gi);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) g[half][e] = static_cast<float>(gv[e]);
+      } else {
+        const f32x4* gp = reinterpret_cast<const f32x4*>(static_cast<const float*>(grad.p[b * s.tp + f]) + gi);
+        const f32x4 g0 = gp[0], g1 = gp[1];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) g[half][e] = g0[e], g[half][4 + e] = g1[e];
+      }
+      const f32x4* mp4 = reinterpret_cast<const f32x4*>(mptr + static_cast<int64_t>(row) * cols + col);
+      const f32x4 m0 = mp4[0], m1 = mp4[1];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) mo[half][e] = m0[e], mo[half][4 + e] = m1[e];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int c = col + e;
+        if (c < cols) {
+          const int f = c / wf;
+          const int64_t gi = static_cast<int64_t>(row) * wf + (c - f * wf);
+          g[half][e] = grad_dtype == CANZ_DT_BF16
+                           ? static_cast<float>(static_cast<const __bf16*>(grad.p[b * s.tp + f])[gi])
+                           : static_cast<const float*>(grad.p[b * s.tp + f])[gi];
+          mo[half][e] = mptr[static_cast<int64_t>(row) * cols + c];
+        }
+      }
+    }
+  }
+  // Phase 2: momentum, stores, working copies
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
     const int rl = (t >> 3) + half * 32;
     const int row = r0 + rl, col = c0 + cv;
-    float u[8];
+    float u[8], mn[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) u[e] = 0.f;
-    if (row < rows && col < cols) {
-      float g[8], mo[8];
+    for (int e = 0; e < 8; ++e) {
+      mn[e] = beta * mo[half][e] + g[half][e];
+      u[e] = nesterov ? g[half][e] + beta * mn[e] : mn[e];
+    }
+    if (live[half]) {
       if (VEC) {
-        // cols and wfrag are multiples of 8 here: the vector lies in one fragment
-        const int f = col / wf;
-        const int64_t gi = static_cast<int64_t>(row) * wf + (col - f * wf);
-        if (grad_dtype == CANZ_DT_BF16) {
-          const bf16x8 gv = *reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(grad.p[b * s.tp + f]) + gi);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) g[e] = static_cast<float>(gv[e]);
-        } else {
-          const f32x4* gp = reinterpret_cast<const f32x4*>(static_cast<const float*>(grad.p[b * s.tp + f]) + gi);
-          const f32x4 g0 = gp[0], g1 = gp[1];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) g[e] = g0[e], g[4 + e] = g1[e];
-        }
-        f32x4* mp4 = reinterpret_cast<f32x4*>(mptr + static_cast<int64_t>(row) * cols + col);
-        const f32x4 m0 = mp4[0], m1 = mp4[1];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) mo[e] = m0[e], mo[4 + e] = m1[e];
         f32x4 n0, n1;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float mn = beta * mo[e] + g[e];
-          u[e] = nesterov ? g[e] + beta * mn : mn;
-          if (e < 4) n0[e] = mn; else n1[e - 4] = mn;
-        }
+        for (int e = 0; e < 4; ++e) n0[e] = mn[e], n1[e] = mn[4 + e];
+        f32x4* mp4 = reinterpret_cast<f32x4*>(mptr + static_cast<int64_t>(row) * cols + col);
         mp4[0] = n0;
         mp4[1] = n1;
       } else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int c = col + e;
-          if (c < cols) {
-            const int f = c / wf;
-            const int64_t gi = static_cast<int64_t>(row) * wf + (c - f * wf);
-            const float gg = grad_dtype == CANZ_DT_BF16
-                                 ? static_cast<float>(static_cast<const __bf16*>(grad.p[b * s.tp + f])[gi])
-                                 : static_cast<const float*>(grad.p[b * s.tp + f])[gi];
-            float* mq = mptr + static_cast<int64_t>(row) * cols + c;
-            const float mn = beta * (*mq) + gg;
-            *mq = mn;
-            u[e] = nesterov ? gg + beta * mn : mn;
-          }
-        }
+        for (int e = 0; e < 8; ++e)
+          if (col + e < cols) mptr[static_cast<int64_t>(row) * cols + col + e] = mn[e];
       }
     }
     Vec8<T> o;
