@@ -83,6 +83,21 @@ int canz_partition_alpha(int64_t n_mats, const int64_t* rows, const int64_t* col
                          int64_t* cut_out, int32_t* owner_out, int64_t* load_out);
 
 /*
+ * canz_partition_naive - the Atomic Ownership Rule (Sec. 3.1, Eq. 1): the static layout
+ * without load balancing, kept as the baseline Algorithm 1 is compared with.  Applied to
+ * every bucket on its own (each bucket is cut into R equal segments, App. B.1): with stride
+ * S = |B_i| / R, rank r owns parameter p iff r S <= Start_Index(p) < (r + 1) S, the start
+ * index taken inside the bucket; computed exactly as r = floor(Start_Index(p) * R / |B_i|).
+ * One bucket spanning everything gives the rule over the whole buffer.
+ *   numel [n_mats] elements per parameter, in buffer order; bucket_off [n_buckets+1] as in
+ *   canz_partition_alpha; owner_out [n_mats]; load_out [n_ranks] elements owned per rank.
+ * Host pointers, caller-owned.
+ * Errors: CANZ_EINVAL for null pointers, n_ranks < 1, negative sizes, malformed bucket_off.
+ */
+int canz_partition_naive(int64_t n_mats, const int64_t* numel, int64_t n_buckets, const int64_t* bucket_off,
+                         int32_t n_ranks, int32_t* owner_out, int64_t* load_out);
+
+/*
  * canz_microgroup_plan - group the matrices one rank owns into same-shape batches.
  *
  * The paper's micro-groups fuse tensors for one collective (Sec. 4, Algorithm 2); here a

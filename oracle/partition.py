@@ -214,13 +214,19 @@ def rank_loads(owner, values, n_ranks):
     return out
 
 
-def ownership_naive(numel, n_ranks):
-    """Atomic Ownership Rule (Eq. 1), 0-based: with stride S = |B|/R over the
-    whole flattened buffer, rank r owns p iff r*S <= Start_Index(p) < (r+1)*S.
-    Integer arithmetic: r = floor(start * R / |B|)."""
-    total = sum(int(x) for x in numel)
-    owner, start = [], 0
-    for x in numel:
-        owner.append(min(n_ranks - 1, (start * n_ranks) // total) if total > 0 else 0)
-        start += int(x)
+def ownership_naive(numel, n_ranks, bucket_off=None):
+    """Atomic Ownership Rule (Eq. 1), 0-based, applied to every bucket on its own (the
+    uniform partition rule of App. B.1 cuts each bucket into R equal segments): with stride
+    S = |B_i|/R, rank r owns p iff r*S <= Start_Index(p) < (r+1)*S, the start index taken
+    inside the bucket.  Integer arithmetic: r = floor(start * R / |B_i|).  Without
+    bucket_off the whole buffer is one bucket (the reading of Sec. 3.1's "total buffer")."""
+    if bucket_off is None:
+        bucket_off = [0, len(numel)]
+    owner = []
+    for lo, hi in zip(bucket_off[:-1], bucket_off[1:]):
+        total = sum(int(x) for x in numel[lo:hi])
+        start = 0
+        for x in numel[lo:hi]:
+            owner.append(min(n_ranks - 1, (start * n_ranks) // total) if total > 0 else 0)
+            start += int(x)
     return owner

@@ -25,7 +25,7 @@ SCALE_NONE, SCALE_ASPECT, SCALE_RMS = 0, 1, 2
 PREC_BF16, PREC_F32 = 0, 1
 OUT_PARAM, OUT_DELTA = 0, 1
 
-EXPORTS = ("canz_last_error", "canz_version", "canz_partition_alpha", "canz_microgroup_plan", "canz_tp_schedule",
+EXPORTS = ("canz_last_error", "canz_version", "canz_partition_alpha", "canz_partition_naive", "canz_microgroup_plan", "canz_tp_schedule",
            "canz_muon_workspace_bytes", "canz_muon_step",
            "canz_profile_enable", "canz_profile_collect", "canz_profile_disable")
 KERNEL_KINDS = ("momentum", "norm", "gram", "poly", "update", "final", "apply")
@@ -71,6 +71,8 @@ def _load():
     lib.canz_microgroup_plan.argtypes = [C.c_int64, i64p, i64p, i32p, i32p, C.c_int32, C.c_int32, C.c_int64,
                                          i64p, i64p, i64p]
     lib.canz_microgroup_plan.restype = C.c_int
+    lib.canz_partition_naive.argtypes = [C.c_int64, i64p, C.c_int64, i64p, C.c_int32, i32p, i64p]
+    lib.canz_partition_naive.restype = C.c_int
     lib.canz_tp_schedule.argtypes = [C.c_int64, i64p, C.c_int32, C.c_int64, i64p, i64p, i64p, i32p, i64p]
     lib.canz_tp_schedule.restype = C.c_int
     lib.canz_muon_workspace_bytes.argtypes = [C.POINTER(_Group), C.c_int32, C.POINTER(_Hparams),
@@ -132,6 +134,17 @@ def canz_partition_alpha(rows, cols, bucket_off, n_ranks, alpha, cost=None, cost
                                      int(cost_kind), n_buckets, _p64(bucket_off), int(n_ranks), float(alpha),
                                      _p64(cuts), _p32(owner), _p64(load)))
     return cuts, owner, load
+
+
+def canz_partition_naive(numel, n_ranks, bucket_off=None):
+    """Eq. 1 per bucket (atomic ownership without balancing).  Returns (owner, load)."""
+    numel = _i64(numel)
+    bucket_off = _i64([0, numel.shape[0]] if bucket_off is None else bucket_off)
+    owner = np.full(numel.shape[0], -1, dtype=np.int32)
+    load = np.zeros(max(int(n_ranks), 0), dtype=np.int64)
+    _check(_lib.canz_partition_naive(numel.shape[0], _p64(numel), bucket_off.shape[0] - 1, _p64(bucket_off),
+                                     int(n_ranks), _p32(owner), _p64(load)))
+    return owner, load
 
 
 def canz_microgroup_plan(rows, cols, dtype, owner, rank, max_mats=8, cmax_bytes=0) -> List[List[int]]:

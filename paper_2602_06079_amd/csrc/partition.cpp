@@ -114,3 +114,36 @@ extern "C" int canz_partition_alpha(int64_t n_mats, const int64_t* rows, const i
   for (int r = 0; r < R; ++r) load_out[r] = load[r];
   return CANZ_OK;
 }
+
+// canz_partition_naive: the Atomic Ownership Rule of Sec. 3.1 (Eq. 1) - the static layout
+// without load balancing that Algorithm 1 improves on - applied to every bucket on its own
+// (App. B.1: each bucket is cut into R equal segments).  With stride S = |B_i| / R, rank r
+// owns parameter p iff r S <= Start_Index(p) < (r + 1) S, the start taken inside the bucket.
+extern "C" int canz_partition_naive(int64_t n_mats, const int64_t* numel, int64_t n_buckets,
+                                    const int64_t* bucket_off, int32_t n_ranks, int32_t* owner_out,
+                                    int64_t* load_out) {
+  using canz::fail;
+  if (n_mats < 0 || n_buckets < 0) return fail(CANZ_EINVAL, "negative size");
+  if (!owner_out || !load_out || !bucket_off || (n_mats > 0 && !numel)) return fail(CANZ_EINVAL, "null pointer");
+  if (n_ranks < 1) return fail(CANZ_EINVAL, "n_ranks must be >= 1");
+  if (bucket_off[0] != 0 || bucket_off[n_buckets] != n_mats)
+    return fail(CANZ_EINVAL, "bucket_off must run from 0 to n_mats");
+  for (int64_t i = 0; i < n_buckets; ++i)
+    if (bucket_off[i + 1] < bucket_off[i]) return fail(CANZ_EINVAL, "bucket_off must be non-decreasing");
+  for (int64_t p = 0; p < n_mats; ++p)
+    if (numel[p] < 0) return fail(CANZ_EINVAL, "negative size at %lld", (long long)p);
+  for (int r = 0; r < n_ranks; ++r) load_out[r] = 0;
+  for (int64_t i = 0; i < n_buckets; ++i) {
+    __int128 total = 0, start = 0;
+    for (int64_t p = bucket_off[i]; p < bucket_off[i + 1]; ++p) total += numel[p];
+    for (int64_t p = bucket_off[i]; p < bucket_off[i + 1]; ++p) {
+      // r = floor(start * R / |B_i|), exact in integers
+      int64_t r = total > 0 ? static_cast<int64_t>(start * n_ranks / total) : 0;
+      r = std::min<int64_t>(r, n_ranks - 1);
+      owner_out[p] = static_cast<int32_t>(r);
+      load_out[r] += numel[p];
+      start += numel[p];
+    }
+  }
+  return CANZ_OK;
+}

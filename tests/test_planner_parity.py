@@ -105,3 +105,38 @@ def test_partition_errors(canz):
     assert code([2, 2], [2, 2], [0, 2], 2, 0.5, cost=[1, -1]) == canz.EINVAL
     assert code([2, 2], [2, 2], [0, 2], 2, 0.5, cost_kind=5) == canz.EUNSUPPORTED
     assert "cost_kind" in canz.canz_last_error()
+
+
+def test_partition_naive_matches_oracle_and_eq1(canz):
+    """Eq. 1 per bucket: rank r owns p iff r*S <= start(p) < (r+1)*S, S = |B_i|/R."""
+    from fractions import Fraction
+    rng = random.Random(5)
+    for _ in range(200):
+        nb, R = rng.randint(1, 4), rng.randint(1, 9)
+        numel, off = [], [0]
+        for _ in range(nb):
+            numel += [rng.choice([0, 1, 7, 1024, 4096 * 4096, 25600 * 5120]) for _ in range(rng.randint(0, 9))]
+            off.append(len(numel))
+        owner, load = canz.canz_partition_naive(numel, R, off)
+        assert owner.tolist() == OP.ownership_naive(numel, R, off)
+        assert load.tolist() == OP.rank_loads(owner.tolist(), numel, R)
+        for lo, hi in zip(off[:-1], off[1:]):
+            total, start = sum(numel[lo:hi]), 0
+            for p in range(lo, hi):
+                if total > 0 and owner[p] < R - 1:
+                    S = Fraction(total, R)
+                    assert owner[p] * S <= start < (owner[p] + 1) * S
+                start += numel[p]
+    # one bucket = the whole buffer
+    assert canz.canz_partition_naive([4, 2, 6], 3)[0].tolist() == [0, 1, 1]
+    with pytest.raises(canz.CanzError):
+        canz.canz_partition_naive([1, 2], 0)
+
+
+def test_balance_report_runs_and_alpha1_beats_naive(canz):
+    from paper_2602_06079_amd import balance_report
+    text = balance_report.report((2,))
+    rows = [l for l in text.splitlines() if l.startswith("| 2 ")]
+    naive = float([l for l in rows if "per bucket" in l][0].split("|")[3])
+    best = float([l for l in rows if "numel, alpha = 1.0" in l][0].split("|")[3])
+    assert best < naive and best < 1.05
