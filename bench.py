@@ -22,10 +22,62 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2516.6     # 256 CUs x 4096 FLOP/clk/CU x 2.4 GHz, dense
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch (read + written) of the GEMM kernels on the default workload, from the
+# two rocprofv3 --pmc runs summarised in profiles/hbm_traffic_config4.md (FETCH_SIZE scaled by
+# 2.000, WRITE_SIZE by 1.000, the factors a plain 1 GiB copy gives).  Counters cannot be read
+# from inside this process, so the figures are carried here; other workloads report null.
+MEASURED_TRAFFIC_BYTES = {(4, "bf16", 1): {"gram": 3.91e9 + 0.22e9, "poly": 1.00e9 + 0.21e9,
+                                           "update": 10.76e9 + 2.23e9, "final": 11.38e9 + 2.40e9}}
+
 
 def log(msg):
     sys.stderr.write("[bench] %s\n" % msg)
     sys.stderr.flush()
+
+
+class ClockSampler:
+    """Best-effort sampler of the current shader clock from the amdgpu sysfs file
+    pp_dpm_sclk (the line marked with '*'), read every few milliseconds on a host thread
+    while the timed steps run.  Reports None where the file is absent or unreadable."""
+
+    def __init__(self):
+        import glob
+        import threading
+        self.paths = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+        self.samples, self.stop = [], threading.Event()
+        self.thread = threading.Thread(target=self._run, daemon=True)
+
+    def _read(self):
+        best = None
+        for p in self.paths:
+            try:
+                for line in open(p).read().splitlines():
+                    if line.rstrip().endswith("*"):
+                        mhz = float(line.split(":")[1].lower().replace("mhz", "").replace("*", "").strip())
+                        best = mhz if best is None else max(best, mhz)
+            except (OSError, ValueError, IndexError):
+                pass
+        return best
+
+    def _run(self):
+        while not self.stop.is_set():
+            v = self._read()
+            if v is not None:
+                self.samples.append(v)
+            self.stop.wait(0.005)
+
+    def __enter__(self):
+        if self.paths:
+            self.thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self.stop.set()
+        if self.paths:
+            self.thread.join(timeout=1.0)
+
+    def mean_mhz(self):
+        return sum(self.samples) / len(self.samples) if self.samples else None
 
 
 def pick_share(canz, W, cfg):
@@ -144,13 +196,15 @@ def main():
     canz.canz_profile_enable(launches_per_step * args.steps + 8)
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
-    t_start = time.perf_counter()
-    ev[0].record()
-    for i in range(args.steps):
-        step()
-        ev[i + 1].record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t_start) * 1e3
+    clock = ClockSampler()
+    with clock:
+        t_start = time.perf_counter()
+        ev[0].record()
+        for i in range(args.steps):
+            step()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t_start) * 1e3
     prof = canz.canz_profile_collect()
     canz.canz_profile_disable()
     per_step = [ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]
@@ -197,8 +251,18 @@ def main():
     achieved = dom_flops_per_launch / (kernels[dom]["avg_ms"] * 1e-3) / 1e12
     achieved_issued = dom_issued_per_launch / (kernels[dom]["avg_ms"] * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if bf16 else 157.3
+    # the same peak from what the device reports, and at the shader clock sampled during the run
+    props = torch.cuda.get_device_properties(0)
+    cus, nominal_mhz = int(props.multi_processor_count), float(getattr(props, "clock_rate", 0)) / 1e3
+    flop_per_clk_cu = 4096.0 if bf16 else 256.0
+    seen_mhz = clock.mean_mhz()
+    device = dict(name=props.name, compute_units=cus, nominal_clock_mhz=nominal_mhz,
+                  peak_tflops_at_nominal_clock=cus * flop_per_clk_cu * nominal_mhz * 1e6 / 1e12,
+                  sampled_clock_mhz=seen_mhz, clock_samples=len(clock.samples),
+                  peak_tflops_at_sampled_clock=(cus * flop_per_clk_cu * seen_mhz * 1e6 / 1e12) if seen_mhz else None)
     roofline = dict(bound="mfma", kernel="k_gemm_nt_%s<%s>" % (args.precision, dom), achieved=achieved, peak=peak,
-                    unit="TFLOP/s", frac=achieved / peak, traffic=None,
+                    unit="TFLOP/s", frac=achieved / peak,
+                    traffic=MEASURED_TRAFFIC_BYTES.get((cfg, args.precision, tp), {}).get(dom), traffic_unit="B",
                     achieved_issued=achieved_issued, frac_issued=achieved_issued / peak,
                     flops_per_launch=dom_flops_per_launch, issued_flops_per_launch=dom_issued_per_launch,
                     avg_launch_ms=kernels[dom]["avg_ms"])
@@ -232,20 +296,22 @@ def main():
         t0 = time.perf_counter()
         OM.muon_step(g64, mom0, OM.Hparams(ns_steps=0, **base), param=mom0)
         t_ew = time.perf_counter() - t0
+        n_sample = min(3, hp.ns_steps)      # iterations timed: about 12 s on the default workload
         t0 = time.perf_counter()
-        OM.muon_step(g64, mom0, OM.Hparams(ns_steps=1, **base), param=mom0)
-        t_one = time.perf_counter() - t0
-        t_iter = max(t_one - t_ew, 0.0)
+        OM.muon_step(g64, mom0, OM.Hparams(ns_steps=n_sample, **base), param=mom0)
+        t_some = time.perf_counter() - t0
+        t_iter = max(t_some - t_ew, 0.0) / max(n_sample, 1)
         f0 = ns_flops(rows, cols, 1)
         est_s = 0.0
         for g in groups:
             r, c = s["rows"][g[0]], s["cols"][g[0]]
             est_s += len(g) * (t_ew * (r * c) / (rows * cols) + hp.ns_steps * t_iter * ns_flops(r, c, 1) / f0)
         cpu = dict(value=est_s * 1e3, unit="ms", cores=int(cores), kind="oracle",
-                   sample="fp64 oracle on matrix %d (%dx%d): elementwise part %.2f s + one of %d Newton-Schulz "
-                          "iterations %.2f s (%.0f GFLOP/s), scaled by FLOPs and elements to the %d-matrix share"
-                          % (g0[0], rows, cols, t_ew, hp.ns_steps, t_iter, f0 / max(t_iter, 1e-9) / 1e9, n_share))
-        log("oracle sample: %.2f s measured, share estimated at %.1f s on %d threads" % (t_ew + t_one, est_s, cores))
+                   sample="fp64 oracle on matrix %d (%dx%d): elementwise part %.2f s + %d of %d Newton-Schulz "
+                          "iterations at %.2f s each (%.0f GFLOP/s), scaled by FLOPs and elements to the %d-matrix share"
+                          % (g0[0], rows, cols, t_ew, n_sample, hp.ns_steps, t_iter, f0 / max(t_iter, 1e-9) / 1e9,
+                             n_share))
+        log("oracle sample: %.2f s measured, share estimated at %.1f s on %d threads" % (t_ew + t_some, est_s, cores))
 
     out = {
         "metric": "optimizer_step_latency_ms", "value": ms_per_step, "unit": "ms",
@@ -263,7 +329,7 @@ def main():
         "frac_mfma_peak_issued": issued_step / (ms_per_step * 1e-3) / 1e12 / peak,
         "frac_mfma_peak_algorithmic": tflops / peak,
         "step_ms_events": {"median": float(np.median(per_step)), "min": float(min(per_step))},
-        "planner": diag, "kernels": kernels, "roofline": roofline, "cpu_baseline": cpu,
+        "device": device, "planner": diag, "kernels": kernels, "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
 
