@@ -80,6 +80,36 @@ class ClockSampler:
         return sum(self.samples) / len(self.samples) if self.samples else None
 
 
+def pick_tp_share(canz, W, cfg, cmax_bytes):
+    """TP planner (Algorithms 2-4): micro-groups with a host rank per tensor; the share is what
+    the most loaded host rank computes, micro-group by micro-group, same shapes side by side."""
+    s = W.matrix_set(cfg)
+    cost = [r * c for r, c in zip(s["rows"], s["cols"])]
+    t0 = time.perf_counter()
+    mgroups, loads = canz.canz_tp_schedule(cost, s["tp"], cmax_bytes // 2)      # capacity in bf16 elements
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    per_rank = [0] * s["tp"]
+    for mg in mgroups:
+        for t, h in mg:
+            per_rank[h] += cost[t]
+    rank = max(range(s["tp"]), key=lambda r: (per_rank[r], -r))
+    groups = []
+    for mg in mgroups:
+        mine = sorted((t for t, h in mg if h == rank), key=lambda t: (-cost[t], s["rows"][t], s["cols"][t], t))
+        for t in mine:
+            shape = (s["rows"][t], s["cols"][t])
+            if groups and groups[-1][0] == shape and groups[-1][2] is mg:
+                groups[-1][1].append(t)
+            else:
+                groups.append((shape, [t], mg))
+    groups = [g[1] for g in groups]
+    mean = sum(per_rank) / len(per_rank)
+    diag = dict(rank=rank, n_ranks=s["tp"], alpha=None, r_lb_numel=max(per_rank) / mean if mean else 1.0,
+                planner_ms=plan_ms, tp_micro_groups=len(mgroups), cmax_bytes=cmax_bytes,
+                largest_group_load_elems=max(loads) if loads else 0)
+    return s, rank, groups, diag
+
+
 def pick_share(canz, W, cfg):
     """Planner calls (timed) -> (set, rank, groups of matrix ids, diagnostics)."""
     import numpy as np
@@ -108,6 +138,12 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default 4: Qwen3-32B share)")
     ap.add_argument("--precision", choices=["bf16", "f32"], default="bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tp-schedule", type=int, default=0, metavar="MB",
+                    help="config 5 only: plan with canz_tp_schedule at this micro-group capacity (MB of bf16 per host "
+                         "rank) and run the share of the most loaded host rank instead of all matrices")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time replays of it (the per-kernel breakdown then "
+                         "comes from one extra eager pass outside the timed region)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the warm-up: under `rocprofv3 --pmc FETCH_SIZE` / "
                          "`WRITE_SIZE` its known traffic gives the scale of the counters")
@@ -128,7 +164,11 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     cfg = args.config
-    s, rank, groups, diag = pick_share(canz, W, cfg)
+    if args.tp_schedule:
+        assert cfg == 5, "--tp-schedule applies to the TP configuration (5)"
+        s, rank, groups, diag = pick_tp_share(canz, W, cfg, args.tp_schedule << 20)
+    else:
+        s, rank, groups, diag = pick_share(canz, W, cfg)
     tp = s["tp"]
     n_share = sum(len(g) for g in groups)
     log("config %d (%s): rank %d owns %d matrices in %d groups; planner %.2f ms" %
@@ -193,7 +233,25 @@ def main():
     log("warm-up done")
 
     launches_per_step = sum(((len(g) + 15) // 16) * (2 + 3 * hp.ns_steps) for g in groups)
-    canz.canz_profile_enable(launches_per_step * args.steps + 8)
+    graph = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            canz.canz_muon_step(dgroups, hp, ws, ws_bytes, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        canz.canz_profile_enable(launches_per_step * args.steps + 8)
+        for i in range(args.steps):                 # eager pass for the per-kernel breakdown, not timed
+            step()
+        torch.cuda.synchronize()
+        prof_eager = canz.canz_profile_collect()
+        canz.canz_profile_disable()
+        step = graph.replay
+        step()
+        torch.cuda.synchronize()
+        log("graph captured; timing replays")
+    else:
+        canz.canz_profile_enable(launches_per_step * args.steps + 8)
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     clock = ClockSampler()
@@ -205,8 +263,11 @@ def main():
             ev[i + 1].record()
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t_start) * 1e3
-    prof = canz.canz_profile_collect()
-    canz.canz_profile_disable()
+    if graph is None:
+        prof = canz.canz_profile_collect()
+        canz.canz_profile_disable()
+    else:
+        prof = prof_eager
     per_step = [ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]
     ms_per_step = wall_ms / args.steps
     log("timed %d steps: %.3f ms/step (events: median %.3f, min %.3f)" %
@@ -317,10 +378,13 @@ def main():
         "metric": "optimizer_step_latency_ms", "value": ms_per_step, "unit": "ms",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": args.precision, "data": "synthetic",
-        "config": {"workload": "config %d %s: rank %d of %d (alpha=%.2g), %d matrices %s in %d micro-groups, "
+        "dtype": args.precision, "data": "synthetic", "launch": "hip graph replay" if graph is not None else "eager",
+        "config": {"workload": "config %d %s: %s, %d matrices %s in %d micro-groups, "
                                "%d Newton-Schulz steps" %
-                               (cfg, s["name"], rank, s["n_ranks"], s["alpha"], n_share,
+                               (cfg, s["name"],
+                                ("host rank %d of %d under the TP schedule (capacity %d MB)" % (rank, tp, args.tp_schedule))
+                                if args.tp_schedule else
+                                "rank %d of %d (alpha=%.2g)" % (rank, s["n_ranks"], s["alpha"]), n_share,
                                 sorted({(s["rows"][p], s["cols"][p]) for g in groups for p in g}), len(groups),
                                 hp.ns_steps),
                    "tp": tp, "elements": total_elems},

@@ -210,6 +210,8 @@ class Group:
 
 
 def _addr(x) -> int:
+    if x is None:
+        return 0
     return int(x.data_ptr()) if hasattr(x, "data_ptr") else int(x)
 
 

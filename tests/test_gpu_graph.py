@@ -1,0 +1,95 @@
+"""GPU: canz_muon_step under HIP graph capture, and calls with empty groups.
+
+The step issues kernels only (scratch counters are cleared by a kernel, never by a
+memset), allocates nothing and never synchronises, so a caller may capture it.  A graph
+is replayed several times with eager work and synchronisations in between, and every
+replay must reproduce the eager result bit for bit."""
+import numpy as np
+import pytest
+
+from paper_2602_06079_amd import workloads as W
+from tests.gpu_harness import DeviceGroup, log, run_step
+
+pytestmark = pytest.mark.gpu
+
+
+def _make_groups(canz, in_place):
+    shapes = [(256, 512, 3), (300, 77, 2), (520, 1032, 1)]
+    dgs, inputs = [], []
+    for k, (rows, cols, n) in enumerate(shapes):
+        grads = [W.gen_grad(80 + k, i, rows, cols)[0] for i in range(n)]
+        moms = [W.gen_normal_f32(80 + k, i, 5, rows, cols, 0.01) for i in range(n)]
+        params = [W.gen_param(80 + k, i, rows, cols) for i in range(n)] if in_place else None
+        dgs.append(DeviceGroup(canz, rows, cols, grads, moms, outs=params))
+        inputs.append((grads, moms, params))
+    return dgs, inputs
+
+
+@pytest.mark.parametrize("precision", [0, 1])
+def test_hip_graph_replay_matches_eager(canz, precision):
+    import torch
+    hp = canz.Hparams(precision=precision, out_mode=canz.OUT_PARAM)
+    dgs, _ = _make_groups(canz, in_place=True)
+    groups = [d.group() for d in dgs]
+    state = [t for d in dgs for t in d.mom_t + d.out_t]
+    saved = [t.clone() for t in state]
+    nbytes = canz.canz_muon_workspace_bytes(groups, hp)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+
+    def restore():
+        for t, s0 in zip(state, saved):
+            t.copy_(s0)
+
+    # eager result
+    canz.canz_muon_step(groups, hp, ws, nbytes, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in state]
+    assert any(not torch.equal(a, b) for a, b in zip(want, saved))
+
+    # capture on a side stream
+    restore()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    log("capturing canz_muon_step (precision %d)" % precision)
+    with torch.cuda.graph(graph, stream=side):
+        canz.canz_muon_step(groups, hp, ws, nbytes, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    # capture runs nothing: the state is still the saved one
+    assert all(torch.equal(a, b) for a, b in zip(state, saved))
+
+    for rep in range(4):
+        restore()
+        ws.fill_(0xA5 if rep % 2 else 0)          # eager work between replays; scratch content must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(zip(state, want)):
+            assert torch.equal(a, b), "replay %d: state tensor %d differs from the eager result" % (rep, i)
+        log("replay %d matches the eager step" % rep)
+
+
+def test_empty_groups_are_skipped(canz):
+    """Groups without matrices and a call without groups change nothing and need no workspace."""
+    import torch
+    hp = canz.Hparams(out_mode=canz.OUT_DELTA)
+    stream = torch.cuda.current_stream().cuda_stream
+    canz.canz_muon_step([], hp, None, 0, stream)
+    empty = canz.Group(rows=64, cols=64, grad=[], mom=[], out=[], tp=1, grad_dtype=W.DT_BF16, out_dtype=W.DT_F32)
+    assert canz.canz_muon_workspace_bytes([empty], hp) <= 256      # the alignment minimum
+    canz.canz_muon_step([empty], hp, None, 0, stream)
+
+    rows, cols, n = 200, 333, 3
+    grads = [W.gen_grad(81, i, rows, cols)[0] for i in range(n)]
+    zeros = [np.zeros((rows, cols), np.float32) for _ in range(n)]
+    alone = DeviceGroup(canz, rows, cols, grads, zeros)
+    run_step(canz, [alone], hp)
+    mixed = DeviceGroup(canz, rows, cols, grads, zeros)
+    groups = [empty, mixed.group(), empty]
+    nbytes = canz.canz_muon_workspace_bytes(groups, hp)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    canz.canz_muon_step(groups, hp, ws, nbytes, stream)
+    torch.cuda.synchronize()
+    for i in range(n):
+        assert np.array_equal(alone.out_host(i), mixed.out_host(i))
+        assert np.array_equal(alone.mom_host(i), mixed.mom_host(i))
