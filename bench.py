@@ -59,6 +59,18 @@ class ClockSampler:
                 pass
         return best
 
+    def max_level_mhz(self):
+        """Highest level the file lists (the nominal peak clock)."""
+        best = None
+        for p in self.paths:
+            try:
+                for line in open(p).read().splitlines():
+                    mhz = float(line.split(":")[1].lower().replace("mhz", "").replace("*", "").strip())
+                    best = mhz if best is None else max(best, mhz)
+            except (OSError, ValueError, IndexError):
+                pass
+        return best
+
     def _run(self):
         while not self.stop.is_set():
             v = self._read()
@@ -314,7 +326,8 @@ def main():
     peak = PEAK_BF16_TFLOPS if bf16 else 157.3
     # the same peak from what the device reports, and at the shader clock sampled during the run
     props = torch.cuda.get_device_properties(0)
-    cus, nominal_mhz = int(props.multi_processor_count), float(getattr(props, "clock_rate", 0)) / 1e3
+    cus = int(props.multi_processor_count)
+    nominal_mhz = float(getattr(props, "clock_rate", 0)) / 1e3 or clock.max_level_mhz() or 2400.0
     flop_per_clk_cu = 4096.0 if bf16 else 256.0
     seen_mhz = clock.mean_mhz()
     device = dict(name=props.name, compute_units=cus, nominal_clock_mhz=nominal_mhz,

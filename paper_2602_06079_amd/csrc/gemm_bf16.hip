@@ -139,24 +139,42 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[4][4], __bf16* stage
 
   // scale (first iteration: folded normalisation), or the polynomial in A for EPI_POLY
   if (EPI == EPI_POLY) {
+    // A is symmetric bit for bit (the Gram epilogue writes both halves from the same
+    // accumulators), so element (i, j) is read as (j, i): the wavefront's part of the mirrored
+    // tile is copied linearly into its staging area (global -> LDS, 16 bytes per lane) and is
+    // then the transposed image, in which a lane's four consecutive rows are four consecutive k.
     const __bf16* A = static_cast<const __bf16*>(e.aux) + static_cast<int64_t>(b) * d.M * d.N;
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+      const __bf16* src = A + (static_cast<int64_t>(tn) * (d.M >> 5) + 8 * tm + 4 * wm + kb) * PANEL_ELEMS +
+                          wn * 128 * PANEL_K + lane * 8;
+#pragma unroll
+      for (int x = 0; x < 8; ++x)
+        __builtin_amdgcn_global_load_lds(CANZ_GLB(src + x * 512), CANZ_LDS(stage + kb * 4096 + x * 512), 16, 0, 0);
+    }
+    int a_base[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) a_base[g] = lj * 32 + ((g ^ ((lj >> 2) & 3)) << 3) + 4 * lh;
+    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): the copy has landed
 #pragma unroll
     for (int it = 0; it < 4; ++it)
 #pragma unroll
       for (int jt = 0; jt < 4; ++jt) {
         const int col = tn * BN + wn * 128 + jt * 32 + lj;
         const int row0 = tm * BM + wm * 128 + it * 32 + 4 * lh;
-        float av[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          av[r] = static_cast<float>(A[panel_chunk_off(row0 + 8 * (r >> 2) + (r & 3), col & ~7, d.N) + (col & 7)]);
+        for (int g = 0; g < 4; ++g) {
+          const bf16x4 av = *reinterpret_cast<const bf16x4*>(stage + it * 4096 + jt * 32 * 32 + a_base[g]);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float v = e.cb * av[r] + e.cc * acc[it][jt][r];
-          if (row0 + 8 * (r >> 2) + (r & 3) == col) v += e.ca;
-          acc[it][jt][r] = v;
+          for (int q = 0; q < 4; ++q) {
+            float v = e.cb * static_cast<float>(av[q]) + e.cc * acc[it][jt][4 * g + q];
+            if (row0 + 8 * g + q == col) v += e.ca;
+            acc[it][jt][4 * g + q] = v;
+          }
         }
       }
+    // every read of the staging area is done before the images below overwrite it
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
   } else if (e.scale) {
     const float sc = e.scale[b];
 #pragma unroll
@@ -265,21 +283,74 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[4][4], __bf16* stage
         }
         char* base = static_cast<char*>(o.out.p[col_ok ? tab : b * (MODE == CANZ_OUT_DELTA ? s.tp : 1)]);
         constexpr int ESZ = DTYPE == CANZ_DT_F32 ? 4 : 2;
+        // whole 128 x 128 part inside the matrix (uniform over the wavefront): no predicates
+        const bool inside = tm * BM + wm * 128 + 128 <= s.rows && tn * BN + wn * 128 + 128 <= s.cols;
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-#pragma unroll
-          for (int i2 = 0; i2 < 2; ++i2)
-#pragma unroll
-            for (int jt = 0; jt < 4; ++jt)
-#pragma unroll
-              for (int r = 0; r < 16; ++r) {
-                // (32 jt + lj) ^ (32 lh) = lj + 32 (jt ^ lh): lane base per parity of jt
-                const int fixed = (i2 * 32 + 8 * (r >> 2) + (r & 3)) * 128 + (jt & ~1) * 32;
-                sf[fixed + f_base[jt & 1]] = acc[half * 2 + i2][jt][r];
-              }
           const int row_base = tm * BM + wm * 128 + half * 64 + lh;
+          auto stage_half = [&]() {
 #pragma unroll
-          for (int x4 = 0; x4 < 8; ++x4) {  // 4 rows at a time: loads of old values first
+            for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+              for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                  // (32 jt + lj) ^ (32 lh) = lj + 32 (jt ^ lh): lane base per parity of jt
+                  const int fixed = (i2 * 32 + 8 * (r >> 2) + (r & 3)) * 128 + (jt & ~1) * 32;
+                  sf[fixed + f_base[jt & 1]] = acc[half * 2 + i2][jt][r];
+                }
+          };
+          if (inside) {
+            // The lane handles 4 columns of the 32 rows row_base + 2 i.  All old values of the
+            // half are requested at once and every one of them is consumed before the first
+            // store is issued: the half then costs one memory latency (with loads and stores
+            // interleaved, each group of rows would wait for the stores of the one before).
+            char* const ptr0 = base + (static_cast<int64_t>(row_base) * ld + c_in) * ESZ;
+            const int64_t pitch2 = static_cast<int64_t>(2) * ld * ESZ;
+            f32x4 val[32];
+            if (MODE == CANZ_OUT_PARAM) {
+#pragma unroll
+              for (int i = 0; i < 32; ++i) {
+                if (DTYPE == CANZ_DT_F32) {
+                  val[i] = *reinterpret_cast<const f32x4*>(ptr0 + i * pitch2);
+                } else {
+                  const bf16x4 ob = *reinterpret_cast<const bf16x4*>(ptr0 + i * pitch2);
+#pragma unroll
+                  for (int q = 0; q < 4; ++q) val[i][q] = static_cast<float>(ob[q]);
+                }
+              }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            stage_half();
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+              // row 2 i + lh of the staged half; bit 2 of that row is bit 1 of i
+              const f32x4 v = *reinterpret_cast<const f32x4*>(sf + 2 * i * 128 + r_base[(i >> 1) & 1]);
+              if (MODE == CANZ_OUT_PARAM)
+                val[i] = val[i] * o.decay + o.neg_lr_scale * v;
+              else
+                val[i] = o.neg_lr_scale * v;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+              if (DTYPE == CANZ_DT_F32) {
+                *reinterpret_cast<f32x4*>(ptr0 + i * pitch2) = val[i];
+              } else {
+                bf16x4 rb;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) rb[q] = static_cast<__bf16>(val[i][q]);
+                *reinterpret_cast<bf16x4*>(ptr0 + i * pitch2) = rb;
+              }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            continue;
+          }
+          // ragged edge of the matrix: rows and columns checked one by one, 4 rows at a time
+          stage_half();
+#pragma unroll
+          for (int x4 = 0; x4 < 8; ++x4) {  // loads of old values first
             f32x4 v[4], old[4];
             char* ptr[4];
             bool live[4];
@@ -378,6 +449,7 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
   const int wm = wave >> 1, wn = wave & 1;
 
   const int nk_all = static_cast<int>(d.K / BK);  // multiple of 8: K is a multiple of 256
+
   for (int work = 0;; ++work) {
   // ---- what to do in this round: a whole tile, or one k-slice of a left-over tile.  When
   //      the tiles do not fill the last round, each left-over tile is cut along k so that the
