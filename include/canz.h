@@ -157,8 +157,9 @@ int canz_tp_schedule(int64_t n_mats, const int64_t* cost, int32_t n_ranks, int64
  * and scattered after the computation, Sec. 4.1 stages (1) and (3)).
  * The three pointer tables are HOST arrays of DEVICE pointers; they are read during the
  * call and may be freed on return.  The device buffers must stay valid until the stream
- * has finished the step.  Device pointers must be 16-byte aligned; cols/tp must be a
- * multiple of 8.  grad, mom and out buffers must not overlap.
+ * has finished the step.  Device pointers must be 16-byte aligned; with tp > 1 the
+ * fragment width cols/tp must be a multiple of 8 (whole matrices may have any extents).
+ * rows and cols are at most 4194240 each.  grad, mom and out buffers must not overlap.
  */
 typedef struct {
   int64_t rows, cols;
@@ -208,7 +209,8 @@ int canz_muon_workspace_bytes(const canz_group* g, int32_t n_groups,
  * Returns after enqueueing; completion follows stream order.  Results per matrix do not
  * depend on which other matrices share the group or the call.
  * Errors: CANZ_EINVAL (null pointers, n_mats < 0, tp outside 1..8, ns_steps < 0),
- * CANZ_ESHAPE (cols not divisible by tp, fragment width not a multiple of 8),
+ * CANZ_ESHAPE (cols not divisible by tp, fragment width not a multiple of 8, an extent
+ * above 4194240),
  * CANZ_EWORKSPACE, CANZ_EUNSUPPORTED (dtype / mode enums), CANZ_EHIP (launch failure;
  * earlier groups of the call may already be enqueued).
  */

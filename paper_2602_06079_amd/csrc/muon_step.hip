@@ -74,8 +74,10 @@ int check_hparams(const canz_muon_hparams* hp) {
 int check_group(const canz_group& g, int idx, bool need_ptrs, int out_mode) {
   if (g.n_mats < 0) return fail(CANZ_EINVAL, "group %d: n_mats < 0", idx);
   if (g.rows < 1 || g.cols < 1) return fail(CANZ_EINVAL, "group %d: empty shape", idx);
-  if (g.rows > (int64_t(1) << 30) || g.cols > (int64_t(1) << 30))
-    return fail(CANZ_ESHAPE, "group %d: extent above 2^30", idx);
+  // 65535 grid rows of 64-row tiles in the element-wise kernels
+  constexpr int64_t MAX_EXTENT = 65535 * 64;
+  if (g.rows > MAX_EXTENT || g.cols > MAX_EXTENT)
+    return fail(CANZ_ESHAPE, "group %d: extent above %lld", idx, static_cast<long long>(MAX_EXTENT));
   if (g.tp < 1 || g.tp > MAX_TP) return fail(CANZ_EINVAL, "group %d: tp must be in 1..%d", idx, MAX_TP);
   if (g.cols % g.tp) return fail(CANZ_ESHAPE, "group %d: cols not divisible by tp", idx);
   if (g.tp > 1 && (g.cols / g.tp) % 8) return fail(CANZ_ESHAPE, "group %d: fragment width not a multiple of 8", idx);

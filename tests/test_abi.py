@@ -64,6 +64,7 @@ def test_step_argument_errors_without_device(canz):
     assert code([canz.Group(**{**ok, "tp": 9})], hp) == canz.EINVAL
     assert code([canz.Group(**{**ok, "tp": 3})], hp) == canz.ESHAPE                 # 512 % 3
     assert code([canz.Group(**{**ok, "cols": 36, "tp": 3, "grad": [4096] * 3})], hp) == canz.ESHAPE  # width 12
+    assert code([canz.Group(**{**ok, "rows": 65535 * 64 + 1})], hp) == canz.ESHAPE  # above the documented limit
     assert code([canz.Group(**{**ok, "grad_dtype": 7})], hp) == canz.EUNSUPPORTED
     assert code([canz.Group(**ok)], canz.Hparams(ns_steps=-1)) == canz.EINVAL
     assert code([canz.Group(**ok)], canz.Hparams(scale_mode=9)) == canz.EUNSUPPORTED

@@ -230,3 +230,18 @@ def test_workspace_is_scratch(canz):
     b = DeviceGroup(canz, rows, cols, grads, zeros)
     run_step(canz, [b], hp, ws)
     assert np.array_equal(a.out_host(0), b.out_host(0))
+
+
+@pytest.mark.parametrize("shape", [(8, 300000), (70000, 16), (3, 4194240 // 16)], ids=lambda s: "%dx%d" % s)
+def test_extreme_aspect_ratios(canz, shape):
+    """Very wide and very tall matrices: one tile row, a k range of thousands of steps (the
+    Gram product of a single tile is cut along k over the whole chip) and, the other way
+    round, a k range of one panel."""
+    rows, cols = shape
+    grads = [W.gen_grad(96, i, rows, cols)[0] for i in range(2)]
+    zeros = [np.zeros((rows, cols), np.float32) for _ in range(2)]
+    for precision in (0, 1):
+        hp = canz.Hparams(out_mode=canz.OUT_DELTA, precision=precision)
+        dg = DeviceGroup(canz, rows, cols, grads, zeros)
+        run_step(canz, [dg], hp)
+        _check_group(canz, dg, grads, zeros, None, hp, "%dx%d prec%d" % (rows, cols, precision))
