@@ -17,13 +17,15 @@
 namespace canz {
 
 constexpr int PAD = 256;           // working extents are multiples of this
-constexpr int MAX_BATCH = 16;      // matrices per launch (larger groups are split)
 constexpr int MAX_TP = 8;
+constexpr int MAX_PTRS = 128;      // buffers per pointer table: a launch takes up to MAX_PTRS / tp matrices
+// ... and no more than this many padded elements, which bounds the workspace of a launch
+constexpr int64_t MAX_BATCH_ELEMS = int64_t(1) << 30;
 constexpr int EW_TILE = 64;        // elementwise kernels work on 64 x 64 tiles
 
 // Pointer tables travel as kernel arguments, so nothing is copied to the device.
 struct PtrTable {
-  void* p[MAX_BATCH * MAX_TP];
+  void* p[MAX_PTRS];
 };
 
 struct Shape {

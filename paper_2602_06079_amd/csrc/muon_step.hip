@@ -134,11 +134,21 @@ inline void prof_mark(hipStream_t st, int kind, bool begin) {
   } while (0)
 
 // Launch batches: consecutive matrices of the call that share shape and dtypes are batched
-// together, up to MAX_BATCH per launch, across micro-group boundaries (a matrix's result
+// together, up to batch_cap() per launch, across micro-group boundaries (a matrix's result
 // does not depend on its batch, and small matrices need the larger batch to fill the chip).
 bool same_kind(const canz_group& a, const canz_group& b) {
   return a.rows == b.rows && a.cols == b.cols && a.tp == b.tp && a.grad_dtype == b.grad_dtype &&
          a.out_dtype == b.out_dtype;
+}
+
+// matrices of this kind per launch: bounded by the pointer tables (kernel arguments) and by
+// the workspace a launch needs.  Small matrices go many to a launch, so that the persistent
+// GEMM grids have whole rounds of tiles and the launch count stays low.
+int batch_cap(const canz_group& g) {
+  const Shape s = make_shape(g);
+  const int64_t by_ptrs = MAX_PTRS / g.tp;
+  const int64_t by_elems = std::max<int64_t>(1, MAX_BATCH_ELEMS / (s.mp * s.np));
+  return static_cast<int>(std::min(by_ptrs, by_elems));
 }
 
 // calls fn(proto group, first group index, first matrix in it, count) for every launch batch
@@ -147,7 +157,7 @@ int for_each_batch(const canz_group* g, int n_groups, F&& fn) {
   int proto = -1, count = 0, start_group = 0, start_mat = 0;
   for (int i = 0; i < n_groups; ++i) {
     for (int m = 0; m < g[i].n_mats; ++m) {
-      if (count > 0 && (count == MAX_BATCH || !same_kind(g[proto], g[i]))) {
+      if (count > 0 && (count == batch_cap(g[proto]) || !same_kind(g[proto], g[i]))) {
         if (int rc = fn(g[proto], start_group, start_mat, count)) return rc;
         count = 0;
       }
@@ -159,7 +169,7 @@ int for_each_batch(const canz_group* g, int n_groups, F&& fn) {
   return CANZ_OK;
 }
 
-// One launch batch (<= MAX_BATCH same-kind matrices).
+// One launch batch (<= batch_cap() same-kind matrices).
 template <typename T>
 int run_batch(const canz_group& g, const void* const* g_grad, void* const* g_mom, void* const* g_out, int nb,
               const canz_muon_hparams& hp, char* ws, hipStream_t st) {

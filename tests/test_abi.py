@@ -43,10 +43,18 @@ def test_workspace_bytes_formula(canz):
     hp32 = canz.Hparams(precision=canz.PREC_F32)
     want2 = 3 * 256 * 512 * 4 + 2 * 256 * 256 * 4 + 256 + 256 + 256 + 256 * 4
     assert canz.canz_muon_workspace_bytes([g2], hp32) == want2
-    # the maximum over groups, and batches above 16 matrices are split
-    g3 = canz.Group(rows=256, cols=512, n_mats=40)
-    want3 = 3 * 16 * 256 * 512 * 2 + 2 * 16 * 256 * 256 * 2 + 16 * 32 * 4 + 256 + 256 + split
+    # the maximum over groups; a launch takes at most 128 matrices (the pointer-table size) ...
+    g3 = canz.Group(rows=256, cols=512, n_mats=150)
+    want3 = 3 * 128 * 256 * 512 * 2 + 2 * 128 * 256 * 256 * 2 + 128 * 32 * 4 + 512 + 512 + split
     assert canz.canz_muon_workspace_bytes([g, g3], hp) == want3
+    # ... at most 128 / tp with column fragments, and at most 2^30 padded elements
+    g4 = canz.Group(rows=256, cols=512, n_mats=150, tp=4)
+    want4 = 3 * 32 * 256 * 512 * 2 + 2 * 32 * 256 * 256 * 2 + 32 * 32 * 4 + 256 + 256 + split
+    assert canz.canz_muon_workspace_bytes([g4], hp) == want4
+    g5 = canz.Group(rows=12288, cols=4096, n_mats=36)
+    nb = (1 << 30) // (12288 * 4096)
+    want5 = 3 * nb * 12288 * 4096 * 2 + 2 * nb * 4096 * 4096 * 2 + nb * (192 * 64) * 4 + 256 + 256 + split
+    assert nb == 21 and canz.canz_muon_workspace_bytes([g5], hp) == want5
     assert canz.canz_muon_workspace_bytes([], hp) == 256
 
 

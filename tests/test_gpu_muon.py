@@ -163,14 +163,14 @@ def test_batch_independence_and_determinism(canz):
 
 
 def test_group_larger_than_launch_batch(canz):
-    """20 matrices in one group: split internally into launches of at most 16."""
-    rows, cols, n = 256, 256, 20
+    """150 matrices in one group: split internally into launches of at most 128."""
+    rows, cols, n = 256, 256, 150
     grads = [W.gen_grad(95, i, rows, cols)[0] for i in range(n)]
     zeros = [np.zeros((rows, cols), np.float32) for _ in range(n)]
     hp = canz.Hparams(out_mode=canz.OUT_DELTA, precision=1)
     dg = DeviceGroup(canz, rows, cols, grads, zeros)
     run_step(canz, [dg], hp)
-    _check_group(canz, dg, grads, zeros, None, hp, "20-matrix group")
+    _check_group(canz, dg, grads, zeros, None, hp, "150-matrix group")
 
 
 @pytest.mark.parametrize("precision", [0, 1])
