@@ -4,7 +4,9 @@
  *
  * Three calls follow the paper's statement of the problem:
  *   canz_partition_alpha   Algorithm 1 (Sec. 3.2): which rank owns which whole matrix.  CPU.
+ *                          (canz_partition_naive: the static rule of Eq. 1 it replaces.)
  *   canz_microgroup_plan   batches one rank's same-shape matrices for one launch.        CPU.
+ *                          (canz_tp_schedule: TP micro-groups with rollback, Algorithms 2-4.)
  *   canz_muon_step         Delta W = Muon_step(G, States) (Sec. 4.1 stage (2), Sec. 3.3
  *                          stage (2)): momentum, Frobenius normalisation, k Newton-Schulz
  *                          steps, scaled update - enqueued on a HIP stream.
@@ -15,6 +17,7 @@
  *   - The library never allocates or frees device memory and never synchronises a
  *     stream or the device.  Host arrays passed in are read during the call only.
  *   - "host" / "device" in a comment says where a pointer must point.
+ *   - An array whose stated size is zero may be passed as NULL.
  *   - Ranks are numbered 0 .. n_ranks-1 (the paper counts from 1).
  */
 #ifndef CANZ_H

@@ -15,9 +15,12 @@ extern "C" int canz_microgroup_plan(int64_t n_mats, const int64_t* rows, const i
                                     int64_t* group_off_out, int64_t* member_out) {
   using canz::fail;
   if (n_mats < 0) return fail(CANZ_EINVAL, "negative n_mats");
-  if (!n_groups_out || !group_off_out || !member_out) return fail(CANZ_EINVAL, "null output pointer");
+  if (!n_groups_out || !group_off_out) return fail(CANZ_EINVAL, "null output pointer");
   if (n_mats > 0 && (!rows || !cols || !dtype || !owner)) return fail(CANZ_EINVAL, "null input pointer");
   if (max_mats < 0 || cmax_bytes < 0) return fail(CANZ_EINVAL, "caps must be non-negative");
+  int64_t n_owned = 0;
+  for (int64_t p = 0; p < n_mats; ++p) n_owned += owner[p] == rank;
+  if (n_owned > 0 && !member_out) return fail(CANZ_EINVAL, "null output pointer");  // an array of size zero may be null
 
   using Key = std::tuple<int64_t, int64_t, int32_t>;
   std::map<Key, std::vector<int64_t>> classes;

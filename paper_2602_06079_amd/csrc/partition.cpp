@@ -26,7 +26,8 @@ extern "C" int canz_partition_alpha(int64_t n_mats, const int64_t* rows, const i
                                     int64_t* cut_out, int32_t* owner_out, int64_t* load_out) {
   using canz::fail;
   if (n_mats < 0 || n_buckets < 0) return fail(CANZ_EINVAL, "negative size");
-  if (!bucket_off || !cut_out || !owner_out || !load_out) return fail(CANZ_EINVAL, "null pointer");
+  if (!bucket_off || !load_out || (n_buckets > 0 && !cut_out) || (n_mats > 0 && !owner_out))
+    return fail(CANZ_EINVAL, "null pointer");  // arrays of size zero may be null
   if (!cost && (!rows || !cols) && n_mats > 0) return fail(CANZ_EINVAL, "need cost or rows/cols");
   if (n_ranks < 1) return fail(CANZ_EINVAL, "n_ranks must be >= 1");
   if (!(alpha >= 0.0 && alpha <= 1.0)) return fail(CANZ_EINVAL, "alpha must lie in [0,1]");
@@ -124,7 +125,7 @@ extern "C" int canz_partition_naive(int64_t n_mats, const int64_t* numel, int64_
                                     int64_t* load_out) {
   using canz::fail;
   if (n_mats < 0 || n_buckets < 0) return fail(CANZ_EINVAL, "negative size");
-  if (!owner_out || !load_out || !bucket_off || (n_mats > 0 && !numel)) return fail(CANZ_EINVAL, "null pointer");
+  if (!load_out || !bucket_off || (n_mats > 0 && (!numel || !owner_out))) return fail(CANZ_EINVAL, "null pointer");
   if (n_ranks < 1) return fail(CANZ_EINVAL, "n_ranks must be >= 1");
   if (bucket_off[0] != 0 || bucket_off[n_buckets] != n_mats)
     return fail(CANZ_EINVAL, "bucket_off must run from 0 to n_mats");

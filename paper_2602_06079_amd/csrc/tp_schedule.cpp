@@ -43,8 +43,8 @@ extern "C" int canz_tp_schedule(int64_t n_mats, const int64_t* cost, int32_t n_r
                                 int32_t* host_rank_out, int64_t* group_load_out) {
   using canz::fail;
   if (n_mats < 0) return fail(CANZ_EINVAL, "negative n_mats");
-  if (!n_groups_out || !group_off_out || !member_out || !host_rank_out || !group_load_out)
-    return fail(CANZ_EINVAL, "null output pointer");
+  if (!n_groups_out || !group_off_out || (n_mats > 0 && (!member_out || !host_rank_out || !group_load_out)))
+    return fail(CANZ_EINVAL, "null output pointer");  // arrays of size zero may be null
   if (n_mats > 0 && !cost) return fail(CANZ_EINVAL, "null cost");
   if (n_ranks < 1) return fail(CANZ_EINVAL, "n_ranks must be >= 1");
   if (cmax < 0) return fail(CANZ_EINVAL, "capacity must be non-negative");
