@@ -17,6 +17,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 OUT = os.path.join(HERE, "libcanz.so")
+EXAMPLE_SRC = os.path.join(CSRC, "example_c_abi_step.cpp")
+EXAMPLE_OUT = os.path.join(HERE, "c_abi_step")      # a C++ program that uses the C ABI directly, no Python
 
 HOST_SOURCES = ["error.cpp", "partition.cpp", "microgroup.cpp", "tp_schedule.cpp"]
 HIP_SOURCES = ["muon_step.hip", "elementwise.hip", "gemm_bf16.hip", "gemm_f32.hip"]
@@ -61,6 +63,9 @@ def build(verbose: bool = False) -> str:
     tmp = OUT + ".tmp"
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + [obj for _, obj in jobs])
     os.replace(tmp, OUT)
+    if os.path.exists(EXAMPLE_SRC):
+        _run([HIPCC, "-O2", "-std=c++17", "-I", INCLUDE, EXAMPLE_SRC, "-o", EXAMPLE_OUT, "-L", HERE, "-lcanz",
+              "-Wl,-rpath,$ORIGIN"])
     return OUT
 
 

@@ -143,3 +143,33 @@ def test_two_streams_with_separate_workspaces(canz):
         for i in range(a.n):
             assert np.array_equal(a.out_host(i), b.out_host(i))
             assert np.array_equal(a.mom_host(i), b.mom_host(i))
+
+
+@pytest.mark.parametrize("precision", [0, 1])
+def test_plain_cpp_consumer_of_the_c_abi(canz, precision, tmp_path):
+    """A C++ program with no Python and no torch in its process plans, allocates with
+    hipMalloc and runs one step through the C ABI; its outputs match the oracle."""
+    import os
+    import subprocess
+    from oracle import muon as OM
+    from paper_2602_06079_amd import build as B
+    assert os.path.exists(B.EXAMPLE_OUT), "c_abi_step is built by build()"
+    out = str(tmp_path / "step.bin")
+    run = subprocess.run([B.EXAMPLE_OUT, out, str(precision)], stdout=subprocess.PIPE, stderr=subprocess.STDOUT,
+                         text=True, timeout=100)
+    assert run.returncode == 0, run.stdout
+    log(run.stdout.strip())
+    raw = np.fromfile(out, dtype=np.uint8)
+    n, rows, cols = (int(v) for v in raw[:24].view(np.int64))
+    assert (n, rows, cols) == (3, 300, 200)
+    data = raw[24:].view(np.float32).reshape(n, 4, rows, cols)
+    f = lambda v: float(np.float32(v))
+    ohp = OM.Hparams(beta=f(0.95), lr=f(0.02), weight_decay=f(0.01), eps=f(1e-7), ns_steps=5,
+                     a=f(3.4445), b=f(-4.7750), c=f(2.0315), scale_mode=canz.SCALE_RMS)
+    tol = 3e-2 if precision == 0 else 1e-4
+    for i in range(n):
+        grad, before, after, mom = (data[i, k].astype(np.float64) for k in range(4))
+        ref = OM.muon_step(grad, np.zeros((rows, cols)), ohp, param=before)
+        assert np.linalg.norm(mom - ref["mom"]) <= 1e-6 * np.linalg.norm(ref["mom"])
+        err = np.linalg.norm(after - ref["param"]) / np.linalg.norm(ref["delta"])
+        assert err <= tol, "matrix %d: error %.3g" % (i, err)
