@@ -149,12 +149,9 @@ __global__ __launch_bounds__(NTHREADS) void k_momentum(Shape s, PtrTable grad, i
 // Step 3 of the operator, as a scalar: 1 / (||U||_F + eps).  One block per matrix; the
 // tile sums are added in fp64 in a fixed order, so the result does not depend on timing.
 __global__ __launch_bounds__(NTHREADS) void k_norm_scale(int n_partial, const float* __restrict__ partial, float eps,
-                                                          float* __restrict__ scale, float* __restrict__ scale2,
-                                                          int* __restrict__ counters, int n_counters) {
+                                                          float* __restrict__ scale, float* __restrict__ scale2) {
   __shared__ double red[NTHREADS];
   const int b = blockIdx.x, t = threadIdx.x;
-  if (b == 0)
-    for (int i = t; i < n_counters; i += NTHREADS) counters[i] = 0;
   double acc = 0.0;
   for (int i = t; i < n_partial; i += NTHREADS) acc += static_cast<double>(partial[static_cast<int64_t>(b) * n_partial + i]);
   red[t] = acc;
@@ -209,9 +206,8 @@ template hipError_t launch_momentum<float>(const Shape&, int, const PtrTable&, i
                                            float*, float*, float*, hipStream_t);
 
 hipError_t launch_norm_scale(int nb, int n_partial, const float* partial, float eps, float* scale, float* scale2,
-                             int* counters, int n_counters, hipStream_t st) {
-  hipLaunchKernelGGL(k_norm_scale, dim3(nb), dim3(NTHREADS), 0, st, n_partial, partial, eps, scale, scale2, counters,
-                     n_counters);
+                             hipStream_t st) {
+  hipLaunchKernelGGL(k_norm_scale, dim3(nb), dim3(NTHREADS), 0, st, n_partial, partial, eps, scale, scale2);
   return hipGetLastError();
 }
 

@@ -46,10 +46,9 @@ hipError_t launch_momentum(const Shape& s, int nb, const PtrTable& grad, int gra
                            float* partial, hipStream_t st);
 int momentum_tiles(const Shape& s);  // partial sums per matrix
 
-// scale[b] = 1 / (sqrt(sum partial[b][*]) + eps), scale2[b] = scale[b]^2; also zeroes the
-// n_counters arrival counters used by the GEMMs' k-split
+// scale[b] = 1 / (sqrt(sum partial[b][*]) + eps), scale2[b] = scale[b]^2
 hipError_t launch_norm_scale(int nb, int n_partial, const float* partial, float eps, float* scale,
-                             float* scale2, int* counters, int n_counters, hipStream_t st);
+                             float* scale2, hipStream_t st);
 
 struct OutSpec {
   PtrTable out;
@@ -72,10 +71,9 @@ struct GemmDims {
   int nb;
 };
 // Scratch for the k-split of left-over tiles: fp32 accumulators of up to max_blocks blocks
-// (256 KiB each) and one arrival counter per left-over tile (zero between launches).
+// (256 KiB each), written by the split launch and read by the kernel that finishes the tiles.
 struct SplitWs {
   float* partial;
-  int* counter;
   int max_blocks;
 };
 constexpr int SPLIT_MAX_BLOCKS = 256;                       // CU count of MI355X; fewer blocks split on a smaller part

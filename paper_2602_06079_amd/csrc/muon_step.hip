@@ -24,7 +24,7 @@ inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 inline int64_t pad_up(int64_t x) { return (x + PAD - 1) / PAD * PAD; }
 
 struct Carve {
-  size_t xw, xt0, xt1, a, b, partial, scale, scale2, split_partial, split_counter, total;
+  size_t xw, xt0, xt1, a, b, partial, scale, scale2, split_partial, total;
 };
 
 Shape make_shape(const canz_group& g) {
@@ -52,7 +52,6 @@ Carve carve(const Shape& s, int nb, int precision) {
   c.partial = off, off += align_up(static_cast<size_t>(nb) * momentum_tiles(s) * sizeof(float));
   c.scale = off, off += align_up(nb * sizeof(float));
   c.scale2 = off, off += align_up(nb * sizeof(float));
-  c.split_counter = off, off += align_up(SPLIT_MAX_BLOCKS * sizeof(int));
   c.split_partial = off;
   if (precision == CANZ_PREC_BF16) off += align_up(SPLIT_MAX_BLOCKS * SPLIT_BLOCK_BYTES);
   c.total = off;
@@ -133,12 +132,13 @@ inline void prof_mark(hipStream_t st, int kind, bool begin) {
     if (err__ != hipSuccess) return fail(CANZ_EHIP, "%s: %s", what, hipGetErrorString(err__)); \
   } while (0)
 
-// Launch batches: consecutive matrices of the call that share shape and dtypes are batched
+// Launch batches: consecutive matrices of the call that share dtypes and shape - up to a
+// transpose, since the iteration runs on the wide orientation of either - are batched
 // together, up to batch_cap() per launch, across micro-group boundaries (a matrix's result
 // does not depend on its batch, and small matrices need the larger batch to fill the chip).
 bool same_kind(const canz_group& a, const canz_group& b) {
-  return a.rows == b.rows && a.cols == b.cols && a.tp == b.tp && a.grad_dtype == b.grad_dtype &&
-         a.out_dtype == b.out_dtype;
+  return std::min(a.rows, a.cols) == std::min(b.rows, b.cols) && std::max(a.rows, a.cols) == std::max(b.rows, b.cols) &&
+         a.tp == b.tp && a.grad_dtype == b.grad_dtype && a.out_dtype == b.out_dtype;
 }
 
 // matrices of this kind per launch: bounded by the pointer tables (kernel arguments) and by
@@ -169,12 +169,24 @@ int for_each_batch(const canz_group* g, int n_groups, F&& fn) {
   return CANZ_OK;
 }
 
-// One launch batch (<= batch_cap() same-kind matrices).
+// The matrices of one orientation inside a launch batch.
+struct Part {
+  const canz_group* proto = nullptr;
+  std::vector<const void*> grad;
+  std::vector<void*> mom, out;
+  int n() const { return static_cast<int>(mom.size()); }
+};
+
+// One launch batch: part[0] holds its wide (rows <= cols) matrices, part[1] the tall ones of
+// the transposed shape.  They occupy consecutive slots of the workspace arrays, the wide
+// ones first; the kernels that touch the caller's buffers (momentum, last product, apply)
+// run once per part, everything between runs once over the whole batch.
 template <typename T>
-int run_batch(const canz_group& g, const void* const* g_grad, void* const* g_mom, void* const* g_out, int nb,
-              const canz_muon_hparams& hp, char* ws, hipStream_t st) {
-  const Shape s = make_shape(g);
-  const Carve c = carve(s, nb, hp.precision);
+int run_batch(const Part (&part)[2], const canz_muon_hparams& hp, char* ws, hipStream_t st) {
+  const int nb = part[0].n() + part[1].n();
+  const canz_group& any = *(part[0].n() ? part[0].proto : part[1].proto);
+  const Shape s0 = make_shape(any);
+  const Carve c = carve(s0, nb, hp.precision);
   T* xw = reinterpret_cast<T*>(ws + c.xw);
   T* xt[2] = {reinterpret_cast<T*>(ws + c.xt0), reinterpret_cast<T*>(ws + c.xt1)};
   T* a = reinterpret_cast<T*>(ws + c.a);
@@ -182,37 +194,53 @@ int run_batch(const canz_group& g, const void* const* g_grad, void* const* g_mom
   float* partial = reinterpret_cast<float*>(ws + c.partial);
   float* scale = reinterpret_cast<float*>(ws + c.scale);
   float* scale2 = reinterpret_cast<float*>(ws + c.scale2);
-  int* counters = reinterpret_cast<int*>(ws + c.split_counter);
-  const SplitWs split{reinterpret_cast<float*>(ws + c.split_partial), counters, SPLIT_MAX_BLOCKS};
+  const SplitWs split{reinterpret_cast<float*>(ws + c.split_partial), SPLIT_MAX_BLOCKS};
   constexpr bool is_bf16 = sizeof(T) == 2;
+  const int64_t x_elems = s0.mp * s0.np, a_elems = s0.mp * s0.mp;
+  const int tiles = momentum_tiles(s0);
 
-  PtrTable grad{}, mom{};
-  OutSpec o{};
-  const int n_out = hp.out_mode == CANZ_OUT_DELTA ? nb * g.tp : nb;
-  for (int i = 0; i < nb * g.tp; ++i) grad.p[i] = const_cast<void*>(g_grad[i]);
-  for (int i = 0; i < nb; ++i) mom.p[i] = g_mom[i];
-  for (int i = 0; i < n_out; ++i) o.out.p[i] = g_out[i];
-  o.out_dtype = g.out_dtype;
-  o.out_mode = hp.out_mode;
-  o.decay = static_cast<float>(1.0 - static_cast<double>(hp.lr) * static_cast<double>(hp.weight_decay));
-  o.neg_lr_scale = static_cast<float>(-static_cast<double>(hp.lr) * update_scale(g, hp.scale_mode));
-
-  CANZ_HIP(CANZ_KERNEL_MOMENTUM, launch_momentum<T>(s, nb, grad, g.grad_dtype, mom, hp.beta, hp.nesterov, xw, xt[0], partial, st),
-           "momentum kernel");
-  CANZ_HIP(CANZ_KERNEL_NORM, launch_norm_scale(nb, momentum_tiles(s), partial, hp.eps, scale, scale2, counters, SPLIT_MAX_BLOCKS, st), "norm kernel");
+  Shape shape[2];
+  OutSpec out[2];
+  int first[2] = {0, part[0].n()};
+  for (int k = 0; k < 2; ++k) {
+    const int n = part[k].n();
+    if (n == 0) continue;
+    const canz_group& g = *part[k].proto;
+    shape[k] = make_shape(g);
+    PtrTable grad{}, mom{};
+    OutSpec& o = out[k];
+    o = OutSpec{};
+    const int n_out = hp.out_mode == CANZ_OUT_DELTA ? n * g.tp : n;
+    for (int i = 0; i < n * g.tp; ++i) grad.p[i] = const_cast<void*>(part[k].grad[i]);
+    for (int i = 0; i < n; ++i) mom.p[i] = part[k].mom[i];
+    for (int i = 0; i < n_out; ++i) o.out.p[i] = part[k].out[i];
+    o.out_dtype = g.out_dtype;
+    o.out_mode = hp.out_mode;
+    o.decay = static_cast<float>(1.0 - static_cast<double>(hp.lr) * static_cast<double>(hp.weight_decay));
+    o.neg_lr_scale = static_cast<float>(-static_cast<double>(hp.lr) * update_scale(g, hp.scale_mode));
+    CANZ_HIP(CANZ_KERNEL_MOMENTUM,
+             launch_momentum<T>(shape[k], n, grad, g.grad_dtype, mom, hp.beta, hp.nesterov, xw + first[k] * x_elems,
+                                xt[0] + first[k] * x_elems, partial + static_cast<int64_t>(first[k]) * tiles, st),
+             "momentum kernel");
+  }
+  CANZ_HIP(CANZ_KERNEL_NORM, launch_norm_scale(nb, tiles, partial, hp.eps, scale, scale2, st), "norm kernel");
 
   if (hp.ns_steps == 0) {
-    const T* straight = s.tall ? xt[0] : xw;
-    const int64_t ld = s.tall ? s.mp : s.np;
-    CANZ_HIP(CANZ_KERNEL_APPLY, launch_apply<T>(s, nb, straight, ld, s.mp * s.np, scale, o, st), "apply kernel");
+    for (int k = 0; k < 2; ++k) {
+      if (part[k].n() == 0) continue;
+      const Shape& s = shape[k];
+      const T* straight = (s.tall ? xt[0] : xw) + first[k] * x_elems;
+      const int64_t ld = s.tall ? s.mp : s.np;
+      CANZ_HIP(CANZ_KERNEL_APPLY, launch_apply<T>(s, part[k].n(), straight, ld, x_elems, scale + first[k], out[k], st),
+               "apply kernel");
+    }
     return CANZ_OK;
   }
 
-  GemmDims gram{s.mp, s.mp, s.np, s.np, s.np, s.mp * s.np, s.mp * s.np, nb};
-  GemmDims poly{s.mp, s.mp, s.mp, s.mp, s.mp, s.mp * s.mp, s.mp * s.mp, nb};
-  GemmDims upd{s.mp, s.np, s.mp, s.mp, s.mp, s.mp * s.mp, s.np * s.mp, nb};
-  // last product in the caller's orientation: for a tall matrix the roles of B and XT swap
-  GemmDims fin = s.tall ? GemmDims{s.np, s.mp, s.mp, s.mp, s.mp, s.np * s.mp, s.mp * s.mp, nb} : upd;
+  const Shape& s = s0;
+  GemmDims gram{s.mp, s.mp, s.np, s.np, s.np, x_elems, x_elems, nb};
+  GemmDims poly{s.mp, s.mp, s.mp, s.mp, s.mp, a_elems, a_elems, nb};
+  GemmDims upd{s.mp, s.np, s.mp, s.mp, s.mp, a_elems, x_elems, nb};
   int cur = 0;
   for (int it = 0; it < hp.ns_steps; ++it) {
     const float* sc1 = it == 0 ? scale : nullptr;
@@ -221,17 +249,34 @@ int run_batch(const canz_group& g, const void* const* g_grad, void* const* g_mom
     if (is_bf16) {
       CANZ_HIP(CANZ_KERNEL_GRAM, launch_gram_bf16(gram, xw, a, sc2, split, st), "gram kernel");
       CANZ_HIP(CANZ_KERNEL_POLY, launch_poly_bf16(poly, a, bm, hp.a, hp.b, hp.c, split, st), "poly kernel");
-      if (!last)
-        CANZ_HIP(CANZ_KERNEL_UPDATE, launch_update_bf16(upd, bm, xt[cur], xw, xt[cur ^ 1], sc1, split, st), "update kernel");
-      else
-        CANZ_HIP(CANZ_KERNEL_FINAL, launch_final_bf16(fin, s.tall ? (const void*)xt[cur] : (const void*)bm, s.tall ? (const void*)bm : (const void*)xt[cur], sc1, split, s, o, st), "final kernel");
     } else {
       CANZ_HIP(CANZ_KERNEL_GRAM, launch_gram_f32(gram, xw, a, sc2, st), "gram kernel");
       CANZ_HIP(CANZ_KERNEL_POLY, launch_poly_f32(poly, a, bm, hp.a, hp.b, hp.c, st), "poly kernel");
-      if (!last)
-        CANZ_HIP(CANZ_KERNEL_UPDATE, launch_update_f32(upd, bm, xt[cur], xw, xt[cur ^ 1], sc1, st), "update kernel");
+    }
+    if (!last) {
+      if (is_bf16)
+        CANZ_HIP(CANZ_KERNEL_UPDATE, launch_update_bf16(upd, bm, xt[cur], xw, xt[cur ^ 1], sc1, split, st), "update kernel");
       else
-        CANZ_HIP(CANZ_KERNEL_FINAL, launch_final_f32(fin, s.tall ? (const void*)xt[cur] : (const void*)bm, s.tall ? (const void*)bm : (const void*)xt[cur], sc1, s, o, st), "final kernel");
+        CANZ_HIP(CANZ_KERNEL_UPDATE, launch_update_f32(upd, bm, xt[cur], xw, xt[cur ^ 1], sc1, st), "update kernel");
+    } else {
+      // last product, written in the caller's orientation: for the tall part the roles of
+      // the polynomial and of X swap, so that C comes out as rows x cols
+      for (int k = 0; k < 2; ++k) {
+        const int n = part[k].n();
+        if (n == 0) continue;
+        const T* bk = bm + first[k] * a_elems;
+        const T* xk = xt[cur] + first[k] * x_elems;
+        const float* sk = sc1 ? sc1 + first[k] : nullptr;
+        GemmDims fin = upd;
+        if (shape[k].tall) fin = GemmDims{s.np, s.mp, s.mp, s.mp, s.mp, x_elems, a_elems, n};
+        fin.nb = n;
+        const void* P = shape[k].tall ? static_cast<const void*>(xk) : static_cast<const void*>(bk);
+        const void* Q = shape[k].tall ? static_cast<const void*>(bk) : static_cast<const void*>(xk);
+        if (is_bf16)
+          CANZ_HIP(CANZ_KERNEL_FINAL, launch_final_bf16(fin, P, Q, sk, split, shape[k], out[k], st), "final kernel");
+        else
+          CANZ_HIP(CANZ_KERNEL_FINAL, launch_final_f32(fin, P, Q, sk, shape[k], out[k], st), "final kernel");
+      }
     }
     cur ^= 1;
   }
@@ -277,24 +322,25 @@ extern "C" int canz_muon_step(const canz_group* g, int32_t n_groups, const canz_
 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
-  std::vector<const void*> grad;
-  std::vector<void*> mom, out;
-  return for_each_batch(g, n_groups, [&](const canz_group& proto, int gi, int mi, int count) {
-    // gather the batch's pointers (it may continue into the following groups)
-    grad.clear(), mom.clear(), out.clear();
-    const int per_out = hp->out_mode == CANZ_OUT_DELTA ? proto.tp : 1;
+  Part part[2];
+  return for_each_batch(g, n_groups, [&](const canz_group&, int gi, int mi, int count) {
+    // gather the batch's pointers by orientation (the batch may continue into following groups)
+    for (Part& p : part) p.proto = nullptr, p.grad.clear(), p.mom.clear(), p.out.clear();
     for (int left = count; left > 0; ++gi, mi = 0) {
-      const int take = std::min(left, g[gi].n_mats - mi);
+      const canz_group& src = g[gi];
+      const int take = std::min(left, src.n_mats - mi);
+      if (take <= 0) continue;
+      Part& p = part[src.rows > src.cols ? 1 : 0];
+      if (!p.proto) p.proto = &src;
+      const int per_out = hp->out_mode == CANZ_OUT_DELTA ? src.tp : 1;
       for (int m = mi; m < mi + take; ++m) {
-        for (int f = 0; f < proto.tp; ++f) grad.push_back(g[gi].grad[m * proto.tp + f]);
-        mom.push_back(g[gi].mom[m]);
-        for (int f = 0; f < per_out; ++f) out.push_back(g[gi].out[m * per_out + f]);
+        for (int f = 0; f < src.tp; ++f) p.grad.push_back(src.grad[m * src.tp + f]);
+        p.mom.push_back(src.mom[m]);
+        for (int f = 0; f < per_out; ++f) p.out.push_back(src.out[m * per_out + f]);
       }
       left -= take;
     }
-    return hp->precision == CANZ_PREC_BF16
-               ? run_batch<__bf16>(proto, grad.data(), mom.data(), out.data(), count, *hp, ws, st)
-               : run_batch<float>(proto, grad.data(), mom.data(), out.data(), count, *hp, ws, st);
+    return hp->precision == CANZ_PREC_BF16 ? run_batch<__bf16>(part, *hp, ws, st) : run_batch<float>(part, *hp, ws, st);
   });
 }
 

@@ -245,3 +245,32 @@ def test_extreme_aspect_ratios(canz, shape):
         dg = DeviceGroup(canz, rows, cols, grads, zeros)
         run_step(canz, [dg], hp)
         _check_group(canz, dg, grads, zeros, None, hp, "%dx%d prec%d" % (rows, cols, precision))
+
+
+@pytest.mark.parametrize("precision", [0, 1])
+@pytest.mark.parametrize("tp", [1, 2])
+def test_transposed_shapes_share_a_launch(canz, precision, tp):
+    """rows x cols and cols x rows matrices are batched into the same launches (both run in
+    the wide orientation): parity for each, and the same bits as when run on their own."""
+    shapes = [(320, 208, 3), (208, 320, 2), (320, 208, 1)]
+    hp = canz.Hparams(out_mode=canz.OUT_DELTA if tp > 1 else canz.OUT_PARAM, precision=precision)
+
+    def make(k):
+        rows, cols, n = shapes[k]
+        whole = [W.gen_grad(97 + k, i, rows, cols)[0] for i in range(n)]
+        grads = [W.split_columns(g, tp) for g in whole] if tp > 1 else whole
+        moms = [W.gen_normal_f32(97 + k, i, 5, rows, cols, 0.01) for i in range(n)]
+        params = None if tp > 1 else [W.gen_param(97 + k, i, rows, cols) for i in range(n)]
+        dg = DeviceGroup(canz, rows, cols, grads, moms, outs=params, tp=tp)
+        return dg, grads, moms, params
+
+    together = [make(k) for k in range(3)]
+    run_step(canz, [t[0] for t in together], hp)
+    for k, (dg, grads, moms, params) in enumerate(together):
+        _check_group(canz, dg, grads, moms, params, hp, "merged batch, group %d, tp %d, prec %d" % (k, tp, precision))
+    for k in range(3):
+        alone = make(k)[0]
+        run_step(canz, [alone], hp)
+        for i in range(alone.n):
+            assert np.array_equal(alone.out_host(i), together[k][0].out_host(i))
+            assert np.array_equal(alone.mom_host(i), together[k][0].mom_host(i))
