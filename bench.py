@@ -114,10 +114,16 @@ def pick_tp_share(canz, W, cfg, cmax_bytes):
                 groups[-1][1].append(t)
             else:
                 groups.append((shape, [t], mg))
+    # one library call per TP micro-group (each sits between its own pair of exchanges)
+    calls, start = [], 0
+    for k in range(1, len(groups) + 1):
+        if k == len(groups) or groups[k][2] is not groups[start][2]:
+            calls.append((start, k))
+            start = k
     groups = [g[1] for g in groups]
     mean = sum(per_rank) / len(per_rank)
     diag = dict(rank=rank, n_ranks=s["tp"], alpha=None, r_lb_numel=max(per_rank) / mean if mean else 1.0,
-                planner_ms=plan_ms, tp_micro_groups=len(mgroups), cmax_bytes=cmax_bytes,
+                planner_ms=plan_ms, tp_micro_groups=len(mgroups), cmax_bytes=cmax_bytes, calls=calls,
                 largest_group_load_elems=max(loads) if loads else 0)
     return s, rank, groups, diag
 
@@ -229,8 +235,11 @@ def main():
 
     stream = torch.cuda.current_stream().cuda_stream
 
+    calls = diag.pop("calls", [(0, len(dgroups))])
+
     def step():
-        canz.canz_muon_step(dgroups, hp, ws, ws_bytes, stream)
+        for lo, hi in calls:
+            canz.canz_muon_step(dgroups[lo:hi], hp, ws, ws_bytes, stream)
 
     if args.calibration_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB
@@ -250,7 +259,8 @@ def main():
         side = torch.cuda.Stream()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
-            canz.canz_muon_step(dgroups, hp, ws, ws_bytes, torch.cuda.current_stream().cuda_stream)
+            for lo, hi in calls:
+                canz.canz_muon_step(dgroups[lo:hi], hp, ws, ws_bytes, torch.cuda.current_stream().cuda_stream)
         torch.cuda.synchronize()
         canz.canz_profile_enable(launches_per_step * args.steps + 8)
         for i in range(args.steps):                 # eager pass for the per-kernel breakdown, not timed
