@@ -15,7 +15,7 @@ def pytest_configure(config):
 def ensure_built():
     """Load what is built; build only if nothing is."""
     from paper_2602_06079_amd import build as _build
-    if not os.path.exists(_build.OUT):
+    if not os.path.exists(_build.OUT) or not os.path.exists(_build.EXAMPLE_OUT):
         _build.build()
     return _build.OUT
 
