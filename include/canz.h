@@ -210,7 +210,10 @@ int canz_muon_workspace_bytes(const canz_group* g, int32_t n_groups,
  *                   caller-owned; contents are scratch and need not be initialised
  *   hip_stream      a hipStream_t (NULL = the null stream)
  * Returns after enqueueing; completion follows stream order.  Results per matrix do not
- * depend on which other matrices share the group or the call.
+ * depend on which other matrices share the group or the call.  The call issues kernel
+ * launches only (no memset, no copy, no allocation, no synchronisation), so with profiling
+ * off it may be recorded into a HIP graph; the pointer tables are baked into the recorded
+ * launches.  Calls on different streams may overlap if their workspaces are distinct.
  * Errors: CANZ_EINVAL (null pointers, n_mats < 0, tp outside 1..8, ns_steps < 0),
  * CANZ_ESHAPE (cols not divisible by tp, fragment width not a multiple of 8, an extent
  * above 4194240),
