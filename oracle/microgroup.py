@@ -5,7 +5,7 @@ Test infrastructure only (see the package docstring).
 The paper's micro-groups (Sec. 4, Algorithm 2) fuse the tensors of one
 All-to-All; the per-rank step built here batches the matrices a rank owns so
 that one launch handles several of them, which needs equal shapes.  The rule,
-stated once here and in the design doc:
+stated once here and in the design notes:
 
 1. take the ids with owner == rank in ascending id;
 2. a shape class is the exact triple (rows, cols, dtype) - a matrix and its

@@ -7,7 +7,7 @@ independent implementation using the same order reproduces every decision
 bit for bit.  ``partition_alpha_exact`` replays the same algorithm in exact
 rationals and reports how close any decision came to a tie.
 
-Readings of points the paper leaves open (each is also listed in the design doc):
+Readings of points the paper leaves open (the design notes of the repository list them too):
 
 * cuts are parameter indices inside the bucket (the domain of Phi_i in the
   "Define" lines of Algorithm 1), not element offsets;

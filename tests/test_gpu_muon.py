@@ -192,16 +192,16 @@ def test_zero_steps_reduces_to_normalised_gradient(canz, precision):
 
 @pytest.mark.parametrize("variant", ["cubic", "nesterov", "one_step", "three_steps", "scale_none"])
 def test_hyper_parameter_variants(canz, variant):
-    rows, cols = 256, 640
     kw = dict(cubic=dict(a=1.5, b=-0.5, c=0.0, ns_steps=8), nesterov=dict(nesterov=True),
               one_step=dict(ns_steps=1), three_steps=dict(ns_steps=3), scale_none=dict(scale_mode=0))[variant]
-    grads = [W.gen_grad(97, i, rows, cols)[0] for i in range(2)]
-    moms = [W.gen_normal_f32(97, i, 3, rows, cols, 0.02) for i in range(2)]
-    for precision in (0, 1):
-        hp = canz.Hparams(precision=precision, out_mode=canz.OUT_DELTA, **kw)
-        dg = DeviceGroup(canz, rows, cols, grads, moms)
-        run_step(canz, [dg], hp)
-        _check_group(canz, dg, grads, moms, None, hp, "%s prec%d" % (variant, precision))
+    for rows, cols in ((256, 640), (640, 256)):        # wide, and tall (runs transposed)
+        grads = [W.gen_grad(97, i, rows, cols)[0] for i in range(2)]
+        moms = [W.gen_normal_f32(97, i, 3, rows, cols, 0.02) for i in range(2)]
+        for precision in (0, 1):
+            hp = canz.Hparams(precision=precision, out_mode=canz.OUT_DELTA, **kw)
+            dg = DeviceGroup(canz, rows, cols, grads, moms)
+            run_step(canz, [dg], hp)
+            _check_group(canz, dg, grads, moms, None, hp, "%s %dx%d prec%d" % (variant, rows, cols, precision))
 
 
 @pytest.mark.parametrize("precision", [0, 1])
