@@ -523,13 +523,17 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
   // clusters the loads and the matrix pipe drains meanwhile).
 #define CANZ_FENCE() __builtin_amdgcn_sched_barrier(0)
   // One k-step on stage `cur`; `nxt` holds step kt+1, `prv` (free since the barrier of the
-  // previous step) receives the second half of step kt+3, `cur` after this step's barrier
-  // the first half of step kt+4.  Fetch indices are clamped instead of guarded (a branch
-  // here costs the compiler its knowledge of which stage is in flight, and the number of
-  // loads in flight must not depend on kt); the clamped refetches land in stages nobody
-  // reads any more.
-  auto k_step = [&](__bf16* cur, const __bf16* nxt, __bf16* prv, int kt) {
-    const int64_t k3 = min(kt + 3, nk - 1), k4 = min(kt + 4, nk - 1);
+  // previous step) receives the Q panel of step kt+3, `cur` after this step's barrier the P
+  // panel of step kt+4.  The loads of the whole tile are issued in the order P0 Q0 P1 Q1 ...;
+  // in the middle of step kt the youngest is Q(kt+3), so "all but the 16 youngest have
+  // landed" means that step kt+1 is complete.  The last four steps of a tile have nothing
+  // left to request: they are separate instances (compile-time flags, no branch in the
+  // body - a branch would cost the compiler its count of the loads in flight) with the
+  // wait counts that follow from the shorter queue.
+  using Yes = std::true_type;
+  using No = std::false_type;
+  auto k_step = [&](auto fetch_q, auto fetch_p, auto read_next, auto wait_code, __bf16* cur, const __bf16* nxt,
+                    __bf16* prv, int kt) {
 #pragma unroll
     for (int idx = 0; idx < 16; ++idx) {
       mma_one(0, idx);
@@ -538,45 +542,58 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
         frag_one(cur, 1, 1, idx);  // second half-step's operands, land under the next 8 MFMAs
         CANZ_FENCE();
       }
-      if ((idx & 3) == 2) {
-        fetch_one(prv, k3, 4 + (idx >> 2));  // Q panel of step kt+3
+      if (decltype(fetch_q)::value && (idx & 3) == 2) {
+        fetch_one(prv, kt + 3, 4 + (idx >> 2));  // Q panel of step kt+3
         CANZ_FENCE();
       }
     }
-    // own share of step kt+1 has landed (16 younger loads may be in flight); this wavefront's
-    // reads of `cur` are complete.  simm16 = vmcnt[3:0] | expcnt 7 << 4 | lgkmcnt << 8 | vmcnt[5:4] << 14
-    __builtin_amdgcn_s_waitcnt(0x4070);  // vmcnt(16) lgkmcnt(0)
+    // own share of step kt+1 has landed; this wavefront's reads of `cur` are complete.
+    // simm16 = vmcnt[3:0] | expcnt 7 << 4 | lgkmcnt << 8 | vmcnt[5:4] << 14
+    __builtin_amdgcn_s_waitcnt(decltype(wait_code)::value);
     __builtin_amdgcn_s_barrier();
     CANZ_FENCE();
 #pragma unroll
     for (int idx = 0; idx < 16; ++idx) {
       mma_one(1, idx);
       CANZ_FENCE();
-      if (idx < 8) {
+      if (decltype(read_next)::value && idx < 8) {
         frag_one(nxt, 0, 0, idx);  // first operands of step kt+1
         CANZ_FENCE();
       }
-      if ((idx & 3) == 2) {
-        fetch_one(cur, k4, idx >> 2);  // P panel of step kt+4
+      if (decltype(fetch_p)::value && (idx & 3) == 2) {
+        fetch_one(cur, kt + 4, idx >> 2);  // P panel of step kt+4
         CANZ_FENCE();
       }
     }
   };
+  using Vm16 = std::integral_constant<int, 0x4070>;  // vmcnt(16) lgkmcnt(0)
+  using Vm8 = std::integral_constant<int, 0x0078>;   // vmcnt(8)  lgkmcnt(0)
+  using Vm0 = std::integral_constant<int, 0x0070>;   // vmcnt(0)  lgkmcnt(0)
 
+  // steps 0..2 whole and the P panel of step 3; its Q panel is the first request of step 0
   fetch(st0, 0);
   fetch(st1, 1);
   fetch(st2, 2);
-  fetch(st3, 3);
+#pragma unroll
+  for (int idx = 0; idx < 4; ++idx) fetch_one(st3, 3, idx);
   __syncthreads();
 #pragma unroll
   for (int idx = 0; idx < 8; ++idx) frag_one(st0, 0, 0, idx);
-  for (int kt = 0; kt < nk; kt += 4) {
-    k_step(st0, st1, st3, kt);
-    k_step(st1, st2, st0, kt + 1);
-    k_step(st2, st3, st1, kt + 2);
-    k_step(st3, st0, st2, kt + 3);
+  for (int kt = 0; kt < nk - 4; kt += 4) {
+    k_step(Yes{}, Yes{}, Yes{}, Vm16{}, st0, st1, st3, kt);
+    k_step(Yes{}, Yes{}, Yes{}, Vm16{}, st1, st2, st0, kt + 1);
+    k_step(Yes{}, Yes{}, Yes{}, Vm16{}, st2, st3, st1, kt + 2);
+    k_step(Yes{}, Yes{}, Yes{}, Vm16{}, st3, st0, st2, kt + 3);
   }
-  __syncthreads();  // the clamped tail fetches have drained; LDS is free for the epilogue
+  {
+    // the tail: Q(nk-1) is the last request; then the queue drains: 16, 8, 0 younger loads
+    const int kt = nk - 4;
+    k_step(Yes{}, No{}, Yes{}, Vm16{}, st0, st1, st3, kt);
+    k_step(No{}, No{}, Yes{}, Vm8{}, st1, st2, st0, kt + 1);
+    k_step(No{}, No{}, Yes{}, Vm0{}, st2, st3, st1, kt + 2);
+    k_step(No{}, No{}, No{}, Vm0{}, st3, st0, st2, kt + 3);
+  }
+  __syncthreads();  // every wavefront is done with the stages; LDS is free for the epilogue
 #undef CANZ_FENCE
 
   if (SPLIT) {
