@@ -496,13 +496,8 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
     for (int idx = 0; idx < 8; ++idx) fetch_one(st, kt, idx);
   };
 
+  // not cleared: the first 16 MFMAs of a tile take the constant 0 as their addend
   f32x16 acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   // MFMA operand fragments, double-buffered in registers: idx 0..3 -> rows of P, 4..7 -> rows of Q
   const int frag_row = lane & 31, frag_kg = lane >> 5;
@@ -514,9 +509,14 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
       fb[set][idx - 4] =
           *reinterpret_cast<const bf16x8*>(st + QOFF + swz(wn * 128 + (idx - 4) * 32 + frag_row, kk * 2 + frag_kg));
   };
-  auto mma_one = [&](int set, int idx) {
+  auto mma_one = [&](auto first, int set, int idx) {
     const int i = idx >> 2, j = idx & 3;
-    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+    if (decltype(first)::value) {
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], zero, 0, 0, 0);
+    } else {
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+    }
   };
 
   // The issue order below is pinned with scheduling fences (left to itself the compiler
@@ -532,11 +532,11 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
   // wait counts that follow from the shorter queue.
   using Yes = std::true_type;
   using No = std::false_type;
-  auto k_step = [&](auto fetch_q, auto fetch_p, auto read_next, auto wait_code, __bf16* cur, const __bf16* nxt,
-                    __bf16* prv, int kt) {
+  auto k_step = [&](auto first, auto fetch_q, auto fetch_p, auto read_next, auto wait_code, __bf16* cur,
+                    const __bf16* nxt, __bf16* prv, int kt) {
 #pragma unroll
     for (int idx = 0; idx < 16; ++idx) {
-      mma_one(0, idx);
+      mma_one(first, 0, idx);
       CANZ_FENCE();
       if (idx < 8) {
         frag_one(cur, 1, 1, idx);  // second half-step's operands, land under the next 8 MFMAs
@@ -554,7 +554,7 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
     CANZ_FENCE();
 #pragma unroll
     for (int idx = 0; idx < 16; ++idx) {
-      mma_one(1, idx);
+      mma_one(No{}, 1, idx);
       CANZ_FENCE();
       if (decltype(read_next)::value && idx < 8) {
         frag_one(nxt, 0, 0, idx);  // first operands of step kt+1
@@ -579,19 +579,25 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
   __syncthreads();
 #pragma unroll
   for (int idx = 0; idx < 8; ++idx) frag_one(st0, 0, 0, idx);
-  for (int kt = 0; kt < nk - 4; kt += 4) {
-    k_step(Yes{}, Yes{}, Yes{}, Vm16{}, st0, st1, st3, kt);
-    k_step(Yes{}, Yes{}, Yes{}, Vm16{}, st1, st2, st0, kt + 1);
-    k_step(Yes{}, Yes{}, Yes{}, Vm16{}, st2, st3, st1, kt + 2);
-    k_step(Yes{}, Yes{}, Yes{}, Vm16{}, st3, st0, st2, kt + 3);
+  // first four steps (the very first one starts the accumulators), whole groups of four,
+  // last four steps; nk is a multiple of 4 and at least 8
+  k_step(Yes{}, Yes{}, Yes{}, Yes{}, Vm16{}, st0, st1, st3, 0);
+  k_step(No{}, Yes{}, Yes{}, Yes{}, Vm16{}, st1, st2, st0, 1);
+  k_step(No{}, Yes{}, Yes{}, Yes{}, Vm16{}, st2, st3, st1, 2);
+  k_step(No{}, Yes{}, Yes{}, Yes{}, Vm16{}, st3, st0, st2, 3);
+  for (int kt = 4; kt < nk - 4; kt += 4) {
+    k_step(No{}, Yes{}, Yes{}, Yes{}, Vm16{}, st0, st1, st3, kt);
+    k_step(No{}, Yes{}, Yes{}, Yes{}, Vm16{}, st1, st2, st0, kt + 1);
+    k_step(No{}, Yes{}, Yes{}, Yes{}, Vm16{}, st2, st3, st1, kt + 2);
+    k_step(No{}, Yes{}, Yes{}, Yes{}, Vm16{}, st3, st0, st2, kt + 3);
   }
   {
     // the tail: Q(nk-1) is the last request; then the queue drains: 16, 8, 0 younger loads
     const int kt = nk - 4;
-    k_step(Yes{}, No{}, Yes{}, Vm16{}, st0, st1, st3, kt);
-    k_step(No{}, No{}, Yes{}, Vm8{}, st1, st2, st0, kt + 1);
-    k_step(No{}, No{}, Yes{}, Vm0{}, st2, st3, st1, kt + 2);
-    k_step(No{}, No{}, No{}, Vm0{}, st3, st0, st2, kt + 3);
+    k_step(No{}, Yes{}, No{}, Yes{}, Vm16{}, st0, st1, st3, kt);
+    k_step(No{}, No{}, No{}, Yes{}, Vm8{}, st1, st2, st0, kt + 1);
+    k_step(No{}, No{}, No{}, Yes{}, Vm0{}, st2, st3, st1, kt + 2);
+    k_step(No{}, No{}, No{}, No{}, Vm0{}, st3, st0, st2, kt + 3);
   }
   __syncthreads();  // every wavefront is done with the stages; LDS is free for the epilogue
 #undef CANZ_FENCE
