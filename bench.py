@@ -26,8 +26,8 @@ PEAK_HBM_GBS = 8000.0
 # two rocprofv3 --pmc runs summarised in profiles/hbm_traffic_config4.md (FETCH_SIZE scaled by
 # 2.000, WRITE_SIZE by 1.000, the factors a plain 1 GiB copy gives).  Counters cannot be read
 # from inside this process, so the figures are carried here; other workloads report null.
-MEASURED_TRAFFIC_BYTES = {(4, "bf16", 1): {"gram": 3.91e9 + 0.22e9, "poly": 0.97e9 + 0.21e9,
-                                           "update": 9.76e9 + 2.23e9, "final": 10.96e9 + 2.37e9}}
+MEASURED_TRAFFIC_BYTES = {(4, "bf16", 1): {"gram": 3.90e9 + 0.21e9, "poly": 0.97e9 + 0.21e9,
+                                           "update": 10.14e9 + 2.24e9, "final": 10.60e9 + 2.37e9}}
 
 
 def log(msg):
