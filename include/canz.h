@@ -75,9 +75,11 @@ const char* canz_version(void);
  *   load_out     [n_ranks] final accumulated load L_r
  * Real-valued steps run in IEEE fp64 in a fixed order (mu = total/R; deficits summed by
  * ascending rank; v = (1-alpha)*(1/R) + alpha*(d/D); target = W^k * v; C += target), so
- * results are reproducible bit for bit.  Total load must stay below 2^53.
+ * results are reproducible bit for bit.  Total load must stay below 2^53 (integers above
+ * that are not exact in fp64).
  * Errors: CANZ_EINVAL for null pointers, n_ranks < 1, alpha outside [0,1], malformed
- * bucket_off, negative cost; CANZ_EUNSUPPORTED for an unknown cost_kind.
+ * bucket_off, negative cost, a load or a total load of 2^53 or more (computed without
+ * wrap-around); CANZ_EUNSUPPORTED for an unknown cost_kind.
  */
 int canz_partition_alpha(int64_t n_mats, const int64_t* rows, const int64_t* cols,
                          const int64_t* cost, int32_t cost_kind,

@@ -19,7 +19,12 @@ extern "C" int canz_microgroup_plan(int64_t n_mats, const int64_t* rows, const i
   if (n_mats > 0 && (!rows || !cols || !dtype || !owner)) return fail(CANZ_EINVAL, "null input pointer");
   if (max_mats < 0 || cmax_bytes < 0) return fail(CANZ_EINVAL, "caps must be non-negative");
   int64_t n_owned = 0;
-  for (int64_t p = 0; p < n_mats; ++p) n_owned += owner[p] == rank;
+  for (int64_t p = 0; p < n_mats; ++p) {
+    if (owner[p] != rank) continue;
+    ++n_owned;
+    if (rows[p] < 0 || cols[p] < 0 || rows[p] >= (int64_t(1) << 31) || cols[p] >= (int64_t(1) << 31))
+      return fail(CANZ_EINVAL, "shape of matrix %lld outside [0, 2^31)", (long long)p);
+  }
   if (n_owned > 0 && !member_out) return fail(CANZ_EINVAL, "null output pointer");  // an array of size zero may be null
 
   using Key = std::tuple<int64_t, int64_t, int32_t>;
@@ -47,7 +52,7 @@ extern "C" int canz_microgroup_plan(int64_t n_mats, const int64_t* rows, const i
     int64_t in_group = 0;
     for (int64_t p : *c.ids) {
       const bool full = (max_mats && in_group == max_mats) ||
-                        (cmax_bytes && (in_group + 1) * one_bytes > cmax_bytes);
+                        (cmax_bytes && static_cast<__int128>(in_group + 1) * one_bytes > cmax_bytes);
       if (in_group > 0 && full) {
         group_off_out[++n_groups] = n_members;
         in_group = 0;

@@ -13,9 +13,14 @@
 
 namespace {
 
-int64_t ns_flops(int64_t rows, int64_t cols) {
-  const int64_t m = std::min(rows, cols), n = std::max(rows, cols);
-  return 5 * (4 * m * m * n + 2 * m * m * m);
+constexpr __int128 LOAD_LIMIT = __int128(1) << 53;  // loads above this are not exact in fp64
+
+// W(p) in 128-bit arithmetic; -1 if it does not stay below LOAD_LIMIT
+int64_t checked_cost(int64_t rows, int64_t cols, int cost_kind) {
+  const __int128 m = std::min(rows, cols), n = std::max(rows, cols);
+  if (n >= (int64_t(1) << 31)) return -1;  // keeps every product below 2^127
+  const __int128 w = cost_kind == CANZ_COST_NUMEL ? m * n : 5 * (4 * m * m * n + 2 * m * m * m);
+  return w < LOAD_LIMIT ? static_cast<int64_t>(w) : -1;
 }
 
 }  // namespace
@@ -45,9 +50,11 @@ extern "C" int canz_partition_alpha(int64_t n_mats, const int64_t* rows, const i
       w[p] = cost[p];
     } else {
       if (rows[p] < 0 || cols[p] < 0) return fail(CANZ_EINVAL, "negative shape at %lld", (long long)p);
-      w[p] = cost_kind == CANZ_COST_NUMEL ? rows[p] * cols[p] : ns_flops(rows[p], cols[p]);
+      w[p] = checked_cost(rows[p], cols[p], cost_kind);
+      if (w[p] < 0) return fail(CANZ_EINVAL, "load of parameter %lld exceeds 2^53", (long long)p);
     }
     if (w[p] < 0) return fail(CANZ_EINVAL, "negative cost at %lld", (long long)p);
+    if (w[p] >= LOAD_LIMIT) return fail(CANZ_EINVAL, "load of parameter %lld exceeds 2^53", (long long)p);
   }
 
   const int R = n_ranks;
@@ -59,11 +66,15 @@ extern "C" int canz_partition_alpha(int64_t n_mats, const int64_t* rows, const i
     int64_t* ph = phi.data() + bucket_off[i] + i;
     ph[0] = 0;
     const int64_t len = bucket_off[i + 1] - bucket_off[i];
-    for (int64_t u = 0; u < len; ++u) ph[u + 1] = ph[u] + w[bucket_off[i] + u];
+    for (int64_t u = 0; u < len; ++u) {
+      // both terms are below 2^53, so the sum cannot wrap before this test trips
+      ph[u + 1] = ph[u] + w[bucket_off[i] + u];
+      if (ph[u + 1] >= LOAD_LIMIT) return fail(CANZ_EINVAL, "total load exceeds 2^53");
+    }
     wk[i] = ph[len];
     total += wk[i];
+    if (total >= LOAD_LIMIT) return fail(CANZ_EINVAL, "total load exceeds 2^53");
   }
-  if (total >= (int64_t(1) << 53)) return fail(CANZ_EINVAL, "total load exceeds 2^53");
 
   std::vector<int64_t> order(n_buckets);
   std::iota(order.begin(), order.end(), int64_t(0));

@@ -48,8 +48,12 @@ extern "C" int canz_tp_schedule(int64_t n_mats, const int64_t* cost, int32_t n_r
   if (n_mats > 0 && !cost) return fail(CANZ_EINVAL, "null cost");
   if (n_ranks < 1) return fail(CANZ_EINVAL, "n_ranks must be >= 1");
   if (cmax < 0) return fail(CANZ_EINVAL, "capacity must be non-negative");
-  for (int64_t p = 0; p < n_mats; ++p)
+  __int128 total = 0;
+  for (int64_t p = 0; p < n_mats; ++p) {
     if (cost[p] < 0) return fail(CANZ_EINVAL, "negative cost at %lld", (long long)p);
+    total += cost[p];
+  }
+  if (total >= (__int128(1) << 62)) return fail(CANZ_EINVAL, "total cost exceeds 2^62");  // rank loads are int64 sums
 
   std::vector<int64_t> order(n_mats);
   std::iota(order.begin(), order.end(), int64_t(0));

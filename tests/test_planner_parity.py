@@ -140,3 +140,24 @@ def test_balance_report_runs_and_alpha1_beats_naive(canz):
     naive = float([l for l in rows if "per bucket" in l][0].split("|")[3])
     best = float([l for l in rows if "numel, alpha = 1.0" in l][0].split("|")[3])
     assert best < naive and best < 1.05
+
+
+def test_overflowing_loads_are_errors_not_wraparound(canz):
+    """Loads that do not stay exact (2^53 and above) and sums that would wrap int64 are refused."""
+    big = 1 << 52
+    with pytest.raises(canz.CanzError):
+        canz.canz_partition_alpha([1, 1], [1, 1], [0, 2], 2, 1.0, cost=[big, big])
+    with pytest.raises(canz.CanzError):
+        canz.canz_partition_alpha([1], [1], [0, 1], 2, 1.0, cost=[1 << 62])
+    with pytest.raises(canz.CanzError):        # 5 * (4 m^2 n + 2 m^3) far above 2^53
+        canz.canz_partition_alpha([1 << 20], [1 << 20], [0, 1], 2, 1.0, cost_kind=canz.COST_NS_FLOPS)
+    with pytest.raises(canz.CanzError):        # rows * cols would wrap int64
+        canz.canz_partition_alpha([1 << 40], [1 << 40], [0, 1], 2, 1.0)
+    with pytest.raises(canz.CanzError):
+        canz.canz_tp_schedule([1 << 61, 1 << 61, 1 << 61], 2, (1 << 63) - 1)
+    with pytest.raises(canz.CanzError):
+        canz.canz_microgroup_plan([1 << 40], [8], [1], [0], 0)
+    # just below the limits still works, bit-exact against the oracle
+    ok = (1 << 51) - 3
+    got = canz.canz_partition_alpha([1, 1], [1, 1], [0, 2], 2, 1.0, cost=[ok, ok])
+    assert got[1].tolist() == OP.partition_alpha([1, 1], [1, 1], [0, 2], 2, 1.0, cost=[ok, ok])[1]
