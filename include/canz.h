@@ -198,8 +198,11 @@ typedef struct {
 } canz_muon_hparams;
 
 /*
- * canz_muon_workspace_bytes - device scratch needed by canz_muon_step for these groups
- * (the maximum over groups; groups run one after another on the stream).
+ * canz_muon_workspace_bytes - device scratch needed by canz_muon_step for these groups:
+ * the maximum over the launch batches the call will form (consecutive matrices of equal
+ * dtypes and equal shape up to a transpose, at most 128 / tp of them and at most 2^30
+ * padded elements per batch; batches run one after another on the stream, so at most
+ * about 10 GB are asked for whatever the share).
  * g: host array [n_groups]; pointer tables inside may be NULL for this call.
  */
 int canz_muon_workspace_bytes(const canz_group* g, int32_t n_groups,
