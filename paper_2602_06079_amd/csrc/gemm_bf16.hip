@@ -78,8 +78,8 @@ __device__ __forceinline__ int swz(int row, int chunk) {
 }
 
 // value of the neighbouring lane (lane ^ 1), through the DPP quad permute [1, 0, 3, 2]
-__device__ __forceinline__ float lane_xor1(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));
+__device__ __forceinline__ unsigned lane_xor1(unsigned v) {
+  return static_cast<unsigned>(__builtin_amdgcn_mov_dpp(static_cast<int>(v), 0xB1, 0xF, 0xF, false));
 }
 
 // logical tile index -> (matrix b, tile row tm, tile column tn)
@@ -203,13 +203,16 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[4][4], __bf16* stage
   if (EPI != EPI_FINAL) {
     // ---- straight image: element (i, j) of C is (row i, k = j) of the result's panels.
     // A 16-byte chunk is 8 consecutive j of one row, i.e. one value from each of 8 lanes:
-    // neighbouring lanes swap one value so that every lane writes two packed bf16.
+    // neighbouring lanes exchange their packed pairs so that every lane writes two bf16 of
+    // one row.
     __bf16* C = static_cast<__bf16*>(e.c) + static_cast<int64_t>(b) * d.M * d.N;
     // Staging offset = (lane-only base) + (compile-time part), so that the compiler keeps two
     // address registers instead of one per store.  Element (row_l, col_l) of the wavefront's
     // part, row_l = 32 it + 8 g + 2 p + 4 lh + odd (rp = 2 g + p), col_l = 32 jt + lj, lies in
     // k-block jt at row_l * 32 + ((chunk ^ swizzle) << 3) with chunk = lj >> 3 and
     // swizzle = (row_l >> 2) & 3 = 2 (g & 1) + lh: lane bits except for g & 1.
+    // byte selector of v_perm_b32 over {theirs (bytes 4..7), mine (bytes 0..3)}
+    const unsigned pair_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
     int s_base[2];
 #pragma unroll
     for (int g1 = 0; g1 < 2; ++g1)
@@ -220,14 +223,17 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[4][4], __bf16* stage
       for (int jt = 0; jt < 4; ++jt)
 #pragma unroll
         for (int rp = 0; rp < 8; ++rp) {  // register pairs (2 rp, 2 rp + 1): rows differ by one
-          const float own0 = acc[it][jt][2 * rp], own1 = acc[it][jt][2 * rp + 1];
-          const float got = lane_xor1((lane & 1) ? own0 : own1);
-          bf16x2 pk;
-          pk[0] = static_cast<__bf16>((lane & 1) ? got : own0);
-          pk[1] = static_cast<__bf16>((lane & 1) ? own1 : got);
+          // both rows of this lane's column, packed; the even lane keeps the low halves of
+          // the pair of lanes (row 2 rp), the odd lane the high halves (row 2 rp + 1)
+          bf16x2 own;
+          own[0] = static_cast<__bf16>(acc[it][jt][2 * rp]);
+          own[1] = static_cast<__bf16>(acc[it][jt][2 * rp + 1]);
+          const unsigned mine = __builtin_bit_cast(unsigned, own);
+          const unsigned theirs = lane_xor1(mine);
+          const unsigned pk = __builtin_amdgcn_perm(theirs, mine, pair_sel);
           const int g = rp >> 1, p = rp & 1;
           const int fixed = jt * 4096 + (it * 32 + 8 * g + 2 * p) * 32;
-          *reinterpret_cast<bf16x2*>(stage + fixed + s_base[g & 1]) = pk;
+          *reinterpret_cast<unsigned*>(stage + fixed + s_base[g & 1]) = pk;
         }
     flush_stage(C, tm, d.N, 8 * tn + 4 * wn, wm);
 
