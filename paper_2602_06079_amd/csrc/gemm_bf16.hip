@@ -422,10 +422,22 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[4][4], __bf16* stage
   }
 }
 
-template <int EPI, bool SPLIT>
-__global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __bf16* __restrict__ P,
-                                                            const __bf16* __restrict__ Q, EpiArgs e, Shape s,
-                                                            OutSpec o) {
+// Operands of a launch: one product (the usual case), or several of different shapes.
+struct OneProblem {
+  static constexpr bool multi = false;
+  GemmDims d;
+  const __bf16* P;
+  const __bf16* Q;
+};
+struct ManyProblems {
+  static constexpr bool multi = true;
+  int n;
+  int begin[MAX_KINDS + 1];  // first logical tile of each problem, then the total
+  GemmProblem pr[MAX_KINDS];
+};
+
+template <int EPI, bool SPLIT, typename Args>
+__global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(Args args, EpiArgs e_launch, Shape s, OutSpec o) {
   // one array per stage (not one carved buffer): the compiler then knows that a fetch into
   // one stage does not alias the operand reads of another and keeps them overlapped.
   // Elements [0, 8192) hold the P panel, [8192, 16384) the Q panel.
@@ -439,9 +451,13 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
   //      logical tiles round * gridDim + slot(bid).  slot() makes the 32 blocks of one XCD
   //      (blockIdx % 8 selects the XCD) neighbours, so that in every round they form a 4 x 8
   //      patch of tiles of one matrix and share panels in that XCD's L2.
-  const int tiles_n = static_cast<int>(d.N / BN);
-  const int tiles_m = static_cast<int>(d.M / BM);
-  const int per_batch = (EPI == EPI_GRAM || EPI == EPI_POLY) ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
+  GemmDims d{};
+  const __bf16 *P = nullptr, *Q = nullptr;
+  EpiArgs e = e_launch;
+  if constexpr (!Args::multi) d = args.d, P = args.P, Q = args.Q;
+  int tiles_n = static_cast<int>(d.N / BN);
+  int tiles_m = static_cast<int>(d.M / BM);
+  int per_batch = (EPI == EPI_GRAM || EPI == EPI_POLY) ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
   int slot;
   {
     const int nblocks = gridDim.x, bid = blockIdx.x;
@@ -454,7 +470,7 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wm = wave >> 1, wn = wave & 1;
 
-  const int nk_all = static_cast<int>(d.K / BK);  // multiple of 8: K is a multiple of 256
+  int nk_all = static_cast<int>(d.K / BK);  // multiple of 8: K is a multiple of 256
 
   for (int work = 0;; ++work) {
   // ---- what to do in this round: a whole tile, or one k-slice of a left-over tile.  When
@@ -481,6 +497,20 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(GemmDims d, const __b
   // loop body (hundreds of them) is hoisted out of the tile loop and kept alive in scratch.
   int lane = t & 63;
   asm volatile("" : "+v"(lane));
+  if constexpr (Args::multi) {
+    // which product this tile belongs to; its extents, operands and outputs
+    int j = 0;
+    while (j + 1 < args.n && logical >= args.begin[j + 1]) ++j;
+    const GemmProblem& pr = args.pr[j];
+    d = pr.d;
+    P = static_cast<const __bf16*>(pr.p), Q = static_cast<const __bf16*>(pr.q);
+    e.c = pr.c, e.ct = pr.ct, e.aux = pr.aux, e.scale = pr.scale;
+    logical -= args.begin[j];
+    tiles_n = static_cast<int>(d.N / BN), tiles_m = static_cast<int>(d.M / BM);
+    per_batch = (EPI == EPI_GRAM || EPI == EPI_POLY) ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
+    nk_all = static_cast<int>(d.K / BK);
+    nk = nk_all;
+  }
   int b, tm, tn;
   decode_tile<EPI>(logical, tiles_m, tiles_n, per_batch, b, tm, tn);
 
@@ -704,18 +734,55 @@ hipError_t launch(const GemmDims& d, const void* P, const void* Q, EpiArgs e, co
   // whole tiles: one persistent block per CU (fewer if there are fewer tiles)
   const int64_t whole = e.splits > 1 ? e.full_rounds * cus : tiles;
   e.main_grid = static_cast<int>(std::min<int64_t>(cus, std::max<int64_t>(whole, 1)));
+  const OneProblem one{d, static_cast<const __bf16*>(P), static_cast<const __bf16*>(Q)};
   if (whole > 0)
-    hipLaunchKernelGGL((k_gemm_nt_bf16<EPI, false>), dim3(static_cast<unsigned>(e.main_grid)), dim3(NTHREADS), 0, st, d,
-                       static_cast<const __bf16*>(P), static_cast<const __bf16*>(Q), e, s, o);
+    hipLaunchKernelGGL((k_gemm_nt_bf16<EPI, false, OneProblem>), dim3(static_cast<unsigned>(e.main_grid)), dim3(NTHREADS),
+                       0, st, one, e, s, o);
   if (e.splits > 1) {
-    hipLaunchKernelGGL((k_gemm_nt_bf16<EPI, true>), dim3(static_cast<unsigned>(e.left * e.splits)), dim3(NTHREADS), 0,
-                       st, d, static_cast<const __bf16*>(P), static_cast<const __bf16*>(Q), e, s, o);
+    hipLaunchKernelGGL((k_gemm_nt_bf16<EPI, true, OneProblem>), dim3(static_cast<unsigned>(e.left * e.splits)),
+                       dim3(NTHREADS), 0, st, one, e, s, o);
     hipLaunchKernelGGL((k_split_finish<EPI>), dim3(static_cast<unsigned>(e.left)), dim3(NTHREADS), 0, st, d, e, s, o);
   }
   return hipGetLastError();
 }
 
+// Several products in one launch: whole tiles only (no k-split), one persistent block per CU.
+template <int EPI>
+hipError_t launch_multi(const GemmBatch& g, EpiArgs e, hipStream_t st) {
+  ManyProblems many{};
+  many.n = g.n;
+  int64_t tiles = 0;
+  for (int j = 0; j < g.n; ++j) {
+    const GemmDims& d = g.pr[j].d;
+    const int64_t tm = d.M / BM, tn = d.N / BN;
+    many.begin[j] = static_cast<int>(tiles);
+    many.pr[j] = g.pr[j];
+    tiles += ((EPI == EPI_GRAM || EPI == EPI_POLY) ? tm * (tm + 1) / 2 : tm * tn) * d.nb;
+  }
+  for (int j = g.n; j <= MAX_KINDS; ++j) many.begin[j] = static_cast<int>(tiles);
+  const int64_t cus = cu_count();
+  e.full_rounds = static_cast<int>(tiles / cus);
+  e.left = static_cast<int>(tiles % cus);
+  e.splits = 1;
+  e.partial = nullptr;
+  e.main_grid = static_cast<int>(std::min<int64_t>(cus, std::max<int64_t>(tiles, 1)));
+  if (tiles > 0)
+    hipLaunchKernelGGL((k_gemm_nt_bf16<EPI, false, ManyProblems>), dim3(static_cast<unsigned>(e.main_grid)),
+                       dim3(NTHREADS), 0, st, many, e, Shape{}, OutSpec{});
+  return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_gram_bf16_multi(const GemmBatch& g, hipStream_t st) { return launch_multi<EPI_GRAM>(g, EpiArgs{}, st); }
+
+hipError_t launch_poly_bf16_multi(const GemmBatch& g, float ca, float cb, float cc, hipStream_t st) {
+  EpiArgs e{};
+  e.ca = ca, e.cb = cb, e.cc = cc;
+  return launch_multi<EPI_POLY>(g, e, st);
+}
+
+hipError_t launch_update_bf16_multi(const GemmBatch& g, hipStream_t st) { return launch_multi<EPI_UPDATE>(g, EpiArgs{}, st); }
 
 hipError_t launch_gram_bf16(const GemmDims& d, const void* xw, void* a_out, const float* scale2, const SplitWs& w,
                             hipStream_t st) {

@@ -78,6 +78,27 @@ struct SplitWs {
 };
 constexpr int SPLIT_MAX_BLOCKS = 256;                       // CU count of MI355X; fewer blocks split on a smaller part
 constexpr size_t SPLIT_BLOCK_BYTES = 256 * 256 * sizeof(float);
+// Several products of one kind in one launch (matrices of different shapes): the persistent
+// blocks walk the tiles of problem 0, then of problem 1, ...  Used for shares whose shape
+// classes are too small to fill the chip on their own.
+constexpr int MAX_KINDS = 4;
+struct GemmProblem {
+  GemmDims d;
+  const void* p;       // first operand  [nb][M][K] panels
+  const void* q;       // second operand [nb][N][K] panels
+  void* c;             // output (UPDATE: the straight image)
+  void* ct;            // UPDATE: the transposed image
+  const void* aux;     // POLY: A
+  const float* scale;  // per-matrix factor or nullptr
+};
+struct GemmBatch {
+  int n;
+  GemmProblem pr[MAX_KINDS];
+};
+hipError_t launch_gram_bf16_multi(const GemmBatch& g, hipStream_t st);
+hipError_t launch_poly_bf16_multi(const GemmBatch& g, float ca, float cb, float cc, hipStream_t st);
+hipError_t launch_update_bf16_multi(const GemmBatch& g, hipStream_t st);
+
 // A = scale2[b] * X X^T                      (P = Q = XW)
 hipError_t launch_gram_bf16(const GemmDims& d, const void* xw, void* a_out, const float* scale2, const SplitWs& w,
                             hipStream_t st);

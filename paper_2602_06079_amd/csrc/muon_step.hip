@@ -23,8 +23,8 @@ constexpr size_t ALIGN = 256;
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 inline int64_t pad_up(int64_t x) { return (x + PAD - 1) / PAD * PAD; }
 
-struct Carve {
-  size_t xw, xt0, xt1, a, b, partial, scale, scale2, split_partial, total;
+struct Carve {   // byte offsets of one launch batch's arrays, relative to its own base
+  size_t xw, xt0, xt1, a, b, partial, scale, scale2, total;
 };
 
 Shape make_shape(const canz_group& g) {
@@ -52,10 +52,13 @@ Carve carve(const Shape& s, int nb, int precision) {
   c.partial = off, off += align_up(static_cast<size_t>(nb) * momentum_tiles(s) * sizeof(float));
   c.scale = off, off += align_up(nb * sizeof(float));
   c.scale2 = off, off += align_up(nb * sizeof(float));
-  c.split_partial = off;
-  if (precision == CANZ_PREC_BF16) off += align_up(SPLIT_MAX_BLOCKS * SPLIT_BLOCK_BYTES);
   c.total = off;
   return c;
+}
+
+// scratch of the k-split, shared by all launches of a call (bf16 mode only)
+size_t split_bytes(int precision) {
+  return precision == CANZ_PREC_BF16 ? align_up(SPLIT_MAX_BLOCKS * SPLIT_BLOCK_BYTES) : 0;
 }
 
 int check_hparams(const canz_muon_hparams* hp) {
@@ -178,104 +181,220 @@ struct Part {
 };
 
 // One launch batch: part[0] holds its wide (rows <= cols) matrices, part[1] the tall ones of
-// the transposed shape.  They occupy consecutive slots of the workspace arrays, the wide
-// ones first; the kernels that touch the caller's buffers (momentum, last product, apply)
-// run once per part, everything between runs once over the whole batch.
-template <typename T>
-int run_batch(const Part (&part)[2], const canz_muon_hparams& hp, char* ws, hipStream_t st) {
-  const int nb = part[0].n() + part[1].n();
-  const canz_group& any = *(part[0].n() ? part[0].proto : part[1].proto);
-  const Shape s0 = make_shape(any);
-  const Carve c = carve(s0, nb, hp.precision);
-  T* xw = reinterpret_cast<T*>(ws + c.xw);
-  T* xt[2] = {reinterpret_cast<T*>(ws + c.xt0), reinterpret_cast<T*>(ws + c.xt1)};
-  T* a = reinterpret_cast<T*>(ws + c.a);
-  T* bm = reinterpret_cast<T*>(ws + c.b);
-  float* partial = reinterpret_cast<float*>(ws + c.partial);
-  float* scale = reinterpret_cast<float*>(ws + c.scale);
-  float* scale2 = reinterpret_cast<float*>(ws + c.scale2);
-  const SplitWs split{reinterpret_cast<float*>(ws + c.split_partial), SPLIT_MAX_BLOCKS};
-  constexpr bool is_bf16 = sizeof(T) == 2;
-  const int64_t x_elems = s0.mp * s0.np, a_elems = s0.mp * s0.mp;
-  const int tiles = momentum_tiles(s0);
+// the transposed shape.  They occupy consecutive slots of the batch's workspace arrays, the
+// wide ones first; the kernels that touch the caller's buffers (momentum, last product,
+// apply) run once per part.
+struct Batch {
+  Part part[2];
+  Shape s0{};     // shape of any member: the padded extents are those of the whole batch
+  int nb = 0;
+  int64_t update_tiles() const { return (s0.mp / PAD) * (s0.np / PAD) * nb; }
+};
 
-  Shape shape[2];
-  OutSpec out[2];
-  int first[2] = {0, part[0].n()};
-  for (int k = 0; k < 2; ++k) {
-    const int n = part[k].n();
-    if (n == 0) continue;
-    const canz_group& g = *part[k].proto;
-    shape[k] = make_shape(g);
-    PtrTable grad{}, mom{};
-    OutSpec& o = out[k];
-    o = OutSpec{};
-    const int n_out = hp.out_mode == CANZ_OUT_DELTA ? n * g.tp : n;
-    for (int i = 0; i < n * g.tp; ++i) grad.p[i] = const_cast<void*>(part[k].grad[i]);
-    for (int i = 0; i < n; ++i) mom.p[i] = part[k].mom[i];
-    for (int i = 0; i < n_out; ++i) o.out.p[i] = part[k].out[i];
-    o.out_dtype = g.out_dtype;
-    o.out_mode = hp.out_mode;
-    o.decay = static_cast<float>(1.0 - static_cast<double>(hp.lr) * static_cast<double>(hp.weight_decay));
-    o.neg_lr_scale = static_cast<float>(-static_cast<double>(hp.lr) * update_scale(g, hp.scale_mode));
-    CANZ_HIP(CANZ_KERNEL_MOMENTUM,
-             launch_momentum<T>(shape[k], n, grad, g.grad_dtype, mom, hp.beta, hp.nesterov, xw + first[k] * x_elems,
-                                xt[0] + first[k] * x_elems, partial + static_cast<int64_t>(first[k]) * tiles, st),
-             "momentum kernel");
+// Collects the launch batches of a call (pointers only when `with_ptrs`).
+int collect_batches(const canz_group* g, int n_groups, int out_mode, bool with_ptrs, std::vector<Batch>& out) {
+  return for_each_batch(g, n_groups, [&](const canz_group& proto, int gi, int mi, int count) {
+    out.emplace_back();
+    Batch& bt = out.back();
+    bt.s0 = make_shape(proto);
+    bt.nb = count;
+    for (int left = count; left > 0; ++gi, mi = 0) {
+      const canz_group& src = g[gi];
+      const int take = std::min(left, src.n_mats - mi);
+      if (take <= 0) continue;
+      Part& p = bt.part[src.rows > src.cols ? 1 : 0];
+      if (!p.proto) p.proto = &src;
+      const int per_out = out_mode == CANZ_OUT_DELTA ? src.tp : 1;
+      for (int m = mi; m < mi + take; ++m) {
+        if (with_ptrs) {
+          for (int f = 0; f < src.tp; ++f) p.grad.push_back(src.grad[m * src.tp + f]);
+          for (int f = 0; f < per_out; ++f) p.out.push_back(src.out[m * per_out + f]);
+        }
+        p.mom.push_back(with_ptrs ? src.mom[m] : nullptr);
+      }
+      left -= take;
+    }
+    return CANZ_OK;
+  });
+}
+
+// Launch batches that are too small to fill the chip on their own for long (fewer than 8
+// rounds of update tiles on 256 CUs) are run together, up to MAX_KINDS of them: their Gram,
+// polynomial and update products then share launches.  first[i] .. first[i + 1] are the
+// batches of run i.  Only in bf16 mode; the fp32 verification path keeps one batch per run.
+constexpr int64_t SMALL_BATCH_TILES = 8 * 256;
+std::vector<int> group_runs(const std::vector<Batch>& batches, int precision) {
+  std::vector<int> first;
+  const int n = static_cast<int>(batches.size());
+  for (int i = 0; i < n;) {
+    first.push_back(i);
+    int j = i + 1;
+    if (precision == CANZ_PREC_BF16 && batches[i].update_tiles() < SMALL_BATCH_TILES) {
+      int64_t elems = batches[i].s0.mp * batches[i].s0.np * batches[i].nb;
+      while (j < n && j - i < MAX_KINDS && batches[j].update_tiles() < SMALL_BATCH_TILES) {
+        const int64_t more = batches[j].s0.mp * batches[j].s0.np * batches[j].nb;
+        if (elems + more > MAX_BATCH_ELEMS) break;
+        elems += more;
+        ++j;
+      }
+    }
+    i = j;
   }
-  CANZ_HIP(CANZ_KERNEL_NORM, launch_norm_scale(nb, tiles, partial, hp.eps, scale, scale2, st), "norm kernel");
+  first.push_back(n);
+  return first;
+}
+
+size_t run_bytes(const std::vector<Batch>& batches, int lo, int hi, int precision) {
+  size_t total = 0;
+  for (int k = lo; k < hi; ++k) total += carve(batches[k].s0, batches[k].nb, precision).total;
+  return total + split_bytes(precision);
+}
+
+// One run: the batches lo .. hi-1 side by side in the workspace, then the split scratch.
+template <typename T>
+int run_batches(const std::vector<Batch>& batches, int lo, int hi, const canz_muon_hparams& hp, char* ws,
+                hipStream_t st) {
+  constexpr bool is_bf16 = sizeof(T) == 2;
+  const int nk = hi - lo;
+  struct Kind {
+    T *xw, *xt[2], *a, *bm;
+    float *partial, *scale, *scale2;
+    int64_t x_elems, a_elems;
+    int tiles, nb;
+    Shape s0, shape[2];
+    OutSpec out[2];
+    int first[2];
+    GemmDims gram, poly, upd;
+  };
+  Kind kind[MAX_KINDS];
+  size_t base = 0;
+  for (int k = 0; k < nk; ++k) {
+    const Batch& bt = batches[lo + k];
+    Kind& kd = kind[k];
+    const Carve c = carve(bt.s0, bt.nb, hp.precision);
+    char* w = ws + base;
+    kd.xw = reinterpret_cast<T*>(w + c.xw);
+    kd.xt[0] = reinterpret_cast<T*>(w + c.xt0), kd.xt[1] = reinterpret_cast<T*>(w + c.xt1);
+    kd.a = reinterpret_cast<T*>(w + c.a), kd.bm = reinterpret_cast<T*>(w + c.b);
+    kd.partial = reinterpret_cast<float*>(w + c.partial);
+    kd.scale = reinterpret_cast<float*>(w + c.scale), kd.scale2 = reinterpret_cast<float*>(w + c.scale2);
+    base += c.total;
+    const Shape& s = kd.s0 = bt.s0;
+    kd.nb = bt.nb;
+    kd.x_elems = s.mp * s.np, kd.a_elems = s.mp * s.mp;
+    kd.tiles = momentum_tiles(s);
+    kd.first[0] = 0, kd.first[1] = bt.part[0].n();
+    kd.gram = GemmDims{s.mp, s.mp, s.np, s.np, s.np, kd.x_elems, kd.x_elems, bt.nb};
+    kd.poly = GemmDims{s.mp, s.mp, s.mp, s.mp, s.mp, kd.a_elems, kd.a_elems, bt.nb};
+    kd.upd = GemmDims{s.mp, s.np, s.mp, s.mp, s.mp, kd.a_elems, kd.x_elems, bt.nb};
+  }
+  const SplitWs split{reinterpret_cast<float*>(ws + base), SPLIT_MAX_BLOCKS};
+
+  // momentum (+ gather, cast, both orientations, tile sums of U^2) per part, norm per batch
+  for (int k = 0; k < nk; ++k) {
+    const Batch& bt = batches[lo + k];
+    Kind& kd = kind[k];
+    for (int h = 0; h < 2; ++h) {
+      const Part& part = bt.part[h];
+      const int n = part.n();
+      if (n == 0) continue;
+      const canz_group& g = *part.proto;
+      kd.shape[h] = make_shape(g);
+      PtrTable grad{}, mom{};
+      OutSpec& o = kd.out[h];
+      o = OutSpec{};
+      const int n_out = hp.out_mode == CANZ_OUT_DELTA ? n * g.tp : n;
+      for (int i = 0; i < n * g.tp; ++i) grad.p[i] = const_cast<void*>(part.grad[i]);
+      for (int i = 0; i < n; ++i) mom.p[i] = part.mom[i];
+      for (int i = 0; i < n_out; ++i) o.out.p[i] = part.out[i];
+      o.out_dtype = g.out_dtype;
+      o.out_mode = hp.out_mode;
+      o.decay = static_cast<float>(1.0 - static_cast<double>(hp.lr) * static_cast<double>(hp.weight_decay));
+      o.neg_lr_scale = static_cast<float>(-static_cast<double>(hp.lr) * update_scale(g, hp.scale_mode));
+      const int f = kd.first[h];
+      CANZ_HIP(CANZ_KERNEL_MOMENTUM,
+               launch_momentum<T>(kd.shape[h], n, grad, g.grad_dtype, mom, hp.beta, hp.nesterov, kd.xw + f * kd.x_elems,
+                                  kd.xt[0] + f * kd.x_elems, kd.partial + static_cast<int64_t>(f) * kd.tiles, st),
+               "momentum kernel");
+    }
+    CANZ_HIP(CANZ_KERNEL_NORM, launch_norm_scale(kd.nb, kd.tiles, kd.partial, hp.eps, kd.scale, kd.scale2, st),
+             "norm kernel");
+  }
 
   if (hp.ns_steps == 0) {
-    for (int k = 0; k < 2; ++k) {
-      if (part[k].n() == 0) continue;
-      const Shape& s = shape[k];
-      const T* straight = (s.tall ? xt[0] : xw) + first[k] * x_elems;
-      const int64_t ld = s.tall ? s.mp : s.np;
-      CANZ_HIP(CANZ_KERNEL_APPLY, launch_apply<T>(s, part[k].n(), straight, ld, x_elems, scale + first[k], out[k], st),
-               "apply kernel");
-    }
+    for (int k = 0; k < nk; ++k)
+      for (int h = 0; h < 2; ++h) {
+        const int n = batches[lo + k].part[h].n();
+        if (n == 0) continue;
+        const Kind& kd = kind[k];
+        const Shape& s = kd.shape[h];
+        const T* straight = (s.tall ? kd.xt[0] : kd.xw) + kd.first[h] * kd.x_elems;
+        const int64_t ld = s.tall ? s.mp : s.np;
+        CANZ_HIP(CANZ_KERNEL_APPLY,
+                 launch_apply<T>(s, n, straight, ld, kd.x_elems, kd.scale + kd.first[h], kd.out[h], st), "apply kernel");
+      }
     return CANZ_OK;
   }
 
-  const Shape& s = s0;
-  GemmDims gram{s.mp, s.mp, s.np, s.np, s.np, x_elems, x_elems, nb};
-  GemmDims poly{s.mp, s.mp, s.mp, s.mp, s.mp, a_elems, a_elems, nb};
-  GemmDims upd{s.mp, s.np, s.mp, s.mp, s.mp, a_elems, x_elems, nb};
+  const bool together = is_bf16 && nk > 1;   // shared launches for Gram, polynomial and update
   int cur = 0;
   for (int it = 0; it < hp.ns_steps; ++it) {
-    const float* sc1 = it == 0 ? scale : nullptr;
-    const float* sc2 = it == 0 ? scale2 : nullptr;
-    const bool last = it + 1 == hp.ns_steps;
-    if (is_bf16) {
-      CANZ_HIP(CANZ_KERNEL_GRAM, launch_gram_bf16(gram, xw, a, sc2, split, st), "gram kernel");
-      CANZ_HIP(CANZ_KERNEL_POLY, launch_poly_bf16(poly, a, bm, hp.a, hp.b, hp.c, split, st), "poly kernel");
-    } else {
-      CANZ_HIP(CANZ_KERNEL_GRAM, launch_gram_f32(gram, xw, a, sc2, st), "gram kernel");
-      CANZ_HIP(CANZ_KERNEL_POLY, launch_poly_f32(poly, a, bm, hp.a, hp.b, hp.c, st), "poly kernel");
+    const bool first_it = it == 0, last = it + 1 == hp.ns_steps;
+    if (together) {
+      GemmBatch gb{};
+      gb.n = nk;
+      for (int k = 0; k < nk; ++k)
+        gb.pr[k] = GemmProblem{kind[k].gram, kind[k].xw, kind[k].xw, kind[k].a, nullptr, nullptr,
+                               first_it ? kind[k].scale2 : nullptr};
+      CANZ_HIP(CANZ_KERNEL_GRAM, launch_gram_bf16_multi(gb, st), "gram kernel");
+      for (int k = 0; k < nk; ++k)
+        gb.pr[k] = GemmProblem{kind[k].poly, kind[k].a, kind[k].a, kind[k].bm, nullptr, kind[k].a, nullptr};
+      CANZ_HIP(CANZ_KERNEL_POLY, launch_poly_bf16_multi(gb, hp.a, hp.b, hp.c, st), "poly kernel");
+      if (!last) {
+        for (int k = 0; k < nk; ++k)
+          gb.pr[k] = GemmProblem{kind[k].upd, kind[k].bm, kind[k].xt[cur], kind[k].xw, kind[k].xt[cur ^ 1], nullptr,
+                                 first_it ? kind[k].scale : nullptr};
+        CANZ_HIP(CANZ_KERNEL_UPDATE, launch_update_bf16_multi(gb, st), "update kernel");
+      }
     }
-    if (!last) {
-      if (is_bf16)
-        CANZ_HIP(CANZ_KERNEL_UPDATE, launch_update_bf16(upd, bm, xt[cur], xw, xt[cur ^ 1], sc1, split, st), "update kernel");
-      else
-        CANZ_HIP(CANZ_KERNEL_UPDATE, launch_update_f32(upd, bm, xt[cur], xw, xt[cur ^ 1], sc1, st), "update kernel");
-    } else {
+    for (int k = 0; k < nk; ++k) {
+      const Kind& kd = kind[k];
+      const float* sc1 = first_it ? kd.scale : nullptr;
+      const float* sc2 = first_it ? kd.scale2 : nullptr;
+      if (!together) {
+        if (is_bf16) {
+          CANZ_HIP(CANZ_KERNEL_GRAM, launch_gram_bf16(kd.gram, kd.xw, kd.a, sc2, split, st), "gram kernel");
+          CANZ_HIP(CANZ_KERNEL_POLY, launch_poly_bf16(kd.poly, kd.a, kd.bm, hp.a, hp.b, hp.c, split, st), "poly kernel");
+          if (!last)
+            CANZ_HIP(CANZ_KERNEL_UPDATE,
+                     launch_update_bf16(kd.upd, kd.bm, kd.xt[cur], kd.xw, kd.xt[cur ^ 1], sc1, split, st), "update kernel");
+        } else {
+          CANZ_HIP(CANZ_KERNEL_GRAM, launch_gram_f32(kd.gram, kd.xw, kd.a, sc2, st), "gram kernel");
+          CANZ_HIP(CANZ_KERNEL_POLY, launch_poly_f32(kd.poly, kd.a, kd.bm, hp.a, hp.b, hp.c, st), "poly kernel");
+          if (!last)
+            CANZ_HIP(CANZ_KERNEL_UPDATE, launch_update_f32(kd.upd, kd.bm, kd.xt[cur], kd.xw, kd.xt[cur ^ 1], sc1, st),
+                     "update kernel");
+        }
+      }
+      if (!last) continue;
       // last product, written in the caller's orientation: for the tall part the roles of
       // the polynomial and of X swap, so that C comes out as rows x cols
-      for (int k = 0; k < 2; ++k) {
-        const int n = part[k].n();
+      for (int h = 0; h < 2; ++h) {
+        const int n = batches[lo + k].part[h].n();
         if (n == 0) continue;
-        const T* bk = bm + first[k] * a_elems;
-        const T* xk = xt[cur] + first[k] * x_elems;
-        const float* sk = sc1 ? sc1 + first[k] : nullptr;
-        GemmDims fin = upd;
-        if (shape[k].tall) fin = GemmDims{s.np, s.mp, s.mp, s.mp, s.mp, x_elems, a_elems, n};
+        const Shape& s = kd.s0;
+        const T* bk = kd.bm + kd.first[h] * kd.a_elems;
+        const T* xk = kd.xt[cur] + kd.first[h] * kd.x_elems;
+        const float* sk = sc1 ? sc1 + kd.first[h] : nullptr;
+        const bool tall = kd.shape[h].tall;
+        GemmDims fin = tall ? GemmDims{s.np, s.mp, s.mp, s.mp, s.mp, kd.x_elems, kd.a_elems, n} : kd.upd;
         fin.nb = n;
-        const void* P = shape[k].tall ? static_cast<const void*>(xk) : static_cast<const void*>(bk);
-        const void* Q = shape[k].tall ? static_cast<const void*>(bk) : static_cast<const void*>(xk);
+        const void* P = tall ? static_cast<const void*>(xk) : static_cast<const void*>(bk);
+        const void* Q = tall ? static_cast<const void*>(bk) : static_cast<const void*>(xk);
         if (is_bf16)
-          CANZ_HIP(CANZ_KERNEL_FINAL, launch_final_bf16(fin, P, Q, sk, split, shape[k], out[k], st), "final kernel");
+          CANZ_HIP(CANZ_KERNEL_FINAL, launch_final_bf16(fin, P, Q, sk, split, kd.shape[h], kd.out[h], st), "final kernel");
         else
-          CANZ_HIP(CANZ_KERNEL_FINAL, launch_final_f32(fin, P, Q, sk, shape[k], out[k], st), "final kernel");
+          CANZ_HIP(CANZ_KERNEL_FINAL, launch_final_f32(fin, P, Q, sk, kd.shape[h], kd.out[h], st), "final kernel");
       }
     }
     cur ^= 1;
@@ -295,10 +414,11 @@ extern "C" int canz_muon_workspace_bytes(const canz_group* g, int32_t n_groups, 
   size_t need = ALIGN;
   for (int i = 0; i < n_groups; ++i)
     if (int rc = check_group(g[i], i, false, hp->out_mode)) return rc;
-  for_each_batch(g, n_groups, [&](const canz_group& proto, int, int, int count) {
-    need = std::max(need, carve(make_shape(proto), count, hp->precision).total);
-    return CANZ_OK;
-  });
+  std::vector<Batch> batches;
+  collect_batches(g, n_groups, hp->out_mode, false, batches);
+  const std::vector<int> first = group_runs(batches, hp->precision);
+  for (size_t r = 0; r + 1 < first.size(); ++r)
+    need = std::max(need, run_bytes(batches, first[r], first[r + 1], hp->precision));
   *bytes_out = need;
   return CANZ_OK;
 }
@@ -322,26 +442,15 @@ extern "C" int canz_muon_step(const canz_group* g, int32_t n_groups, const canz_
 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
-  Part part[2];
-  return for_each_batch(g, n_groups, [&](const canz_group&, int gi, int mi, int count) {
-    // gather the batch's pointers by orientation (the batch may continue into following groups)
-    for (Part& p : part) p.proto = nullptr, p.grad.clear(), p.mom.clear(), p.out.clear();
-    for (int left = count; left > 0; ++gi, mi = 0) {
-      const canz_group& src = g[gi];
-      const int take = std::min(left, src.n_mats - mi);
-      if (take <= 0) continue;
-      Part& p = part[src.rows > src.cols ? 1 : 0];
-      if (!p.proto) p.proto = &src;
-      const int per_out = hp->out_mode == CANZ_OUT_DELTA ? src.tp : 1;
-      for (int m = mi; m < mi + take; ++m) {
-        for (int f = 0; f < src.tp; ++f) p.grad.push_back(src.grad[m * src.tp + f]);
-        p.mom.push_back(src.mom[m]);
-        for (int f = 0; f < per_out; ++f) p.out.push_back(src.out[m * per_out + f]);
-      }
-      left -= take;
-    }
-    return hp->precision == CANZ_PREC_BF16 ? run_batch<__bf16>(part, *hp, ws, st) : run_batch<float>(part, *hp, ws, st);
-  });
+  std::vector<Batch> batches;
+  collect_batches(g, n_groups, hp->out_mode, true, batches);
+  const std::vector<int> first = group_runs(batches, hp->precision);
+  for (size_t r = 0; r + 1 < first.size(); ++r) {
+    const int rc = hp->precision == CANZ_PREC_BF16 ? run_batches<__bf16>(batches, first[r], first[r + 1], *hp, ws, st)
+                                                   : run_batches<float>(batches, first[r], first[r + 1], *hp, ws, st);
+    if (rc) return rc;
+  }
+  return CANZ_OK;
 }
 
 extern "C" int canz_profile_enable(int32_t max_launches) {

@@ -43,14 +43,18 @@ def test_workspace_bytes_formula(canz):
     hp32 = canz.Hparams(precision=canz.PREC_F32)
     want2 = 3 * 256 * 512 * 4 + 2 * 256 * 256 * 4 + 256 + 256 + 256
     assert canz.canz_muon_workspace_bytes([g2], hp32) == want2
-    # the maximum over groups; a launch takes at most 128 matrices (the pointer-table size) ...
+    # the maximum over runs.  A launch batch takes at most 128 matrices (the pointer-table size); batches
+    # too small to fill the chip for long share a run (up to 4 of them), side by side in the workspace
+    def batch_bytes(n):
+        up = lambda x: (x + 255) // 256 * 256
+        return 3 * n * 256 * 512 * 2 + 2 * n * 256 * 256 * 2 + up(n * 32 * 4) + 2 * up(n * 4)
     g3 = canz.Group(rows=256, cols=512, n_mats=150)
-    want3 = 3 * 128 * 256 * 512 * 2 + 2 * 128 * 256 * 256 * 2 + 128 * 32 * 4 + 512 + 512 + split
-    assert canz.canz_muon_workspace_bytes([g, g3], hp) == want3
+    assert canz.canz_muon_workspace_bytes([g, g3], hp) == batch_bytes(128) + batch_bytes(30) + split
     # ... at most 128 / tp with column fragments, and at most 2^30 padded elements
     g4 = canz.Group(rows=256, cols=512, n_mats=150, tp=4)
-    want4 = 3 * 32 * 256 * 512 * 2 + 2 * 32 * 256 * 256 * 2 + 32 * 32 * 4 + 256 + 256 + split
-    assert canz.canz_muon_workspace_bytes([g4], hp) == want4
+    assert canz.canz_muon_workspace_bytes([g4], hp) == 4 * batch_bytes(32) + split
+    # the fp32 verification path keeps one batch per run
+    assert canz.canz_muon_workspace_bytes([g4], hp32) == 2 * (batch_bytes(32) - 32 * 32 * 4 - 512) + 32 * 32 * 4 + 512
     g5 = canz.Group(rows=12288, cols=4096, n_mats=36)
     nb = (1 << 30) // (12288 * 4096)
     want5 = 3 * nb * 12288 * 4096 * 2 + 2 * nb * 4096 * 4096 * 2 + nb * (192 * 64) * 4 + 256 + 256 + split

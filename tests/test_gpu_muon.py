@@ -274,3 +274,29 @@ def test_transposed_shapes_share_a_launch(canz, precision, tp):
         for i in range(alone.n):
             assert np.array_equal(alone.out_host(i), together[k][0].out_host(i))
             assert np.array_equal(alone.mom_host(i), together[k][0].mom_host(i))
+
+
+@pytest.mark.parametrize("precision", [0, 1])
+def test_groups_of_different_shapes_share_launches(canz, precision):
+    """Six small shape classes in one call: in bf16 mode their Gram, polynomial and update
+    products run four classes to a launch.  Parity for each, and the same bits as alone."""
+    shapes = [(300, 200, 3), (520, 1032, 2), (64, 1000, 2), (1000, 64, 1), (256, 256, 2), (130, 770, 1)]
+    hp = canz.Hparams(out_mode=canz.OUT_PARAM, precision=precision, weight_decay=0.1)
+
+    def make(k):
+        rows, cols, n = shapes[k]
+        grads = [W.gen_grad(60 + k, i, rows, cols)[0] for i in range(n)]
+        moms = [W.gen_normal_f32(60 + k, i, 5, rows, cols, 0.01) for i in range(n)]
+        params = [W.gen_param(60 + k, i, rows, cols) for i in range(n)]
+        return DeviceGroup(canz, rows, cols, grads, moms, outs=params), grads, moms, params
+
+    together = [make(k) for k in range(len(shapes))]
+    run_step(canz, [t[0] for t in together], hp)
+    for k, (dg, grads, moms, params) in enumerate(together):
+        _check_group(canz, dg, grads, moms, params, hp, "mixed shapes, group %d, prec %d" % (k, precision))
+    for k in range(len(shapes)):
+        alone = make(k)[0]
+        run_step(canz, [alone], hp)
+        for i in range(alone.n):
+            assert np.array_equal(alone.out_host(i), together[k][0].out_host(i))
+            assert np.array_equal(alone.mom_host(i), together[k][0].mom_host(i))
