@@ -201,7 +201,8 @@ typedef struct {
  * canz_muon_workspace_bytes - device scratch needed by canz_muon_step for these groups:
  * the maximum over the launch batches the call will form (consecutive matrices of equal
  * dtypes and equal shape up to a transpose, at most 128 / tp of them and at most 2^30
- * padded elements per batch unless one matrix alone is larger; batches run one after
+ * padded elements per batch unless one matrix alone is larger; up to four consecutive small
+ * batches run side by side within the same 2^30 elements, otherwise batches run one after
  * another on the stream, so for matrices below 2^30 elements at most about 10 GB are
  * asked for in bf16 mode, twice that in fp32 mode, whatever the share).
  * g: host array [n_groups]; pointer tables inside may be NULL for this call.
