@@ -231,6 +231,28 @@ int canz_muon_step(const canz_group* g, int32_t n_groups, const canz_muon_hparam
                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * canz_muon_step_static - canz_muon_step without a workspace argument, for callers that
+ * cannot allocate device memory or may not call an allocator where the step is issued
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).
+ * The scratch is an array of CANZ_STATIC_WORKSPACE_BYTES bytes inside the library's device
+ * code; each GPU the library runs on holds its own copy until the process ends.  Same
+ * kernels, same launch batches and bit-identical results as canz_muon_step with a workspace
+ * of its own.  The call allocates and frees nothing on the device; on its first use on a
+ * device it looks up that device's address of the array (hipGetSymbolAddress), afterwards it
+ * only enqueues kernels on hip_stream.
+ * The array's contents are scratch: nothing in it has to start at zero and nothing is kept
+ * from one call to the next.  All calls on one GPU share the array, so steps that may run at
+ * the same time on one GPU (two streams, two threads) race: serialise them, or give the
+ * others their own workspace through canz_muon_step.
+ * Errors: as canz_muon_step; CANZ_EWORKSPACE if canz_muon_workspace_bytes() for these groups
+ * exceeds CANZ_STATIC_WORKSPACE_BYTES (nothing is enqueued then); CANZ_EHIP if the array's
+ * address cannot be obtained.
+ */
+#define CANZ_STATIC_WORKSPACE_BYTES (128u << 20)
+int canz_muon_step_static(const canz_group* g, int32_t n_groups, const canz_muon_hparams* hp,
+                          void* hip_stream);
+
+/*
  * Per-kernel timing of canz_muon_step, for benchmarks (the measurement protocol of
  * App. C.1 reports the optimizer time; this splits it by kernel).  While enabled, every
  * kernel launch of a step is bracketed by a pair of HIP events on the step's own stream.

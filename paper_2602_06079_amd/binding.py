@@ -26,7 +26,7 @@ PREC_BF16, PREC_F32 = 0, 1
 OUT_PARAM, OUT_DELTA = 0, 1
 
 EXPORTS = ("canz_last_error", "canz_version", "canz_partition_alpha", "canz_partition_naive", "canz_microgroup_plan", "canz_tp_schedule",
-           "canz_muon_workspace_bytes", "canz_muon_step",
+           "canz_muon_workspace_bytes", "canz_muon_step", "canz_muon_step_static",
            "canz_profile_enable", "canz_profile_collect", "canz_profile_disable")
 KERNEL_KINDS = ("momentum", "norm", "gram", "poly", "update", "final", "apply")
 
@@ -81,6 +81,8 @@ def _load():
     lib.canz_muon_step.argtypes = [C.POINTER(_Group), C.c_int32, C.POINTER(_Hparams), C.c_void_p, C.c_size_t,
                                    C.c_void_p]
     lib.canz_muon_step.restype = C.c_int
+    lib.canz_muon_step_static.argtypes = [C.POINTER(_Group), C.c_int32, C.POINTER(_Hparams), C.c_void_p]
+    lib.canz_muon_step_static.restype = C.c_int
     lib.canz_profile_enable.argtypes = [C.c_int32]
     lib.canz_profile_enable.restype = C.c_int
     lib.canz_profile_collect.argtypes = [C.POINTER(C.c_double), i64p]
@@ -244,6 +246,16 @@ def canz_muon_step(groups: Sequence[Group], hp: Hparams, workspace, workspace_by
     h = hp._c()
     _check(_lib.canz_muon_step(arr, len(groups), C.byref(h), C.c_void_p(_addr(workspace)), int(workspace_bytes),
                                C.c_void_p(int(stream))))
+
+
+STATIC_WORKSPACE_BYTES = 128 << 20
+
+
+def canz_muon_step_static(groups: Sequence[Group], hp: Hparams, stream=0) -> None:
+    """canz_muon_step on the workspace built into the library (no device allocation)."""
+    arr, _keep = _marshal(groups)
+    h = hp._c()
+    _check(_lib.canz_muon_step_static(arr, len(groups), C.byref(h), C.c_void_p(int(stream))))
 
 
 def canz_profile_enable(max_launches: int) -> None:

@@ -10,6 +10,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <mutex>
 #include <vector>
 
 #include "canz.h"
@@ -415,7 +416,7 @@ extern "C" int canz_muon_workspace_bytes(const canz_group* g, int32_t n_groups, 
   for (int i = 0; i < n_groups; ++i)
     if (int rc = check_group(g[i], i, false, hp->out_mode)) return rc;
   std::vector<Batch> batches;
-  collect_batches(g, n_groups, hp->out_mode, false, batches);
+  if (int rc = collect_batches(g, n_groups, hp->out_mode, false, batches)) return rc;
   const std::vector<int> first = group_runs(batches, hp->precision);
   for (size_t r = 0; r + 1 < first.size(); ++r)
     need = std::max(need, run_bytes(batches, first[r], first[r + 1], hp->precision));
@@ -423,9 +424,12 @@ extern "C" int canz_muon_workspace_bytes(const canz_group* g, int32_t n_groups, 
   return CANZ_OK;
 }
 
-extern "C" int canz_muon_step(const canz_group* g, int32_t n_groups, const canz_muon_hparams* hp, void* workspace,
-                              size_t workspace_bytes, void* hip_stream) {
-  using namespace canz;
+namespace canz {
+namespace {
+
+// Validates the call and enqueues every run of launch batches on `st`, using `workspace`.
+int muon_step_on(const canz_group* g, int32_t n_groups, const canz_muon_hparams* hp, void* workspace,
+                 size_t workspace_bytes, hipStream_t st) {
   if (n_groups < 0 || (n_groups > 0 && !g)) return fail(CANZ_EINVAL, "bad group array");
   if (int rc = check_hparams(hp)) return rc;
   size_t need = 0;
@@ -440,10 +444,9 @@ extern "C" int canz_muon_step(const canz_group* g, int32_t n_groups, const canz_
   if (workspace_bytes < need)
     return fail(CANZ_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
 
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
   std::vector<Batch> batches;
-  collect_batches(g, n_groups, hp->out_mode, true, batches);
+  if (int rc = collect_batches(g, n_groups, hp->out_mode, true, batches)) return rc;
   const std::vector<int> first = group_runs(batches, hp->precision);
   for (size_t r = 0; r + 1 < first.size(); ++r) {
     const int rc = hp->precision == CANZ_PREC_BF16 ? run_batches<__bf16>(batches, first[r], first[r + 1], *hp, ws, st)
@@ -451,6 +454,59 @@ extern "C" int canz_muon_step(const canz_group* g, int32_t n_groups, const canz_
     if (rc) return rc;
   }
   return CANZ_OK;
+}
+
+// ---- workspace that lives in the library (canz_muon_step_static).  The array sits in the
+// code object of this file; every device that loads the library holds its own copy at its own
+// address until the process ends.  Host code never uses the array's name as an address: the
+// device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[CANZ_STATIC_WORKSPACE_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[MAX_DEVICES] = {nullptr};
+
+// Device address of `scratch` on the current device (nullptr + error message on failure).
+void* scratch_address() {
+  int dev = -1;
+  hipError_t err = hipGetDevice(&dev);
+  if (err != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+    fail(CANZ_EHIP, "hipGetDevice: %s (device %d)", hipGetErrorString(err), dev);
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (err != hipSuccess || !ptr) {
+      fail(CANZ_EHIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(err));
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
+}  // namespace
+}  // namespace canz
+
+extern "C" int canz_muon_step(const canz_group* g, int32_t n_groups, const canz_muon_hparams* hp, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  return canz::muon_step_on(g, n_groups, hp, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int canz_muon_step_static(const canz_group* g, int32_t n_groups, const canz_muon_hparams* hp,
+                                     void* hip_stream) {
+  using namespace canz;
+  if (n_groups < 0 || (n_groups > 0 && !g)) return fail(CANZ_EINVAL, "bad group array");
+  size_t need = 0;
+  if (int rc = canz_muon_workspace_bytes(g, n_groups, hp, &need)) return rc;
+  if (need > CANZ_STATIC_WORKSPACE_BYTES)
+    return fail(CANZ_EWORKSPACE, "step needs %zu bytes of scratch, the built-in workspace holds %zu", need,
+                static_cast<size_t>(CANZ_STATIC_WORKSPACE_BYTES));
+  void* ptr = scratch_address();
+  if (!ptr) return CANZ_EHIP;
+  return muon_step_on(g, n_groups, hp, ptr, CANZ_STATIC_WORKSPACE_BYTES, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" int canz_profile_enable(int32_t max_launches) {
