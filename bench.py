@@ -25,8 +25,10 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch (read + written) of the GEMM kernels on the default workload, from the
 # two rocprofv3 --pmc runs summarised in profiles/hbm_traffic_config4.md (FETCH_SIZE scaled by
 # 2.000, WRITE_SIZE by 1.000, the factors a plain 1 GiB copy gives).  Counters cannot be read
-# from inside this process, so the figures are carried here; other workloads report null.
-MEASURED_TRAFFIC_BYTES = {(4, "bf16", 1): {"gram": 3.90e9 + 0.21e9, "poly": 0.97e9 + 0.21e9,
+# from inside this process, so the figures are carried here, keyed by the library version they
+# were measured on (a library whose kernels changed since reports null until the profile is
+# taken again); other workloads report null.
+MEASURED_TRAFFIC_BYTES = {("0.1.0", 4, "bf16", 1): {"gram": 3.90e9 + 0.21e9, "poly": 0.97e9 + 0.21e9,
                                            "update": 10.14e9 + 2.24e9, "final": 10.60e9 + 2.37e9}}
 
 
@@ -94,33 +96,22 @@ class ClockSampler:
 
 def pick_tp_share(canz, W, cfg, cmax_bytes):
     """TP planner (Algorithms 2-4): micro-groups with a host rank per tensor; the share is what
-    the most loaded host rank computes, micro-group by micro-group, same shapes side by side."""
+    the most loaded host rank computes, one library call per micro-group of the sequence
+    (paper_2602_06079_amd.tp_runtime holds the walk; here only the share is chosen)."""
+    from paper_2602_06079_amd import tp_runtime as T
     s = W.matrix_set(cfg)
     cost = [r * c for r, c in zip(s["rows"], s["cols"])]
     t0 = time.perf_counter()
     mgroups, loads = canz.canz_tp_schedule(cost, s["tp"], cmax_bytes // 2)      # capacity in bf16 elements
-    plan_ms = (time.perf_counter() - t0) * 1e3
-    per_rank = [0] * s["tp"]
-    for mg in mgroups:
-        for t, h in mg:
-            per_rank[h] += cost[t]
+    per_rank = T.host_rank_loads(mgroups, cost, s["tp"])
     rank = max(range(s["tp"]), key=lambda r: (per_rank[r], -r))
-    groups = []
-    for mg in mgroups:
-        mine = sorted((t for t, h in mg if h == rank), key=lambda t: (-cost[t], s["rows"][t], s["cols"][t], t))
-        for t in mine:
-            shape = (s["rows"][t], s["cols"][t])
-            if groups and groups[-1][0] == shape and groups[-1][2] is mg:
-                groups[-1][1].append(t)
-            else:
-                groups.append((shape, [t], mg))
-    # one library call per TP micro-group (each sits between its own pair of exchanges)
-    calls, start = [], 0
-    for k in range(1, len(groups) + 1):
-        if k == len(groups) or groups[k][2] is not groups[start][2]:
-            calls.append((start, k))
-            start = k
-    groups = [g[1] for g in groups]
+    per_call = T.host_rank_calls(mgroups, rank, s["rows"], s["cols"], s["dtype"])
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    groups, calls = [], []
+    for batches in per_call:
+        if batches:
+            calls.append((len(groups), len(groups) + len(batches)))
+            groups += batches
     mean = sum(per_rank) / len(per_rank)
     diag = dict(rank=rank, n_ranks=s["tp"], alpha=None, r_lb_numel=max(per_rank) / mean if mean else 1.0,
                 planner_ms=plan_ms, tp_micro_groups=len(mgroups), cmax_bytes=cmax_bytes, calls=calls,
@@ -253,7 +244,13 @@ def main():
     torch.cuda.synchronize()
     log("warm-up done")
 
-    launches_per_step = sum(((len(g) + 15) // 16) * (2 + 3 * hp.ns_steps) for g in groups)
+    # launch records of one step, counted by the library itself in one profiled step (so the
+    # event pool of the timed run holds every launch whatever batches the library forms)
+    canz.canz_profile_enable(n_share * (6 + 3 * hp.ns_steps) + 8)
+    step()
+    torch.cuda.synchronize()
+    launches_per_step = sum(n for _ms, n in canz.canz_profile_collect().values())
+    canz.canz_profile_disable()
     graph = None
     if args.graph:
         side = torch.cuda.Stream()
@@ -326,8 +323,11 @@ def main():
         if n:
             kernels[k] = dict(ms_per_step=ms / args.steps, launches_per_step=n / args.steps, avg_ms=ms / n)
             if k in kind_flops:
-                kernels[k]["tflops_algorithmic"] = kind_flops[k] * args.steps / (ms * 1e-3) / 1e12
+                # "issued" is what the MFMA units execute and what belongs next to a peak;
+                # "effective" counts the method's nominal FLOPs (the symmetric products compute
+                # only the tiles on or above the diagonal, so it can exceed the peak)
                 kernels[k]["tflops_issued"] = kind_issued[k] * args.steps / (ms * 1e-3) / 1e12
+                kernels[k]["tflops_effective"] = kind_flops[k] * args.steps / (ms * 1e-3) / 1e12
     dom = max((k for k in kernels if k in kind_flops), key=lambda k: kernels[k]["ms_per_step"])
     dom_flops_per_launch = kind_flops[dom] / kernels[dom]["launches_per_step"]
     dom_issued_per_launch = kind_issued[dom] / kernels[dom]["launches_per_step"]
@@ -346,7 +346,7 @@ def main():
                   peak_tflops_at_sampled_clock=(cus * flop_per_clk_cu * seen_mhz * 1e6 / 1e12) if seen_mhz else None)
     roofline = dict(bound="mfma", kernel="k_gemm_nt_%s<%s>" % (args.precision, dom), achieved=achieved, peak=peak,
                     unit="TFLOP/s", frac=achieved / peak,
-                    traffic=MEASURED_TRAFFIC_BYTES.get((cfg, args.precision, tp), {}).get(dom), traffic_unit="B",
+                    traffic=MEASURED_TRAFFIC_BYTES.get((canz.canz_version(), cfg, args.precision, tp), {}).get(dom), traffic_unit="B",
                     achieved_issued=achieved_issued, frac_issued=achieved_issued / peak,
                     flops_per_launch=dom_flops_per_launch, issued_flops_per_launch=dom_issued_per_launch,
                     avg_launch_ms=kernels[dom]["avg_ms"])
@@ -378,24 +378,15 @@ def main():
         base = dict(beta=f(hp.beta), lr=f(hp.lr), eps=f(hp.eps), a=f(hp.a), b=f(hp.b), c=f(hp.c),
                     scale_mode=hp.scale_mode)
         t0 = time.perf_counter()
-        OM.muon_step(g64, mom0, OM.Hparams(ns_steps=0, **base), param=mom0)
-        t_ew = time.perf_counter() - t0
-        n_sample = min(3, hp.ns_steps)      # iterations timed: about 12 s on the default workload
-        t0 = time.perf_counter()
-        OM.muon_step(g64, mom0, OM.Hparams(ns_steps=n_sample, **base), param=mom0)
-        t_some = time.perf_counter() - t0
-        t_iter = max(t_some - t_ew, 0.0) / max(n_sample, 1)
-        f0 = ns_flops(rows, cols, 1)
-        est_s = 0.0
-        for g in groups:
-            r, c = s["rows"][g[0]], s["cols"][g[0]]
-            est_s += len(g) * (t_ew * (r * c) / (rows * cols) + hp.ns_steps * t_iter * ns_flops(r, c, 1) / f0)
+        OM.muon_step(g64, mom0, OM.Hparams(ns_steps=hp.ns_steps, **base), param=mom0)
+        t_one = time.perf_counter() - t0
+        f0 = ns_flops(rows, cols, hp.ns_steps)
+        est_s = sum(len(g) * t_one * ns_flops(s["rows"][g[0]], s["cols"][g[0]], hp.ns_steps) / f0 for g in groups)
         cpu = dict(value=est_s * 1e3, unit="ms", cores=int(cores), kind="oracle",
-                   sample="fp64 oracle on matrix %d (%dx%d): elementwise part %.2f s + %d of %d Newton-Schulz "
-                          "iterations at %.2f s each (%.0f GFLOP/s), scaled by FLOPs and elements to the %d-matrix share"
-                          % (g0[0], rows, cols, t_ew, n_sample, hp.ns_steps, t_iter, f0 / max(t_iter, 1e-9) / 1e9,
-                             n_share))
-        log("oracle sample: %.2f s measured, share estimated at %.1f s on %d threads" % (t_ew + t_some, est_s, cores))
+                   sample="fp64 oracle, one whole step (momentum, normalisation, %d Newton-Schulz iterations, update) "
+                          "of matrix %d (%dx%d): %.2f s (%.0f GFLOP/s), scaled by FLOPs to the %d-matrix share"
+                          % (hp.ns_steps, g0[0], rows, cols, t_one, f0 / max(t_one, 1e-9) / 1e9, n_share))
+        log("oracle sample: %.2f s measured, share estimated at %.1f s on %d threads" % (t_one, est_s, cores))
 
     out = {
         "metric": "optimizer_step_latency_ms", "value": ms_per_step, "unit": "ms",

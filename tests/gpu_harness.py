@@ -115,3 +115,23 @@ def run_step(canz, dgroups, hp, workspace=None):
 def rel_fro(got: np.ndarray, want: np.ndarray) -> float:
     den = float(np.linalg.norm(want))
     return float(np.linalg.norm(got - want)) / den if den > 0 else float(np.linalg.norm(got))
+
+
+TILE = 256
+
+
+def tile_errors(diff, ref):
+    """(largest per-tile relative Frobenius error, largest |diff| / rms(ref)) over the grid of
+    256 x 256 tiles; edge tiles are smaller.  A tile whose reference is all zero counts by its
+    absolute error against the matrix rms."""
+    rows, cols = ref.shape
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    pr, pc = -rows % TILE, -cols % TILE
+    d2 = np.pad(diff * diff, ((0, pr), (0, pc)))
+    r2 = np.pad(ref * ref, ((0, pr), (0, pc)))
+    shape = (d2.shape[0] // TILE, TILE, d2.shape[1] // TILE, TILE)
+    dt = d2.reshape(shape).sum(axis=(1, 3))
+    rt = r2.reshape(shape).sum(axis=(1, 3))
+    floor = (rms * 1e-3) ** 2
+    worst_tile = float(np.sqrt(np.max(dt / np.maximum(rt, floor))))
+    return worst_tile, float(np.max(np.abs(diff))) / rms if rms > 0 else float(np.max(np.abs(diff)))

@@ -1,7 +1,7 @@
 """GPU: canz_muon_step under HIP graph capture, and calls with empty groups.
 
-The step issues kernels only (scratch counters are cleared by a kernel, never by a
-memset), allocates nothing and never synchronises, so a caller may capture it.  A graph
+The step issues kernels only (no memset, no copy: nothing in the workspace has to start
+at zero), allocates nothing and never synchronises, so a caller may capture it.  A graph
 is replayed several times with eager work and synchronisations in between, and every
 replay must reproduce the eager result bit for bit."""
 import numpy as np
@@ -104,6 +104,10 @@ def test_rank_latency_tool_on_config2(canz):
     worst = {r[2].strip(): float(r[4]) for r in rows}
     assert all(v > 0 for v in worst.values())
     log("slowest rank, ms: %s" % worst)
+    static = worst["static, Eq. 1 per bucket"]
+    # measured gaps on this set are 20 - 30 %; the bound leaves room for timing noise of two steps
+    assert worst["Alg. 1, alpha = 1, W = numel"] <= static * 1.02
+    assert worst["Alg. 1, alpha = 1, W = FLOPs"] <= static * 1.02
 
 
 def test_two_streams_with_separate_workspaces(canz):

@@ -162,15 +162,22 @@ def test_batch_independence_and_determinism(canz):
         assert np.array_equal(got, outs[0][i])
 
 
-def test_group_larger_than_launch_batch(canz):
-    """150 matrices in one group: split internally into launches of at most 128."""
+@pytest.mark.parametrize("precision", [0, 1])
+def test_group_larger_than_launch_batch(canz, precision):
+    """150 matrices in one group: split internally into launches of at most 128 (in bf16 mode
+    the two launch batches, 128 + 22, then share their Gram, polynomial and update launches).
+    Matrices on both sides of the cut also give the same bits as when run alone."""
     rows, cols, n = 256, 256, 150
     grads = [W.gen_grad(95, i, rows, cols)[0] for i in range(n)]
     zeros = [np.zeros((rows, cols), np.float32) for _ in range(n)]
-    hp = canz.Hparams(out_mode=canz.OUT_DELTA, precision=1)
+    hp = canz.Hparams(out_mode=canz.OUT_DELTA, precision=precision)
     dg = DeviceGroup(canz, rows, cols, grads, zeros)
     run_step(canz, [dg], hp)
-    _check_group(canz, dg, grads, zeros, None, hp, "150-matrix group")
+    _check_group(canz, dg, grads, zeros, None, hp, "150-matrix group prec%d" % precision)
+    for i in (0, 127, 128, 149):
+        solo = DeviceGroup(canz, rows, cols, [grads[i]], [zeros[i]])
+        run_step(canz, [solo], hp)
+        assert np.array_equal(solo.out_host(0), dg.out_host(i))
 
 
 @pytest.mark.parametrize("precision", [0, 1])
