@@ -108,11 +108,13 @@ def _check_oracle(p, dg, hg, k, hp, label):
         diff, extra = got - ref["param"], 1e-5
     err = float(np.linalg.norm(diff) / np.linalg.norm(ref["delta"]))
     worst_tile, worst_abs = tile_errors(diff, ref["delta"])
+    # a bf16 store is off by up to 2^-8 of the element, the largest element is several rms
+    abs_extra = (2.0 ** -8 * float(np.max(np.abs(ref["delta"]))) / float(np.sqrt(np.mean(ref["delta"] ** 2)))) if dg.delta else 4 * extra
     log("%s: matrix %d error %.3g (tol %.2g), worst tile %.3g (tol %.2g), largest element error %.3g rms (tol %.2g)"
-        % (label, p, err, TOL[prec] + extra, worst_tile, TILE_TOL[prec] + extra, worst_abs, MAXABS_TOL[prec] + 4 * extra))
+        % (label, p, err, TOL[prec] + extra, worst_tile, TILE_TOL[prec] + extra, worst_abs, MAXABS_TOL[prec] + abs_extra))
     assert err <= TOL[prec] + extra, "%s: matrix %d error %.3g" % (label, p, err)
     assert worst_tile <= TILE_TOL[prec] + extra, "%s: matrix %d has a tile off by %.3g" % (label, p, worst_tile)
-    assert worst_abs <= MAXABS_TOL[prec] + 4 * extra, "%s: matrix %d has an element off by %.3g rms" % (label, p, worst_abs)
+    assert worst_abs <= MAXABS_TOL[prec] + abs_extra, "%s: matrix %d has an element off by %.3g rms" % (label, p, worst_abs)
 
 
 def _whole_share(canz, cfg, s, groups, precision, samples, label):
