@@ -16,13 +16,17 @@ microgroup  Same-shape batching of one rank's matrices (the deterministic
             classes, with a capacity cap in the spirit of C_max).
 tp_schedule TP micro-group construction with greedy rollback and the min-heap LPT solver
             (Algorithm 2; Algorithms 3 and 4 in App. C).
+shampoo     The Shampoo operator the paper runs through the same planner (App. C,
+            "Generalization to Other Optimizers"): Kronecker-factor statistics, inverse
+            fourth roots by eigendecomposition, preconditioned update.
 muon        The Muon operator named in Sec. 4.1 / App. B.3: momentum,
             Frobenius normalisation, k Newton-Schulz steps, scaled update;
             TP column-fragment gather/scatter of Sec. 4.1 stages (1) and (3).
 
 Parity pins (tests/test_oracle_*.py): every function here is pinned to
 something other than itself - SVD closed forms and the polar factor for the
-Newton-Schulz iteration, a scalar-map grid for the quintic band, hand-worked
+Newton-Schulz iteration, a scalar-map grid for the quintic band, defining identities
+and diagonal / rank-one / SVD closed forms for the Shampoo step, hand-worked
 partitions, exact-rational replays, brute-force enumeration of cut vectors,
 and structural invariants.  The paper's measured load-balance ratios depend on
 a bucket layout it does not give; they are not pinned.

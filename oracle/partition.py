@@ -24,6 +24,7 @@ from fractions import Fraction
 
 COST_NUMEL = 0      # W(p) = numel(p), the paper's default (Sec. 3.2)
 COST_NS_FLOPS = 1   # W(p) = FLOPs of the Newton-Schulz chain (App. D.5 ablation)
+COST_SHAMPOO_FLOPS = 2  # W(p) = FLOPs of a Shampoo step in units of 2^20 (App. D.5: cost follows the operator)
 
 
 def ns_flops(rows: int, cols: int, ns_steps: int = 5) -> int:
@@ -37,8 +38,22 @@ def ns_flops(rows: int, cols: int, ns_steps: int = 5) -> int:
     return ns_steps * (4 * m * m * n + 2 * m * m * m)
 
 
+def shampoo_flops(rows: int, cols: int, root_iters: int = 25) -> int:
+    """FLOPs of one Shampoo step on a rows x cols matrix (the non-linear cost of
+    App. D.5 for this operator): the two statistics G G^T and G^T G
+    (2 r^2 c + 2 c^2 r), the two preconditioning products L^(-1/4) G and (.) R^(-1/4)
+    (the same again), and the two inverse fourth roots, each root_iters rounds of four
+    d x d products of 2 d^3 (the matmul-only root finder): 8 root_iters (r^3 + c^3).
+    """
+    r, c = int(rows), int(cols)
+    return 4 * r * r * c + 4 * c * c * r + 8 * root_iters * (r ** 3 + c ** 3)
+
+
 def param_cost(rows, cols, cost_kind: int = COST_NUMEL, ns_steps: int = 5):
     """W(p) for every parameter, as Python ints."""
+    if cost_kind == COST_SHAMPOO_FLOPS:
+        # in units of 2^20 FLOPs, rounded down, so that the loads of a large model stay exact in fp64
+        return [shampoo_flops(int(r), int(c)) >> 20 for r, c in zip(rows, cols)]
     if cost_kind == COST_NUMEL:
         return [int(r) * int(c) for r, c in zip(rows, cols)]
     if cost_kind == COST_NS_FLOPS:

@@ -19,7 +19,16 @@ constexpr __int128 LOAD_LIMIT = __int128(1) << 53;  // loads above this are not 
 int64_t checked_cost(int64_t rows, int64_t cols, int cost_kind) {
   const __int128 m = std::min(rows, cols), n = std::max(rows, cols);
   if (n >= (int64_t(1) << 31)) return -1;  // keeps every product below 2^127
-  const __int128 w = cost_kind == CANZ_COST_NUMEL ? m * n : 5 * (4 * m * m * n + 2 * m * m * m);
+  __int128 w;
+  if (cost_kind == CANZ_COST_NUMEL) {
+    w = m * n;
+  } else if (cost_kind == CANZ_COST_NS_FLOPS) {
+    w = 5 * (4 * m * m * n + 2 * m * m * m);
+  } else {
+    // Shampoo step: statistics and preconditioning products 4 (r^2 c + c^2 r), two inverse roots
+    // of 25 rounds x 4 products each: 200 (r^3 + c^3); counted in units of 2^20 FLOPs
+    w = (4 * m * n * (m + n) + 200 * (m * m * m + n * n * n)) >> 20;
+  }
   return w < LOAD_LIMIT ? static_cast<int64_t>(w) : -1;
 }
 
@@ -36,7 +45,7 @@ extern "C" int canz_partition_alpha(int64_t n_mats, const int64_t* rows, const i
   if (!cost && (!rows || !cols) && n_mats > 0) return fail(CANZ_EINVAL, "need cost or rows/cols");
   if (n_ranks < 1) return fail(CANZ_EINVAL, "n_ranks must be >= 1");
   if (!(alpha >= 0.0 && alpha <= 1.0)) return fail(CANZ_EINVAL, "alpha must lie in [0,1]");
-  if (!cost && cost_kind != CANZ_COST_NUMEL && cost_kind != CANZ_COST_NS_FLOPS)
+  if (!cost && cost_kind != CANZ_COST_NUMEL && cost_kind != CANZ_COST_NS_FLOPS && cost_kind != CANZ_COST_SHAMPOO_FLOPS)
     return fail(CANZ_EUNSUPPORTED, "unknown cost_kind %d", cost_kind);
   if (bucket_off[0] != 0 || bucket_off[n_buckets] != n_mats)
     return fail(CANZ_EINVAL, "bucket_off must run from 0 to n_mats");

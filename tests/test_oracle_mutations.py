@@ -1,5 +1,6 @@
 """Pin strength: mistakes planted in a copy of the oracle's source must each be caught by
-at least one of the pins in test_oracle_partition / test_oracle_muon / test_tp_schedule.
+at least one of the pins in test_oracle_partition / test_oracle_muon / test_oracle_shampoo /
+test_tp_schedule.
 
 A mutant is the oracle module's source with one expression replaced (a dropped term, a
 wrong sign, a transposed operand, a flipped comparison), executed as a fresh module; the
@@ -13,9 +14,11 @@ import pytest
 
 import oracle.muon as OM
 import oracle.partition as OP
+import oracle.shampoo as SHO
 import oracle.tp_schedule as TS
 from tests import test_oracle_muon as PINS_MUON
 from tests import test_oracle_partition as PINS_PART
+from tests import test_oracle_shampoo as PINS_SHAMPOO
 from tests import test_tp_schedule as PINS_TP
 
 
@@ -117,6 +120,46 @@ TP_MUTANTS = [
 ]
 
 
+SHAMPOO_MUTANTS = [
+    ("left statistic from G^T G", "+ g @ g.T", "+ (g.T @ g if g.shape[0] == g.shape[1] else g @ g.T)"),
+    ("right statistic from G G^T", "+ g.T @ g", "+ (g @ g.T if g.shape[0] == g.shape[1] else g.T @ g)"),
+    ("decay on the new term", "new_left = beta * np.asarray(left, dtype=np.float64) + g @ g.T",
+     "new_left = np.asarray(left, dtype=np.float64) + beta * (g @ g.T)"),
+    ("inverse square root instead of fourth root", "return (vec * lam ** -0.25) @ vec.T", "return (vec * lam ** -0.5) @ vec.T"),
+    ("ridge not added", "lam = np.maximum(lam, 0.0) + eps", "lam = np.maximum(lam, 0.0) + 0.0 * eps + 1e-300"),
+    ("eigenvectors transposed", "return (vec * lam ** -0.25) @ vec.T", "return (vec.T * lam ** -0.25) @ vec"),
+    ("preconditioned on the left only", "precond = left_root @ g @ right_root", "precond = left_root @ g"),
+    ("roots on the wrong sides", "precond = left_root @ g @ right_root",
+     "precond = right_root @ g @ left_root if g.shape[0] == g.shape[1] else left_root @ g @ right_root"),
+    ("update with the wrong sign", "delta = -hp.lr * precond", "delta = hp.lr * precond"),
+    ("weight decay without the learning rate", "* (1.0 - hp.lr * hp.weight_decay) + delta", "* (1.0 - hp.weight_decay) + delta"),
+    ("right root taken of the left statistic", "right_root = inverse_fourth_root(new_right, hp.eps)",
+     "right_root = inverse_fourth_root(new_left if new_left.shape == new_right.shape else new_right, hp.eps)"),
+    ("roots of the statistics before the update", "left_root = inverse_fourth_root(new_left, hp.eps)",
+     "left_root = inverse_fourth_root(np.asarray(left, dtype=np.float64), hp.eps)"),
+    ("fragments gathered along rows", "return np.concatenate([np.asarray(f, dtype=np.float64) for f in fragments], axis=1)",
+     "return np.concatenate([np.asarray(f, dtype=np.float64) for f in fragments], axis=0).reshape(fragments[0].shape[0], -1)"),
+]
+
+SHAMPOO_COST_MUTANTS = [
+    ("cubic cost of the roots dropped", "+ 8 * root_iters * (r ** 3 + c ** 3)", ""),
+    ("cost of the statistics counted for one side", "return 4 * r * r * c + 4 * c * c * r", "return 4 * r * r * c"),
+    ("cost units not scaled", "return [shampoo_flops(int(r), int(c)) >> 20", "return [shampoo_flops(int(r), int(c))"),
+]
+
+
+@pytest.mark.parametrize("what,old,new", SHAMPOO_MUTANTS, ids=[m[0] for m in SHAMPOO_MUTANTS])
+def test_shampoo_pins_catch(what, old, new):
+    failed = _caught(PINS_SHAMPOO, "SH", _mutant(SHO, old, new))
+    assert failed, "no pin notices: " + what
+
+
+@pytest.mark.parametrize("what,old,new", SHAMPOO_COST_MUTANTS, ids=[m[0] for m in SHAMPOO_COST_MUTANTS])
+def test_shampoo_cost_pins_catch(what, old, new):
+    failed = _caught(PINS_SHAMPOO, "OP", _mutant(OP, old, new))
+    assert failed, "no pin notices: " + what
+
+
 @pytest.mark.parametrize("what,old,new", TP_MUTANTS, ids=[m[0] for m in TP_MUTANTS])
 def test_tp_schedule_pins_catch(what, old, new):
     failed = _caught(PINS_TP, "TS", _mutant(TS, old, new))
@@ -140,3 +183,4 @@ def test_unmutated_oracle_passes_the_same_harness():
     assert _caught(PINS_MUON, "M", importlib.import_module("oracle.muon")) == []
     assert _caught(PINS_PART, "P", importlib.import_module("oracle.partition")) == []
     assert _caught(PINS_TP, "TS", importlib.import_module("oracle.tp_schedule")) == []
+    assert _caught(PINS_SHAMPOO, "SH", importlib.import_module("oracle.shampoo")) == []

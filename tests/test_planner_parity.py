@@ -23,7 +23,7 @@ def _same_partition(canz, rows, cols, off, R, alpha, cost=None, cost_kind=0):
 def test_configs_bit_exact(canz, cfg):
     s = W.matrix_set(cfg)
     for alpha in sorted({s["alpha"], 0.0, 0.1, 0.5, 1.0}):
-        for kind in (OP.COST_NUMEL, OP.COST_NS_FLOPS):
+        for kind in (OP.COST_NUMEL, OP.COST_NS_FLOPS, OP.COST_SHAMPOO_FLOPS):
             owner, load = _same_partition(canz, s["rows"], s["cols"], s["bucket_off"], s["n_ranks"], alpha,
                                           cost_kind=kind)
     owner, load = _same_partition(canz, s["rows"], s["cols"], s["bucket_off"], s["n_ranks"], s["alpha"])
@@ -60,7 +60,7 @@ def test_random_cases_bit_exact(canz):
             off.append(len(rows))
         R = rng.randint(1, 9)
         alpha = rng.choice([0.0, 0.1, 1 / 3, 0.5, 0.9, 1.0])
-        kind = rng.randint(0, 1)
+        kind = rng.randint(0, 2)
         if not rows:
             continue
         owner, _ = _same_partition(canz, rows, cols, off, R, alpha, cost_kind=kind)
