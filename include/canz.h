@@ -234,6 +234,67 @@ int canz_muon_step(const canz_group* g, int32_t n_groups, const canz_muon_hparam
                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Shampoo, the second matrix optimizer the paper runs through the same planner ("Generalization
+ * to Other Optimizers (Shampoo & SOAP)", App. C; "preconditioning matrices derived from the
+ * Kronecker product of gradients", App. B.3), under the generic update of App. B.3, Eq. 5.
+ * Per matrix G (rows x cols), with its two statistics as optimizer state:
+ *   L <- beta L + G G^T   (rows x rows),   R <- beta R + G^T G   (cols x cols)
+ *   O = (L + eps I)^(-1/4) G (R + eps I)^(-1/4)
+ *   CANZ_OUT_PARAM: P <- P (1 - lr weight_decay) - lr O;   CANZ_OUT_DELTA: Delta W = - lr O
+ * beta = 1 gives the running sums of the original algorithm (initialise L and R to eps0 I for
+ * its L_0 = eps0 I, or to zero and pass eps).  The inverse fourth roots are computed in fp32
+ * by root_iters rounds of a matmul-only coupled Newton iteration
+ * (T = (5 I - M) / 4; X <- X T; M <- T^4 M; from M = z A, X = z^(1/4) I, z = 5 / (2 ||A||_F)),
+ * which converges to A^(-1/4) for symmetric positive definite A = S + eps I once the
+ * smallest eigenvalue of M has grown to 1: about log(cond(A)) / log(2.44) + 5 rounds (25 rounds
+ * cover cond(A) <= 10^6).  eps must be large enough that A is positive definite in fp32:
+ * eps >= 10^-6 lambda_max(S) is safe; below that the iteration may diverge (NaN output).
+ * Because the statistics are held in fp32, the update's relative error against exact arithmetic
+ * grows like 1.3e-8 lambda_max(S) / eps: below 5e-3 for eps >= 10^-5 lambda_max(S).
+ *
+ * One micro-group: n_mats matrices of identical shape and dtypes; grad / out / tp as in
+ * canz_group; left[i] (rows x rows) and right[i] (cols x cols) are fp32, dense, row-major,
+ * device, 16-byte aligned, updated in place (they stay exactly symmetric).
+ */
+typedef struct {
+  int64_t rows, cols;
+  int32_t n_mats;
+  int32_t tp;
+  int32_t grad_dtype;       /* CANZ_DT_F32 or CANZ_DT_BF16 */
+  int32_t out_dtype;
+  const void* const* grad;  /* [n_mats*tp] */
+  void* const* left;        /* [n_mats] */
+  void* const* right;       /* [n_mats] */
+  void* const* out;         /* [n_mats] parameters, or [n_mats*tp] Delta W fragments */
+} canz_shampoo_group;
+
+typedef struct {
+  float beta, lr, weight_decay, eps;
+  int32_t root_iters;       /* >= 1; 25 is the default of the cost model CANZ_COST_SHAMPOO_FLOPS */
+  int32_t out_mode;         /* CANZ_OUT_* */
+} canz_shampoo_hparams;
+
+/*
+ * canz_shampoo_workspace_bytes - device scratch canz_shampoo_step needs for these groups (the
+ * largest of its launch batches: same-shape matrices of one group, as many as fit in about
+ * 8 GB of fp32 working matrices, at least one).  Pointer tables may be NULL for this call.
+ */
+int canz_shampoo_workspace_bytes(const canz_shampoo_group* g, int32_t n_groups,
+                                 const canz_shampoo_hparams* hp, size_t* bytes_out);
+
+/*
+ * canz_shampoo_step - enqueue one Shampoo step for the given micro-groups on hip_stream.
+ * Same conventions as canz_muon_step: host tables of device pointers read during the call,
+ * caller-owned 256-byte aligned workspace whose contents are scratch, kernel launches only
+ * (no allocation, copy, memset or synchronisation), completion in stream order.
+ * Errors: CANZ_EINVAL (null pointers, n_mats < 0, tp outside 1..8, root_iters < 1, eps < 0),
+ * CANZ_ESHAPE (cols not divisible by tp, fragment width not a multiple of 8, an extent above
+ * 32768), CANZ_EWORKSPACE, CANZ_EUNSUPPORTED (dtype / mode enums), CANZ_EHIP.
+ */
+int canz_shampoo_step(const canz_shampoo_group* g, int32_t n_groups, const canz_shampoo_hparams* hp,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * canz_muon_step_static - canz_muon_step without a workspace argument, for callers that
  * cannot allocate device memory or may not call an allocator where the step is issued
  * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).
@@ -256,7 +317,7 @@ int canz_muon_step_static(const canz_group* g, int32_t n_groups, const canz_muon
                           void* hip_stream);
 
 /*
- * Per-kernel timing of canz_muon_step, for benchmarks (the measurement protocol of
+ * Per-kernel timing of canz_muon_step / canz_shampoo_step, for benchmarks (the measurement protocol of
  * App. C.1 reports the optimizer time; this splits it by kernel).  While enabled, every
  * kernel launch of a step is bracketed by a pair of HIP events on the step's own stream.
  * Process-wide state: use from one thread, with steps that do not overlap.
@@ -276,7 +337,12 @@ enum {
   CANZ_KERNEL_UPDATE = 4,   /* X <- B X (both orientations)                 */
   CANZ_KERNEL_FINAL = 5,    /* last B X fused with the parameter update     */
   CANZ_KERNEL_APPLY = 6,    /* update without Newton-Schulz steps           */
-  CANZ_KERNEL_KINDS = 7
+  CANZ_KERNEL_SH_LOAD = 7,  /* Shampoo: gather + cast of G, both orientations */
+  CANZ_KERNEL_SH_STAT = 8,  /* Shampoo: L, R statistics                       */
+  CANZ_KERNEL_SH_INIT = 9,  /* Shampoo: norm and start of the root iteration  */
+  CANZ_KERNEL_SH_ROOT = 10, /* Shampoo: products of the root iteration        */
+  CANZ_KERNEL_SH_APPLY = 11,/* Shampoo: L^(-1/4) G and (.) R^(-1/4) + update   */
+  CANZ_KERNEL_KINDS = 12
 };
 int canz_profile_enable(int32_t max_launches);
 int canz_profile_collect(double* ms_out, int64_t* launches_out);

@@ -27,8 +27,10 @@ OUT_PARAM, OUT_DELTA = 0, 1
 
 EXPORTS = ("canz_last_error", "canz_version", "canz_partition_alpha", "canz_partition_naive", "canz_microgroup_plan", "canz_tp_schedule",
            "canz_muon_workspace_bytes", "canz_muon_step", "canz_muon_step_static",
+           "canz_shampoo_workspace_bytes", "canz_shampoo_step",
            "canz_profile_enable", "canz_profile_collect", "canz_profile_disable")
-KERNEL_KINDS = ("momentum", "norm", "gram", "poly", "update", "final", "apply")
+KERNEL_KINDS = ("momentum", "norm", "gram", "poly", "update", "final", "apply",
+                "sh_load", "sh_stat", "sh_init", "sh_root", "sh_apply")
 
 
 class CanzError(RuntimeError):
@@ -48,6 +50,18 @@ class _Hparams(C.Structure):
                 ("nesterov", C.c_int32), ("ns_steps", C.c_int32),
                 ("a", C.c_float), ("b", C.c_float), ("c", C.c_float),
                 ("scale_mode", C.c_int32), ("precision", C.c_int32), ("out_mode", C.c_int32)]
+
+
+class _ShGroup(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("n_mats", C.c_int32), ("tp", C.c_int32),
+                ("grad_dtype", C.c_int32), ("out_dtype", C.c_int32),
+                ("grad", C.POINTER(C.c_void_p)), ("left", C.POINTER(C.c_void_p)), ("right", C.POINTER(C.c_void_p)),
+                ("out", C.POINTER(C.c_void_p))]
+
+
+class _ShHparams(C.Structure):
+    _fields_ = [("beta", C.c_float), ("lr", C.c_float), ("weight_decay", C.c_float), ("eps", C.c_float),
+                ("root_iters", C.c_int32), ("out_mode", C.c_int32)]
 
 
 def _load():
@@ -83,6 +97,12 @@ def _load():
     lib.canz_muon_step.restype = C.c_int
     lib.canz_muon_step_static.argtypes = [C.POINTER(_Group), C.c_int32, C.POINTER(_Hparams), C.c_void_p]
     lib.canz_muon_step_static.restype = C.c_int
+    lib.canz_shampoo_workspace_bytes.argtypes = [C.POINTER(_ShGroup), C.c_int32, C.POINTER(_ShHparams),
+                                                 C.POINTER(C.c_size_t)]
+    lib.canz_shampoo_workspace_bytes.restype = C.c_int
+    lib.canz_shampoo_step.argtypes = [C.POINTER(_ShGroup), C.c_int32, C.POINTER(_ShHparams), C.c_void_p, C.c_size_t,
+                                      C.c_void_p]
+    lib.canz_shampoo_step.restype = C.c_int
     lib.canz_profile_enable.argtypes = [C.c_int32]
     lib.canz_profile_enable.restype = C.c_int
     lib.canz_profile_collect.argtypes = [C.POINTER(C.c_double), i64p]
@@ -246,6 +266,64 @@ def canz_muon_step(groups: Sequence[Group], hp: Hparams, workspace, workspace_by
     h = hp._c()
     _check(_lib.canz_muon_step(arr, len(groups), C.byref(h), C.c_void_p(_addr(workspace)), int(workspace_bytes),
                                C.c_void_p(int(stream))))
+
+
+@dataclass
+class ShampooHparams:
+    beta: float = 1.0
+    lr: float = 0.02
+    weight_decay: float = 0.0
+    eps: float = 1e-6
+    root_iters: int = 25
+    out_mode: int = OUT_PARAM
+
+    def _c(self) -> _ShHparams:
+        return _ShHparams(self.beta, self.lr, self.weight_decay, self.eps, int(self.root_iters), int(self.out_mode))
+
+
+@dataclass
+class ShampooGroup:
+    """One micro-group of canz_shampoo_step: device buffers given as addresses or objects with data_ptr()."""
+    rows: int
+    cols: int
+    grad: Sequence = field(default_factory=list)    # n_mats * tp
+    left: Sequence = field(default_factory=list)    # n_mats, fp32 rows x rows
+    right: Sequence = field(default_factory=list)   # n_mats, fp32 cols x cols
+    out: Sequence = field(default_factory=list)     # n_mats (params) or n_mats * tp (delta fragments)
+    tp: int = 1
+    grad_dtype: int = DT_BF16
+    out_dtype: int = DT_F32
+    n_mats: int = -1                                # -1: len(left)
+
+
+def _marshal_shampoo(groups: Sequence[ShampooGroup]):
+    arr = (_ShGroup * max(len(groups), 1))()
+    keep = []
+    for i, g in enumerate(groups):
+        n_mats = len(g.left) if g.n_mats < 0 else g.n_mats
+        tabs = []
+        for seq in (g.grad, g.left, g.right, g.out):
+            t = (C.c_void_p * max(len(seq), 1))(*[_addr(x) for x in seq])
+            keep.append(t)
+            tabs.append(C.cast(t, C.POINTER(C.c_void_p)) if len(seq) else None)
+        arr[i] = _ShGroup(int(g.rows), int(g.cols), int(n_mats), int(g.tp), int(g.grad_dtype), int(g.out_dtype), *tabs)
+    return arr, keep
+
+
+def canz_shampoo_workspace_bytes(groups: Sequence[ShampooGroup], hp: ShampooHparams) -> int:
+    arr, _keep = _marshal_shampoo(groups)
+    out = C.c_size_t(0)
+    h = hp._c()
+    _check(_lib.canz_shampoo_workspace_bytes(arr, len(groups), C.byref(h), C.byref(out)))
+    return int(out.value)
+
+
+def canz_shampoo_step(groups: Sequence[ShampooGroup], hp: ShampooHparams, workspace, workspace_bytes: int, stream=0) -> None:
+    """Enqueue one Shampoo step on ``stream`` (an integer hipStream_t)."""
+    arr, _keep = _marshal_shampoo(groups)
+    h = hp._c()
+    _check(_lib.canz_shampoo_step(arr, len(groups), C.byref(h), C.c_void_p(_addr(workspace)), int(workspace_bytes),
+                                  C.c_void_p(int(stream))))
 
 
 STATIC_WORKSPACE_BYTES = 128 << 20

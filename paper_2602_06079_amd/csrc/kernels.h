@@ -14,6 +14,8 @@
 
 #include <cstdint>
 
+#include "canz_internal.h"
+
 namespace canz {
 
 constexpr int PAD = 256;           // working extents are multiples of this
@@ -36,6 +38,19 @@ struct Shape {
   int tp;               // column fragments of grad / delta
   int64_t wfrag;        // cols / tp
 };
+
+// ---- per-kernel timing (canz_profile_*) --------------------------------------------
+// Records an event on `st` before (begin) or after a launch of the given CANZ_KERNEL_* kind;
+// does nothing while profiling is off.
+void prof_mark(hipStream_t st, int kind, bool begin);
+
+#define CANZ_HIP(kind, expr, what)                                                      \
+  do {                                                                                  \
+    ::canz::prof_mark(st, kind, true);                                                  \
+    hipError_t err__ = (expr);                                                          \
+    ::canz::prof_mark(st, kind, false);                                                 \
+    if (err__ != hipSuccess) return ::canz::fail(CANZ_EHIP, "%s: %s", what, hipGetErrorString(err__)); \
+  } while (0)
 
 // ---- elementwise -----------------------------------------------------------------
 // M <- beta M + G; U = M or G + beta M; U written (type T = bf16 or float) to XW and XT

@@ -18,6 +18,33 @@
 #include "kernels.h"
 
 namespace canz {
+
+// ---- optional per-kernel timing (canz_profile_*): a pool of event pairs recorded around
+// each launch on the step's own stream.  Process-wide state; not meant for concurrent steps.
+namespace {
+struct Profiler {
+  bool on = false;
+  std::vector<hipEvent_t> ev;   // 2 per launch
+  std::vector<int> kind;        // kind of each recorded launch
+  size_t used = 0;              // launches recorded
+};
+Profiler g_prof;
+}  // namespace
+
+void prof_mark(hipStream_t st, int kind, bool begin) {
+  if (!g_prof.on || g_prof.used * 2 + 1 >= g_prof.ev.size()) return;
+  if (begin) {
+    (void)hipEventRecord(g_prof.ev[g_prof.used * 2], st);
+  } else {
+    (void)hipEventRecord(g_prof.ev[g_prof.used * 2 + 1], st);
+    g_prof.kind[g_prof.used] = kind;
+    ++g_prof.used;
+  }
+}
+
+}  // namespace canz
+
+namespace canz {
 namespace {
 
 constexpr size_t ALIGN = 256;
@@ -106,35 +133,6 @@ double update_scale(const canz_group& g, int mode) {
   if (mode == CANZ_SCALE_RMS) return 0.2 * std::sqrt(static_cast<double>(std::max(g.rows, g.cols)));
   return 1.0;
 }
-
-// ---- optional per-kernel timing (canz_profile_*): a pool of event pairs recorded around
-// each launch on the step's own stream.  Process-wide state; not meant for concurrent steps.
-struct Profiler {
-  bool on = false;
-  std::vector<hipEvent_t> ev;   // 2 per launch
-  std::vector<int> kind;        // kind of each recorded launch
-  size_t used = 0;              // launches recorded
-};
-Profiler g_prof;
-
-inline void prof_mark(hipStream_t st, int kind, bool begin) {
-  if (!g_prof.on || g_prof.used * 2 + 1 >= g_prof.ev.size()) return;
-  if (begin) {
-    (void)hipEventRecord(g_prof.ev[g_prof.used * 2], st);
-  } else {
-    (void)hipEventRecord(g_prof.ev[g_prof.used * 2 + 1], st);
-    g_prof.kind[g_prof.used] = kind;
-    ++g_prof.used;
-  }
-}
-
-#define CANZ_HIP(kind, expr, what)                                                      \
-  do {                                                                                  \
-    prof_mark(st, kind, true);                                                          \
-    hipError_t err__ = (expr);                                                          \
-    prof_mark(st, kind, false);                                                         \
-    if (err__ != hipSuccess) return fail(CANZ_EHIP, "%s: %s", what, hipGetErrorString(err__)); \
-  } while (0)
 
 // Launch batches: consecutive matrices of the call that share dtypes and shape - up to a
 // transpose, since the iteration runs on the wide orientation of either - are batched

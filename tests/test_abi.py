@@ -88,3 +88,34 @@ def test_step_argument_errors_without_device(canz):
     # nothing to do: no device work, no workspace needed
     canz.canz_muon_step([], hp, 0, 0, 0)
     canz.canz_muon_step([canz.Group(rows=4, cols=4, n_mats=0)], hp, 0, 0, 0)
+
+
+def test_shampoo_argument_errors_and_workspace_without_device(canz):
+    hp = canz.ShampooHparams()
+    ok = dict(rows=256, cols=512, grad=[4096], left=[8192], right=[12288], out=[16384])
+
+    def code(groups, hp_, ws=256 * 1024, ws_bytes=1 << 40):
+        with pytest.raises(canz.CanzError) as e:
+            canz.canz_shampoo_step(groups, hp_, ws, ws_bytes, 0)
+        return e.value.code
+
+    G = canz.ShampooGroup
+    assert code([G(**{**ok, "grad": [4100]})], hp) == canz.EINVAL
+    assert code([G(**{**ok, "right": [0]})], hp) == canz.EINVAL
+    assert code([G(**{**ok, "tp": 9})], hp) == canz.EINVAL
+    assert code([G(**{**ok, "tp": 3})], hp) == canz.ESHAPE
+    assert code([G(**{**ok, "rows": 32769})], hp) == canz.ESHAPE
+    assert code([G(**{**ok, "out_dtype": 7})], hp) == canz.EUNSUPPORTED
+    assert code([G(**ok)], canz.ShampooHparams(root_iters=0)) == canz.EINVAL
+    assert code([G(**ok)], canz.ShampooHparams(eps=-1.0)) == canz.EINVAL
+    assert code([G(**ok)], canz.ShampooHparams(out_mode=3)) == canz.EUNSUPPORTED
+    assert code([G(**ok)], hp, ws=0) == canz.EWORKSPACE
+    assert code([G(**ok)], hp, ws_bytes=1024) == canz.EWORKSPACE
+    canz.canz_shampoo_step([], hp, 0, 0, 0)
+    # workspace: fp32 working matrices padded to multiples of 128; rows 256, cols 512, one matrix:
+    # G in two orientations and L^(-1/4) G (3 x 256 x 512), the two roots (256^2 + 512^2), eight
+    # 512 x 512 matrices of the root iteration, 64 partial sums
+    want = 4 * (3 * 256 * 512 + 256 * 256 + 512 * 512 + 8 * 512 * 512 + 64)
+    assert canz.canz_shampoo_workspace_bytes([G(rows=256, cols=512, n_mats=1)], hp) == want
+    assert canz.canz_shampoo_workspace_bytes([G(rows=200, cols=500, n_mats=1)], hp) == want
+    assert ctypes.sizeof(canz._ShGroup) == 16 + 16 + 32 and ctypes.sizeof(canz._ShHparams) == 24
