@@ -139,12 +139,146 @@ def ns_flops(rows, cols, steps):
     return steps * (4 * m * m * n + 2 * m ** 3)
 
 
+def main_shampoo(args, canz, W, np, torch):
+    """One rank's Shampoo step (canz_shampoo_step): Algorithm 1 with W(p) = Shampoo FLOPs
+    (App. D.5) on the set of --config, alpha = 1, the most loaded rank's share."""
+    cfg = 2 if args.config is None else args.config
+    s = W.matrix_set(cfg)
+    R = s["n_ranks"]
+    t0 = time.perf_counter()
+    cuts, owner, load = canz.canz_partition_alpha(s["rows"], s["cols"], s["bucket_off"], R, 1.0,
+                                                  cost_kind=canz.COST_SHAMPOO_FLOPS)
+    rank = int(np.argmax(load))
+    groups = canz.canz_microgroup_plan(s["rows"], s["cols"], s["dtype"], owner, rank, max_mats=8)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    mean = float(load.sum()) / len(load)
+    n_share = sum(len(g) for g in groups)
+    log("shampoo on config %d (%s): rank %d owns %d matrices in %d groups; planner %.2f ms, R_LB(FLOPs) %.3f" %
+        (cfg, s["name"], rank, n_share, len(groups), plan_ms, float(load.max()) / mean))
+    hp = canz.ShampooHparams(beta=0.9, eps=1e-2, lr=0.02, root_iters=25)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(W.SEED_BASE + cfg)
+    dgroups, keep = [], []
+    for g in groups:
+        rows, cols = s["rows"][g[0]], s["cols"][g[0]]
+        grads = [(torch.randn(rows, cols, device="cuda", generator=gen) * s["grad_std"]).to(torch.bfloat16) for _ in g]
+        lefts = [torch.zeros(rows, rows, device="cuda") for _ in g]
+        rights = [torch.zeros(cols, cols, device="cuda") for _ in g]
+        outs = [torch.randn(rows, cols, device="cuda", generator=gen) * 0.02 for _ in g]
+        keep.append((grads, lefts, rights, outs))
+        dgroups.append(canz.ShampooGroup(rows=rows, cols=cols, grad=grads, left=lefts, right=rights, out=outs,
+                                         grad_dtype=canz.DT_BF16, out_dtype=canz.DT_F32))
+    ws_bytes = canz.canz_shampoo_workspace_bytes(dgroups, hp)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        canz.canz_shampoo_step(dgroups, hp, ws, ws_bytes, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    canz.canz_profile_enable(n_share * (12 + 8 * hp.root_iters) + 8)
+    step()
+    torch.cuda.synchronize()
+    launches_per_step = sum(n for _ms, n in canz.canz_profile_collect().values())
+    canz.canz_profile_enable(launches_per_step * args.steps + 8)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t_start) * 1e3 / args.steps
+    prof = canz.canz_profile_collect()
+    canz.canz_profile_disable()
+    log("timed %d steps: %.3f ms/step" % (args.steps, ms_per_step))
+
+    # FLOPs.  A product of two commuting symmetric d x d matrices has d (d + 1) / 2 distinct entries of
+    # 2 d FLOPs each: that is the algorithmic count of the statistics and of the four products of a
+    # root round; the kernels compute whole 128 x 128 tiles on or above the diagonal ("issued").
+    def pad(x):
+        return (x + 127) // 128 * 128
+
+    def sym(d, k):
+        return d * (d + 1) * k, (pad(d) // 128) * (pad(d) // 128 + 1) // 2 * 128 * 128 * 2 * pad(k)
+
+    alg = dict(sh_stat=0.0, sh_root=0.0, sh_apply=0.0)
+    iss = dict(sh_stat=0.0, sh_root=0.0, sh_apply=0.0)
+    for g in groups:
+        r, c = s["rows"][g[0]], s["cols"][g[0]]
+        n = len(g)
+        for d, k in ((r, c), (c, r)):
+            a, i = sym(d, k)
+            alg["sh_stat"] += n * a
+            iss["sh_stat"] += n * i
+            a, i = sym(d, d)
+            alg["sh_root"] += n * a * (4 * hp.root_iters - 3)
+            iss["sh_root"] += n * i * (4 * hp.root_iters - 3)
+        alg["sh_apply"] += n * (2.0 * r * r * c + 2.0 * r * c * c)
+        iss["sh_apply"] += n * (2.0 * pad(r) * pad(r) * pad(c) + 2.0 * pad(r) * pad(c) * pad(c))
+    kernels = {}
+    for k, (ms, n) in prof.items():
+        if n:
+            kernels[k] = dict(ms_per_step=ms / args.steps, launches_per_step=n / args.steps, avg_ms=ms / n)
+            if k in alg:
+                kernels[k]["tflops_algorithmic"] = alg[k] * args.steps / (ms * 1e-3) / 1e12
+                kernels[k]["tflops_issued"] = iss[k] * args.steps / (ms * 1e-3) / 1e12
+    dom = max((k for k in kernels if k in alg), key=lambda k: kernels[k]["ms_per_step"])
+    peak = 157.3
+    per_launch = alg[dom] / kernels[dom]["launches_per_step"]
+    achieved = per_launch / (kernels[dom]["avg_ms"] * 1e-3) / 1e12
+    issued = iss[dom] / kernels[dom]["launches_per_step"] / (kernels[dom]["avg_ms"] * 1e-3) / 1e12
+    roofline = dict(bound="mfma", kernel="k_sh_gemm (%s)" % dom, achieved=achieved, peak=peak, unit="TFLOP/s",
+                    frac=achieved / peak, traffic=None, achieved_issued=issued, frac_issued=issued / peak,
+                    flops_per_launch=per_launch, avg_launch_ms=kernels[dom]["avg_ms"])
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import shampoo as OS
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [os.cpu_count()])
+        except Exception:
+            cores = os.cpu_count()
+        g0 = groups[0]
+        rows, cols = s["rows"][g0[0]], s["cols"][g0[0]]
+        g64 = keep[0][0][0].float().cpu().numpy().astype(np.float64)
+        t0 = time.perf_counter()
+        OS.shampoo_step(g64, np.zeros((rows, rows)), np.zeros((cols, cols)), OS.Hparams(eps=1e-2), param=np.zeros((rows, cols)))
+        t_one = time.perf_counter() - t0
+        cost = lambda r, c: r ** 3 + c ** 3
+        est_s = sum(len(g) * t_one * cost(s["rows"][g[0]], s["cols"][g[0]]) / cost(rows, cols) for g in groups)
+        cpu = dict(value=est_s * 1e3, unit="ms", cores=int(cores), kind="oracle",
+                   sample="fp64 oracle (two symmetric eigendecompositions and the products), one whole step of matrix "
+                          "%d (%dx%d): %.2f s, scaled by rows^3 + cols^3 to the %d-matrix share" % (g0[0], rows, cols, t_one, n_share))
+    total_alg, total_iss = sum(alg.values()), sum(iss.values())
+    out = {
+        "metric": "optimizer_step_latency_ms", "value": ms_per_step, "unit": "ms",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic", "launch": "eager",
+        "config": {"workload": "shampoo step, config %d %s partitioned by Shampoo FLOPs: rank %d of %d (alpha=1), %d matrices %s "
+                               "in %d micro-groups, %d root rounds" %
+                               (cfg, s["name"], rank, R, n_share, sorted({(s["rows"][p], s["cols"][p]) for g in groups for p in g}),
+                                len(groups), hp.root_iters),
+                   "elements": sum(s["rows"][p] * s["cols"][p] for g in groups for p in g)},
+        "tflops_algorithmic": total_alg / (ms_per_step * 1e-3) / 1e12, "tflops_issued": total_iss / (ms_per_step * 1e-3) / 1e12,
+        "frac_mfma_peak_issued": total_iss / (ms_per_step * 1e-3) / 1e12 / peak,
+        "planner": dict(rank=rank, n_ranks=R, alpha=1.0, cost="shampoo_flops", r_lb_flops=float(load.max()) / mean, planner_ms=plan_ms),
+        "kernels": kernels, "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default 4: Qwen3-32B share)")
+    ap.add_argument("--config", type=int, default=None, help="benchmark configuration 1..5 (default 4: Qwen3-32B share; "
+                                                             "2 with --optimizer shampoo)")
+    ap.add_argument("--optimizer", choices=["muon", "shampoo"], default="muon",
+                    help="muon (default): canz_muon_step on the share of --config; shampoo: canz_shampoo_step on the "
+                         "share Algorithm 1 assigns under the Shampoo FLOPs cost (default set: config 2, the 0.6B shapes)")
     ap.add_argument("--precision", choices=["bf16", "f32"], default="bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tp-schedule", type=int, default=0, metavar="MB",
@@ -172,7 +306,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    cfg = args.config
+    if args.optimizer == "shampoo":
+        return main_shampoo(args, canz, W, np, torch)
+    cfg = 4 if args.config is None else args.config
     if args.tp_schedule:
         assert cfg == 5, "--tp-schedule applies to the TP configuration (5)"
         s, rank, groups, diag = pick_tp_share(canz, W, cfg, args.tp_schedule << 20)
