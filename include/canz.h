@@ -168,6 +168,10 @@ int canz_tp_schedule(int64_t n_mats, const int64_t* cost, int32_t n_ranks, int64
  * has finished the step.  Device pointers must be 16-byte aligned; with tp > 1 the
  * fragment width cols/tp must be a multiple of 8 (whole matrices may have any extents).
  * rows and cols are at most 4194240 each.  grad, mom and out buffers must not overlap.
+ * Magnitudes: the normalisation is applied as a scalar after squares of the unnormalised
+ * U = M (or G + beta M) have been formed in fp32, so the root-mean-square of U must lie within
+ * about [1e-15, 1e+15] (sums of squares must neither underflow nor overflow fp32); gradients of
+ * any realistic scale, including loss-scaled ones, are far inside.
  */
 typedef struct {
   int64_t rows, cols;
@@ -220,7 +224,10 @@ int canz_muon_workspace_bytes(const canz_group* g, int32_t n_groups,
  *                   caller-owned; contents are scratch and need not be initialised
  *   hip_stream      a hipStream_t (NULL = the null stream)
  * Returns after enqueueing; completion follows stream order.  Results per matrix do not
- * depend on which other matrices share the group or the call.  The call issues kernel
+ * depend on which other matrices share the group or the call, with one exception in bf16 mode:
+ * Gram products with more than 12800 columns (k-steps) may have the tiles left over behind the
+ * last full round of a launch summed in several k-slices, which changes fp32 rounding (far
+ * below the tolerance) for matrices whose tiles fall there.  The call issues kernel
  * launches only (no memset, no copy, no allocation, no synchronisation), so with profiling
  * off it may be recorded into a HIP graph; the pointer tables are baked into the recorded
  * launches.  Calls on different streams may overlap if their workspaces are distinct.

@@ -31,6 +31,19 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+// The two places where an epilogue combines several terms, written once with the roundings
+// pinned (one product, then one fused multiply-add), so that every kernel that produces the
+// same element produces the same bits whatever its tile shape.
+//   polynomial  a I + b A + c (A A)
+__device__ __forceinline__ float poly_value(float a_elem, float aa_elem, float ca, float cb, float cc, bool diag) {
+  const float v = __builtin_fmaf(cb, a_elem, cc * aa_elem);
+  return diag ? v + ca : v;
+}
+//   update      old * decay + neg_lr_scale * O   (old = 0 gives Delta W = neg_lr_scale * O exactly)
+__device__ __forceinline__ float apply_update(float old, float decay, float neg_lr_scale, float ortho) {
+  return __builtin_fmaf(neg_lr_scale, ortho, old * decay);
+}
+
 // O (one element of the orthogonalised matrix, caller's orientation) -> caller's buffer.
 //   CANZ_OUT_PARAM: P <- P * decay + neg_lr_scale * O       (Sec. 3.3 stage (2))
 //   CANZ_OUT_DELTA: Delta W fragment <- neg_lr_scale * O     (Sec. 4.1 stage (3))
@@ -40,10 +53,10 @@ __device__ __forceinline__ void store_out(const OutSpec& o, const Shape& s, int 
     const int64_t idx = static_cast<int64_t>(row) * s.cols + col;
     if (o.out_dtype == CANZ_DT_F32) {
       float* p = static_cast<float*>(o.out.p[b]);
-      p[idx] = p[idx] * o.decay + delta;
+      p[idx] = apply_update(p[idx], o.decay, o.neg_lr_scale, ortho);
     } else {
       __bf16* p = static_cast<__bf16*>(o.out.p[b]);
-      p[idx] = static_cast<__bf16>(static_cast<float>(p[idx]) * o.decay + delta);
+      p[idx] = static_cast<__bf16>(apply_update(static_cast<float>(p[idx]), o.decay, o.neg_lr_scale, ortho));
     }
   } else {
     const int wf = static_cast<int>(s.wfrag);
@@ -87,15 +100,13 @@ __device__ __forceinline__ void store_out_tile(const OutSpec& o, const Shape& s,
                                             : static_cast<float>(static_cast<const __bf16*>(base)[idx]);
       }
     }
-#pragma unroll
-    for (int r = 0; r < 16; ++r) val[r] *= o.decay;
   }
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const int row = row0 + 8 * (r >> 2) + (r & 3);
     if (row < rows) {
       const int64_t idx = static_cast<int64_t>(row) * ld + c;
-      const float v = val[r] + o.neg_lr_scale * ortho[r];
+      const float v = apply_update(val[r], o.decay, o.neg_lr_scale, ortho[r]);
       if (o.out_dtype == CANZ_DT_F32)
         static_cast<float*>(base)[idx] = v;
       else

@@ -167,9 +167,8 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[4][4], __bf16* stage
           const bf16x4 av = *reinterpret_cast<const bf16x4*>(stage + it * 4096 + jt * 32 * 32 + a_base[g]);
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            float v = e.cb * static_cast<float>(av[q]) + e.cc * acc[it][jt][4 * g + q];
-            if (row0 + 8 * g + q == col) v += e.ca;
-            acc[it][jt][4 * g + q] = v;
+            acc[it][jt][4 * g + q] =
+                poly_value(static_cast<float>(av[q]), acc[it][jt][4 * g + q], e.ca, e.cb, e.cc, row0 + 8 * g + q == col);
           }
         }
       }
@@ -333,10 +332,10 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[4][4], __bf16* stage
             for (int i = 0; i < 32; ++i) {
               // row 2 i + lh of the staged half; bit 2 of that row is bit 1 of i
               const f32x4 v = *reinterpret_cast<const f32x4*>(sf + 2 * i * 128 + r_base[(i >> 1) & 1]);
-              if (MODE == CANZ_OUT_PARAM)
-                val[i] = val[i] * o.decay + o.neg_lr_scale * v;
-              else
-                val[i] = o.neg_lr_scale * v;
+#pragma unroll
+              for (int q = 0; q < 4; ++q)
+                val[i][q] = MODE == CANZ_OUT_PARAM ? apply_update(val[i][q], o.decay, o.neg_lr_scale, v[q])
+                                                   : o.neg_lr_scale * v[q];
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -384,8 +383,11 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[4][4], __bf16* stage
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
               if (!live[u]) continue;
-              f32x4 res = o.neg_lr_scale * v[u];
-              if (MODE == CANZ_OUT_PARAM) res = old[u] * o.decay + res;
+              f32x4 res;
+#pragma unroll
+              for (int q = 0; q < 4; ++q)
+                res[q] = MODE == CANZ_OUT_PARAM ? apply_update(old[u][q], o.decay, o.neg_lr_scale, v[u][q])
+                                                : o.neg_lr_scale * v[u][q];
               if (DTYPE == CANZ_DT_F32) {
                 *reinterpret_cast<f32x4*>(ptr[u]) = res;
               } else {
@@ -698,6 +700,227 @@ __global__ __launch_bounds__(NTHREADS) void k_split_finish(GemmDims d, EpiArgs e
   tile_epilogue<EPI>(acc, stg[wave], lane, wave >> 1, wave & 1, b, tm, tn, d, e, s, o);
 }
 
+// ---------------------------------------------------------------------------------------
+// Small-product variant: 128 x 128 tiles, one block per tile, three resident blocks per CU.
+//
+// The persistent 256 x 256 kernel above is built for products with many rounds of long tiles.
+// A launch with few tiles (the 0.6B-shaped shares: 260 Gram tiles for 256 CUs) leaves most
+// of its last round idle and pays the un-overlapped prologue and epilogue of a tile on every
+// short k range.  Here a tile is a quarter of that: four times as many blocks balance over
+// the chip, 48 KiB of LDS and 64 accumulator registers per lane let three blocks share a CU, so
+// that one block's loads and epilogue run under the others' MFMAs.  The price is twice the
+// L2 -> LDS traffic per FLOP, which is why long products stay with the large tile.
+// It therefore takes what the large kernel handles badly: launches with few tiles, and the
+// left-over tiles behind the last full round of a launch with a short k range (each left-over
+// 256 x 256 tile becomes four blocks here).
+//
+// Same operands (panel layout: the 128 rows of a tile are one contiguous 8 KiB half of a
+// panel), same MFMA, same order of accumulation over k, same epilogue arithmetic: an element
+// comes out with the same bits from either kernel.  Epilogues store straight from the
+// accumulators (4 bytes per lane for the straight image after the lane-pair exchange, 8 bytes
+// per lane for the transposed one): there is no LDS to spare for staging with three blocks
+// per CU, and the stores of one block drain under the work of the others.
+constexpr int SM = 128;                  // tile rows and columns
+constexpr int S_STAGE = 2 * SM * BK;     // elements per stage: P half-panel + Q half-panel (16 KiB)
+
+template <int EPI, typename Args>
+__global__ __launch_bounds__(NTHREADS, 3) void k_gemm_nt_bf16_small(Args args, EpiArgs e_launch, Shape s, OutSpec o) {
+  __shared__ __attribute__((aligned(1024))) __bf16 sa[S_STAGE];
+  __shared__ __attribute__((aligned(1024))) __bf16 sb[S_STAGE];
+  __shared__ __attribute__((aligned(1024))) __bf16 sc[S_STAGE];
+
+  GemmDims d{};
+  const __bf16 *P = nullptr, *Q = nullptr;
+  EpiArgs e = e_launch;
+  // neighbouring tiles on one XCD (blockIdx % 8 selects the XCD): they share panels in its L2
+  int logical;
+  {
+    const int nblocks = gridDim.x, bid = blockIdx.x;
+    const int per = nblocks / N_XCD, rem = nblocks % N_XCD;
+    const int xcd = bid % N_XCD, q = bid / N_XCD;
+    logical = xcd < rem ? xcd * (per + 1) + q : rem * (per + 1) + (xcd - rem) * per + q;
+  }
+  // four consecutive blocks are the quadrants of one 256 x 256 tile of the large kernel's
+  // numbering, starting at tile e.main_grid (the launcher's "first tile" here)
+  const int quad = logical & 3;
+  logical = e.main_grid + (logical >> 2);
+  if constexpr (Args::multi) {
+    int j = 0;
+    while (j + 1 < args.n && logical >= args.begin[j + 1]) ++j;
+    const GemmProblem& pr = args.pr[j];
+    d = pr.d;
+    P = static_cast<const __bf16*>(pr.p), Q = static_cast<const __bf16*>(pr.q);
+    e.c = pr.c, e.ct = pr.ct, e.aux = pr.aux, e.scale = pr.scale;
+    logical -= args.begin[j];
+  } else {
+    d = args.d, P = args.P, Q = args.Q;
+  }
+  const int tiles_m = static_cast<int>(d.M / BM), tiles_n = static_cast<int>(d.N / BN);
+  const bool symmetric = EPI == EPI_GRAM || EPI == EPI_POLY;
+  const int per_batch = symmetric ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
+  int b, tm, tn;
+  decode_tile<EPI>(logical, tiles_m, tiles_n, per_batch, b, tm, tn);
+  // the lower-left quadrant of a diagonal tile of a symmetric product is the mirror of the upper-right one
+  if (symmetric && tm == tn && quad == 2) return;
+  tm = 2 * tm + (quad >> 1), tn = 2 * tn + (quad & 1);
+
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int nk = static_cast<int>(d.K / BK);
+  const int64_t nkb = d.K / BK;
+
+  // global -> LDS: a stage is 16 pieces of 1 KiB (8 of P, 8 of Q); wavefront w copies the
+  // pieces w and w + 4 of both, lane l the 16 bytes at l * 16
+  const __bf16* pl = P + static_cast<int64_t>(b) * d.sp + (static_cast<int64_t>(tm >> 1) * nkb) * PANEL_ELEMS +
+                     (tm & 1) * (SM * BK) + wave * 512 + lane * 8;
+  const __bf16* ql = Q + static_cast<int64_t>(b) * d.sq + (static_cast<int64_t>(tn >> 1) * nkb) * PANEL_ELEMS +
+                     (tn & 1) * (SM * BK) + wave * 512 + lane * 8;
+  auto fetch = [&](__bf16* st, int kt) {
+    const int64_t off = static_cast<int64_t>(kt < nk ? kt : nk - 1) * PANEL_ELEMS;  // past the end: a harmless re-read
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      __builtin_amdgcn_global_load_lds(CANZ_GLB(pl + off + g * 2048), CANZ_LDS(st + wave * 512 + g * 2048), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(CANZ_GLB(ql + off + g * 2048), CANZ_LDS(st + SM * BK + wave * 512 + g * 2048), 16, 0, 0);
+    }
+  };
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int frag_row = lane & 31, frag_kg = lane >> 5;
+  auto multiply = [&](const __bf16* st) {
+    bf16x8 fa[2][2], fb[2][2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        fa[kk][i] = *reinterpret_cast<const bf16x8*>(st + swz(wm * 64 + i * 32 + frag_row, kk * 2 + frag_kg));
+        fb[kk][i] = *reinterpret_cast<const bf16x8*>(st + SM * BK + swz(wn * 64 + i * 32 + frag_row, kk * 2 + frag_kg));
+      }
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk][i], fb[kk][j], acc[i][j], 0, 0, 0);
+  };
+  // One k-step on stage `cur`: the 4 loads of the following step may stay in flight; after the
+  // barrier every wavefront has finished the step before, whose stage `nxt2` then receives step kt + 2.
+  auto k_step = [&](const __bf16* cur, __bf16* nxt2, int kt) {
+    __builtin_amdgcn_s_waitcnt(0x0074);  // vmcnt(4) lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    fetch(nxt2, kt + 2);
+    multiply(cur);
+  };
+  fetch(sa, 0);
+  fetch(sb, 1);
+  int kt = 0;
+  for (; kt + 3 <= nk; kt += 3) {
+    k_step(sa, sc, kt);
+    k_step(sb, sa, kt + 1);
+    k_step(sc, sb, kt + 2);
+  }
+  if (kt < nk) k_step(sa, sc, kt), ++kt;
+  if (kt < nk) k_step(sb, sa, kt), ++kt;
+  __builtin_amdgcn_s_waitcnt(0x0070);  // the re-reads past the end have landed before the block leaves
+
+  // ---- epilogue.  Accumulator register r of lane l in MFMA tile (i, j): row 32 i + 8 (r / 4) + 4 (l / 32) + (r % 4),
+  //      column 32 j + (l % 32) of the wavefront's 64 x 64 part.
+  const int lj = lane & 31, lh = lane >> 5;
+  const int row_w = tm * SM + wm * 64, col_w = tn * SM + wn * 64;
+  if (EPI == EPI_POLY) {
+    // A(i, j) is read as A(j, i) (symmetric bit for bit): the lane's four consecutive rows are
+    // four consecutive k of row j, one 8-byte load
+    const __bf16* A = static_cast<const __bf16*>(e.aux) + static_cast<int64_t>(b) * d.M * d.N;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = col_w + 32 * j + lj;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int row0 = row_w + 32 * i + 8 * g + 4 * lh;
+          const bf16x4 av = *reinterpret_cast<const bf16x4*>(A + panel_chunk_off(col, row0 & ~7, d.M) + (row0 & 7));
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            acc[i][j][4 * g + q] = poly_value(static_cast<float>(av[q]), acc[i][j][4 * g + q], e.ca, e.cb, e.cc, row0 + q == col);
+        }
+      }
+  } else if (e.scale) {
+    const float sc1 = e.scale[b];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] *= sc1;
+  }
+
+  if (EPI == EPI_FINAL) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        float v[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) v[r] = acc[i][j][r];
+        store_out_tile(o, s, b, row_w + 32 * i + 4 * lh, col_w + 32 * j + lj, v);
+      }
+    return;
+  }
+
+  __bf16* C = static_cast<__bf16*>(e.c) + static_cast<int64_t>(b) * d.M * d.N;
+  // straight image: (row i, k = j).  Neighbouring lanes exchange their packed pairs so that each
+  // lane holds two consecutive columns of one row: the even lane of row 2 rp, the odd lane of row 2 rp + 1.
+  const unsigned pair_sel = (lane & 1) ? 0x03020706u : 0x05040100u;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = col_w + 32 * j + (lj & ~1);
+#pragma unroll
+      for (int rp = 0; rp < 8; ++rp) {
+        bf16x2 own;
+        own[0] = static_cast<__bf16>(acc[i][j][2 * rp]);
+        own[1] = static_cast<__bf16>(acc[i][j][2 * rp + 1]);
+        const unsigned mine = __builtin_bit_cast(unsigned, own);
+        const unsigned theirs = lane_xor1(mine);
+        const unsigned pk = __builtin_amdgcn_perm(theirs, mine, pair_sel);
+        const int row = row_w + 32 * i + 8 * (rp >> 1) + 4 * lh + 2 * (rp & 1) + (lane & 1);
+        *reinterpret_cast<unsigned*>(C + panel_chunk_off(row, col & ~7, d.N) + (col & 7)) = pk;
+      }
+    }
+  // transposed image: (row j, k = i) of CT (UPDATE) or of the mirror tile of C (symmetric products)
+  if (!symmetric || tm != tn) {
+    __bf16* CT = symmetric ? C : static_cast<__bf16*>(e.ct) + static_cast<int64_t>(b) * d.M * d.N;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = col_w + 32 * j + lj;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int row0 = row_w + 32 * i + 8 * g + 4 * lh;
+          bf16x4 pk;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) pk[q] = static_cast<__bf16>(acc[i][j][4 * g + q]);
+          *reinterpret_cast<bf16x4*>(CT + panel_chunk_off(col, row0 & ~7, d.M) + (row0 & 7)) = pk;
+        }
+      }
+  }
+}
+
+// Compute units of the current device.  The answer is cached per device in a plain array: the
+// first calls from several threads may each query the attribute and store the same value
+// (a benign race on an int that only ever takes one non-zero value).
 int cu_count() {
   static int cached[64] = {0};
   int dev = 0;
@@ -710,12 +933,47 @@ int cu_count() {
   return cached[dev];
 }
 
+// How a launch is divided between the two kernels.  Long products (k above SMALL_MAX_K; the small
+// tile moves twice the bytes per FLOP) stay with the large kernel and its k-split.  Otherwise
+// the large kernel runs the full rounds of one tile per CU, and the left-over tiles go to the
+// small kernel when they would leave at least half of the chip idle for a whole tile time -
+// which includes launches with no full round at all.
+constexpr int64_t SMALL_MAX_K = 4096;
+
+template <int EPI>
+int64_t tile_count(const GemmDims& d) {
+  const int64_t tm = d.M / BM, tn = d.N / BN;
+  return ((EPI == EPI_GRAM || EPI == EPI_POLY) ? tm * (tm + 1) / 2 : tm * tn) * d.nb;
+}
+
+// number of tiles [0, whole) for the large kernel; the rest, if any, for the small one
+inline int64_t large_share(int64_t tiles, int64_t cus, int64_t longest_k) {
+  const int64_t left = tiles % cus;
+  return (longest_k <= SMALL_MAX_K && left > 0 && 2 * left <= cus) ? tiles - left : tiles;
+}
+
 template <int EPI>
 hipError_t launch(const GemmDims& d, const void* P, const void* Q, EpiArgs e, const SplitWs& w, const Shape& s,
                   const OutSpec& o, hipStream_t st) {
-  const int64_t tm = d.M / BM, tn = d.N / BN;
-  const int64_t tiles = ((EPI == EPI_GRAM || EPI == EPI_POLY) ? tm * (tm + 1) / 2 : tm * tn) * d.nb;
+  // the k loop of both kernels takes whole panels in groups of four with a tail of four: K is a
+  // multiple of 256 (the producers pad to PAD), hence at least 8 k-steps
+  if (d.K < 8 * BK || d.K % (8 * BK) || d.M % BM || d.N % BN) return hipErrorInvalidValue;
+  const int64_t tiles = tile_count<EPI>(d);
   const int64_t cus = cu_count();
+  const OneProblem one{d, static_cast<const __bf16*>(P), static_cast<const __bf16*>(Q)};
+  const int64_t whole_large = large_share(tiles, cus, d.K);
+  if (whole_large < tiles) {
+    if (whole_large > 0) {
+      e.full_rounds = static_cast<int>(whole_large / cus), e.left = 0, e.splits = 1, e.partial = nullptr;
+      e.main_grid = static_cast<int>(cus);
+      hipLaunchKernelGGL((k_gemm_nt_bf16<EPI, false, OneProblem>), dim3(static_cast<unsigned>(cus)), dim3(NTHREADS), 0, st,
+                         one, e, s, o);
+    }
+    e.main_grid = static_cast<int>(whole_large);   // first tile of the small kernel
+    hipLaunchKernelGGL((k_gemm_nt_bf16_small<EPI, OneProblem>), dim3(static_cast<unsigned>(4 * (tiles - whole_large))),
+                       dim3(NTHREADS), 0, st, one, e, s, o);
+    return hipGetLastError();
+  }
   // full rounds of one tile per block, then the left-over tiles cut into k-slices (each at
   // least 8 k-steps long) so that they occupy as many blocks as fit
   e.full_rounds = static_cast<int>(tiles / cus);
@@ -734,7 +992,6 @@ hipError_t launch(const GemmDims& d, const void* P, const void* Q, EpiArgs e, co
   // whole tiles: one persistent block per CU (fewer if there are fewer tiles)
   const int64_t whole = e.splits > 1 ? e.full_rounds * cus : tiles;
   e.main_grid = static_cast<int>(std::min<int64_t>(cus, std::max<int64_t>(whole, 1)));
-  const OneProblem one{d, static_cast<const __bf16*>(P), static_cast<const __bf16*>(Q)};
   if (whole > 0)
     hipLaunchKernelGGL((k_gemm_nt_bf16<EPI, false, OneProblem>), dim3(static_cast<unsigned>(e.main_grid)), dim3(NTHREADS),
                        0, st, one, e, s, o);
@@ -749,26 +1006,35 @@ hipError_t launch(const GemmDims& d, const void* P, const void* Q, EpiArgs e, co
 // Several products in one launch: whole tiles only (no k-split), one persistent block per CU.
 template <int EPI>
 hipError_t launch_multi(const GemmBatch& g, EpiArgs e, hipStream_t st) {
+  const int64_t cus = cu_count();
   ManyProblems many{};
   many.n = g.n;
-  int64_t tiles = 0;
+  int64_t tiles = 0, longest_k = 0;
   for (int j = 0; j < g.n; ++j) {
-    const GemmDims& d = g.pr[j].d;
-    const int64_t tm = d.M / BM, tn = d.N / BN;
     many.begin[j] = static_cast<int>(tiles);
     many.pr[j] = g.pr[j];
-    tiles += ((EPI == EPI_GRAM || EPI == EPI_POLY) ? tm * (tm + 1) / 2 : tm * tn) * d.nb;
+    const GemmDims& d = g.pr[j].d;
+    if (d.K < 8 * BK || d.K % (8 * BK) || d.M % BM || d.N % BN) return hipErrorInvalidValue;
+    tiles += tile_count<EPI>(d);
+    longest_k = std::max(longest_k, d.K);
   }
   for (int j = g.n; j <= MAX_KINDS; ++j) many.begin[j] = static_cast<int>(tiles);
-  const int64_t cus = cu_count();
-  e.full_rounds = static_cast<int>(tiles / cus);
-  e.left = static_cast<int>(tiles % cus);
+  if (tiles == 0) return hipSuccess;
+  const int64_t whole_large = large_share(tiles, cus, longest_k);
   e.splits = 1;
   e.partial = nullptr;
-  e.main_grid = static_cast<int>(std::min<int64_t>(cus, std::max<int64_t>(tiles, 1)));
-  if (tiles > 0)
-    hipLaunchKernelGGL((k_gemm_nt_bf16<EPI, false, ManyProblems>), dim3(static_cast<unsigned>(e.main_grid)),
+  if (whole_large > 0) {
+    e.full_rounds = static_cast<int>(whole_large / cus);
+    e.left = static_cast<int>(whole_large % cus);
+    e.main_grid = static_cast<int>(std::min<int64_t>(cus, whole_large));
+    hipLaunchKernelGGL((k_gemm_nt_bf16<EPI, false, ManyProblems>), dim3(static_cast<unsigned>(e.main_grid)), dim3(NTHREADS),
+                       0, st, many, e, Shape{}, OutSpec{});
+  }
+  if (whole_large < tiles) {
+    e.main_grid = static_cast<int>(whole_large);   // first tile of the small kernel
+    hipLaunchKernelGGL((k_gemm_nt_bf16_small<EPI, ManyProblems>), dim3(static_cast<unsigned>(4 * (tiles - whole_large))),
                        dim3(NTHREADS), 0, st, many, e, Shape{}, OutSpec{});
+  }
   return hipGetLastError();
 }
 

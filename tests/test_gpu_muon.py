@@ -307,3 +307,19 @@ def test_groups_of_different_shapes_share_launches(canz, precision):
         for i in range(alone.n):
             assert np.array_equal(alone.out_host(i), together[k][0].out_host(i))
             assert np.array_equal(alone.mom_host(i), together[k][0].mom_host(i))
+
+
+@pytest.mark.parametrize("precision", [0, 1])
+@pytest.mark.parametrize("log2_scale", [-40, 40])
+def test_gradient_magnitudes_far_from_one(canz, precision, log2_scale):
+    """Gradients scaled by 2^-40 and 2^+40 (exact in bf16): inside the documented magnitude range
+    the step still matches the oracle, which carries the same eps in the normalisation (at
+    2^-40 the norm is below eps and the update shrinks accordingly on both sides)."""
+    rows, cols, n = 300, 520, 2
+    scale = np.float32(2.0 ** log2_scale)
+    grads = [W.f32_to_bf16_bits(W.bf16_bits_to_f32(W.gen_grad(89, i, rows, cols)[0]) * scale) for i in range(n)]
+    zeros = [np.zeros((rows, cols), np.float32) for _ in range(n)]
+    hp = canz.Hparams(out_mode=canz.OUT_DELTA, precision=precision)
+    dg = DeviceGroup(canz, rows, cols, grads, zeros)
+    run_step(canz, [dg], hp)
+    _check_group(canz, dg, grads, zeros, None, hp, "scale 2^%d prec%d" % (log2_scale, precision))
