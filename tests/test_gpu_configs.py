@@ -23,8 +23,11 @@ from tests.gpu_harness import DeviceGroup, log, oracle_hparams, run_step, tile_e
 pytestmark = pytest.mark.gpu
 
 TOL = {0: 3e-2, 1: 1e-4}
-TILE_TOL = {0: 4.5e-2, 1: 1.5e-4}     # per-tile relative Frobenius error: 1.5 x the matrix tolerance
-MAXABS_TOL = {0: 0.25, 1: 1e-3}       # largest element error, in units of the reference's rms
+# per-tile relative Frobenius error.  Measured over all five configurations: at most 1.1e-2 in
+# bf16 mode and 2.8e-6 in fp32 mode (the error is spread evenly: a tile is never worse than
+# 1.07 x its matrix); a lost or stale tile is off by 0.1 to 1.4.
+TILE_TOL = {0: 2e-2, 1: 5e-5}
+MAXABS_TOL = {0: 0.25, 1: 5e-4}       # largest element error, in units of the reference's rms (measured: 0.13, 4.5e-5)
 LR_SCALE_BAND = (0.68, 1.14)          # singular values after 5 quintic steps, inputs in [0.01, 1]
 
 
