@@ -946,10 +946,16 @@ int64_t tile_count(const GemmDims& d) {
   return ((EPI == EPI_GRAM || EPI == EPI_POLY) ? tm * (tm + 1) / 2 : tm * tn) * d.nb;
 }
 
-// number of tiles [0, whole) for the large kernel; the rest, if any, for the small one
-inline int64_t large_share(int64_t tiles, int64_t cus, int64_t longest_k) {
+// number of tiles [0, whole) for the large kernel; the rest, if any, for the small one.  The last
+// product's small-tile epilogue updates the parameters with 4-byte accesses (the large one stages
+// rows and uses 16-byte accesses), which costs more than the idle part of a round: its left-over
+// tiles stay with the large kernel unless there is no full round at all.
+template <int EPI>
+int64_t large_share(int64_t tiles, int64_t cus, int64_t longest_k) {
   const int64_t left = tiles % cus;
-  return (longest_k <= SMALL_MAX_K && left > 0 && 2 * left <= cus) ? tiles - left : tiles;
+  if (longest_k > SMALL_MAX_K || left == 0 || 2 * left > cus) return tiles;
+  if (EPI == EPI_FINAL && tiles > cus) return tiles;
+  return tiles - left;
 }
 
 template <int EPI>
@@ -961,7 +967,7 @@ hipError_t launch(const GemmDims& d, const void* P, const void* Q, EpiArgs e, co
   const int64_t tiles = tile_count<EPI>(d);
   const int64_t cus = cu_count();
   const OneProblem one{d, static_cast<const __bf16*>(P), static_cast<const __bf16*>(Q)};
-  const int64_t whole_large = large_share(tiles, cus, d.K);
+  const int64_t whole_large = large_share<EPI>(tiles, cus, d.K);
   if (whole_large < tiles) {
     if (whole_large > 0) {
       e.full_rounds = static_cast<int>(whole_large / cus), e.left = 0, e.splits = 1, e.partial = nullptr;
@@ -1020,7 +1026,7 @@ hipError_t launch_multi(const GemmBatch& g, EpiArgs e, hipStream_t st) {
   }
   for (int j = g.n; j <= MAX_KINDS; ++j) many.begin[j] = static_cast<int>(tiles);
   if (tiles == 0) return hipSuccess;
-  const int64_t whole_large = large_share(tiles, cus, longest_k);
+  const int64_t whole_large = large_share<EPI>(tiles, cus, longest_k);
   e.splits = 1;
   e.partial = nullptr;
   if (whole_large > 0) {
