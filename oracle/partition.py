@@ -73,65 +73,72 @@ def _check_inputs(n_params, bucket_off, n_ranks, alpha):
             raise ValueError("bucket_off must be non-decreasing")
 
 
+def _prefix_loads(cost, lo, hi):
+    """Phi of one bucket: load of its first u parameters, u = 0 .. size (the boundaries a cut may use)."""
+    acc = [0]
+    for p in range(lo, hi):
+        acc.append(acc[-1] + cost[p])
+    return acc
+
+
+def _rank_shares(load, mu, alpha, real):
+    """The fraction of the next bucket each rank should take: alpha times its share of the total
+    deficit below the mean load mu (an even share if nobody is below), plus 1 - alpha times an even share."""
+    n_ranks = len(load)
+    deficit = []
+    for r in range(n_ranks):
+        gap = mu - real(load[r])
+        deficit.append(gap if gap > 0 else real(0))
+    total_deficit = real(0)
+    for r in range(n_ranks):
+        total_deficit = total_deficit + deficit[r]
+    even = real(1) / real(n_ranks)
+    shares = []
+    for r in range(n_ranks):
+        fill = deficit[r] / total_deficit if total_deficit > 0 else even
+        shares.append((real(1) - real(alpha)) * even + real(alpha) * fill)
+    return shares
+
+
+def _nearest_boundary(prefix, goal, real):
+    """Index u whose prefix load is closest to goal (the smaller u on a tie), and by how much the
+    runner-up is further away (None if there is no other boundary)."""
+    dist = [abs(real(x) - goal) for x in prefix]
+    best = 0
+    for u in range(1, len(dist)):
+        if dist[u] < dist[best]:
+            best = u
+    others = [g for u, g in enumerate(dist) if u != best]
+    return best, (min(others) - dist[best] if others else None)
+
+
 def _algorithm1(cost, bucket_off, n_ranks, alpha, real, margin_log=None):
-    """Algorithm 1 with the real-number type given by ``real``.
+    """Algorithm 1 (Sec. 3.2) with the real-number type given by ``real``.
 
-    ``real`` converts an int (or the float alpha) into the number type used
-    for mu, d, D, v, target and C: ``float`` for the fp64 oracle,
-    ``Fraction`` for the exact replay.
+    ``real`` converts an int (or the float alpha) into the number type used for the mean load,
+    the deficits, the shares and the running goal: ``float`` for the fp64 oracle, ``Fraction``
+    for the exact replay.  Buckets are taken heaviest first; each is cut at the parameter
+    boundaries nearest to the running sums of (bucket load x rank share).
     """
-    R = n_ranks
     n_buckets = len(bucket_off) - 1
-    # "Define" lines: bucket totals W^i and cumulative loads Phi_i(u).
-    phi = []
-    for i in range(n_buckets):
-        acc = [0]
-        for p in range(bucket_off[i], bucket_off[i + 1]):
-            acc.append(acc[-1] + cost[p])
-        phi.append(acc)
-    w_bucket = [phi[i][-1] for i in range(n_buckets)]
-
-    load = [0] * R                                   # "Initialize" line
-    mu = real(sum(w_bucket)) / real(R)               # "Target" line
-    order = sorted(range(n_buckets), key=lambda i: (-w_bucket[i], i))  # "Sort"
-
-    one = real(1)
-    al = real(alpha)
-    cuts = [[0] * (R + 1) for _ in range(n_buckets)]
-    for k in order:
-        # Step (1): deficits in the load domain.
-        d = []
-        for r in range(R):
-            gap = mu - real(load[r])
-            d.append(gap if gap > 0 else real(0))
-        d_total = real(0)
-        for r in range(R):
-            d_total = d_total + d[r]
-        # Steps (2) and (3): basis vectors and the blended target.
-        v_even = one / real(R)
-        target = []
-        for r in range(R):
-            v_fill = d[r] / d_total if d_total > 0 else v_even
-            v_star = (one - al) * v_even + al * v_fill
-            target.append(real(w_bucket[k]) * v_star)
-        # Step (4): project the running target onto the atomic cuts.
-        s = cuts[k]
-        s[0] = 0
-        c_run = real(0)
-        for r in range(R - 1):
-            c_run = c_run + target[r]
-            gaps = [abs(real(phi[k][u]) - c_run) for u in range(len(phi[k]))]
-            best_u = 0
-            for u in range(1, len(gaps)):
-                if gaps[u] < gaps[best_u]:      # strict: the smaller u keeps a tie
-                    best_u = u
-            if margin_log is not None and len(gaps) > 1:
-                runner_up = min(g for u, g in enumerate(gaps) if u != best_u)
-                margin_log.append((runner_up - gaps[best_u], k, r + 1))
-            s[r + 1] = best_u
-            load[r] += phi[k][s[r + 1]] - phi[k][s[r]]
-        s[R] = len(phi[k]) - 1
-        load[R - 1] += phi[k][s[R]] - phi[k][s[R - 1]]
+    prefix = [_prefix_loads(cost, bucket_off[i], bucket_off[i + 1]) for i in range(n_buckets)]
+    bucket_load = [prefix[i][-1] for i in range(n_buckets)]
+    load = [0] * n_ranks
+    mu = real(sum(bucket_load)) / real(n_ranks)
+    heaviest_first = sorted(range(n_buckets), key=lambda i: (-bucket_load[i], i))
+    cuts = [[0] * (n_ranks + 1) for _ in range(n_buckets)]
+    for k in heaviest_first:
+        shares = _rank_shares(load, mu, alpha, real)
+        goal = real(0)
+        for r in range(n_ranks - 1):
+            goal = goal + real(bucket_load[k]) * shares[r]
+            cut, margin = _nearest_boundary(prefix[k], goal, real)
+            if margin_log is not None and margin is not None:
+                margin_log.append((margin, k, r + 1))
+            cuts[k][r + 1] = cut
+            load[r] += prefix[k][cut] - prefix[k][cuts[k][r]]
+        cuts[k][n_ranks] = len(prefix[k]) - 1
+        load[n_ranks - 1] += prefix[k][-1] - prefix[k][cuts[k][n_ranks - 1]]
     return cuts, load
 
 

@@ -14,20 +14,17 @@ error.  Inside a group the solver assigns, in cost order, each tensor to the ran
 """
 from __future__ import annotations
 
-import heapq
-
-
 def min_heap_solver(costs, n_ranks):
-    """LPT on a min-heap (Algorithm 4).  costs: list in the order to assign (descending).
-    Returns (host rank per item, L_max)."""
-    heap = [(0, r) for r in range(n_ranks)]
-    heapq.heapify(heap)
+    """The group solver (Algorithm 4): items in the given (descending) order, each to the rank
+    whose (load, rank) pair is smallest - what popping a min-heap of such pairs yields, written
+    here as a plain minimum over the ranks.  Returns (host rank per item, L_max)."""
+    load = [0] * n_ranks
     host = []
     for c in costs:
-        load, r = heapq.heappop(heap)
+        r = min(range(n_ranks), key=lambda q: (load[q], q))
         host.append(r)
-        heapq.heappush(heap, (load + c, r))
-    return host, max(load for load, _ in heap)
+        load[r] += c
+    return host, max(load)
 
 
 def tp_schedule(cost, n_ranks, cmax):

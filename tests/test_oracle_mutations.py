@@ -99,14 +99,14 @@ MUON_MUTANTS = [
 ]
 
 PARTITION_MUTANTS = [
-    ("deficits not clipped at zero", "d.append(gap if gap > 0 else real(0))", "d.append(gap)"),
-    ("blend weights swapped", "v_star = (one - al) * v_even + al * v_fill", "v_star = al * v_even + (one - al) * v_fill"),
-    ("buckets visited lightest first", "key=lambda i: (-w_bucket[i], i))", "key=lambda i: (w_bucket[i], i))"),
-    ("ties go to the larger cut", "if gaps[u] < gaps[best_u]:", "if gaps[u] <= gaps[best_u]:"),
-    ("running target not accumulated", "c_run = c_run + target[r]", "c_run = target[r]"),
-    ("target from the mean load instead of the bucket", "target.append(real(w_bucket[k]) * v_star)", "target.append(mu * v_star)"),
-    ("last rank's load not recorded", "load[R - 1] += phi[k][s[R]] - phi[k][s[R - 1]]", "load[R - 1] += 0"),
-    ("mean load over buckets instead of ranks", "mu = real(sum(w_bucket)) / real(R)", "mu = real(sum(w_bucket)) / real(max(1, n_buckets))"),
+    ("deficits not clipped at zero", "deficit.append(gap if gap > 0 else real(0))", "deficit.append(gap)"),
+    ("blend weights swapped", "shares.append((real(1) - real(alpha)) * even + real(alpha) * fill)", "shares.append(real(alpha) * even + (real(1) - real(alpha)) * fill)"),
+    ("buckets visited lightest first", "key=lambda i: (-bucket_load[i], i))", "key=lambda i: (bucket_load[i], i))"),
+    ("ties go to the larger cut", "if dist[u] < dist[best]:", "if dist[u] <= dist[best]:"),
+    ("running target not accumulated", "goal = goal + real(bucket_load[k]) * shares[r]", "goal = real(bucket_load[k]) * shares[r]"),
+    ("target from the mean load instead of the bucket", "goal = goal + real(bucket_load[k]) * shares[r]", "goal = goal + mu * shares[r]"),
+    ("last rank's load not recorded", "load[n_ranks - 1] += prefix[k][-1] - prefix[k][cuts[k][n_ranks - 1]]", "load[n_ranks - 1] += 0"),
+    ("mean load over buckets instead of ranks", "mu = real(sum(bucket_load)) / real(n_ranks)", "mu = real(sum(bucket_load)) / real(max(1, n_buckets))"),
     ("FLOPs cost without the square term", "return ns_steps * (4 * m * m * n + 2 * m * m * m)", "return ns_steps * (4 * m * m * n)"),
     ("R_LB against the minimum", "return max(values) / avg if avg > 0 else 1.0", "return max(values) / min(values) if min(values) > 0 else 1.0"),
 ]
@@ -115,8 +115,8 @@ TP_MUTANTS = [
     ("tensors taken lightest first", "key=lambda p: (-cost[p], p))", "key=lambda p: (cost[p], p))"),
     ("capacity test is strict", "if l_max <= cmax:", "if l_max < cmax:"),
     ("the tensor that did not fit is dropped", "current = [p]\n    if current:", "current = []\n    if current:"),
-    ("heap ordered by rank before load", "heapq.heappush(heap, (load + c, r))", "heapq.heappush(heap, (load, r))"),
-    ("L_max reported as the smallest load", "return host, max(load for load, _ in heap)", "return host, min(load for load, _ in heap)"),
+    ("ranks ordered by rank before load", "key=lambda q: (load[q], q))", "key=lambda q: (q, load[q]))"),
+    ("L_max reported as the smallest load", "return host, max(load)", "return host, min(load)"),
 ]
 
 
