@@ -37,10 +37,10 @@ namespace canz {
 namespace {
 
 constexpr int SB = 128;          // block tile (rows and columns)
-constexpr int SK = 16;           // k extent of one LDS stage
+constexpr int SK = 32;           // k extent of one LDS stage: long enough that the next stage's global loads land under it
 constexpr int NTH = 256;
-constexpr int LDS_LD = SB + 4;
-constexpr int FLUSH = 32;        // stages (512 k) between folds of the running accumulator
+constexpr int LDS_LD = SB + 5;   // odd row length: the k-major stores of a stage spread over all banks
+constexpr int FLUSH = 16;        // stages (512 k) between folds of the running accumulator
 constexpr int NPART = 64;        // partial sums per matrix of the Frobenius norm
 constexpr int64_t MAX_EXTENT = 32768;
 constexpr size_t BATCH_BYTES = size_t(8) << 30;
@@ -52,7 +52,7 @@ inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 enum { SE_STAT = 0, SE_PLAIN = 1, SE_MT = 2, SE_OUT = 3 };
 
 struct ShGemm {
-  int64_t M, N, K;      // multiples of 128, 128, 16
+  int64_t M, N, K;      // multiples of 128, 128, 32
   int64_t ldp, ldq;     // row strides of P [M][K] and Q [N][K]
   int64_t sp, sq;       // batch strides
   const float* P;
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
   const float* Pg = g.P + static_cast<int64_t>(b) * g.sp + static_cast<int64_t>(tm) * SB * g.ldp;
   const float* Qg = g.Q + static_cast<int64_t>(b) * g.sq + static_cast<int64_t>(tn) * SB * g.ldq;
 
-  const int ld_row = t >> 2, ld_k = (t & 3) * 4;  // rows ld_row and ld_row + 64, 4 consecutive k
+  const int ld_row = t >> 3, ld_k = (t & 7) * 4;  // rows ld_row + 32 x (x = 0..3), 4 consecutive k
   f32x16 acc[2][2], tot[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -115,22 +115,23 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f, tot[i][j][r] = 0.f;
 
-  f32x4 p0, p1, q0, q1;
+  f32x4 pv[4], qv[4];
   auto fetch = [&](int kt) {
     const int64_t k0 = static_cast<int64_t>(kt) * SK + ld_k;
-    p0 = *reinterpret_cast<const f32x4*>(Pg + static_cast<int64_t>(ld_row) * g.ldp + k0);
-    p1 = *reinterpret_cast<const f32x4*>(Pg + static_cast<int64_t>(ld_row + 64) * g.ldp + k0);
-    q0 = *reinterpret_cast<const f32x4*>(Qg + static_cast<int64_t>(ld_row) * g.ldq + k0);
-    q1 = *reinterpret_cast<const f32x4*>(Qg + static_cast<int64_t>(ld_row + 64) * g.ldq + k0);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      pv[x] = *reinterpret_cast<const f32x4*>(Pg + static_cast<int64_t>(ld_row + 32 * x) * g.ldp + k0);
+      qv[x] = *reinterpret_cast<const f32x4*>(Qg + static_cast<int64_t>(ld_row + 32 * x) * g.ldq + k0);
+    }
   };
   auto stash = [&](int buf) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      sP[buf][ld_k + c][ld_row] = p0[c];
-      sP[buf][ld_k + c][ld_row + 64] = p1[c];
-      sQ[buf][ld_k + c][ld_row] = q0[c];
-      sQ[buf][ld_k + c][ld_row + 64] = q1[c];
-    }
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        sP[buf][ld_k + c][ld_row + 32 * x] = pv[x][c];
+        sQ[buf][ld_k + c][ld_row + 32 * x] = qv[x][c];
+      }
   };
 
   // two LDS stages: while stage kt is multiplied, stage kt + 1 travels global -> registers -> LDS

@@ -206,3 +206,46 @@ def test_8b_shaped_class_1024x4096(canz):
     run(canz, [dev], hp)
     log("shampoo 1024x4096: oracle (two eigendecompositions per matrix)")
     check(dev, grads, lefts, rights, params, hp, "shampoo 1024x4096")
+
+
+def test_hip_graph_replay_matches_eager(canz):
+    """canz_shampoo_step issues kernels only, so it can be captured; replays with eager work in
+    between reproduce the eager result bit for bit (statistics and parameters)."""
+    import torch
+    rows, cols, n = 200, 333, 2
+    hp = canz.ShampooHparams(beta=0.9, eps=1e-5)
+    grads = [W.gen_grad(45, i, rows, cols)[0] for i in range(n)]
+    lefts = [np.eye(rows, dtype=np.float32) * np.float32(1e-3) for _ in range(n)]
+    rights = [np.eye(cols, dtype=np.float32) * np.float32(1e-3) for _ in range(n)]
+    params = [W.gen_param(45, i, rows, cols) for i in range(n)]
+    dev = ShampooDevice(canz, rows, cols, grads, lefts, rights, outs=params)
+    groups = [dev.group()]
+    state = dev.left_t + dev.right_t + dev.out_t
+    saved = [t.clone() for t in state]
+    nbytes = canz.canz_shampoo_workspace_bytes(groups, hp)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    canz.canz_shampoo_step(groups, hp, ws, nbytes, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in state]
+    assert any(not torch.equal(a, b) for a, b in zip(want, saved))
+
+    def restore():
+        for t, s0 in zip(state, saved):
+            t.copy_(s0)
+
+    restore()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        canz.canz_shampoo_step(groups, hp, ws, nbytes, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(state, saved))     # capture runs nothing
+    for rep in range(3):
+        restore()
+        ws.fill_(0x5A if rep % 2 else 0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(zip(state, want)):
+            assert torch.equal(a, b), "replay %d: state tensor %d differs from the eager result" % (rep, i)
