@@ -107,6 +107,11 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
   const float* Qg = g.Q + static_cast<int64_t>(b) * g.sq + static_cast<int64_t>(tn) * SB * g.ldq;
 
   const int ld_row = t >> 3, ld_k = (t & 7) * 4;  // rows ld_row + 32 x (x = 0..3), 4 consecutive k
+  // Long sums of the statistics (k up to the other extent of the matrix, terms of one sign on the
+  // diagonal) are folded into a second accumulator every FLUSH stages; the products of the root
+  // iteration and the preconditioning accumulate in one go (their rounding, about 1e-5 relative,
+  // is corrected by the following rounds and is far below the tolerance of the update).
+  constexpr bool FOLD = EPI == SE_STAT;
   f32x16 acc[2][2], tot[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -115,33 +120,30 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f, tot[i][j][r] = 0.f;
 
-  f32x4 pv[4], qv[4];
-  auto fetch = [&](int kt) {
+  // Two register sets: stage kt + 2 is requested while stage kt is multiplied and stage kt + 1
+  // waits in the other set, so a request has two stage times (about 3.5 us) to land.
+  f32x4 pv[2][4], qv[2][4];
+  auto fetch = [&](int kt, int set) {
     const int64_t k0 = static_cast<int64_t>(kt) * SK + ld_k;
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
-      pv[x] = *reinterpret_cast<const f32x4*>(Pg + static_cast<int64_t>(ld_row + 32 * x) * g.ldp + k0);
-      qv[x] = *reinterpret_cast<const f32x4*>(Qg + static_cast<int64_t>(ld_row + 32 * x) * g.ldq + k0);
+      pv[set][x] = *reinterpret_cast<const f32x4*>(Pg + static_cast<int64_t>(ld_row + 32 * x) * g.ldp + k0);
+      qv[set][x] = *reinterpret_cast<const f32x4*>(Qg + static_cast<int64_t>(ld_row + 32 * x) * g.ldq + k0);
     }
   };
-  auto stash = [&](int buf) {
+  auto stash = [&](int buf, int set) {
 #pragma unroll
     for (int x = 0; x < 4; ++x)
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        sP[buf][ld_k + c][ld_row + 32 * x] = pv[x][c];
-        sQ[buf][ld_k + c][ld_row + 32 * x] = qv[x][c];
+        sP[buf][ld_k + c][ld_row + 32 * x] = pv[set][x][c];
+        sQ[buf][ld_k + c][ld_row + 32 * x] = qv[set][x][c];
       }
   };
-
-  // two LDS stages: while stage kt is multiplied, stage kt + 1 travels global -> registers -> LDS
-  const int nk = static_cast<int>(g.K / SK);
-  fetch(0);
-  stash(0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) fetch(kt + 1);
+  // one stage: LDS buffer `buf` holds stage kt, register set `other` stage kt + 1, set `mine` is free
+  const int nk = static_cast<int>(g.K / SK);   // a multiple of 4: K is a multiple of 128
+  auto stage = [&](int kt, int buf, int mine, int other) {
+    if (kt + 2 < nk) fetch(kt + 2, mine);
 #pragma unroll
     for (int k = 0; k < SK; k += 2) {
       float fa[2], fb[2];
@@ -154,7 +156,7 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    if ((kt + 1) % FLUSH == 0 || kt + 1 == nk) {
+    if (FOLD && ((kt + 1) % FLUSH == 0 || kt + 1 == nk)) {
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -162,8 +164,22 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
 #pragma unroll
           for (int r = 0; r < 16; ++r) tot[i][j][r] += acc[i][j][r], acc[i][j][r] = 0.f;
     }
-    if (kt + 1 < nk) stash(buf ^ 1);
-    __syncthreads();  // stage kt + 1 is complete; every wavefront is done reading stage kt
+    if (kt + 1 < nk) stash(buf ^ 1, other);
+    __syncthreads();  // stage kt + 1 is complete in LDS; every wavefront is done reading stage kt
+  };
+  fetch(0, 0);
+  fetch(1, 1);
+  stash(0, 0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; kt += 2) {
+    stage(kt, 0, 0, 1);
+    stage(kt + 1, 1, 1, 0);
+  }
+  if (!FOLD) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) tot[i][j] = acc[i][j];
   }
 
   const int row_base = tm * SB + wm * 64 + 4 * (lane >> 5);
