@@ -101,3 +101,32 @@ def test_config5_schedule(canz):
     _check_valid(cost, 4, cmax, groups, loads)
     # the heaviest matrices (12288 x 4096 = 50 M elements) fill a rank alone 5 times over
     assert all(l <= cmax for l in loads) and len(groups) >= 252 * 33_554_432 // (4 * cmax)
+
+
+def test_host_rank_walk_of_the_schedule(canz):
+    """tp_runtime.host_rank_calls: per micro-group of the sequence, the tensors one host rank hosts,
+    batched by shape - every tensor exactly once over all ranks, batches shape-homogeneous and equal
+    to the oracle's micro-group plan restricted to that micro-group (CPU only)."""
+    from oracle import microgroup as OMG
+    from paper_2602_06079_amd import tp_runtime as T
+    layer = [(512, 512), (128, 512), (128, 512), (512, 512), (1536, 512), (1536, 512), (512, 1536)]
+    rows = [r for _ in range(5) for r, _c in layer]
+    cols = [c for _ in range(5) for _r, c in layer]
+    cost = [r * c for r, c in zip(rows, cols)]
+    dtype = [1] * len(rows)
+    schedule, loads = canz.canz_tp_schedule(cost, 4, 1_600_000)
+    assert (schedule, loads) == TS.tp_schedule(cost, 4, 1_600_000)
+    seen = []
+    for rank in range(4):
+        calls = T.host_rank_calls(schedule, rank, rows, cols, dtype)
+        assert len(calls) == len(schedule)
+        for mg, batches in zip(schedule, calls):
+            owner = [-1] * len(rows)
+            for t, h in mg:
+                owner[t] = h
+            assert batches == OMG.microgroup_plan(rows, cols, dtype, owner, rank, max_mats=0)
+            for ids in batches:
+                assert len({(rows[p], cols[p]) for p in ids}) == 1
+                seen += ids
+    assert sorted(seen) == list(range(len(rows)))
+    assert T.host_rank_loads(schedule, cost, 4) == [sum(cost[t] for mg in schedule for t, h in mg if h == r) for r in range(4)]
