@@ -323,3 +323,31 @@ def test_gradient_magnitudes_far_from_one(canz, precision, log2_scale):
     dg = DeviceGroup(canz, rows, cols, grads, zeros)
     run_step(canz, [dg], hp)
     _check_group(canz, dg, grads, zeros, None, hp, "scale 2^%d prec%d" % (log2_scale, precision))
+
+
+def test_shared_launches_split_between_large_and_small_tiles(canz):
+    """Two shape classes whose launch batches share launches, sized so that every shared launch
+    has full rounds for the persistent 256 x 256 kernel AND left-over tiles for the 128 x 128 one
+    (Gram: 120 + 180 = 300 tiles on 256 CUs, update: 240 + 360 = 600): the tile numbering runs across
+    both products in both kernels.  Oracle parity on matrices of both classes, and the same bits as
+    each matrix run alone (where every product runs on the small kernel only)."""
+    classes = [(512, 768, 40), (768, 1024, 30)]
+    hp = canz.Hparams(out_mode=canz.OUT_DELTA)
+    devs, ins = [], []
+    for k, (rows, cols, n) in enumerate(classes):
+        grads = [W.gen_grad(70 + k, i, rows, cols)[0] for i in range(n)]
+        zeros = [np.zeros((rows, cols), np.float32) for _ in range(n)]
+        devs.append(DeviceGroup(canz, rows, cols, grads, zeros))
+        ins.append((grads, zeros))
+    run_step(canz, devs, hp)
+    ohp = oracle_hparams(hp)
+    for k, (rows, cols, n) in enumerate(classes):
+        for i in (0, n // 2, n - 1):
+            ref = OM.muon_step(widen(ins[k][0][i]), widen(ins[k][1][i]), ohp)
+            err = rel_fro(devs[k].out_host(i), ref["delta"])
+            assert err <= TOL[0], "class %d matrix %d: error %.3g" % (k, i, err)
+            solo = DeviceGroup(canz, rows, cols, [ins[k][0][i]], [ins[k][1][i]])
+            run_step(canz, [solo], hp)
+            assert np.array_equal(solo.out_host(0), devs[k].out_host(i)), "class %d matrix %d differs from the run alone" % (k, i)
+        for i in range(n):
+            assert np.isfinite(devs[k].out_host(i)).all()
