@@ -327,7 +327,8 @@ int canz_muon_step_static(const canz_group* g, int32_t n_groups, const canz_muon
  * Per-kernel timing of canz_muon_step / canz_shampoo_step, for benchmarks (the measurement protocol of
  * App. C.1 reports the optimizer time; this splits it by kernel).  While enabled, every
  * kernel launch of a step is bracketed by a pair of HIP events on the step's own stream.
- * Process-wide state: use from one thread, with steps that do not overlap.
+ * Process-wide state (guarded by a lock; with profiling off a step only reads one flag): meant for
+ * one benchmark thread, with steps that do not overlap.
  *   canz_profile_enable   creates (host-side) events for up to max_launches launches per
  *                         collection period and starts recording; launches beyond that
  *                         are not recorded.

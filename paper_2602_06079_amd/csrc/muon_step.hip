@@ -8,6 +8,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <mutex>
@@ -20,10 +21,13 @@
 namespace canz {
 
 // ---- optional per-kernel timing (canz_profile_*): a pool of event pairs recorded around
-// each launch on the step's own stream.  Process-wide state; not meant for concurrent steps.
+// each launch on the step's own stream.  Process-wide state behind a mutex; while profiling is
+// off a launch only reads one atomic flag.  Steps recorded from several threads at once would
+// interleave their launches in one pool: the timing is meant for one benchmark thread.
 namespace {
 struct Profiler {
-  bool on = false;
+  std::atomic<bool> on{false};
+  std::mutex lock;
   std::vector<hipEvent_t> ev;   // 2 per launch
   std::vector<int> kind;        // kind of each recorded launch
   size_t used = 0;              // launches recorded
@@ -32,7 +36,9 @@ Profiler g_prof;
 }  // namespace
 
 void prof_mark(hipStream_t st, int kind, bool begin) {
-  if (!g_prof.on || g_prof.used * 2 + 1 >= g_prof.ev.size()) return;
+  if (!g_prof.on.load(std::memory_order_relaxed)) return;
+  std::lock_guard<std::mutex> hold(g_prof.lock);
+  if (g_prof.used * 2 + 1 >= g_prof.ev.size()) return;
   if (begin) {
     (void)hipEventRecord(g_prof.ev[g_prof.used * 2], st);
   } else {
@@ -510,6 +516,7 @@ extern "C" int canz_muon_step_static(const canz_group* g, int32_t n_groups, cons
 extern "C" int canz_profile_enable(int32_t max_launches) {
   using namespace canz;
   if (max_launches < 1) return fail(CANZ_EINVAL, "max_launches must be >= 1");
+  std::lock_guard<std::mutex> hold(g_prof.lock);
   while (g_prof.ev.size() < static_cast<size_t>(max_launches) * 2) {
     hipEvent_t e;
     hipError_t err = hipEventCreate(&e);
@@ -518,7 +525,7 @@ extern "C" int canz_profile_enable(int32_t max_launches) {
   }
   g_prof.kind.assign(g_prof.ev.size() / 2, 0);
   g_prof.used = 0;
-  g_prof.on = true;
+  g_prof.on.store(true);
   return CANZ_OK;
 }
 
@@ -526,6 +533,7 @@ extern "C" int canz_profile_collect(double* ms_out, int64_t* launches_out) {
   using namespace canz;
   if (!ms_out || !launches_out) return fail(CANZ_EINVAL, "null output pointer");
   for (int k = 0; k < CANZ_KERNEL_KINDS; ++k) ms_out[k] = 0.0, launches_out[k] = 0;
+  std::lock_guard<std::mutex> hold(g_prof.lock);
   for (size_t i = 0; i < g_prof.used; ++i) {
     hipError_t err = hipEventSynchronize(g_prof.ev[2 * i + 1]);
     float ms = 0.f;
@@ -539,7 +547,8 @@ extern "C" int canz_profile_collect(double* ms_out, int64_t* launches_out) {
 }
 
 extern "C" int canz_profile_disable(void) {
-  canz::g_prof.on = false;
+  std::lock_guard<std::mutex> hold(canz::g_prof.lock);
+  canz::g_prof.on.store(false);
   canz::g_prof.used = 0;
   return CANZ_OK;
 }
