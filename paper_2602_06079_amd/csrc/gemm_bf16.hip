@@ -719,7 +719,9 @@ __global__ __launch_bounds__(NTHREADS) void k_split_finish(GemmDims d, EpiArgs e
 // comes out with the same bits from either kernel.  Epilogues store straight from the
 // accumulators (4 bytes per lane for the straight image after the lane-pair exchange, 8 bytes
 // per lane for the transposed one): there is no LDS to spare for staging with three blocks
-// per CU, and the stores of one block drain under the work of the others.
+// per CU, and the stores of one block drain under the work of the others.  Only the last
+// product, whose rows go to the caller's row-major buffers, stages them through the stages
+// the k loop has left free.
 constexpr int SM = 128;                  // tile rows and columns
 constexpr int S_STAGE = 2 * SM * BK;     // elements per stage: P half-panel + Q half-panel (16 KiB)
 
@@ -865,15 +867,76 @@ __global__ __launch_bounds__(NTHREADS, 3) void k_gemm_nt_bf16_small(Args args, E
   }
 
   if (EPI == EPI_FINAL) {
+    const int ld = static_cast<int>(o.out_mode == CANZ_OUT_DELTA ? s.wfrag : s.cols);
+    if ((ld & 3) != 0) {
+      // unaligned row length: element-wise accesses straight from the accumulators
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        float v[16];
+        for (int j = 0; j < 2; ++j) {
+          float v[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) v[r] = acc[i][j][r];
-        store_out_tile(o, s, b, row_w + 32 * i + 4 * lh, col_w + 32 * j + lj, v);
+          for (int r = 0; r < 16; ++r) v[r] = acc[i][j][r];
+          store_out_tile(o, s, b, row_w + 32 * i + 4 * lh, col_w + 32 * j + lj, v);
+        }
+      return;
+    }
+    // The stages are free once every wavefront has left the k loop: each wavefront turns its
+    // 64 x 64 part through 8 KiB of LDS, 32 rows at a time, into rows of fp32 and updates the
+    // caller's buffer with 16-byte accesses (4 columns per lane, 16 lanes per row).
+    __syncthreads();
+    float* sf = reinterpret_cast<float*>(wave == 0 ? sa : wave == 1 ? sa + 4096 : wave == 2 ? sb : sb + 4096);
+    const int col = col_w + (lane & 15) * 4;
+    const bool col_ok = col < s.cols;
+    int c_in = col, tab = b;
+    if (o.out_mode == CANZ_OUT_DELTA) {
+      const int f = col_ok ? col / ld : 0;
+      c_in = col - f * ld;
+      tab = b * s.tp + f;
+    }
+    char* base = static_cast<char*>(o.out.p[col_ok ? tab : b * (o.out_mode == CANZ_OUT_DELTA ? s.tp : 1)]);
+    const int esz = o.out_dtype == CANZ_DT_F32 ? 4 : 2;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sf[(8 * (r >> 2) + 4 * lh + (r & 3)) * 64 + 32 * j + lj] = acc[i][j][r];
+#pragma unroll
+      for (int x = 0; x < 8; ++x) {
+        const int row_l = 4 * x + (lane >> 4);
+        const f32x4 v = *reinterpret_cast<const f32x4*>(sf + row_l * 64 + (lane & 15) * 4);
+        const int row = row_w + 32 * i + row_l;
+        if (!col_ok || row >= s.rows) continue;
+        char* ptr = base + (static_cast<int64_t>(row) * ld + c_in) * esz;
+        f32x4 res;
+        if (o.out_mode == CANZ_OUT_PARAM) {
+          f32x4 old;
+          if (o.out_dtype == CANZ_DT_F32) {
+            old = *reinterpret_cast<const f32x4*>(ptr);
+          } else {
+            const bf16x4 ob = *reinterpret_cast<const bf16x4*>(ptr);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) old[q] = static_cast<float>(ob[q]);
+          }
+#pragma unroll
+          for (int q = 0; q < 4; ++q) res[q] = apply_update(old[q], o.decay, o.neg_lr_scale, v[q]);
+        } else {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) res[q] = o.neg_lr_scale * v[q];
+        }
+        if (o.out_dtype == CANZ_DT_F32) {
+          *reinterpret_cast<f32x4*>(ptr) = res;
+        } else {
+          bf16x4 rb;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) rb[q] = static_cast<__bf16>(res[q]);
+          *reinterpret_cast<bf16x4*>(ptr) = rb;
+        }
       }
+      // the second half is staged in the same area (this wavefront's own: no barrier needed)
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    }
     return;
   }
 
@@ -946,15 +1009,11 @@ int64_t tile_count(const GemmDims& d) {
   return ((EPI == EPI_GRAM || EPI == EPI_POLY) ? tm * (tm + 1) / 2 : tm * tn) * d.nb;
 }
 
-// number of tiles [0, whole) for the large kernel; the rest, if any, for the small one.  The last
-// product's small-tile epilogue updates the parameters with 4-byte accesses (the large one stages
-// rows and uses 16-byte accesses), which costs more than the idle part of a round: its left-over
-// tiles stay with the large kernel unless there is no full round at all.
+// number of tiles [0, whole) for the large kernel; the rest, if any, for the small one
 template <int EPI>
 int64_t large_share(int64_t tiles, int64_t cus, int64_t longest_k) {
   const int64_t left = tiles % cus;
   if (longest_k > SMALL_MAX_K || left == 0 || 2 * left > cus) return tiles;
-  if (EPI == EPI_FINAL && tiles > cus) return tiles;
   return tiles - left;
 }
 
