@@ -19,6 +19,8 @@ tp_schedule TP micro-group construction with greedy rollback and the min-heap LP
 shampoo     The Shampoo operator the paper runs through the same planner (App. C,
             "Generalization to Other Optimizers"): Kronecker-factor statistics, inverse
             fourth roots by eigendecomposition, preconditioned update.
+soap        The SOAP operator of the same experiment: Adam in the eigenbasis of those
+            statistics, the basis refreshed by one round of orthogonal iteration (QR).
 muon        The Muon operator named in Sec. 4.1 / App. B.3: momentum,
             Frobenius normalisation, k Newton-Schulz steps, scaled update;
             TP column-fragment gather/scatter of Sec. 4.1 stages (1) and (3).
@@ -26,7 +28,8 @@ muon        The Muon operator named in Sec. 4.1 / App. B.3: momentum,
 Parity pins (tests/test_oracle_*.py): every function here is pinned to
 something other than itself - SVD closed forms and the polar factor for the
 Newton-Schulz iteration, a scalar-map grid for the quintic band, defining identities
-and diagonal / rank-one / SVD closed forms for the Shampoo step, hand-worked
+and diagonal / rank-one / SVD closed forms for the Shampoo step, torch's Adam, the polar
+factor and the defining properties of the QR refresh for the SOAP step, hand-worked
 partitions, exact-rational replays, brute-force enumeration of cut vectors,
 and structural invariants.  The paper's measured load-balance ratios depend on
 a bucket layout it does not give; they are not pinned.

@@ -1,6 +1,6 @@
 """Pin strength: mistakes planted in a copy of the oracle's source must each be caught by
 at least one of the pins in test_oracle_partition / test_oracle_muon / test_oracle_shampoo /
-test_tp_schedule.
+test_oracle_soap / test_tp_schedule.
 
 A mutant is the oracle module's source with one expression replaced (a dropped term, a
 wrong sign, a transposed operand, a flipped comparison), executed as a fresh module; the
@@ -15,10 +15,12 @@ import pytest
 import oracle.muon as OM
 import oracle.partition as OP
 import oracle.shampoo as SHO
+import oracle.soap as SOO
 import oracle.tp_schedule as TS
 from tests import test_oracle_muon as PINS_MUON
 from tests import test_oracle_partition as PINS_PART
 from tests import test_oracle_shampoo as PINS_SHAMPOO
+from tests import test_oracle_soap as PINS_SOAP
 from tests import test_tp_schedule as PINS_TP
 
 
@@ -154,6 +156,46 @@ def test_shampoo_pins_catch(what, old, new):
     assert failed, "no pin notices: " + what
 
 
+SOAP_MUTANTS = [
+    ("momentum without the (1 - beta1) weight", "+ (1.0 - hp.beta1) * g", "+ g"),
+    ("momentum decays with beta2", "mom = hp.beta1 *", "mom = hp.beta2 *"),
+    ("left basis not transposed on the way in", "np.asarray(q_left, dtype=np.float64).T @ y", "np.asarray(q_left, dtype=np.float64) @ y"),
+    ("right basis not transposed on the way out", "y @ np.asarray(q_right, dtype=np.float64).T", "y @ np.asarray(q_right, dtype=np.float64)"),
+    ("second moment of the unrotated gradient", "* grad_rot * grad_rot", "* g * g"),
+    ("second moment of the momentum", "* grad_rot * grad_rot", "* mom_rot * mom_rot"),
+    ("second moment without the (1 - beta2) weight", "+ (1.0 - hp.beta2) * grad_rot * grad_rot", "+ grad_rot * grad_rot"),
+    ("eps inside the square root", "np.sqrt(v_hat) + hp.eps", "np.sqrt(v_hat + hp.eps)"),
+    ("second moment corrected with beta1", "v_hat = v_rot / (1.0 - hp.beta2 ** t)", "v_hat = v_rot / (1.0 - hp.beta1 ** t)"),
+    ("bias correction one step late", "m_hat = m_rot / (1.0 - hp.beta1 ** t)", "m_hat = m_rot / (1.0 - hp.beta1 ** (t + 1))"),
+    ("update with the wrong sign", "delta = -hp.lr * direction", "delta = hp.lr * direction"),
+    ("weight decay without the learning rate", "* (1.0 - hp.lr * hp.weight_decay) + delta", "* (1.0 - hp.weight_decay) + delta"),
+    ("left statistic from G^T G", "* (g @ g.T)", "* (g.T @ g if g.shape[0] == g.shape[1] else g @ g.T)"),
+    ("statistics decay with beta1", "left = hp.beta2 *", "left = hp.beta1 *"),
+    ("statistics without the (1 - beta2) weight", "+ (1.0 - hp.beta2) * (g.T @ g)", "+ (g.T @ g)"),
+    ("basis multiplied from the wrong side", "s = np.asarray(stat, dtype=np.float64) @ np.asarray(basis, dtype=np.float64)",
+     "s = np.asarray(basis, dtype=np.float64) @ np.asarray(stat, dtype=np.float64)"),
+    ("triangular factor returned", "q, _ = np.linalg.qr(s)", "_, q = np.linalg.qr(s)"),
+    ("refresh from the statistics before the step", "q_left = refresh_basis(left, q_left)",
+     "q_left = refresh_basis(np.asarray(state['left'], dtype=np.float64), q_left)"),
+    ("right basis refreshed from the left statistic", "q_right = refresh_basis(right, q_right)",
+     "q_right = refresh_basis(left if left is not None and left.shape == right.shape else right, q_right)"),
+    ("step uses the refreshed basis of an earlier call", "grad_rot = rotate_in(g, q_left, q_right)",
+     "grad_rot = rotate_in(g, q_left, None if q_right is None else np.asarray(q_right)[:, ::-1])"),
+    ("limit excludes the extent equal to it", "use_left, use_right = rows <= hp.max_precond_dim, cols <= hp.max_precond_dim",
+     "use_left, use_right = rows < hp.max_precond_dim, cols <= hp.max_precond_dim"),
+    ("side above the limit still rotated", "q_left = np.asarray(state[\"q_left\"], dtype=np.float64) if use_left else None",
+     "q_left = np.asarray(state[\"q_left\"], dtype=np.float64)"),
+    ("fragments gathered along rows", "return np.concatenate([np.asarray(f, dtype=np.float64) for f in fragments], axis=1)",
+     "return np.concatenate([np.asarray(f, dtype=np.float64) for f in fragments], axis=0).reshape(fragments[0].shape[0], -1)"),
+]
+
+
+@pytest.mark.parametrize("what,old,new", SOAP_MUTANTS, ids=[m[0] for m in SOAP_MUTANTS])
+def test_soap_pins_catch(what, old, new):
+    failed = _caught(PINS_SOAP, "SO", _mutant(SOO, old, new))
+    assert failed, "no pin notices: " + what
+
+
 @pytest.mark.parametrize("what,old,new", SHAMPOO_COST_MUTANTS, ids=[m[0] for m in SHAMPOO_COST_MUTANTS])
 def test_shampoo_cost_pins_catch(what, old, new):
     failed = _caught(PINS_SHAMPOO, "OP", _mutant(OP, old, new))
@@ -184,3 +226,4 @@ def test_unmutated_oracle_passes_the_same_harness():
     assert _caught(PINS_PART, "P", importlib.import_module("oracle.partition")) == []
     assert _caught(PINS_TP, "TS", importlib.import_module("oracle.tp_schedule")) == []
     assert _caught(PINS_SHAMPOO, "SH", importlib.import_module("oracle.shampoo")) == []
+    assert _caught(PINS_SOAP, "SO", importlib.import_module("oracle.soap")) == []
