@@ -302,6 +302,78 @@ int canz_shampoo_step(const canz_shampoo_group* g, int32_t n_groups, const canz_
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * SOAP, the third matrix optimizer the paper runs through the same planner ("Generalization to
+ * Other Optimizers (Shampoo & SOAP)", App. C: "distinct cubic-complexity operations (SVD and
+ * Eigendecomposition, respectively)"), under the generic update of App. B.3, Eq. 5: Adam run in
+ * the eigenbasis of Shampoo's statistics.  Per matrix G (rows x cols) at step t = 1, 2, ...:
+ *   M <- beta1 M + (1 - beta1) G                              (momentum, original space)
+ *   G' = Q_L^T G Q_R,   M' = Q_L^T M Q_R                      (rotation into the bases)
+ *   V <- beta2 V + (1 - beta2) G' * G'                        (elementwise, rotated space)
+ *   N' = m / (sqrt(v) + eps),  m = M' / (1 - beta1^t), v = V / (1 - beta2^t) with bias
+ *                              correction, m = M', v = V without
+ *   N = Q_L N' Q_R^T;  CANZ_OUT_PARAM: P <- P (1 - lr weight_decay) - lr N;  CANZ_OUT_DELTA: Delta W = -lr N
+ *   L <- beta2 L + (1 - beta2) G G^T,   R <- beta2 R + (1 - beta2) G^T G
+ *   if refresh:  Q_L <- orthogonal factor of the QR decomposition of L Q_L,  Q_R likewise of R Q_R
+ *                (one round of orthogonal iteration towards the eigenvectors; V is not rotated)
+ * A side longer than max_precond_dim keeps no statistic and no basis (its Q is the identity and
+ * its tables may be NULL); at least one side must be within the limit.  Everything is fp32.
+ * The caller owns all state and decides when to refresh (every f-th step) and how the bases
+ * start (identity, or eigenvectors of the first statistics computed elsewhere).  The QR step is
+ * a blocked Householder factorisation: the basis it writes is orthonormal to fp32 rounding and
+ * its columns are fixed up to sign (which the step does not depend on); where L Q_L is rank
+ * deficient the trailing columns are some orthonormal completion.
+ *
+ * One micro-group: n_mats matrices of identical shape and dtypes; grad / out / tp as in
+ * canz_group; all state is fp32, dense, row-major, device, 16-byte aligned, updated in place:
+ * mom[i], var[i] rows x cols; left[i], qleft[i] rows x rows; right[i], qright[i] cols x cols
+ * (the columns of a basis are its vectors).
+ */
+typedef struct {
+  int64_t rows, cols;
+  int32_t n_mats;
+  int32_t tp;
+  int32_t grad_dtype;       /* CANZ_DT_F32 or CANZ_DT_BF16 */
+  int32_t out_dtype;
+  const void* const* grad;  /* [n_mats*tp] */
+  void* const* mom;         /* [n_mats] */
+  void* const* var;         /* [n_mats] */
+  void* const* left;        /* [n_mats] */
+  void* const* right;       /* [n_mats] */
+  void* const* qleft;       /* [n_mats] */
+  void* const* qright;      /* [n_mats] */
+  void* const* out;         /* [n_mats] parameters, or [n_mats*tp] Delta W fragments */
+} canz_soap_group;
+
+typedef struct {
+  float beta1, beta2, lr, weight_decay, eps;
+  int32_t step;             /* t >= 1, used by the bias correction */
+  int32_t bias_correction;  /* 0 or 1 */
+  int32_t refresh;          /* 1: refresh the bases at the end of this step */
+  int32_t max_precond_dim;  /* >= 1 */
+  int32_t out_mode;         /* CANZ_OUT_* */
+} canz_soap_hparams;
+
+/*
+ * canz_soap_workspace_bytes - device scratch canz_soap_step needs for these groups and these
+ * hyper-parameters (a refresh step needs more).  Pointer tables may be NULL for this call.
+ */
+int canz_soap_workspace_bytes(const canz_soap_group* g, int32_t n_groups, const canz_soap_hparams* hp,
+                              size_t* bytes_out);
+
+/*
+ * canz_soap_step - enqueue one SOAP step for the given micro-groups on hip_stream.
+ * Same conventions as canz_muon_step: host tables of device pointers read during the call,
+ * caller-owned 256-byte aligned workspace whose contents are scratch, kernel launches only
+ * (no allocation, copy, memset or synchronisation), completion in stream order.
+ * Errors: CANZ_EINVAL (null pointers, n_mats < 0, tp outside 1..8, betas outside [0, 1), eps < 0,
+ * step < 1, max_precond_dim < 1), CANZ_ESHAPE (cols not divisible by tp, fragment width not a
+ * multiple of 8, an extent above 32768), CANZ_EWORKSPACE, CANZ_EUNSUPPORTED (dtype / mode enums,
+ * both extents above max_precond_dim), CANZ_EHIP.
+ */
+int canz_soap_step(const canz_soap_group* g, int32_t n_groups, const canz_soap_hparams* hp,
+                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * canz_muon_step_static - canz_muon_step without a workspace argument, for callers that
  * cannot allocate device memory or may not call an allocator where the step is issued
  * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).
@@ -324,7 +396,7 @@ int canz_muon_step_static(const canz_group* g, int32_t n_groups, const canz_muon
                           void* hip_stream);
 
 /*
- * Per-kernel timing of canz_muon_step / canz_shampoo_step, for benchmarks (the measurement protocol of
+ * Per-kernel timing of canz_muon_step / canz_shampoo_step / canz_soap_step, for benchmarks (the measurement protocol of
  * App. C.1 reports the optimizer time; this splits it by kernel).  While enabled, every
  * kernel launch of a step is bracketed by a pair of HIP events on the step's own stream.
  * Process-wide state (guarded by a lock; with profiling off a step only reads one flag): meant for
@@ -350,7 +422,13 @@ enum {
   CANZ_KERNEL_SH_INIT = 9,  /* Shampoo: norm and start of the root iteration  */
   CANZ_KERNEL_SH_ROOT = 10, /* Shampoo: products of the root iteration        */
   CANZ_KERNEL_SH_APPLY = 11,/* Shampoo: L^(-1/4) G and (.) R^(-1/4) + update   */
-  CANZ_KERNEL_KINDS = 12
+  CANZ_KERNEL_SOAP_LOAD = 12,   /* SOAP: momentum, gather + cast, padded copies of the bases */
+  CANZ_KERNEL_SOAP_ROTATE = 13, /* SOAP: rotations into and out of the bases (+ update)    */
+  CANZ_KERNEL_SOAP_ADAM = 14,   /* SOAP: second moment and Adam's direction                */
+  CANZ_KERNEL_SOAP_STAT = 15,   /* SOAP: L, R statistics                                   */
+  CANZ_KERNEL_SOAP_QR = 16,     /* SOAP refresh: products of the blocked QR                */
+  CANZ_KERNEL_SOAP_PANEL = 17,  /* SOAP refresh: panel factorisation, fills, basis store   */
+  CANZ_KERNEL_KINDS = 18
 };
 int canz_profile_enable(int32_t max_launches);
 int canz_profile_collect(double* ms_out, int64_t* launches_out);

@@ -27,10 +27,11 @@ OUT_PARAM, OUT_DELTA = 0, 1
 
 EXPORTS = ("canz_last_error", "canz_version", "canz_partition_alpha", "canz_partition_naive", "canz_microgroup_plan", "canz_tp_schedule",
            "canz_muon_workspace_bytes", "canz_muon_step", "canz_muon_step_static",
-           "canz_shampoo_workspace_bytes", "canz_shampoo_step",
+           "canz_shampoo_workspace_bytes", "canz_shampoo_step", "canz_soap_workspace_bytes", "canz_soap_step",
            "canz_profile_enable", "canz_profile_collect", "canz_profile_disable")
 KERNEL_KINDS = ("momentum", "norm", "gram", "poly", "update", "final", "apply",
-                "sh_load", "sh_stat", "sh_init", "sh_root", "sh_apply")
+                "sh_load", "sh_stat", "sh_init", "sh_root", "sh_apply",
+                "soap_load", "soap_rotate", "soap_adam", "soap_stat", "soap_qr", "soap_panel")
 
 
 class CanzError(RuntimeError):
@@ -62,6 +63,20 @@ class _ShGroup(C.Structure):
 class _ShHparams(C.Structure):
     _fields_ = [("beta", C.c_float), ("lr", C.c_float), ("weight_decay", C.c_float), ("eps", C.c_float),
                 ("root_iters", C.c_int32), ("out_mode", C.c_int32)]
+
+
+class _SoapGroup(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("n_mats", C.c_int32), ("tp", C.c_int32),
+                ("grad_dtype", C.c_int32), ("out_dtype", C.c_int32),
+                ("grad", C.POINTER(C.c_void_p)), ("mom", C.POINTER(C.c_void_p)), ("var", C.POINTER(C.c_void_p)),
+                ("left", C.POINTER(C.c_void_p)), ("right", C.POINTER(C.c_void_p)),
+                ("qleft", C.POINTER(C.c_void_p)), ("qright", C.POINTER(C.c_void_p)), ("out", C.POINTER(C.c_void_p))]
+
+
+class _SoapHparams(C.Structure):
+    _fields_ = [("beta1", C.c_float), ("beta2", C.c_float), ("lr", C.c_float), ("weight_decay", C.c_float),
+                ("eps", C.c_float), ("step", C.c_int32), ("bias_correction", C.c_int32), ("refresh", C.c_int32),
+                ("max_precond_dim", C.c_int32), ("out_mode", C.c_int32)]
 
 
 def _load():
@@ -103,6 +118,12 @@ def _load():
     lib.canz_shampoo_step.argtypes = [C.POINTER(_ShGroup), C.c_int32, C.POINTER(_ShHparams), C.c_void_p, C.c_size_t,
                                       C.c_void_p]
     lib.canz_shampoo_step.restype = C.c_int
+    lib.canz_soap_workspace_bytes.argtypes = [C.POINTER(_SoapGroup), C.c_int32, C.POINTER(_SoapHparams),
+                                              C.POINTER(C.c_size_t)]
+    lib.canz_soap_workspace_bytes.restype = C.c_int
+    lib.canz_soap_step.argtypes = [C.POINTER(_SoapGroup), C.c_int32, C.POINTER(_SoapHparams), C.c_void_p, C.c_size_t,
+                                   C.c_void_p]
+    lib.canz_soap_step.restype = C.c_int
     lib.canz_profile_enable.argtypes = [C.c_int32]
     lib.canz_profile_enable.restype = C.c_int
     lib.canz_profile_collect.argtypes = [C.POINTER(C.c_double), i64p]
@@ -324,6 +345,74 @@ def canz_shampoo_step(groups: Sequence[ShampooGroup], hp: ShampooHparams, worksp
     h = hp._c()
     _check(_lib.canz_shampoo_step(arr, len(groups), C.byref(h), C.c_void_p(_addr(workspace)), int(workspace_bytes),
                                   C.c_void_p(int(stream))))
+
+
+@dataclass
+class SoapHparams:
+    beta1: float = 0.95
+    beta2: float = 0.95
+    lr: float = 3e-3
+    weight_decay: float = 0.0
+    eps: float = 1e-8
+    step: int = 1
+    bias_correction: bool = True
+    refresh: bool = False
+    max_precond_dim: int = 10000
+    out_mode: int = OUT_PARAM
+
+    def _c(self) -> _SoapHparams:
+        return _SoapHparams(self.beta1, self.beta2, self.lr, self.weight_decay, self.eps, int(self.step),
+                            int(bool(self.bias_correction)), int(bool(self.refresh)), int(self.max_precond_dim),
+                            int(self.out_mode))
+
+
+@dataclass
+class SoapGroup:
+    """One micro-group of canz_soap_step: device buffers given as addresses or objects with data_ptr()."""
+    rows: int
+    cols: int
+    grad: Sequence = field(default_factory=list)    # n_mats * tp
+    mom: Sequence = field(default_factory=list)     # n_mats, fp32 rows x cols
+    var: Sequence = field(default_factory=list)     # n_mats, fp32 rows x cols (rotated space)
+    left: Sequence = field(default_factory=list)    # n_mats, fp32 rows x rows (empty if rows > max_precond_dim)
+    right: Sequence = field(default_factory=list)   # n_mats, fp32 cols x cols
+    qleft: Sequence = field(default_factory=list)   # n_mats, fp32 rows x rows, columns are the basis vectors
+    qright: Sequence = field(default_factory=list)  # n_mats, fp32 cols x cols
+    out: Sequence = field(default_factory=list)     # n_mats (params) or n_mats * tp (delta fragments)
+    tp: int = 1
+    grad_dtype: int = DT_BF16
+    out_dtype: int = DT_F32
+    n_mats: int = -1                                # -1: len(mom)
+
+
+def _marshal_soap(groups: Sequence[SoapGroup]):
+    arr = (_SoapGroup * max(len(groups), 1))()
+    keep = []
+    for i, g in enumerate(groups):
+        n_mats = len(g.mom) if g.n_mats < 0 else g.n_mats
+        tabs = []
+        for seq in (g.grad, g.mom, g.var, g.left, g.right, g.qleft, g.qright, g.out):
+            t = (C.c_void_p * max(len(seq), 1))(*[_addr(x) for x in seq])
+            keep.append(t)
+            tabs.append(C.cast(t, C.POINTER(C.c_void_p)) if len(seq) else None)
+        arr[i] = _SoapGroup(int(g.rows), int(g.cols), int(n_mats), int(g.tp), int(g.grad_dtype), int(g.out_dtype), *tabs)
+    return arr, keep
+
+
+def canz_soap_workspace_bytes(groups: Sequence[SoapGroup], hp: SoapHparams) -> int:
+    arr, _keep = _marshal_soap(groups)
+    out = C.c_size_t(0)
+    h = hp._c()
+    _check(_lib.canz_soap_workspace_bytes(arr, len(groups), C.byref(h), C.byref(out)))
+    return int(out.value)
+
+
+def canz_soap_step(groups: Sequence[SoapGroup], hp: SoapHparams, workspace, workspace_bytes: int, stream=0) -> None:
+    """Enqueue one SOAP step on ``stream`` (an integer hipStream_t)."""
+    arr, _keep = _marshal_soap(groups)
+    h = hp._c()
+    _check(_lib.canz_soap_step(arr, len(groups), C.byref(h), C.c_void_p(_addr(workspace)), int(workspace_bytes),
+                               C.c_void_p(int(stream))))
 
 
 STATIC_WORKSPACE_BYTES = 128 << 20

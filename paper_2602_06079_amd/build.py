@@ -21,7 +21,7 @@ EXAMPLE_SRC = os.path.join(CSRC, "example_c_abi_step.cpp")
 EXAMPLE_OUT = os.path.join(HERE, "c_abi_step")      # a C++ program that uses the C ABI directly, no Python
 
 HOST_SOURCES = ["error.cpp", "partition.cpp", "microgroup.cpp", "tp_schedule.cpp"]
-HIP_SOURCES = ["muon_step.hip", "elementwise.hip", "gemm_bf16.hip", "gemm_f32.hip", "shampoo.hip"]
+HIP_SOURCES = ["muon_step.hip", "elementwise.hip", "gemm_bf16.hip", "gemm_f32.hip", "shampoo.hip", "soap.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 CXX = os.environ.get("CXX", "g++")

@@ -31,239 +31,17 @@
 #include "canz.h"
 #include "canz_internal.h"
 #include "device_util.h"
+#include "f32_mfma_gemm.h"
 #include "kernels.h"
 
 namespace canz {
 namespace {
 
-constexpr int SB = 128;          // block tile (rows and columns)
-constexpr int SK = 32;           // k extent of one LDS stage: long enough that the next stage's global loads land under it
-constexpr int NTH = 256;
-constexpr int LDS_LD = SB + 5;   // odd row length: the k-major stores of a stage spread over all banks
-constexpr int FLUSH = 16;        // stages (512 k) between folds of the running accumulator
+using namespace f32mfma;
+
 constexpr int NPART = 64;        // partial sums per matrix of the Frobenius norm
 constexpr int64_t MAX_EXTENT = 32768;
 constexpr size_t BATCH_BYTES = size_t(8) << 30;
-constexpr size_t ALIGN = 256;
-
-inline int64_t pad128(int64_t x) { return (x + SB - 1) / SB * SB; }
-inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
-
-enum { SE_STAT = 0, SE_PLAIN = 1, SE_MT = 2, SE_OUT = 3 };
-
-struct ShGemm {
-  int64_t M, N, K;      // multiples of 128, 128, 32
-  int64_t ldp, ldq;     // row strides of P [M][K] and Q [N][K]
-  int64_t sp, sq;       // batch strides
-  const float* P;
-  const float* Q;
-  float* c;             // [nb][M][N] output, row stride N, batch stride M * N
-  float* c2;            // SE_MT: the next T = 5/4 I - 1/4 C
-  // SE_STAT: the caller's statistic (d x d, dense) is updated in place and A = S + eps I is written to c
-  int64_t d;
-  float beta, eps;
-};
-
-// Straight and (for off-diagonal tiles of a symmetric product) mirrored store of the 16 values
-// a lane holds of a 32 x 32 accumulator tile: rows row0 + 8 (r / 4) + (r % 4), column col.
-__device__ __forceinline__ void put16(float* C, int64_t ld, int row0, int col, const float (&v)[16], bool mirror) {
-#pragma unroll
-  for (int r = 0; r < 16; ++r) C[static_cast<int64_t>(row0 + 8 * (r >> 2) + (r & 3)) * ld + col] = v[r];
-  if (mirror) {
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      f32x4 q;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) q[e] = v[4 * g + e];
-      *reinterpret_cast<f32x4*>(C + static_cast<int64_t>(col) * ld + row0 + 8 * g) = q;
-    }
-  }
-}
-
-template <int EPI, bool SYM>
-__global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape s, OutSpec o) {
-  __shared__ float sP[2][SK][LDS_LD];  // k-major: the lanes of one MFMA operand read consecutive rows
-  __shared__ float sQ[2][SK][LDS_LD];
-
-  const int tiles_m = static_cast<int>(g.M / SB), tiles_n = static_cast<int>(g.N / SB);
-  const int per = SYM ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
-  const int b = blockIdx.x / per;
-  int tix = blockIdx.x - b * per;
-  int tm, tn;
-  if (SYM) {
-    // upper triangle row by row: row tm holds the columns tm .. tiles_m - 1
-    tm = 0;
-    for (int len = tiles_m; tix >= len; --len) tix -= len, ++tm;
-    tn = tm + tix;
-  } else {
-    tm = tix / tiles_n;
-    tn = tix - tm * tiles_n;
-  }
-
-  const int t = threadIdx.x;
-  const int lane = t & 63, wave = t >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const float* Pg = g.P + static_cast<int64_t>(b) * g.sp + static_cast<int64_t>(tm) * SB * g.ldp;
-  const float* Qg = g.Q + static_cast<int64_t>(b) * g.sq + static_cast<int64_t>(tn) * SB * g.ldq;
-
-  const int ld_row = t >> 3, ld_k = (t & 7) * 4;  // rows ld_row + 32 x (x = 0..3), 4 consecutive k
-  // Long sums of the statistics (k up to the other extent of the matrix, terms of one sign on the
-  // diagonal) are folded into a second accumulator every FLUSH stages; the products of the root
-  // iteration and the preconditioning accumulate in one go (their rounding, about 1e-5 relative,
-  // is corrected by the following rounds and is far below the tolerance of the update).
-  constexpr bool FOLD = EPI == SE_STAT;
-  f32x16 acc[2][2], tot[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f, tot[i][j][r] = 0.f;
-
-  // Two register sets: stage kt + 2 is requested while stage kt is multiplied and stage kt + 1
-  // waits in the other set, so a request has two stage times (about 3.5 us) to land.
-  f32x4 pv[2][4], qv[2][4];
-  auto fetch = [&](int kt, int set) {
-    const int64_t k0 = static_cast<int64_t>(kt) * SK + ld_k;
-#pragma unroll
-    for (int x = 0; x < 4; ++x) {
-      pv[set][x] = *reinterpret_cast<const f32x4*>(Pg + static_cast<int64_t>(ld_row + 32 * x) * g.ldp + k0);
-      qv[set][x] = *reinterpret_cast<const f32x4*>(Qg + static_cast<int64_t>(ld_row + 32 * x) * g.ldq + k0);
-    }
-  };
-  auto stash = [&](int buf, int set) {
-#pragma unroll
-    for (int x = 0; x < 4; ++x)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        sP[buf][ld_k + c][ld_row + 32 * x] = pv[set][x][c];
-        sQ[buf][ld_k + c][ld_row + 32 * x] = qv[set][x][c];
-      }
-  };
-  // one stage: LDS buffer `buf` holds stage kt, register set `other` stage kt + 1, set `mine` is free
-  const int nk = static_cast<int>(g.K / SK);   // a multiple of 4: K is a multiple of 128
-  auto stage = [&](int kt, int buf, int mine, int other) {
-    if (kt + 2 < nk) fetch(kt + 2, mine);
-#pragma unroll
-    for (int k = 0; k < SK; k += 2) {
-      float fa[2], fb[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) fa[i] = sP[buf][k + (lane >> 5)][wm * 64 + i * 32 + (lane & 31)];
-#pragma unroll
-      for (int j = 0; j < 2; ++j) fb[j] = sQ[buf][k + (lane >> 5)][wn * 64 + j * 32 + (lane & 31)];
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    if (FOLD && ((kt + 1) % FLUSH == 0 || kt + 1 == nk)) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) tot[i][j][r] += acc[i][j][r], acc[i][j][r] = 0.f;
-    }
-    if (kt + 1 < nk) stash(buf ^ 1, other);
-    __syncthreads();  // stage kt + 1 is complete in LDS; every wavefront is done reading stage kt
-  };
-  fetch(0, 0);
-  fetch(1, 1);
-  stash(0, 0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; kt += 2) {
-    stage(kt, 0, 0, 1);
-    stage(kt + 1, 1, 1, 0);
-  }
-  if (!FOLD) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) tot[i][j] = acc[i][j];
-  }
-
-  const int row_base = tm * SB + wm * 64 + 4 * (lane >> 5);
-  const int col_base = tn * SB + wn * 64 + (lane & 31);
-  const bool mirror = SYM && tm != tn;
-  const int64_t cb = static_cast<int64_t>(b) * g.M * g.N;
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int row0 = row_base + i * 32, col = col_base + j * 32;
-      float v[16];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) v[r] = tot[i][j][r];
-      if (EPI == SE_OUT) {
-        store_out_tile(o, s, b, row0, col, v);
-      } else if (EPI == SE_PLAIN) {
-        put16(g.c + cb, g.N, row0, col, v, mirror);
-      } else if (EPI == SE_MT) {
-        put16(g.c + cb, g.N, row0, col, v, mirror);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) v[r] = (row0 + 8 * (r >> 2) + (r & 3) == col ? 1.25f : 0.f) - 0.25f * v[r];
-        put16(g.c2 + cb, g.N, row0, col, v, mirror);
-      } else {  // SE_STAT
-        float* S = static_cast<float*>(stat.p[b]);
-        const int d = static_cast<int>(g.d);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = row0 + 8 * (r >> 2) + (r & 3);
-          float val = 0.f;
-          if (row < d && col < d) {
-            const int64_t at = static_cast<int64_t>(row) * d + col;
-            val = v[r];
-            if (g.beta != 0.f) val += g.beta * S[at];
-            S[at] = val;
-            if (mirror) S[static_cast<int64_t>(col) * d + row] = val;
-            if (row == col) val += g.eps;
-          }
-          v[r] = val;
-        }
-        put16(g.c + cb, g.N, row0, col, v, mirror);
-      }
-    }
-  }
-}
-
-template <int EPI, bool SYM>
-hipError_t launch_gemm(const ShGemm& g, int nb, const PtrTable& stat, const Shape& s, const OutSpec& o, hipStream_t st) {
-  const int64_t tm = g.M / SB, tn = g.N / SB;
-  const int64_t blocks = (SYM ? tm * (tm + 1) / 2 : tm * tn) * nb;
-  hipLaunchKernelGGL((k_sh_gemm<EPI, SYM>), dim3(static_cast<unsigned>(blocks)), dim3(NTH), 0, st, g, stat, s, o);
-  return hipGetLastError();
-}
-
-// G (bf16 or fp32, whole or tp column fragments) -> fp32 working copies in both orientations,
-// zero outside rows x cols.  One block per 64 x 64 tile; the transposed copy goes through LDS.
-__global__ __launch_bounds__(NTH) void k_sh_load(Shape s, PtrTable grad, int grad_dtype, int64_t rp, int64_t cp,
-                                                  float* __restrict__ gs, float* __restrict__ gt) {
-  __shared__ float tile[64][65];
-  const int b = blockIdx.z, r0 = blockIdx.y * 64, c0 = blockIdx.x * 64, t = threadIdx.x;
-  const int wf = static_cast<int>(s.wfrag);
-  float* gsb = gs + static_cast<int64_t>(b) * rp * cp;
-  float* gtb = gt + static_cast<int64_t>(b) * rp * cp;
-#pragma unroll
-  for (int e = 0; e < 16; ++e) {
-    const int idx = e * NTH + t, r = idx >> 6, c = idx & 63;
-    const int row = r0 + r, col = c0 + c;
-    float val = 0.f;
-    if (row < s.rows && col < s.cols) {
-      const int f = col / wf;
-      const int64_t at = static_cast<int64_t>(row) * wf + (col - f * wf);
-      val = grad_dtype == CANZ_DT_BF16 ? static_cast<float>(static_cast<const __bf16*>(grad.p[b * s.tp + f])[at])
-                                       : static_cast<const float*>(grad.p[b * s.tp + f])[at];
-    }
-    gsb[static_cast<int64_t>(row) * cp + col] = val;
-    tile[r][c] = val;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int e = 0; e < 16; ++e) {
-    const int idx = e * NTH + t, r = idx >> 6, c = idx & 63;  // r: column of G, c: row of G
-    gtb[static_cast<int64_t>(c0 + r) * rp + r0 + c] = tile[c][r];
-  }
-}
 
 // partial[b][p] = sum of squares of the elements p, p + NPART * NTH, ... (in blocks of NTH) of A[b]
 __global__ __launch_bounds__(NTH) void k_sh_sumsq(const float* __restrict__ a, int64_t elems, float* __restrict__ partial) {
@@ -403,7 +181,7 @@ int run_batch(const canz_shampoo_group& g, int first, int nb, const canz_shampoo
     float *tt = ws + c.t, *t2 = ws + c.t2, *t4 = ws + c.t4, *partial = ws + c.partial;
     ShGemm q{};
     q.M = dp, q.N = dp, q.K = kp, q.ldp = kp, q.ldq = kp, q.sp = dp * kp, q.sq = dp * kp;
-    q.P = side, q.Q = side, q.c = a, q.d = d, q.beta = hp.beta, q.eps = hp.eps;
+    q.P = side, q.Q = side, q.c = a, q.d = d, q.beta = hp.beta, q.gscale = 1.f, q.eps = hp.eps;
     CANZ_HIP(CANZ_KERNEL_SH_STAT, (launch_gemm<SE_STAT, true>(q, nb, stat, s, o, st)), "statistics kernel");
     prof_mark(st, CANZ_KERNEL_SH_INIT, true);
     hipLaunchKernelGGL(k_sh_sumsq, dim3(NPART, nb), dim3(NTH), 0, st, a, dd, partial);

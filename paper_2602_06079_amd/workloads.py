@@ -125,6 +125,37 @@ def gen_param(cfg: int, matrix_id: int, rows: int, cols: int, std: float = 0.02)
     return gen_normal_f32(cfg, matrix_id, 1, rows, cols, std)
 
 
+def gen_spd_f32(cfg: int, matrix_id: int, stream: int, d: int, level: float = 1.0, aspect: int = 2) -> np.ndarray:
+    """A symmetric positive definite d x d matrix as an optimizer's accumulated statistic would be:
+    level * H H^T / (aspect d) of a standard Gaussian d x (aspect d) factor (diagonal about `level`),
+    exactly symmetric in fp32.  Its condition number is about ((1 + a) / (1 - a))^2 with
+    a = aspect^-1/2 (34 at aspect 2)."""
+    h = _rng(cfg, matrix_id, stream).standard_normal((d, aspect * d))
+    s = (h @ h.T) * (level / (aspect * d))
+    s = (0.5 * (s + s.T)).astype(np.float32)
+    return np.ascontiguousarray(np.triu(s) + np.triu(s, 1).T)
+
+
+def gen_orthogonal_f32(cfg: int, matrix_id: int, stream: int, d: int) -> np.ndarray:
+    """A random orthogonal d x d matrix (orthonormal to fp32 rounding): the Q factor of a Gaussian matrix."""
+    q, _ = np.linalg.qr(_rng(cfg, matrix_id, stream).standard_normal((d, d)))
+    return np.ascontiguousarray(q.astype(np.float32))
+
+
+def gen_soap_state(cfg: int, matrix_id: int, rows: int, cols: int, std: float = 0.02, identity_bases: bool = False) -> dict:
+    """Seeded state of one matrix for a SOAP step that is under way: momentum and second moment of
+    the size the gradients of gen_grad give, full-rank statistics, orthogonal bases (fp32 arrays)."""
+    return {
+        "mom": gen_normal_f32(cfg, matrix_id, 11, rows, cols, std),
+        # an average of squared gradients over several steps: no mass near zero, unlike one squared sample
+        "var": np.mean(np.square(gen_normal_f32(cfg, matrix_id, 12, 4 * rows, cols, std)).reshape(4, rows, cols), axis=0),
+        "left": gen_spd_f32(cfg, matrix_id, 13, rows, std * std * cols),
+        "right": gen_spd_f32(cfg, matrix_id, 14, cols, std * std * rows),
+        "q_left": np.eye(rows, dtype=np.float32) if identity_bases else gen_orthogonal_f32(cfg, matrix_id, 15, rows),
+        "q_right": np.eye(cols, dtype=np.float32) if identity_bases else gen_orthogonal_f32(cfg, matrix_id, 16, cols),
+    }
+
+
 def split_columns(x: np.ndarray, tp: int):
     """Column fragments (contiguous copies) of a rows x cols array."""
     rows, cols = x.shape

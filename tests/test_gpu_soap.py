@@ -1,0 +1,347 @@
+"""GPU parity of canz_soap_step against the fp64 oracle (oracle/soap.py), through the C ABI.
+
+What is compared, per matrix, on the same seeded inputs (the oracle gets the fp32 state and the
+bf16 / fp32 gradients widened exactly):
+  momentum M, second moment V, statistics L and R   relative Frobenius error;
+  the update (parameters in place, or Delta W)        relative Frobenius error of the step taken;
+  a refreshed basis Q                                 what is unique and what must hold: Q^T Q = I,
+      Q^T (S Q_old) upper triangular, and column by column equality with the oracle's Q up to the
+      column's sign where the QR factor is well conditioned (the columns of a QR factor are fixed
+      up to sign only for a full-rank matrix, and their sensitivity grows with its condition).
+
+Tolerances.  M: 1e-6 (one fused multiply-add per element).  L, R: 1e-5, V: 5e-6 (fp32 products of
+up to 4096 terms, squared for V; measured 1e-7).  Update: 2e-5 (measured 1e-7 to 1.4e-6 with a second
+moment that has history, 8e-6 on a first step).  A first step from V = 0 is N' = m / (|g'| sqrt(c) + eps),
+i.e. the sign of g' for eps -> 0, so an element whose rotated gradient is below the fp32 rounding of the
+rotation (about 1e-6 of the typical size) could flip: the first-step test uses eps = 1e-3 of the gradient
+scale, which bounds the slope of N' in g'.  For the same reason the seeded second moment is an average of
+several squared samples, as a real one is, not one squared sample (whose density piles up at zero).
+Refreshed basis against the oracle's: 1e-4 max-abs per column at condition number 30 to 100 of the
+statistic (measured 3e-7 to 5e-7; 2e-5 on the rank-deficient case, tolerance 1e-3 there);
+orthonormality 5e-6 max-abs (measured 6e-7); triangular remainder below 5e-6 of the largest entry
+(measured 2.5e-7)."""
+import numpy as np
+import pytest
+
+from oracle import soap as SO
+from paper_2602_06079_amd import workloads as W
+from tests.gpu_harness import log, rel_fro, to_device, to_host64, widen
+
+pytestmark = pytest.mark.gpu
+
+TOL_MOM, TOL_STAT, TOL_VAR, TOL_UPDATE = 1e-6, 1e-5, 5e-6, 2e-5
+TOL_ORTH, TOL_TRI, TOL_Q = 5e-6, 5e-6, 1e-4
+STATE_KEYS = ("mom", "var", "left", "right", "q_left", "q_right")
+
+
+def oracle_hparams(hp) -> SO.Hparams:
+    f = lambda v: float(np.float32(v))
+    return SO.Hparams(beta1=f(hp.beta1), beta2=f(hp.beta2), lr=f(hp.lr), weight_decay=f(hp.weight_decay), eps=f(hp.eps),
+                      bias_correction=bool(hp.bias_correction), max_precond_dim=int(hp.max_precond_dim))
+
+
+class SoapDevice:
+    """One micro-group on the device.  grads: per matrix a host array or a list of tp fragments;
+    states: per matrix a dict of fp32 host arrays (STATE_KEYS); outs: parameter arrays, or None
+    for Delta W fragments."""
+
+    def __init__(self, canz, rows, cols, grads, states, outs=None, tp=1, out_np_dtype=np.float32, max_precond_dim=10000):
+        import torch
+        self.canz, self.rows, self.cols, self.tp, self.n = canz, rows, cols, tp, len(states)
+        self.use_left, self.use_right = rows <= max_precond_dim, cols <= max_precond_dim
+        self.t = {k: [to_device(st[k]) for st in states] for k in STATE_KEYS}
+        if not self.use_left:
+            self.t["left"], self.t["q_left"] = [], []
+        if not self.use_right:
+            self.t["right"], self.t["q_right"] = [], []
+        self.set_grads(grads)
+        self.delta = outs is None
+        if self.delta:
+            proto = np.zeros((rows, cols // tp), dtype=out_np_dtype)
+            self.out_dtype = W.DT_BF16 if proto.dtype == np.uint16 else W.DT_F32
+            self.out_t = [to_device(proto) for _ in range(self.n * tp)]
+        else:
+            self.out_dtype = W.DT_BF16 if outs[0].dtype == np.uint16 else W.DT_F32
+            self.out_t = [to_device(p) for p in outs]
+        torch.cuda.synchronize()
+
+    def set_grads(self, grads):
+        first = grads[0][0] if isinstance(grads[0], (list, tuple)) else grads[0]
+        self.grad_dtype = W.DT_BF16 if first.dtype == np.uint16 else W.DT_F32
+        self.grad_t = []
+        for g in grads:
+            frags = g if isinstance(g, (list, tuple)) else [g]
+            assert len(frags) == self.tp
+            self.grad_t += [to_device(f) for f in frags]
+
+    def group(self):
+        return self.canz.SoapGroup(rows=self.rows, cols=self.cols, grad=self.grad_t, mom=self.t["mom"], var=self.t["var"],
+                                   left=self.t["left"], right=self.t["right"], qleft=self.t["q_left"],
+                                   qright=self.t["q_right"], out=self.out_t, tp=self.tp, grad_dtype=self.grad_dtype,
+                                   out_dtype=self.out_dtype)
+
+    def out_host(self, i):
+        if not self.delta:
+            return to_host64(self.out_t[i])
+        return np.concatenate([to_host64(self.out_t[i * self.tp + f]) for f in range(self.tp)], axis=1)
+
+    def state_host(self, key, i):
+        return to_host64(self.t[key][i])
+
+
+def run(canz, devs, hp):
+    import torch
+    groups = [d.group() for d in devs]
+    nbytes = canz.canz_soap_workspace_bytes(groups, hp)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)                                   # the workspace is scratch: NaN patterns must not leak
+    canz.canz_soap_step(groups, hp, ws, nbytes, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+
+
+def widen_state(st):
+    return {k: widen(v) for k, v in st.items()}
+
+
+def widen_grad(g):
+    return [widen(f) for f in g] if isinstance(g, (list, tuple)) else widen(g)
+
+
+def check_basis(got, ref, stat_new, q_old, label, unique_cols=None, tol_q=TOL_Q):
+    """got: the device's refreshed basis; ref: the oracle's; stat_new, q_old: the oracle's new statistic and
+    the basis before the step.  unique_cols: how many leading columns the QR factor fixes (all by default)."""
+    d = got.shape[0]
+    assert np.isfinite(got).all(), label
+    orth = np.abs(got.T @ got - np.eye(d)).max()
+    assert orth <= TOL_ORTH, "%s: Q^T Q - I = %.3g" % (label, orth)
+    s = stat_new @ q_old
+    rem = got.T @ s
+    k = d if unique_cols is None else unique_cols
+    tri = np.abs(np.tril(rem, -1)[:, :k]).max() / np.abs(rem).max()
+    assert tri <= TOL_TRI, "%s: lower part of Q^T (S Q_old) = %.3g of the largest entry" % (label, tri)
+    signs = np.sign(np.sum(got[:, :k] * ref[:, :k], axis=0))
+    diff = np.abs(got[:, :k] * signs - ref[:, :k]).max() if k else 0.0
+    assert diff <= tol_q, "%s: basis differs from the oracle's by %.3g" % (label, diff)
+    return orth, tri, diff
+
+
+def check(dev, grads, states, params, hp, label, tol_update=TOL_UPDATE, basis_kw=None):
+    """Compares the device's state and output after one step with the oracle's step from `states`.
+    Returns the oracle's results (for trajectories)."""
+    ohp = oracle_hparams(hp)
+    worst = {"update": 0.0, "var": 0.0, "orth": 0.0, "tri": 0.0, "q": 0.0}
+    refs = []
+    for i in range(dev.n):
+        ref = SO.soap_step(widen_grad(grads[i]), widen_state(states[i]), ohp, int(hp.step), bool(hp.refresh),
+                           param=None if params is None else widen(params[i]))
+        refs.append(ref)
+        assert rel_fro(dev.state_host("mom", i), ref["mom"]) <= TOL_MOM, "%s: M of matrix %d" % (label, i)
+        ev = rel_fro(dev.state_host("var", i), ref["var"])
+        worst["var"] = max(worst["var"], ev)
+        assert ev <= TOL_VAR, "%s: V of matrix %d: %.3g" % (label, i, ev)
+        for side, stat_key, q_key in ((dev.use_left, "left", "q_left"), (dev.use_right, "right", "q_right")):
+            if not side:
+                continue
+            got_s = dev.state_host(stat_key, i)
+            assert rel_fro(got_s, ref[stat_key]) <= TOL_STAT, "%s: %s of matrix %d" % (label, stat_key, i)
+            assert np.array_equal(got_s, got_s.T), "%s: statistic not symmetric" % label
+            got_q = dev.state_host(q_key, i)
+            if hp.refresh:
+                orth, tri, diff = check_basis(got_q, ref[q_key], ref[stat_key], widen(states[i][q_key]),
+                                              "%s: %s of matrix %d" % (label, q_key, i), **(basis_kw or {}).get(q_key, {}))
+                worst["orth"], worst["tri"], worst["q"] = max(worst["orth"], orth), max(worst["tri"], tri), max(worst["q"], diff)
+            else:
+                assert np.array_equal(got_q, widen(states[i][q_key])), "%s: basis changed without a refresh" % label
+        got = dev.out_host(i)
+        assert np.isfinite(got).all()
+        want = ref["delta"] if params is None else ref["param"]
+        den = np.linalg.norm(ref["delta"])
+        err = np.linalg.norm(got - want) / den if den > 0 else np.linalg.norm(got - want)
+        worst["update"] = max(worst["update"], err)
+        assert err <= tol_update, "%s: matrix %d update error %.3g" % (label, i, err)
+    log("%s: worst update %.3g (tol %.2g), V %.3g%s" % (
+        label, worst["update"], tol_update, worst["var"],
+        ", basis: orth %.3g tri %.3g vs oracle %.3g" % (worst["orth"], worst["tri"], worst["q"]) if hp.refresh else ""))
+    return refs
+
+
+RAGGED = [(300, 77), (77, 300), (200, 333), (256, 256), (130, 1), (1, 9), (520, 1032)]
+
+
+@pytest.mark.parametrize("shape", RAGGED, ids=lambda s: "%dx%d" % s)
+def test_ragged_shapes_one_step(canz, shape):
+    """Shapes that do not fill the 128-wide tiles, tall and wide; bf16 gradients, fp32 parameters in place
+    with weight decay, random orthogonal bases, a state with history."""
+    rows, cols = shape
+    n = 3
+    grads = [W.gen_grad(60, i, rows, cols)[0] for i in range(n)]
+    states = [W.gen_soap_state(60, i, rows, cols) for i in range(n)]
+    params = [W.gen_param(60, i, rows, cols) for i in range(n)]
+    hp = canz.SoapHparams(lr=0.01, weight_decay=0.1, eps=1e-8, step=7)
+    dev = SoapDevice(canz, rows, cols, grads, states, outs=params)
+    run(canz, [dev], hp)
+    check(dev, grads, states, params, hp, "soap ragged %dx%d" % shape)
+
+
+@pytest.mark.parametrize("shape", [(300, 77), (77, 300), (256, 256), (520, 1032), (33, 160)], ids=lambda s: "%dx%d" % s)
+def test_refresh_on_ragged_shapes(canz, shape):
+    """A refresh step: extents that are no multiple of the 32-wide panels or the 128-wide tiles."""
+    rows, cols = shape
+    n = 2
+    grads = [W.gen_grad(61, i, rows, cols)[0] for i in range(n)]
+    states = [W.gen_soap_state(61, i, rows, cols) for i in range(n)]
+    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=10, refresh=True, out_mode=canz.OUT_DELTA)
+    dev = SoapDevice(canz, rows, cols, grads, states)
+    run(canz, [dev], hp)
+    check(dev, grads, states, None, hp, "soap refresh %dx%d" % shape)
+
+
+def test_first_step_from_empty_state_is_adam_in_the_given_bases(canz):
+    """t = 1, M = V = 0, identity bases and random bases; eps at 1e-3 of the gradient scale (see the module text)."""
+    rows, cols, n = 200, 136, 2
+    for identity in (True, False):
+        grads = [W.gen_grad(62, i, rows, cols)[0] for i in range(n)]
+        states = [W.gen_soap_state(62, i, rows, cols, identity_bases=identity) for i in range(n)]
+        for st in states:
+            st["mom"][:] = 0
+            st["var"][:] = 0
+            st["left"][:] = 0
+            st["right"][:] = 0
+        hp = canz.SoapHparams(lr=0.01, eps=2e-5, step=1, out_mode=canz.OUT_DELTA)
+        dev = SoapDevice(canz, rows, cols, grads, states)
+        run(canz, [dev], hp)
+        check(dev, grads, states, None, hp, "soap first step, %s bases" % ("identity" if identity else "random"))
+
+
+def test_trajectory_with_refreshes(canz):
+    """Six steps, refresh on every second one; the oracle carries its own state and, after a refresh, takes the
+    device's bases (they agree to TOL_Q up to column signs; the comparison of the following steps is then on the
+    same bases instead of on two bases that differ by rounding)."""
+    rows, cols, n = 160, 288, 2
+    states = [W.gen_soap_state(63, i, rows, cols) for i in range(n)]
+    params = [W.gen_param(63, i, rows, cols) for i in range(n)]
+    grads = [W.gen_grad(63, i, rows, cols, step=0)[0] for i in range(n)]
+    dev = SoapDevice(canz, rows, cols, grads, states, outs=params)
+    for step in range(1, 7):
+        if step > 1:
+            grads = [W.gen_grad(63, i, rows, cols, step=step - 1)[0] for i in range(n)]
+            dev.set_grads(grads)
+        hp = canz.SoapHparams(lr=0.02, weight_decay=0.01, eps=1e-8, beta1=0.9, beta2=0.95, step=step + 4, refresh=step % 2 == 0)
+        run(canz, [dev], hp)
+        check(dev, grads, states, params, hp, "soap trajectory step %d" % step)
+        # next step starts from what the device holds (fp32), on both sides
+        states = [{k: dev.t[k][i].cpu().numpy() for k in STATE_KEYS} for i in range(n)]
+        params = [dev.out_t[i].cpu().numpy() for i in range(n)]
+
+
+def test_tp_fragments_fp32_gradients_bf16_delta(canz):
+    rows, cols, tp, n = 136, 256, 4, 3
+    grads = [W.split_columns(W.gen_grad(64, i, rows, cols, dtype=W.DT_F32)[0], tp) for i in range(n)]
+    states = [W.gen_soap_state(64, i, rows, cols) for i in range(n)]
+    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=3, refresh=True, out_mode=canz.OUT_DELTA)
+    dev = SoapDevice(canz, rows, cols, grads, states, tp=tp, out_np_dtype=np.uint16)
+    run(canz, [dev], hp)
+    check(dev, grads, states, None, hp, "soap tp=4 bf16 delta", tol_update=2 ** -8)     # bf16 storage of Delta W
+
+
+@pytest.mark.parametrize("shape,limit", [((300, 100), 128), ((100, 300), 128), ((300, 100), 100), ((100, 300), 100)],
+                         ids=lambda v: str(v).replace(" ", ""))
+def test_one_sided_above_the_limit(canz, shape, limit):
+    """The side longer than max_precond_dim has no statistic and no basis: its tables are not passed at all."""
+    rows, cols = shape
+    n = 2
+    grads = [W.gen_grad(65, i, rows, cols)[0] for i in range(n)]
+    states = [W.gen_soap_state(65, i, rows, cols) for i in range(n)]
+    params = [W.gen_param(65, i, rows, cols) for i in range(n)]
+    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=5, refresh=True, max_precond_dim=limit)
+    dev = SoapDevice(canz, rows, cols, grads, states, outs=params, max_precond_dim=limit)
+    assert dev.use_left != dev.use_right
+    run(canz, [dev], hp)
+    check(dev, grads, states, params, hp, "soap one-sided %dx%d limit %d" % (rows, cols, limit))
+
+
+def test_rank_deficient_refresh(canz):
+    """From empty statistics a 96 x 40 gradient gives L = c G G^T of rank 40: the first 40 columns of the QR factor
+    of L Q are fixed, the other 56 are some orthonormal completion (checked as such, not against the oracle)."""
+    rows, cols, n = 96, 40, 2
+    grads = [W.gen_grad(66, i, rows, cols)[0] for i in range(n)]
+    states = [W.gen_soap_state(66, i, rows, cols) for i in range(n)]
+    for st in states:
+        st["left"][:] = 0
+        st["right"][:] = 0
+    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=2, refresh=True, out_mode=canz.OUT_DELTA)
+    dev = SoapDevice(canz, rows, cols, grads, states)
+    run(canz, [dev], hp)
+    # G G^T of a Gaussian 96 x 40 matrix: condition number of the rank-40 part about 20; its QR columns 30 .. 39
+    # are the sensitive ones
+    check(dev, grads, states, None, hp, "soap rank-deficient", basis_kw={"q_left": {"unique_cols": cols, "tol_q": 1e-3}})
+
+
+def test_two_groups_in_one_call_and_batches_are_independent(canz):
+    """Two shape classes in one call; each matrix's results are bit-identical to a call with that matrix alone."""
+    import torch
+    shapes = [(200, 136), (72, 264)]
+    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=4, refresh=True, out_mode=canz.OUT_DELTA)
+    devs, alone = [], []
+    for gi, (rows, cols) in enumerate(shapes):
+        grads = [W.gen_grad(67, 10 * gi + i, rows, cols)[0] for i in range(3)]
+        states = [W.gen_soap_state(67, 10 * gi + i, rows, cols) for i in range(3)]
+        devs.append((SoapDevice(canz, rows, cols, grads, states), grads, states))
+        alone.append(SoapDevice(canz, rows, cols, grads[1:2], states[1:2]))
+    run(canz, [d for d, _, _ in devs], hp)
+    for d, grads, states in devs:
+        check(d, grads, states, None, hp, "soap two groups %dx%d" % (d.rows, d.cols))
+    for (d, _, _), a in zip(devs, alone):
+        run(canz, [a], hp)
+        for key in STATE_KEYS:
+            assert torch.equal(d.t[key][1], a.t[key][0]), "%s differs between the batch and the matrix alone" % key
+        assert torch.equal(d.out_t[1], a.out_t[0])
+
+
+def test_config2_shape_with_refresh(canz):
+    """Four 2048 x 1024 matrices (the 0.6B-shaped share's shape): state and update of every matrix against the oracle,
+    refreshed bases of the first one against the oracle's QR, properties on all."""
+    rows, cols, n = 2048, 1024, 4
+    grads = [W.gen_grad(2, i, rows, cols)[0] for i in range(n)]
+    states = [W.gen_soap_state(2, i, rows, cols) for i in range(n)]
+    hp = canz.SoapHparams(lr=0.003, eps=1e-8, step=10, refresh=True, out_mode=canz.OUT_DELTA)
+    dev = SoapDevice(canz, rows, cols, grads, states)
+    run(canz, [dev], hp)
+    check(dev, grads, states, None, hp, "soap 2048x1024")
+
+
+def test_step_under_graph_capture_replays(canz):
+    """A step without refresh captured in a HIP graph: three replays with eager work in between, each compared
+    with the eager result of the same step from the same state."""
+    import torch
+    rows, cols, n = 200, 136, 2
+    grads = [W.gen_grad(68, i, rows, cols)[0] for i in range(n)]
+    states = [W.gen_soap_state(68, i, rows, cols) for i in range(n)]
+    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=3, out_mode=canz.OUT_DELTA)
+    eager = SoapDevice(canz, rows, cols, grads, states)
+    run(canz, [eager], hp)
+    dev = SoapDevice(canz, rows, cols, grads, states)
+    groups = [dev.group()]
+    nbytes = canz.canz_soap_workspace_bytes(groups, hp)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    saved = {k: [t.clone() for t in dev.t[k]] for k in ("mom", "var", "left", "right")}
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            canz.canz_soap_step(groups, hp, ws, nbytes, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for k, ts in saved.items():
+            for dst, src in zip(dev.t[k], ts):
+                dst.copy_(src)
+        for o in dev.out_t:
+            o.zero_()
+        ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i in range(n):
+            assert torch.equal(dev.out_t[i], eager.out_t[i]), "replay %d: Delta W differs from the eager step" % replay
+            for k in saved:
+                assert torch.equal(dev.t[k][i], eager.t[k][i]), "replay %d: %s differs" % (replay, k)
