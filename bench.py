@@ -269,16 +269,180 @@ def main_shampoo(args, canz, W, np, torch):
     print(json.dumps(out))
 
 
+def main_soap(args, canz, W, np, torch):
+    """One rank's SOAP step (canz_soap_step): Algorithm 1 with W(p) = SOAP FLOPs (App. D.5) on the set of
+    --config, alpha = 1, the most loaded rank's share.  Steps t = 1, 2, ... with a basis refresh on every
+    --refresh-every-th one; with the defaults (3 warm-up + 10 timed steps, refresh every 10th) the timed
+    region holds nine plain steps and one refresh step, one whole refresh period."""
+    cfg = 2 if args.config is None else args.config
+    s = W.matrix_set(cfg)
+    R = s["n_ranks"]
+    t0 = time.perf_counter()
+    cuts, owner, load = canz.canz_partition_alpha(s["rows"], s["cols"], s["bucket_off"], R, 1.0,
+                                                  cost_kind=canz.COST_SOAP_FLOPS)
+    rank = int(np.argmax(load))
+    groups = canz.canz_microgroup_plan(s["rows"], s["cols"], s["dtype"], owner, rank, max_mats=8)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    mean = float(load.sum()) / len(load)
+    n_share = sum(len(g) for g in groups)
+    log("soap on config %d (%s): rank %d owns %d matrices in %d groups; planner %.2f ms, R_LB(FLOPs) %.3f" %
+        (cfg, s["name"], rank, n_share, len(groups), plan_ms, float(load.max()) / mean))
+    f = args.refresh_every
+    limit = args.max_precond_dim
+
+    def hparams(t):
+        return canz.SoapHparams(beta1=0.95, beta2=0.95, lr=3e-3, eps=1e-8, step=t, refresh=(t % f == 0), max_precond_dim=limit)
+
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(W.SEED_BASE + cfg)
+    dgroups, keep = [], []
+    for g in groups:
+        rows, cols = s["rows"][g[0]], s["cols"][g[0]]
+        use_l, use_r = rows <= limit, cols <= limit
+        grads = [(torch.randn(rows, cols, device="cuda", generator=gen) * s["grad_std"]).to(torch.bfloat16) for _ in g]
+        moms = [torch.zeros(rows, cols, device="cuda") for _ in g]
+        vars_ = [torch.zeros(rows, cols, device="cuda") for _ in g]
+        lefts = [torch.zeros(rows, rows, device="cuda") for _ in g] if use_l else []
+        rights = [torch.zeros(cols, cols, device="cuda") for _ in g] if use_r else []
+        qls = [torch.eye(rows, device="cuda") for _ in g] if use_l else []
+        qrs = [torch.eye(cols, device="cuda") for _ in g] if use_r else []
+        outs = [torch.randn(rows, cols, device="cuda", generator=gen) * 0.02 for _ in g]
+        keep.append((grads, moms, vars_, lefts, rights, qls, qrs, outs))
+        dgroups.append(canz.SoapGroup(rows=rows, cols=cols, grad=grads, mom=moms, var=vars_, left=lefts, right=rights,
+                                      qleft=qls, qright=qrs, out=outs, grad_dtype=canz.DT_BF16, out_dtype=canz.DT_F32))
+    ws_bytes = max(canz.canz_soap_workspace_bytes(dgroups, hparams(1)), canz.canz_soap_workspace_bytes(dgroups, hparams(f)))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    t_now = [0]
+
+    def step():
+        t_now[0] += 1
+        canz.canz_soap_step(dgroups, hparams(t_now[0]), ws, ws_bytes, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # launches of a refresh step: per side and panel of 32 columns 4 + 3, plus a few dozen per batch
+    max_d = max(max(s["rows"][g[0]], s["cols"][g[0]]) for g in groups)
+    per_refresh = len(groups) * 8 * (2 * (7 * (max_d // 32 + 1) + 8) + 16)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t_start) * 1e3 / args.steps
+    n_refresh_timed = sum(1 for t in range(args.warmup + 1, args.warmup + args.steps + 1) if t % f == 0)
+    log("timed %d steps (%d with a refresh): %.3f ms/step" % (args.steps, n_refresh_timed, ms_per_step))
+    # the per-kernel breakdown comes from a second pass of the same length outside the timed region: a refresh
+    # issues thousands of short launches, and a pair of events around each would weigh on the timed figure
+    canz.canz_profile_enable(per_refresh * (args.steps // f + 2) + 64 * args.steps * len(groups))
+    first_profiled = t_now[0] + 1
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = canz.canz_profile_collect()
+    canz.canz_profile_disable()
+    n_refresh = sum(1 for t in range(first_profiled, first_profiled + args.steps) if t % f == 0)
+
+    def pad(x):
+        return (x + 127) // 128 * 128
+
+    def sym(d, k):
+        return d * (d + 1) * k, (pad(d) // 128) * (pad(d) // 128 + 1) // 2 * 128 * 128 * 2 * pad(k)
+
+    alg = dict(soap_rotate=0.0, soap_stat=0.0, soap_qr=0.0)
+    iss = dict(soap_rotate=0.0, soap_stat=0.0)
+    for g in groups:
+        r, c = s["rows"][g[0]], s["cols"][g[0]]
+        n = len(g)
+        use_l, use_r = r <= limit, c <= limit
+        per_rot = (2.0 * r * r * c if use_l else 0.0) + (2.0 * r * c * c if use_r else 0.0)
+        per_rot_iss = (2.0 * pad(r) * pad(r) * pad(c) if use_l else 0.0) + (2.0 * pad(r) * pad(c) * pad(c) if use_r else 0.0)
+        alg["soap_rotate"] += 3 * n * per_rot * args.steps          # G and M in, the direction back
+        iss["soap_rotate"] += 3 * n * per_rot_iss * args.steps
+        for d, k, used in ((r, c, use_l), (c, r, use_r)):
+            if used:
+                a, i = sym(d, k)
+                alg["soap_stat"] += n * a * args.steps
+                iss["soap_stat"] += n * i * args.steps
+                alg["soap_qr"] += n * (2.0 + 4.0 / 3.0 + 4.0 / 3.0) * d ** 3 * n_refresh
+    kernels = {}
+    for k, (ms, n) in prof.items():
+        if n:
+            kernels[k] = dict(ms_per_step=ms / args.steps, launches_per_step=n / args.steps, avg_ms=ms / n)
+            if k in alg and alg[k] > 0:
+                kernels[k]["tflops_algorithmic"] = alg[k] / (ms * 1e-3) / 1e12
+            if k in iss and iss[k] > 0:
+                kernels[k]["tflops_issued"] = iss[k] / (ms * 1e-3) / 1e12
+    refresh_ms = sum(kernels[k]["ms_per_step"] * args.steps for k in ("soap_qr", "soap_panel") if k in kernels) / max(n_refresh, 1)
+    plain_ms = sum(v["ms_per_step"] for k, v in kernels.items() if k not in ("soap_qr", "soap_panel"))
+    dom = "soap_rotate"
+    peak = 157.3
+    launches = kernels[dom]["launches_per_step"] * args.steps
+    per_launch = alg[dom] / launches
+    achieved = per_launch / (kernels[dom]["avg_ms"] * 1e-3) / 1e12
+    issued = iss[dom] / launches / (kernels[dom]["avg_ms"] * 1e-3) / 1e12
+    roofline = dict(bound="mfma", kernel="k_sh_gemm (%s)" % dom, achieved=achieved, peak=peak, unit="TFLOP/s",
+                    frac=achieved / peak, traffic=None, achieved_issued=issued, frac_issued=issued / peak,
+                    flops_per_launch=per_launch, avg_launch_ms=kernels[dom]["avg_ms"])
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import soap as OS
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [os.cpu_count()])
+        except Exception:
+            cores = os.cpu_count()
+        g0 = groups[0]
+        rows, cols = s["rows"][g0[0]], s["cols"][g0[0]]
+        st = {k: v.astype(np.float64) for k, v in W.gen_soap_state(cfg, g0[0], rows, cols, identity_bases=True).items()}
+        g64 = keep[0][0][0].float().cpu().numpy().astype(np.float64)
+        ohp = OS.Hparams(max_precond_dim=limit)
+        t0 = time.perf_counter()
+        OS.soap_step(g64, st, ohp, 5, False, param=np.zeros((rows, cols)))
+        t_plain = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        OS.soap_step(g64, st, ohp, 10, True, param=np.zeros((rows, cols)))
+        t_fresh = time.perf_counter() - t0
+        per_step = (t_plain * (args.steps - n_refresh_timed) + t_fresh * n_refresh_timed) / args.steps
+        cost = lambda r, c: r * c * (r + c)
+        est_s = sum(len(g) * per_step * cost(s["rows"][g[0]], s["cols"][g[0]]) / cost(rows, cols) for g in groups)
+        cpu = dict(value=est_s * 1e3, unit="ms", cores=int(cores), kind="oracle",
+                   sample="fp64 oracle, matrix %d (%dx%d): one plain step %.2f s and one refresh step %.2f s, weighted as in "
+                          "the timed region and scaled by rows cols (rows + cols) to the %d-matrix share" %
+                          (g0[0], rows, cols, t_plain, t_fresh, n_share))
+    total_alg = sum(alg.values())
+    out = {
+        "metric": "optimizer_step_latency_ms", "value": ms_per_step, "unit": "ms",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic", "launch": "eager",
+        "config": {"workload": "soap step, config %d %s partitioned by SOAP FLOPs: rank %d of %d (alpha=1), %d matrices %s in %d "
+                               "micro-groups, basis refresh every %d steps (%d of the %d timed steps), max_precond_dim %d" %
+                               (cfg, s["name"], rank, R, n_share, sorted({(s["rows"][p], s["cols"][p]) for g in groups for p in g}),
+                                len(groups), f, n_refresh_timed, args.steps, limit),
+                   "elements": sum(s["rows"][p] * s["cols"][p] for g in groups for p in g)},
+        "plain_step_ms": plain_ms, "refresh_ms": refresh_ms,
+        "tflops_algorithmic": total_alg / (ms_per_step * args.steps * 1e-3) / 1e12,
+        "planner": dict(rank=rank, n_ranks=R, alpha=1.0, cost="soap_flops", r_lb_flops=float(load.max()) / mean, planner_ms=plan_ms),
+        "kernels": kernels, "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=None, help="benchmark configuration 1..5 (default 4: Qwen3-32B share; "
-                                                             "2 with --optimizer shampoo)")
-    ap.add_argument("--optimizer", choices=["muon", "shampoo"], default="muon",
-                    help="muon (default): canz_muon_step on the share of --config; shampoo: canz_shampoo_step on the "
-                         "share Algorithm 1 assigns under the Shampoo FLOPs cost (default set: config 2, the 0.6B shapes)")
+                                                             "2 with --optimizer shampoo or soap)")
+    ap.add_argument("--optimizer", choices=["muon", "shampoo", "soap"], default="muon",
+                    help="muon (default): canz_muon_step on the share of --config; shampoo / soap: canz_shampoo_step / "
+                         "canz_soap_step on the share Algorithm 1 assigns under that operator's FLOPs cost (default set: "
+                         "config 2, the 0.6B shapes)")
+    ap.add_argument("--refresh-every", type=int, default=10, help="soap: basis refresh on every n-th step")
+    ap.add_argument("--max-precond-dim", type=int, default=10000, help="soap: a longer side keeps no basis")
     ap.add_argument("--precision", choices=["bf16", "f32"], default="bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tp-schedule", type=int, default=0, metavar="MB",
@@ -308,6 +472,8 @@ def main():
     torch.cuda.set_device(0)
     if args.optimizer == "shampoo":
         return main_shampoo(args, canz, W, np, torch)
+    if args.optimizer == "soap":
+        return main_soap(args, canz, W, np, torch)
     cfg = 4 if args.config is None else args.config
     if args.tp_schedule:
         assert cfg == 5, "--tp-schedule applies to the TP configuration (5)"

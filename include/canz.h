@@ -39,7 +39,7 @@ enum {
   CANZ_EUNSUPPORTED = -5  /* unknown enum value                                     */
 };
 
-enum { CANZ_COST_NUMEL = 0, CANZ_COST_NS_FLOPS = 1, CANZ_COST_SHAMPOO_FLOPS = 2 };
+enum { CANZ_COST_NUMEL = 0, CANZ_COST_NS_FLOPS = 1, CANZ_COST_SHAMPOO_FLOPS = 2, CANZ_COST_SOAP_FLOPS = 3 };
 enum { CANZ_DT_F32 = 0, CANZ_DT_BF16 = 1 };
 enum { CANZ_SCALE_NONE = 0, CANZ_SCALE_ASPECT = 1, CANZ_SCALE_RMS = 2 };
 enum { CANZ_PREC_BF16 = 0, CANZ_PREC_F32 = 1 };
@@ -68,7 +68,10 @@ const char* canz_version(void);
  *                          CANZ_COST_NS_FLOPS 5*(4 m^2 n + 2 m^3), m = min, n = max,
  *                          CANZ_COST_SHAMPOO_FLOPS the FLOPs of canz_shampoo_step at its default
  *                          25 root iterations, (4 r c (r + c) + 200 (r^3 + c^3)) / 2^20 rounded
- *                          down (the cost follows the operator, App. D.5)
+ *                          down (the cost follows the operator, App. D.5),
+ *                          CANZ_COST_SOAP_FLOPS the FLOPs of canz_soap_step with a refresh every 10th
+ *                          step, ((120 r c (r + c) + 7 (r^3 + c^3)) / 15) / 2^20, both divisions
+ *                          rounded down
  *   bucket_off   [n_buckets+1] non-decreasing, bucket_off[0] = 0, last = n_mats
  *   alpha        blend factor in [0, 1]: 1 = fill deficits, 0 = even split per bucket
  *   cut_out      [n_buckets*(n_ranks+1)] cut vectors s_i in the original bucket order:

@@ -25,6 +25,7 @@ from fractions import Fraction
 COST_NUMEL = 0      # W(p) = numel(p), the paper's default (Sec. 3.2)
 COST_NS_FLOPS = 1   # W(p) = FLOPs of the Newton-Schulz chain (App. D.5 ablation)
 COST_SHAMPOO_FLOPS = 2  # W(p) = FLOPs of a Shampoo step in units of 2^20 (App. D.5: cost follows the operator)
+COST_SOAP_FLOPS = 3     # W(p) = FLOPs of a SOAP step, refresh every 10th step, in units of 2^20
 
 
 def ns_flops(rows: int, cols: int, ns_steps: int = 5) -> int:
@@ -49,8 +50,20 @@ def shampoo_flops(rows: int, cols: int, root_iters: int = 25) -> int:
     return 4 * r * r * c + 4 * c * c * r + 8 * root_iters * (r ** 3 + c ** 3)
 
 
+def soap_flops(rows: int, cols: int, refresh_every: int = 10) -> int:
+    """FLOPs of one SOAP step on a rows x cols matrix, averaged over a refresh period: per step the
+    rotation of G and of M into the bases, the rotation of the direction back and the two statistics,
+    four times 2 r^2 c + 2 r c^2; per refresh and side of extent d the product S Q (2 d^3), the
+    Householder QR (4/3 d^3) and the accumulation of its orthogonal factor (4/3 d^3).  Rounded down.
+    """
+    r, c = int(rows), int(cols)
+    return (3 * refresh_every * 8 * r * c * (r + c) + 14 * (r ** 3 + c ** 3)) // (3 * refresh_every)
+
+
 def param_cost(rows, cols, cost_kind: int = COST_NUMEL, ns_steps: int = 5):
     """W(p) for every parameter, as Python ints."""
+    if cost_kind == COST_SOAP_FLOPS:
+        return [soap_flops(int(r), int(c)) >> 20 for r, c in zip(rows, cols)]
     if cost_kind == COST_SHAMPOO_FLOPS:
         # in units of 2^20 FLOPs, rounded down, so that the loads of a large model stay exact in fp64
         return [shampoo_flops(int(r), int(c)) >> 20 for r, c in zip(rows, cols)]

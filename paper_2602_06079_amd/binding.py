@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcanz.so")
 
 OK, EINVAL, ESHAPE, EWORKSPACE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5
-COST_NUMEL, COST_NS_FLOPS, COST_SHAMPOO_FLOPS = 0, 1, 2
+COST_NUMEL, COST_NS_FLOPS, COST_SHAMPOO_FLOPS, COST_SOAP_FLOPS = 0, 1, 2, 3
 DT_F32, DT_BF16 = 0, 1
 SCALE_NONE, SCALE_ASPECT, SCALE_RMS = 0, 1, 2
 PREC_BF16, PREC_F32 = 0, 1

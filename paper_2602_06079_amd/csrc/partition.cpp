@@ -24,6 +24,11 @@ int64_t checked_cost(int64_t rows, int64_t cols, int cost_kind) {
     w = m * n;
   } else if (cost_kind == CANZ_COST_NS_FLOPS) {
     w = 5 * (4 * m * m * n + 2 * m * m * m);
+  } else if (cost_kind == CANZ_COST_SOAP_FLOPS) {
+    // SOAP step: rotations of G and M into the bases, the rotation back and the statistics, 8 r c (r + c);
+    // a refresh every 10th step (product 2 d^3, QR 4/3 d^3, accumulation of Q 4/3 d^3 per side):
+    // 7/15 (r^3 + c^3) per step; counted in units of 2^20 FLOPs
+    w = ((120 * m * n * (m + n) + 7 * (m * m * m + n * n * n)) / 15) >> 20;
   } else {
     // Shampoo step: statistics and preconditioning products 4 (r^2 c + c^2 r), two inverse roots
     // of 25 rounds x 4 products each: 200 (r^3 + c^3); counted in units of 2^20 FLOPs
@@ -45,7 +50,8 @@ extern "C" int canz_partition_alpha(int64_t n_mats, const int64_t* rows, const i
   if (!cost && (!rows || !cols) && n_mats > 0) return fail(CANZ_EINVAL, "need cost or rows/cols");
   if (n_ranks < 1) return fail(CANZ_EINVAL, "n_ranks must be >= 1");
   if (!(alpha >= 0.0 && alpha <= 1.0)) return fail(CANZ_EINVAL, "alpha must lie in [0,1]");
-  if (!cost && cost_kind != CANZ_COST_NUMEL && cost_kind != CANZ_COST_NS_FLOPS && cost_kind != CANZ_COST_SHAMPOO_FLOPS)
+  if (!cost && cost_kind != CANZ_COST_NUMEL && cost_kind != CANZ_COST_NS_FLOPS && cost_kind != CANZ_COST_SHAMPOO_FLOPS &&
+      cost_kind != CANZ_COST_SOAP_FLOPS)
     return fail(CANZ_EUNSUPPORTED, "unknown cost_kind %d", cost_kind);
   if (bucket_off[0] != 0 || bucket_off[n_buckets] != n_mats)
     return fail(CANZ_EINVAL, "bucket_off must run from 0 to n_mats");

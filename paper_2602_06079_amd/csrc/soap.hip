@@ -43,7 +43,8 @@ namespace {
 using namespace f32mfma;
 
 constexpr int64_t MAX_EXTENT = 32768;
-constexpr size_t BATCH_BYTES = size_t(8) << 30;
+constexpr size_t BATCH_BYTES = size_t(32) << 30;   // working matrices of one launch batch: the more matrices share
+                                                     // a batch, the more workgroups the panel kernel of a refresh has
 constexpr int QB = 32;            // panel width of the QR factorisation
 constexpr int QTH = 1024;         // threads of the panel kernel: 16 wavefronts
 constexpr int QWAVES = QTH / 64;
@@ -170,6 +171,27 @@ struct QrPanel {
   int j0;
 };
 
+// Dot product of two rows of nvec float4 over the lanes of a wavefront (each lane's share; the caller
+// sums over the lanes).  QUN pairs of loads are issued before the first is used, so that a pass over a
+// row costs a few memory round trips instead of one per 256 elements.
+constexpr int QUN = 4;
+__device__ __forceinline__ float row_dot(const f32x4* a, const f32x4* b, int nvec, int lane) {
+  float dot = 0.f;
+  for (int q0 = lane; q0 < nvec; q0 += 64 * QUN) {
+    f32x4 x[QUN], y[QUN];
+#pragma unroll
+    for (int u = 0; u < QUN; ++u) {
+      const int q = min(q0 + 64 * u, nvec - 1);     // in bounds; the surplus loads are not used
+      x[u] = a[q];
+      y[u] = b[q];
+    }
+#pragma unroll
+    for (int u = 0; u < QUN; ++u)
+      if (q0 + 64 * u < nvec) dot += (x[u][0] * y[u][0] + x[u][1] * y[u][1]) + (x[u][2] * y[u][2] + x[u][3] * y[u][3]);
+  }
+  return dot;
+}
+
 __global__ __launch_bounds__(QTH) void k_qr_panel(QrPanel a) {
   __shared__ float s_g[QB][QB + 1], s_t[QB][QB + 1], s_tau[QB], s_part[QWAVES], s_head[2];
   const int b = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -232,43 +254,41 @@ __global__ __launch_bounds__(QTH) void k_qr_panel(QrPanel a) {
     for (int task = wave; task < QB - 1; task += QWAVES) {
       const f32x4* v = vrow(c);
       if (task < c) {                       // v_task . v_c for the triangular factor
-        const f32x4* u = vrow(task);
-        float dot = 0.f;
-        for (int q = lane; q < nvec; q += 64) {
-          const f32x4 x = u[q], y = v[q];
-          dot += (x[0] * y[0] + x[1] * y[1]) + (x[2] * y[2] + x[3] * y[3]);
-        }
-        dot = wave_sum(dot);
+        const float dot = wave_sum(row_dot(vrow(task), v, nvec, lane));
         if (lane == 0) s_g[task][c] = dot;
       } else {                              // column c2 <- H_c column c2
         const int c2 = task + 1;
         f32x4* x = col(c2);
         float f = 0.f;
-        if (tau != 0.f) {
-          float dot = 0.f;
-          for (int q = lane; q < nvec; q += 64) {
-            const f32x4 xv = x[q], y = v[q];
-            dot += (xv[0] * y[0] + xv[1] * y[1]) + (xv[2] * y[2] + xv[3] * y[3]);
-          }
-          f = tau * wave_sum(dot);
-        }
+        if (tau != 0.f) f = tau * wave_sum(row_dot(x, v, nvec, lane));
         const bool next = c2 == c + 1;      // this wavefront also takes the head of the next column
         if (tau != 0.f || next) {
           float ss2 = 0.f, al2 = 0.f;
-          for (int q = lane; q < nvec; q += 64) {
-            f32x4 xv = x[q];
-            if (tau != 0.f) {
-              const f32x4 y = v[q];
+          for (int q0 = lane; q0 < nvec; q0 += 64 * QUN) {
+            f32x4 xv[QUN], y[QUN];
 #pragma unroll
-              for (int e = 0; e < 4; ++e) xv[e] = __builtin_fmaf(-f, y[e], xv[e]);
-              x[q] = xv;
+            for (int u = 0; u < QUN; ++u) {
+              const int q = min(q0 + 64 * u, nvec - 1);
+              xv[u] = x[q];
+              y[u] = v[q];
             }
-            if (next) {
 #pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                const int r = 4 * q + e;
-                if (r > c2) ss2 += xv[e] * xv[e];
-                if (r == c2) al2 = xv[e];
+            for (int u = 0; u < QUN; ++u) {
+              const int q = q0 + 64 * u;
+              if (q < nvec) {
+                if (tau != 0.f) {
+#pragma unroll
+                  for (int e = 0; e < 4; ++e) xv[u][e] = __builtin_fmaf(-f, y[u][e], xv[u][e]);
+                  x[q] = xv[u];
+                }
+                if (next) {
+#pragma unroll
+                  for (int e = 0; e < 4; ++e) {
+                    const int r = 4 * q + e;
+                    if (r > c2) ss2 += xv[u][e] * xv[u][e];
+                    if (r == c2) al2 = xv[u][e];
+                  }
+                }
               }
             }
           }

@@ -119,3 +119,47 @@ def test_shampoo_argument_errors_and_workspace_without_device(canz):
     assert canz.canz_shampoo_workspace_bytes([G(rows=256, cols=512, n_mats=1)], hp) == want
     assert canz.canz_shampoo_workspace_bytes([G(rows=200, cols=500, n_mats=1)], hp) == want
     assert ctypes.sizeof(canz._ShGroup) == 16 + 16 + 32 and ctypes.sizeof(canz._ShHparams) == 24
+
+
+def test_soap_argument_errors_and_workspace_without_device(canz):
+    hp = canz.SoapHparams()
+    ok = dict(rows=256, cols=512, grad=[4096], mom=[8192], var=[12288], left=[16384], right=[20480], qleft=[24576],
+              qright=[28672], out=[32768])
+
+    def code(groups, hp_, ws=256 * 1024, ws_bytes=1 << 40):
+        with pytest.raises(canz.CanzError) as e:
+            canz.canz_soap_step(groups, hp_, ws, ws_bytes, 0)
+        return e.value.code
+
+    G = canz.SoapGroup
+    assert code([G(**{**ok, "grad": [4100]})], hp) == canz.EINVAL
+    assert code([G(**{**ok, "var": [0]})], hp) == canz.EINVAL
+    assert code([G(**{**ok, "qright": []})], hp) == canz.EINVAL                      # a side within the limit needs its tables
+    assert code([G(**{**ok, "tp": 9})], hp) == canz.EINVAL
+    assert code([G(**{**ok, "tp": 3})], hp) == canz.ESHAPE
+    assert code([G(**{**ok, "rows": 32769})], hp) == canz.ESHAPE
+    assert code([G(**{**ok, "out_dtype": 7})], hp) == canz.EUNSUPPORTED
+    assert code([G(**ok)], canz.SoapHparams(beta1=1.0)) == canz.EINVAL
+    assert code([G(**ok)], canz.SoapHparams(eps=-1.0)) == canz.EINVAL
+    assert code([G(**ok)], canz.SoapHparams(step=0)) == canz.EINVAL
+    assert code([G(**ok)], canz.SoapHparams(max_precond_dim=0)) == canz.EINVAL
+    assert code([G(**ok)], canz.SoapHparams(out_mode=3)) == canz.EUNSUPPORTED
+    assert code([G(**ok)], canz.SoapHparams(max_precond_dim=255)) == canz.EUNSUPPORTED     # neither side has a basis
+    assert "max_precond_dim" in canz.canz_last_error()
+    assert code([G(**ok)], hp, ws=0) == canz.EWORKSPACE
+    assert code([G(**ok)], hp, ws_bytes=1024) == canz.EWORKSPACE
+    canz.canz_soap_step([], hp, 0, 0, 0)
+    # workspace in floats, rows 256, cols 512, one matrix, both sides: G and M in two orientations, the half-rotated
+    # and the rotated pair (4 x 2 planes), N' and its half-rotated image (2 planes), the bases in two orientations,
+    # one padded statistic of the larger side; a refresh step adds four square matrices of that side (working copy,
+    # reflectors with 96 spare rows, their transposed panels, Q^T) and three strips of 128 columns
+    plane, sq = 256 * 512, 512 * 512
+    plain = 4 * (10 * plane + 2 * 256 * 256 + 2 * sq + sq)
+    fresh = plain + 4 * (4 * sq + 96 * 512 + 3 * 512 * 128)
+    one = [G(rows=256, cols=512, n_mats=1)]
+    assert canz.canz_soap_workspace_bytes(one, hp) == plain
+    assert canz.canz_soap_workspace_bytes([G(rows=200, cols=500, n_mats=1)], hp) == plain
+    assert canz.canz_soap_workspace_bytes(one, canz.SoapHparams(refresh=True)) == fresh
+    # one-sided: no half-rotated images, no basis of the long side, the statistic of the short side only
+    assert canz.canz_soap_workspace_bytes(one, canz.SoapHparams(max_precond_dim=256)) == 4 * (7 * plane + 3 * 256 * 256)
+    assert ctypes.sizeof(canz._SoapGroup) == 16 + 16 + 64 and ctypes.sizeof(canz._SoapHparams) == 40

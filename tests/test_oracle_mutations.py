@@ -190,6 +190,19 @@ SOAP_MUTANTS = [
 ]
 
 
+SOAP_COST_MUTANTS = [
+    ("refresh not spread over the period", "+ 14 * (r ** 3 + c ** 3)) // (3 * refresh_every)", "+ 14 * (r ** 3 + c ** 3) * refresh_every) // (3 * refresh_every)"),
+    ("three rotations instead of four products", "3 * refresh_every * 8 * r * c * (r + c)", "3 * refresh_every * 6 * r * c * (r + c)"),
+    ("cost units not scaled", "return [soap_flops(int(r), int(c)) >> 20", "return [soap_flops(int(r), int(c))"),
+]
+
+
+@pytest.mark.parametrize("what,old,new", SOAP_COST_MUTANTS, ids=[m[0] for m in SOAP_COST_MUTANTS])
+def test_soap_cost_pins_catch(what, old, new):
+    failed = _caught(PINS_SOAP, "OP", _mutant(OP, old, new))
+    assert failed, "no pin notices: " + what
+
+
 @pytest.mark.parametrize("what,old,new", SOAP_MUTANTS, ids=[m[0] for m in SOAP_MUTANTS])
 def test_soap_pins_catch(what, old, new):
     failed = _caught(PINS_SOAP, "SO", _mutant(SOO, old, new))

@@ -11,6 +11,7 @@ import pytest
 import scipy.linalg
 import torch
 
+import oracle.partition as OP
 import oracle.soap as SO
 
 
@@ -254,3 +255,14 @@ def test_parameter_update_and_fragments():
     assert np.array_equal(whole["param"], split["param"])
     assert np.allclose(whole["param"], p * (1 - 0.1 * 0.5) - 0.1 * whole["direction"], rtol=1e-14, atol=1e-15)
     assert np.array_equal(whole["delta"], -0.1 * whole["direction"])
+
+
+def test_soap_cost_model_by_hand():
+    """W(p) for the planner, r = 2, c = 3, refresh every 10th step: per step 4 * (2*4*3 + 2*2*9) = 240 FLOPs,
+    per refresh 14/3 * (8 + 27) = 163.33, a tenth of it per step: floor(256.33) = 256.  In the planner's units of
+    2^20 FLOPs a 4096 x 4096 matrix costs floor((16 + 14/15) * 65536) = 1109742."""
+    assert OP.soap_flops(2, 3) == 256
+    assert OP.soap_flops(3, 2) == 256
+    assert OP.soap_flops(2, 3, refresh_every=1) == 240 + 163
+    assert OP.param_cost([4096], [4096], OP.COST_SOAP_FLOPS) == [1109742]
+    assert OP.param_cost([2], [3], OP.COST_SOAP_FLOPS) == [0]

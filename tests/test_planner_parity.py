@@ -23,7 +23,7 @@ def _same_partition(canz, rows, cols, off, R, alpha, cost=None, cost_kind=0):
 def test_configs_bit_exact(canz, cfg):
     s = W.matrix_set(cfg)
     for alpha in sorted({s["alpha"], 0.0, 0.1, 0.5, 1.0}):
-        for kind in (OP.COST_NUMEL, OP.COST_NS_FLOPS, OP.COST_SHAMPOO_FLOPS):
+        for kind in (OP.COST_NUMEL, OP.COST_NS_FLOPS, OP.COST_SHAMPOO_FLOPS, OP.COST_SOAP_FLOPS):
             owner, load = _same_partition(canz, s["rows"], s["cols"], s["bucket_off"], s["n_ranks"], alpha,
                                           cost_kind=kind)
     owner, load = _same_partition(canz, s["rows"], s["cols"], s["bucket_off"], s["n_ranks"], s["alpha"])
