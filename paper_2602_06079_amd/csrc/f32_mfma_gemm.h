@@ -62,12 +62,17 @@ __device__ __forceinline__ void put16(float* C, int64_t ld, int row0, int col, c
   }
 }
 
-template <int EPI, bool SYM>
+// BN = 128: 128 x 128 tiles, each wavefront a 64 x 64 quarter.  BN = 32 (for products whose N is 32, the
+// width of a QR panel): 128 x 32 tiles, each wavefront a 32 x 32 block of rows.
+template <int EPI, bool SYM, int BN = SB>
 __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape s, OutSpec o) {
+  static_assert(BN == SB || (BN == 32 && !SYM), "tile widths: 128, or 32 for plain products");
+  constexpr int NI = BN == SB ? 2 : 1;   // 32 x 32 MFMA tiles per wavefront, along M and along N
+  constexpr int QX = BN / 32;            // 32-row groups of the Q tile
   __shared__ float sP[2][SK][LDS_LD];  // k-major: the lanes of one MFMA operand read consecutive rows
   __shared__ float sQ[2][SK][LDS_LD];
 
-  const int tiles_m = static_cast<int>(g.M / SB), tiles_n = static_cast<int>(g.N / SB);
+  const int tiles_m = static_cast<int>(g.M / SB), tiles_n = static_cast<int>(g.N / BN);
   const int per = SYM ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
   const int b = blockIdx.x / per;
   int tix = blockIdx.x - b * per;
@@ -84,9 +89,9 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
 
   const int t = threadIdx.x;
   const int lane = t & 63, wave = t >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = BN == SB ? wave >> 1 : wave, wn = BN == SB ? wave & 1 : 0;
   const float* Pg = g.P + static_cast<int64_t>(b / g.pdiv) * g.sp + static_cast<int64_t>(tm) * SB * g.ldp;
-  const float* Qg = g.Q + static_cast<int64_t>(b / g.qdiv) * g.sq + static_cast<int64_t>(tn) * SB * g.ldq;
+  const float* Qg = g.Q + static_cast<int64_t>(b / g.qdiv) * g.sq + static_cast<int64_t>(tn) * BN * g.ldq;
 
   const int ld_row = t >> 3, ld_k = (t & 7) * 4;  // rows ld_row + 32 x (x = 0..3), 4 consecutive k
   // Long sums of the statistics (k up to the other extent of the matrix, terms of one sign on the
@@ -94,11 +99,11 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
   // iteration and the preconditioning accumulate in one go (their rounding, about 1e-5 relative,
   // is corrected by the following rounds and is far below the tolerance of the update).
   constexpr bool FOLD = EPI == SE_STAT;
-  f32x16 acc[2][2], tot[2][2];
+  f32x16 acc[NI][NI], tot[NI][NI];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < NI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NI; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f, tot[i][j][r] = 0.f;
 
@@ -110,7 +115,7 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
       pv[set][x] = *reinterpret_cast<const f32x4*>(Pg + static_cast<int64_t>(ld_row + 32 * x) * g.ldp + k0);
-      qv[set][x] = *reinterpret_cast<const f32x4*>(Qg + static_cast<int64_t>(ld_row + 32 * x) * g.ldq + k0);
+      if (x < QX) qv[set][x] = *reinterpret_cast<const f32x4*>(Qg + static_cast<int64_t>(ld_row + 32 * x) * g.ldq + k0);
     }
   };
   auto stash = [&](int buf, int set) {
@@ -119,7 +124,7 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         sP[buf][ld_k + c][ld_row + 32 * x] = pv[set][x][c];
-        sQ[buf][ld_k + c][ld_row + 32 * x] = qv[set][x][c];
+        if (x < QX) sQ[buf][ld_k + c][ld_row + 32 * x] = qv[set][x][c];
       }
   };
   // one stage: LDS buffer `buf` holds stage kt, register set `other` stage kt + 1, set `mine` is free
@@ -128,21 +133,21 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
     if (kt + 2 < nk) fetch(kt + 2, mine);
 #pragma unroll
     for (int k = 0; k < SK; k += 2) {
-      float fa[2], fb[2];
+      float fa[NI], fb[NI];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) fa[i] = sP[buf][k + (lane >> 5)][wm * 64 + i * 32 + (lane & 31)];
+      for (int i = 0; i < NI; ++i) fa[i] = sP[buf][k + (lane >> 5)][wm * 32 * NI + i * 32 + (lane & 31)];
 #pragma unroll
-      for (int j = 0; j < 2; ++j) fb[j] = sQ[buf][k + (lane >> 5)][wn * 64 + j * 32 + (lane & 31)];
+      for (int j = 0; j < NI; ++j) fb[j] = sQ[buf][k + (lane >> 5)][wn * 64 + j * 32 + (lane & 31)];
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < NI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
     if (FOLD && ((kt + 1) % FLUSH == 0 || kt + 1 == nk)) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < NI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NI; ++j)
 #pragma unroll
           for (int r = 0; r < 16; ++r) tot[i][j][r] += acc[i][j][r], acc[i][j][r] = 0.f;
     }
@@ -159,19 +164,19 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
   }
   if (!FOLD) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) tot[i][j] = acc[i][j];
+      for (int j = 0; j < NI; ++j) tot[i][j] = acc[i][j];
   }
 
-  const int row_base = tm * SB + wm * 64 + 4 * (lane >> 5);
-  const int col_base = tn * SB + wn * 64 + (lane & 31);
+  const int row_base = tm * SB + wm * 32 * NI + 4 * (lane >> 5);
+  const int col_base = tn * BN + wn * 64 + (lane & 31);
   const bool mirror = SYM && tm != tn;
   const int64_t cb = static_cast<int64_t>(b) * g.sc;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < NI; ++i) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < NI; ++j) {
       const int row0 = row_base + i * 32, col = col_base + j * 32;
       float v[16];
 #pragma unroll
@@ -216,15 +221,15 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
   }
 }
 
-template <int EPI, bool SYM>
+template <int EPI, bool SYM, int BN = SB>
 hipError_t launch_gemm(ShGemm g, int nb, const PtrTable& stat, const Shape& s, const OutSpec& o, hipStream_t st) {
-  if (g.M < SB || g.N < SB || g.K < SK || g.M % SB || g.N % SB || g.K % SK || (SYM && g.M != g.N)) return hipErrorInvalidValue;
+  if (g.M < SB || g.N < BN || g.K < SK || g.M % SB || g.N % BN || g.K % SK || (SYM && g.M != g.N)) return hipErrorInvalidValue;
   if (g.ldc == 0) g.ldc = g.N, g.sc = g.M * g.N;
   if (g.pdiv == 0) g.pdiv = 1;
   if (g.qdiv == 0) g.qdiv = 1;
-  const int64_t tm = g.M / SB, tn = g.N / SB;
+  const int64_t tm = g.M / SB, tn = g.N / BN;
   const int64_t blocks = (SYM ? tm * (tm + 1) / 2 : tm * tn) * nb;
-  hipLaunchKernelGGL((k_sh_gemm<EPI, SYM>), dim3(static_cast<unsigned>(blocks)), dim3(NTH), 0, st, g, stat, s, o);
+  hipLaunchKernelGGL((k_sh_gemm<EPI, SYM, BN>), dim3(static_cast<unsigned>(blocks)), dim3(NTH), 0, st, g, stat, s, o);
   return hipGetLastError();
 }
 

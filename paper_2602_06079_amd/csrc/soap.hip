@@ -155,78 +155,313 @@ __global__ __launch_bounds__(NTH) void k_soap_store_q(PtrTable q, const float* _
 }
 
 // One panel of the Householder QR factorisation: columns j0 .. j0 + 31 of the matrix whose
-// column c is row c of wk (row length dp).  One workgroup per matrix.
-//   vall row j0 + c   <- reflector v_c (zero before row j0 + c, 1 there)
-//   vkt  [dp][32]     <- the same reflectors, row r holds v_0[r] .. v_31[r]       (rows >= j0)
-//   tt   [128][32]    <- rows 0..31 T, rows 32..63 T^T   (H_0 ... H_31 = I - V T V^T)
+// column c is row c of wk (row length dp).  One workgroup of 16 wavefronts per matrix.
+//   vall row j0 + c  <- reflector v_c (zero before row j0 + c, 1 there)
+//   ybuf [dp][32]    <- Y  = V T^T, rows klo .. dp - 1   (H_0 ... H_31 = I - V T V^T, so
+//   y2   [dp][32]    <- Y2 = V T                          H^T A = A - Y (V^T A) and H A = A - Y2 (V^T A))
 // and the panel's later columns are updated in place as each reflector is found.  Columns at or
 // beyond d (padding) and columns that are already zero below the diagonal get tau = 0 (H = I).
+//
+// Column c2 of the panel belongs to wavefront (c2 - 1) mod 16 for the whole kernel: it alone reads and
+// writes that column, so the columns need no synchronisation between wavefronts.  What the others
+// need of step c is the reflector v_c, which its owner leaves in LDS (for rows up to VMAX; in the
+// reflector array otherwise) together with tau_c.  Per step: every wavefront applies H_c to its own later
+// columns; barrier; the owner of column c + 1, which has just updated it and (up to 3072 rows) still
+// holds it in registers, turns it into v_(c+1); barrier.  With v in LDS the barriers only have to
+// order LDS traffic, so they do not wait for the column stores in flight.
+// A second kernel accumulates V V^T (32 x 32, which T needs) on the matrix cores, each wavefront
+// taking every 16th block of 8 rows, sums over the wavefronts in a fixed order, forms T column by
+// column, and Y, Y2 row by row.
 struct QrPanel {
   float* wk;
   float* vall;
-  float* vkt;
-  float* tt;
+  float* ybuf;
+  float* y2;
+  float* tau;      // [nb][32] handed from the first kernel of a panel to the second
   int64_t dp, d;
-  int64_t s_wk, s_vall, s_vkt, s_tt;   // batch strides
-  int j0;
+  int64_t s_wk, s_vall, s_y, s_y2;   // batch strides
+  int j0, klo;
 };
 
-// Dot product of two rows of nvec float4 over the lanes of a wavefront (each lane's share; the caller
-// sums over the lanes).  QUN pairs of loads are issued before the first is used, so that a pass over a
-// row costs a few memory round trips instead of one per 256 elements.
-constexpr int QUN = 4;
-__device__ __forceinline__ float row_dot(const f32x4* a, const f32x4* b, int nvec, int lane) {
-  float dot = 0.f;
-  for (int q0 = lane; q0 < nvec; q0 += 64 * QUN) {
-    f32x4 x[QUN], y[QUN];
-#pragma unroll
-    for (int u = 0; u < QUN; ++u) {
-      const int q = min(q0 + 64 * u, nvec - 1);     // in bounds; the surplus loads are not used
-      x[u] = a[q];
-      y[u] = b[q];
-    }
-#pragma unroll
-    for (int u = 0; u < QUN; ++u)
-      if (q0 + 64 * u < nvec) dot += (x[u][0] * y[u][0] + x[u][1] * y[u][1]) + (x[u][2] * y[u][2] + x[u][3] * y[u][3]);
-  }
-  return dot;
-}
+constexpr int VMAX = 12288;   // rows of a reflector kept in LDS
+constexpr int XR = 12;        // float4 per lane of the next column kept in registers (3072 rows)
+constexpr int QUN = 4;        // loads in flight per lane and operand in the streaming loops
+constexpr int TLD = QB + 4;   // row length of the T factor in LDS (rows 16-byte aligned)
+
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 __global__ __launch_bounds__(QTH) void k_qr_panel(QrPanel a) {
-  __shared__ float s_g[QB][QB + 1], s_t[QB][QB + 1], s_tau[QB], s_part[QWAVES], s_head[2];
+  __shared__ f32x4 s_v4[VMAX / 4];
+  __shared__ float s_tau[QB];
   const int b = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int64_t dp = a.dp;
   const int j0 = a.j0;
-  const int nvec = static_cast<int>(dp - j0) / 4;             // float4 per row in the rows j0 .. dp - 1
+  const int len = static_cast<int>(dp) - j0;     // rows j0 .. dp - 1, a multiple of 32
+  const int nvec = len / 4;
+  const bool vlds = len <= VMAX;
+  const bool in_regs = nvec <= 64 * XR;
   float* wk = a.wk + static_cast<int64_t>(b) * a.s_wk;
   float* vrows = a.vall + static_cast<int64_t>(b) * a.s_vall;
   auto col = [&](int c) { return reinterpret_cast<f32x4*>(wk + static_cast<int64_t>(j0 + c) * dp + j0); };
   auto vrow = [&](int c) { return reinterpret_cast<f32x4*>(vrows + static_cast<int64_t>(j0 + c) * dp + j0); };
+  auto barrier = [&]() {
+    if (vlds)
+      lds_barrier();
+    else
+      __syncthreads();
+  };
+  // tau and the scale of v for a column with diagonal element al and sum of squares ss below it
+  auto reflector = [&](int c, float ss, float al, float& tau, float& scale) {
+    tau = 0.f, scale = 0.f;
+    if (j0 + c < a.d && ss > 0.f) {
+      const float nrm = sqrtf(__builtin_fmaf(al, al, ss));
+      const float beta = al >= 0.f ? -nrm : nrm;
+      tau = (beta - al) / beta;
+      scale = 1.f / (al - beta);
+    }
+  };
+  auto v_of = [&](const f32x4& x, int q, int c, float scale) {
+    f32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int r = 4 * q + e;
+      o[e] = r < c ? 0.f : (r == c ? 1.f : x[e] * scale);
+    }
+    return o;
+  };
+  auto put_v = [&](int c, int q, const f32x4& o) {
+    if (vlds) s_v4[q] = o;
+    vrow(c)[q] = o;
+  };
 
-  // head of column 0: sum of squares below the diagonal, and the diagonal element
-  {
-    float ss = 0.f;
+  if (wave == 0) {   // column 0: its head, then v_0
     const f32x4* x = col(0);
-    for (int q = t; q < nvec; q += QTH) {
+    float ss = 0.f, al = 0.f;
+    for (int q = lane; q < nvec; q += 64) {
       const f32x4 v = x[q];
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
+      for (int e = 0; e < 4; ++e) {
         if (4 * q + e > 0) ss += v[e] * v[e];
+        if (4 * q + e == 0) al = v[e];
+      }
     }
-    ss = wave_sum(ss);
-    if (lane == 0) s_part[wave] = ss;
-    __syncthreads();
-    if (t == 0) {
-      float tot = 0.f;
-      for (int w = 0; w < QWAVES; ++w) tot += s_part[w];
-      s_head[0] = tot;
-      s_head[1] = wk[static_cast<int64_t>(j0) * dp + j0];
-    }
-    __syncthreads();
+    ss = wave_sum(ss), al = wave_sum(al);
+    float tau, scale;
+    reflector(0, ss, al, tau, scale);
+    for (int q = lane; q < nvec; q += 64) put_v(0, q, v_of(x[q], q, 0, scale));
+    if (lane == 0) s_tau[0] = tau;
   }
+  barrier();
 
   for (int c = 0; c < QB; ++c) {
-    const float ss = s_head[0], al = s_head[1];
+    const float tau = s_tau[c];
+    const f32x4* vg = vrow(c);
+    auto ldv = [&](int q) { return vlds ? s_v4[q] : vg[q]; };
+    f32x4 keep[XR];
+    float ss2 = 0.f, al2 = 0.f;
+    for (int c2 = wave + 1; c2 < QB; c2 += QWAVES) {
+      if (c2 <= c) continue;
+      const bool next = c2 == c + 1;
+      if (tau == 0.f && !next) continue;           // H_c = I: nothing to apply
+      f32x4* x = col(c2);
+      if (next && in_regs) {
+        float dot = 0.f;
+#pragma unroll
+        for (int sl = 0; sl < XR; ++sl) {
+          const int q = lane + 64 * sl;
+          if (q < nvec) {
+            keep[sl] = x[q];
+            const f32x4 y = ldv(q);
+            dot += (keep[sl][0] * y[0] + keep[sl][1] * y[1]) + (keep[sl][2] * y[2] + keep[sl][3] * y[3]);
+          }
+        }
+        const float f = tau * wave_sum(dot);
+#pragma unroll
+        for (int sl = 0; sl < XR; ++sl) {
+          const int q = lane + 64 * sl;
+          if (q < nvec) {
+            if (tau != 0.f) {
+              const f32x4 y = ldv(q);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) keep[sl][e] = __builtin_fmaf(-f, y[e], keep[sl][e]);
+              x[q] = keep[sl];
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int r = 4 * q + e;
+              if (r > c2) ss2 += keep[sl][e] * keep[sl][e];
+              if (r == c2) al2 = keep[sl][e];
+            }
+          }
+        }
+      } else {
+        float f = 0.f;
+        if (tau != 0.f) {
+          float dot = 0.f;
+          for (int q0 = lane; q0 < nvec; q0 += 64 * QUN) {
+            f32x4 xv[QUN];
+#pragma unroll
+            for (int u = 0; u < QUN; ++u) xv[u] = x[min(q0 + 64 * u, nvec - 1)];   // in bounds; surplus loads unused
+#pragma unroll
+            for (int u = 0; u < QUN; ++u) {
+              const int q = q0 + 64 * u;
+              if (q < nvec) {
+                const f32x4 y = ldv(q);
+                dot += (xv[u][0] * y[0] + xv[u][1] * y[1]) + (xv[u][2] * y[2] + xv[u][3] * y[3]);
+              }
+            }
+          }
+          f = tau * wave_sum(dot);
+        }
+        for (int q0 = lane; q0 < nvec; q0 += 64 * QUN) {
+          f32x4 xv[QUN];
+#pragma unroll
+          for (int u = 0; u < QUN; ++u) xv[u] = x[min(q0 + 64 * u, nvec - 1)];
+#pragma unroll
+          for (int u = 0; u < QUN; ++u) {
+            const int q = q0 + 64 * u;
+            if (q < nvec) {
+              if (tau != 0.f) {
+                const f32x4 y = ldv(q);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) xv[u][e] = __builtin_fmaf(-f, y[e], xv[u][e]);
+                x[q] = xv[u];
+              }
+              if (next) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const int r = 4 * q + e;
+                  if (r > c2) ss2 += xv[u][e] * xv[u][e];
+                  if (r == c2) al2 = xv[u][e];
+                }
+              }
+            }
+          }
+        }
+      }
+    }
+    barrier();   // every wavefront has finished with v_c
+    if (c + 1 < QB && wave == c % QWAVES) {   // the owner of column c + 1 makes v_(c+1)
+      ss2 = wave_sum(ss2), al2 = wave_sum(al2);   // one lane holds the diagonal element, the others 0
+      float tau2, scale2;
+      reflector(c + 1, ss2, al2, tau2, scale2);
+      if (in_regs) {
+#pragma unroll
+        for (int sl = 0; sl < XR; ++sl) {
+          const int q = lane + 64 * sl;
+          if (q < nvec) put_v(c + 1, q, v_of(keep[sl], q, c + 1, scale2));
+        }
+      } else {
+        const f32x4* x = col(c + 1);               // this wavefront's own stores
+        for (int q = lane; q < nvec; q += 64) put_v(c + 1, q, v_of(x[q], q, c + 1, scale2));
+      }
+      if (lane == 0) s_tau[c + 1] = tau2;
+    }
+    barrier();   // v_(c+1) and tau_(c+1) are in place
+  }
+  if (t < QB) (a.tau + static_cast<int64_t>(b) * QB)[t] = s_tau[t];
+}
+
+// Sum over the 64 lanes through the data-parallel-primitive lanes of the vector ALU (no LDS crossbar
+// round trips, which dominate a step of the register-resident panel kernel otherwise): an inclusive scan
+// inside each row of 16 lanes (shifts by 1, 2, 4, 8, out-of-row sources read as 0), then the row totals
+// are carried into the following rows (row_bcast:15 into rows 1 and 3, row_bcast:31 into rows 2 and 3);
+// lane 63 holds the total, which every lane receives.
+template <int CTRL, int ROW_MASK, bool BOUND>
+__device__ __forceinline__ float dpp_mov(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, BOUND));
+}
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+  v += dpp_mov<0x111, 0xf, true>(v);    // row_shr:1
+  v += dpp_mov<0x112, 0xf, true>(v);    // row_shr:2
+  v += dpp_mov<0x114, 0xf, true>(v);    // row_shr:4
+  v += dpp_mov<0x118, 0xf, true>(v);    // row_shr:8
+  v += dpp_mov<0x142, 0xa, false>(v);   // row_bcast:15 into rows 1 and 3
+  v += dpp_mov<0x143, 0xc, false>(v);   // row_bcast:31 into rows 2 and 3
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
+// Columns ka and / or kb (registers) <- H_c applied to them, v_c in LDS.
+template <int XS, bool DO_A, bool DO_B>
+__device__ __forceinline__ void apply_reflector(f32x4 (&ka)[XS], f32x4 (&kb)[XS], const f32x4* s_v4, int nvec, int lane,
+                                                float tau) {
+  constexpr bool HOLD_V = XS <= 8;
+  f32x4 v[HOLD_V ? XS : 1];
+  float da = 0.f, db = 0.f;
+#pragma unroll
+  for (int sl = 0; sl < XS; ++sl) {
+    const int q = lane + 64 * sl;
+    if (q < nvec) {
+      const f32x4 y = s_v4[q];
+      if (HOLD_V) v[sl] = y;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (DO_A) da = __builtin_fmaf(ka[sl][e], y[e], da);
+        if (DO_B) db = __builtin_fmaf(kb[sl][e], y[e], db);
+      }
+    }
+  }
+  const float fa = DO_A ? tau * wave_sum_dpp(da) : 0.f;
+  const float fb = DO_B ? tau * wave_sum_dpp(db) : 0.f;
+#pragma unroll
+  for (int sl = 0; sl < XS; ++sl) {
+    const int q = lane + 64 * sl;
+    if (q < nvec) {
+      const f32x4 y = HOLD_V ? v[sl] : s_v4[q];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (DO_A) ka[sl][e] = __builtin_fmaf(-fa, y[e], ka[sl][e]);
+        if (DO_B) kb[sl][e] = __builtin_fmaf(-fb, y[e], kb[sl][e]);
+      }
+    }
+  }
+}
+
+// The same first half for panels of at most 256 XS remaining rows (XS = 8: 2048, XS = 12: 3072): every
+// wavefront loads its two columns (wave + 1 and wave + 17) into registers once and keeps them there; a step
+// reads v_c from LDS, and the owner of column c + 1 writes v_(c+1) to LDS and to the reflector array.  The
+// columns are never written back: what the factorisation leaves in them is R, which nothing uses.
+// With XS = 8 there is room to hold v_c in registers between the dot products and the updates.
+template <int XS>
+__global__ __launch_bounds__(QTH) void k_qr_panel_regs(QrPanel a) {
+  __shared__ f32x4 s_v4[64 * XS];
+  __shared__ float s_tau[QB];
+  const int b = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int64_t dp = a.dp;
+  const int j0 = a.j0;
+  const int nvec = (static_cast<int>(dp) - j0) / 4;   // <= 64 XS
+  const float* wk = a.wk + static_cast<int64_t>(b) * a.s_wk;
+  float* vrows = a.vall + static_cast<int64_t>(b) * a.s_vall;
+  const int ca = wave + 1, cb = wave + 1 + QWAVES;    // this wavefront's columns (cb only if < 32)
+  f32x4 ka[XS], kb[XS];
+
+  auto load_col = [&](f32x4 (&k)[XS], int c) {
+    const f32x4* x = reinterpret_cast<const f32x4*>(wk + static_cast<int64_t>(j0 + c) * dp + j0);
+#pragma unroll
+    for (int sl = 0; sl < XS; ++sl) {
+      const int q = lane + 64 * sl;
+      if (q < nvec) k[sl] = x[q];
+    }
+  };
+  // sum of squares below row c and the element at row c, over the wavefront
+  auto head = [&](const f32x4 (&k)[XS], int c, float& ss, float& al) {
+    ss = 0.f, al = 0.f;
+#pragma unroll
+    for (int sl = 0; sl < XS; ++sl) {
+      const int q = lane + 64 * sl;
+      if (q < nvec) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = 4 * q + e;
+          if (r > c) ss += k[sl][e] * k[sl][e];
+          if (r == c) al = k[sl][e];
+        }
+      }
+    }
+    ss = wave_sum_dpp(ss), al = wave_sum_dpp(al);
+  };
+  // column c (in k), whose head is (ss, al), becomes the reflector v_c: to LDS, to the reflector array, tau to LDS
+  auto make_v = [&](const f32x4 (&k)[XS], int c, float ss, float al) {
     float tau = 0.f, scale = 0.f;
     if (j0 + c < a.d && ss > 0.f) {
       const float nrm = sqrtf(__builtin_fmaf(al, al, ss));
@@ -234,114 +469,166 @@ __global__ __launch_bounds__(QTH) void k_qr_panel(QrPanel a) {
       tau = (beta - al) / beta;
       scale = 1.f / (al - beta);
     }
-    {
-      const f32x4* x = col(c);
-      f32x4* v = vrow(c);
-      for (int q = t; q < nvec; q += QTH) {
-        const f32x4 xv = x[q];
+    f32x4* vg = reinterpret_cast<f32x4*>(vrows + static_cast<int64_t>(j0 + c) * dp + j0);
+#pragma unroll
+    for (int sl = 0; sl < XS; ++sl) {
+      const int q = lane + 64 * sl;
+      if (q < nvec) {
         f32x4 o;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * q + e;
-          o[e] = r < c ? 0.f : (r == c ? 1.f : xv[e] * scale);
+          o[e] = r < c ? 0.f : (r == c ? 1.f : k[sl][e] * scale);
         }
-        v[q] = o;
+        s_v4[q] = o;
+        vg[q] = o;
       }
-      if (t == 0) s_tau[c] = tau;
     }
-    __syncthreads();   // v_c is complete; every thread has read the head of column c
+    if (lane == 0) s_tau[c] = tau;
+  };
 
-    for (int task = wave; task < QB - 1; task += QWAVES) {
-      const f32x4* v = vrow(c);
-      if (task < c) {                       // v_task . v_c for the triangular factor
-        const float dot = wave_sum(row_dot(vrow(task), v, nvec, lane));
-        if (lane == 0) s_g[task][c] = dot;
-      } else {                              // column c2 <- H_c column c2
-        const int c2 = task + 1;
-        f32x4* x = col(c2);
-        float f = 0.f;
-        if (tau != 0.f) f = tau * wave_sum(row_dot(x, v, nvec, lane));
-        const bool next = c2 == c + 1;      // this wavefront also takes the head of the next column
-        if (tau != 0.f || next) {
-          float ss2 = 0.f, al2 = 0.f;
-          for (int q0 = lane; q0 < nvec; q0 += 64 * QUN) {
-            f32x4 xv[QUN], y[QUN];
-#pragma unroll
-            for (int u = 0; u < QUN; ++u) {
-              const int q = min(q0 + 64 * u, nvec - 1);
-              xv[u] = x[q];
-              y[u] = v[q];
-            }
-#pragma unroll
-            for (int u = 0; u < QUN; ++u) {
-              const int q = q0 + 64 * u;
-              if (q < nvec) {
-                if (tau != 0.f) {
-#pragma unroll
-                  for (int e = 0; e < 4; ++e) xv[u][e] = __builtin_fmaf(-f, y[u][e], xv[u][e]);
-                  x[q] = xv[u];
-                }
-                if (next) {
-#pragma unroll
-                  for (int e = 0; e < 4; ++e) {
-                    const int r = 4 * q + e;
-                    if (r > c2) ss2 += xv[u][e] * xv[u][e];
-                    if (r == c2) al2 = xv[u][e];
-                  }
-                }
-              }
-            }
-          }
-          if (next) {
-            ss2 = wave_sum(ss2);
-            al2 = wave_sum(al2);            // one lane holds the diagonal element, the others 0
-            if (lane == 0) s_head[0] = ss2, s_head[1] = al2;
-          }
-        }
-      }
-    }
-    __syncthreads();   // the panel is updated; the next head and the dot products are in LDS
+  if (wave == 0) {
+    float ss, al;
+    load_col(ka, 0);
+    head(ka, 0, ss, al);
+    make_v(ka, 0, ss, al);
   }
+  load_col(ka, ca);
+  if (cb < QB) load_col(kb, cb);
+  lds_barrier();
+
+  for (int c = 0; c < QB; ++c) {
+    const float tau = s_tau[c];
+    const bool do_a = ca > c, do_b = cb < QB && cb > c;
+    if (tau != 0.f) {   // columns that have become reflectors are left alone
+      if (do_a && do_b)
+        apply_reflector<XS, true, true>(ka, kb, s_v4, nvec, lane, tau);
+      else if (do_a)
+        apply_reflector<XS, true, false>(ka, kb, s_v4, nvec, lane, tau);
+      else if (do_b)
+        apply_reflector<XS, false, true>(ka, kb, s_v4, nvec, lane, tau);
+    }
+    // the owner of column c + 1 takes its head while the others are still busy with their columns
+    const bool owner = c + 1 < QB && wave == c % QWAVES;
+    float ss = 0.f, al = 0.f;
+    if (owner) {
+      if (c + 1 == ca)
+        head(ka, c + 1, ss, al);
+      else
+        head(kb, c + 1, ss, al);
+    }
+    lds_barrier();   // every wavefront has finished with v_c
+    if (owner) {
+      if (c + 1 == ca)
+        make_v(ka, c + 1, ss, al);
+      else
+        make_v(kb, c + 1, ss, al);
+    }
+    lds_barrier();   // v_(c+1) and tau_(c+1) are in place
+  }
+  if (t < QB) (a.tau + static_cast<int64_t>(b) * QB)[t] = s_tau[t];
+}
+
+// Second half of a panel: T from the reflectors and their tau, then Y and Y2 (see k_qr_panel).
+__global__ __launch_bounds__(QTH) void k_qr_tfactor(QrPanel a) {
+  __shared__ float s_part[8 * 1024];
+  __shared__ float s_g[QB][QB + 1];
+  __shared__ __attribute__((aligned(16))) float s_t[QB][TLD], s_tt[QB][TLD];
+  __shared__ float s_tau[QB];
+  const int b = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int64_t dp = a.dp;
+  const int j0 = a.j0;
+  const int len = static_cast<int>(dp) - j0;
+  const float* vrows = a.vall + static_cast<int64_t>(b) * a.s_vall;
+  if (t < QB) s_tau[t] = (a.tau + static_cast<int64_t>(b) * QB)[t];
+
+  // V V^T on the matrix cores: lane l supplies rows l % 32 at k and k + 4 (l / 32), four k per load
+  {
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    const float* vbase = vrows + static_cast<int64_t>(j0 + (lane & 31)) * dp + j0 + 4 * (lane >> 5);
+    const int nblk = len / 8;
+    for (int kb0 = wave; kb0 < nblk; kb0 += QWAVES * QUN) {
+      f32x4 x[QUN];
+#pragma unroll
+      for (int u = 0; u < QUN; ++u) x[u] = *reinterpret_cast<const f32x4*>(vbase + 8 * min(kb0 + QWAVES * u, nblk - 1));
+#pragma unroll
+      for (int u = 0; u < QUN; ++u)
+        if (kb0 + QWAVES * u < nblk) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[u][e], x[u][e], acc, 0, 0, 0);
+        }
+    }
+    // sum over the wavefronts in a fixed order, eight at a time through LDS
+    float* scratch = s_part;
+    float total = 0.f;
+    for (int round = 0; round < QWAVES / 8; ++round) {
+      if ((wave >> 3) == round) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) scratch[(wave & 7) * 1024 + r * 64 + lane] = acc[r];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int w = 0; w < 8; ++w) total += scratch[w * 1024 + t];
+      __syncthreads();
+    }
+    const int r = t >> 6, l = t & 63;   // thread t holds accumulator register r of lane l
+    s_g[8 * (r >> 2) + (r & 3) + 4 * (l >> 5)][l & 31] = total;
+  }
+  __syncthreads();
 
   // T, forward and column by column: T[c][c] = tau_c, T[0:c, c] = -tau_c T[0:c, 0:c] (V^T v_c)
+  // (thread i keeps row i of T in registers; its entries left of the diagonal are zero, so the sums may start at 0)
   if (t < QB) {
     const int i = t;
+    float trow[QB];
+#pragma unroll
     for (int c = 0; c < QB; ++c) {
-      float val = 0.f;
-      if (i == c) {
-        val = s_tau[c];
-      } else if (i < c) {
-        float sum = 0.f;
-        for (int l = i; l < c; ++l) sum = __builtin_fmaf(s_t[i][l], s_g[l][c], sum);
-        val = -s_tau[c] * sum;
-      }
+      float sum = 0.f;
+#pragma unroll
+      for (int l = 0; l < c; ++l) sum = __builtin_fmaf(trow[l], s_g[l][c], sum);
+      const float val = i == c ? s_tau[c] : (i < c ? -s_tau[c] * sum : 0.f);
+      trow[c] = val;
       s_t[i][c] = val;
+      s_tt[c][i] = val;
     }
   }
   __syncthreads();
-  float* tt = a.tt + static_cast<int64_t>(b) * a.s_tt;
-  for (int idx = t; idx < 2 * QB * QB; idx += QTH) {
-    const int row = idx >> 5, l = idx & 31;
-    tt[idx] = row < QB ? s_t[row][l] : s_t[l][row - QB];
-  }
-  float* vkt = a.vkt + static_cast<int64_t>(b) * a.s_vkt;
-  for (int64_t r = j0 + t; r < dp; r += QTH) {
-    float x[QB];
+
+  // Y = V T^T and Y2 = V T on the matrix cores, 32 rows per wavefront and turn; blocks of rows before j0
+  // (down to the tile boundary klo) are zero.  Lane l supplies V[r0 + l % 32][k] and T[l % 32][k] resp.
+  // T[k][l % 32] for k = 2 kk + l / 32.
+  float* ybuf = a.ybuf + static_cast<int64_t>(b) * a.s_y;
+  float* y2 = a.y2 + static_cast<int64_t>(b) * a.s_y2;
+  const int nrb = (static_cast<int>(dp) - a.klo) / 32;
+  for (int rb = wave; rb < nrb; rb += QWAVES) {
+    const int64_t r0 = a.klo + 32 * rb;
+    f32x16 ay, ay2;
 #pragma unroll
-    for (int l = 0; l < QB; ++l) x[l] = vrows[static_cast<int64_t>(j0 + l) * dp + r];
-    f32x4* dst = reinterpret_cast<f32x4*>(vkt + r * QB);
+    for (int r = 0; r < 16; ++r) ay[r] = 0.f, ay2[r] = 0.f;
+    if (r0 >= j0) {
+      const float* vp = vrows + static_cast<int64_t>(j0 + (lane >> 5)) * dp + r0 + (lane & 31);
+      float xa[QB / 2];
 #pragma unroll
-    for (int q = 0; q < QB / 4; ++q) {
-      f32x4 o;
+      for (int kk = 0; kk < QB / 2; ++kk) xa[kk] = vp[static_cast<int64_t>(2 * kk) * dp];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) o[e] = x[4 * q + e];
-      dst[q] = o;
+      for (int kk = 0; kk < QB / 2; ++kk) {
+        ay = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[kk], s_tt[2 * kk + (lane >> 5)][lane & 31], ay, 0, 0, 0);
+        ay2 = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[kk], s_t[2 * kk + (lane >> 5)][lane & 31], ay2, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int64_t at = (r0 + 8 * (r >> 2) + (r & 3) + 4 * (lane >> 5)) * QB + (lane & 31);
+      ybuf[at] = ay[r];
+      y2[at] = ay2[r];
     }
   }
 }
 
 struct Carve {   // float offsets into the workspace of one launch batch
-  size_t gm, gmt, t1, rot, np, yt, ql, qlt, qr, qrt, stat, wk, vall, vkt, tt, ybuf, wt, qt, total_bytes;
+  size_t gm, gmt, t1, rot, np, yt, ql, qlt, qr, qrt, stat, wk, vall, y2, ybuf, tau, wt, qt, total_bytes;
 };
 
 struct Sides {
@@ -372,11 +659,11 @@ Carve carve(int64_t rows, int64_t cols, int nb, Sides u, bool refresh) {
   c.stat = take(nb * dm * dm);
   if (refresh) {
     c.wk = take(nb * dm * dm);
-    c.vall = take(nb * (dm + 96) * dm);
-    c.vkt = take(nb * dm * dm);
-    c.tt = take(nb * dm * 128);        // dm / 32 panels of [128][32]
-    c.ybuf = take(nb * dm * 128);
-    c.wt = take(nb * dm * 128);
+    c.vall = take(nb * dm * dm);
+    c.y2 = take(nb * dm * dm);         // dm / 32 panels of [dm][32]
+    c.ybuf = take(nb * dm * QB);
+    c.tau = take(nb * QB);
+    c.wt = take(nb * dm * QB);
     c.qt = take(nb * dm * dm);
   }
   c.total_bytes = off * sizeof(float);
@@ -443,18 +730,14 @@ int refresh_side(void* const* q_tab, int first, int nb, int64_t d, int64_t dp, c
                  float* ws, const Carve& c, const Shape& s, const OutSpec& o, hipStream_t st) {
   const PtrTable none{};
   const int64_t dd = dp * dp;
-  float *wk = ws + c.wk, *vall = ws + c.vall, *vkt = ws + c.vkt, *tt = ws + c.tt, *ybuf = ws + c.ybuf, *wt = ws + c.wt,
-        *qt = ws + c.qt;
-  const int64_t s_vall = (dp + 96) * dp, s_thin = dp * 128;
+  float *wk = ws + c.wk, *vall = ws + c.vall, *y2 = ws + c.y2, *ybuf = ws + c.ybuf, *wt = ws + c.wt, *qt = ws + c.qt;
+  const int64_t s_vall = dp * dp, s_y = dp * QB;
   auto fill = [&](float* p, int64_t elems, int64_t ld, int identity) {
     const unsigned blocks = static_cast<unsigned>(std::min<int64_t>(2048, (elems + NTH - 1) / NTH));
     hipLaunchKernelGGL(k_soap_fill, dim3(blocks, nb), dim3(NTH), 0, st, p, elems, ld, identity);
   };
   prof_mark(st, CANZ_KERNEL_SOAP_PANEL, true);
-  fill(vall, s_vall, dp, 0);
-  fill(vkt, dd, dp, 0);
-  fill(tt, s_thin, 128, 0);
-  fill(qt, dd, dp, 1);
+  fill(qt, dd, dp, 1);   // nothing else has to start from a known state: every row that is read is written first
   prof_mark(st, CANZ_KERNEL_SOAP_PANEL, false);
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "refresh fill: %s", hipGetErrorString(e));
 
@@ -464,52 +747,49 @@ int refresh_side(void* const* q_tab, int first, int nb, int64_t d, int64_t dp, c
   p0.P = qt_old, p0.Q = stat, p0.c = wk;
   CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_PLAIN, false>(p0, nb, none, s, o, st)), "refresh product");
 
-  // Y of panel j0: ybuf[r][0..31] = (V T^T)[r], ybuf[r][32..63] = (V T)[r], rows from klo on
-  auto y_product = [&](int64_t j0, int64_t klo) {
-    ShGemm y{};
-    y.M = dp - klo, y.N = 128, y.K = QB, y.ldp = QB, y.ldq = QB, y.sp = dd, y.sq = s_thin;
-    y.P = vkt + (j0 / QB) * dp * QB + klo * QB, y.Q = tt + (j0 / QB) * 128 * QB;
-    y.c = ybuf + klo * 128, y.ldc = 128, y.sc = s_thin;
-    return y;
-  };
   // W = (rows lo.. of m) V_panel over the rows j0.. of the reflectors: wt[j][0..31]
   auto w_product = [&](const float* m, int64_t lo, int64_t j0) {
     ShGemm w{};
-    w.M = dp - lo, w.N = 128, w.K = dp - j0, w.ldp = dp, w.ldq = dp, w.sp = dd, w.sq = s_vall;
+    w.M = dp - lo, w.N = QB, w.K = dp - j0, w.ldp = dp, w.ldq = dp, w.sp = dd, w.sq = s_vall;
     w.P = m + lo * dp + j0, w.Q = vall + j0 * dp + j0;
-    w.c = wt + lo * 128, w.ldc = 128, w.sc = s_thin;
+    w.c = wt + lo * QB, w.ldc = QB, w.sc = s_y;
     return w;
   };
-  // (rows lo.., columns klo.. of m) -= W Y^T with Y the columns ycol .. ycol + 31 of ybuf
-  auto sub_product = [&](float* m, int64_t lo, int64_t klo, int ycol) {
+  // (rows lo.., columns klo.. of m) -= W Y^T with Y given as [dp][32] rows
+  auto sub_product = [&](float* m, int64_t lo, int64_t klo, const float* y, int64_t sy) {
     ShGemm u{};
-    u.M = dp - lo, u.N = dp - klo, u.K = QB, u.ldp = 128, u.ldq = 128, u.sp = s_thin, u.sq = s_thin;
-    u.P = wt + lo * 128, u.Q = ybuf + klo * 128 + ycol;
+    u.M = dp - lo, u.N = dp - klo, u.K = QB, u.ldp = QB, u.ldq = QB, u.sp = s_y, u.sq = sy;
+    u.P = wt + lo * QB, u.Q = y + klo * QB;
     u.c = m + lo * dp + klo, u.ldc = dp, u.sc = dd;
     return u;
   };
 
   for (int64_t j0 = 0; j0 < d; j0 += QB) {
+    const int64_t jlo = floor128(j0 + QB), klo = floor128(j0);
     QrPanel a{};
-    a.wk = wk, a.vall = vall, a.vkt = vkt + (j0 / QB) * dp * QB, a.tt = tt + (j0 / QB) * 128 * QB;
-    a.dp = dp, a.d = d, a.s_wk = dd, a.s_vall = s_vall, a.s_vkt = dd, a.s_tt = s_thin;
-    a.j0 = static_cast<int>(j0);
+    a.wk = wk, a.vall = vall, a.ybuf = ybuf, a.y2 = y2 + (j0 / QB) * dp * QB, a.tau = ws + c.tau;
+    a.dp = dp, a.d = d, a.s_wk = dd, a.s_vall = s_vall, a.s_y = s_y, a.s_y2 = dd;
+    a.j0 = static_cast<int>(j0), a.klo = static_cast<int>(klo);
     prof_mark(st, CANZ_KERNEL_SOAP_PANEL, true);
-    hipLaunchKernelGGL(k_qr_panel, dim3(nb), dim3(QTH), 0, st, a);
+    if (dp - j0 <= 64 * 4 * 8)
+      hipLaunchKernelGGL(k_qr_panel_regs<8>, dim3(nb), dim3(QTH), 0, st, a);
+    else if (dp - j0 <= 64 * 4 * 12)
+      hipLaunchKernelGGL(k_qr_panel_regs<12>, dim3(nb), dim3(QTH), 0, st, a);
+    else
+      hipLaunchKernelGGL(k_qr_panel, dim3(nb), dim3(QTH), 0, st, a);
+    hipLaunchKernelGGL(k_qr_tfactor, dim3(nb), dim3(QTH), 0, st, a);
     prof_mark(st, CANZ_KERNEL_SOAP_PANEL, false);
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "panel kernel: %s", hipGetErrorString(e));
-    const int64_t jlo = floor128(j0 + QB), klo = floor128(j0);
     if (jlo >= dp) continue;   // no columns after this panel
-    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_PLAIN, false>(y_product(j0, klo), nb, none, s, o, st)), "QR (Y)");
-    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_PLAIN, false>(w_product(wk, jlo, j0), nb, none, s, o, st)), "QR (W)");
-    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_SUB, false>(sub_product(wk, jlo, klo, 0), nb, none, s, o, st)), "QR (update)");
+    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_PLAIN, false, QB>(w_product(wk, jlo, j0), nb, none, s, o, st)), "QR (W)");
+    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_SUB, false>(sub_product(wk, jlo, klo, ybuf, s_y), nb, none, s, o, st)), "QR (update)");
   }
   // Q = H(0) H(1) ... applied to the identity from the last panel to the first
   for (int64_t j0 = (d - 1) / QB * QB; j0 >= 0; j0 -= QB) {
     const int64_t lo = floor128(j0);
-    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_PLAIN, false>(y_product(j0, lo), nb, none, s, o, st)), "Q (Y)");
-    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_PLAIN, false>(w_product(qt, lo, j0), nb, none, s, o, st)), "Q (W)");
-    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_SUB, false>(sub_product(qt, lo, lo, QB), nb, none, s, o, st)), "Q (update)");
+    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_PLAIN, false, QB>(w_product(qt, lo, j0), nb, none, s, o, st)), "Q (W)");
+    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_SUB, false>(sub_product(qt, lo, lo, y2 + (j0 / QB) * dp * QB, dd), nb, none, s, o, st)),
+             "Q (update)");
   }
   PtrTable q{};
   for (int i = 0; i < nb; ++i) q.p[i] = q_tab[first + i];

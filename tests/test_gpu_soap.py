@@ -310,6 +310,19 @@ def test_config2_shape_with_refresh(canz):
     check(dev, grads, states, None, hp, "soap 2048x1024")
 
 
+def test_refresh_of_a_long_side(canz):
+    """3200 rows: the first panels of the left side are longer than the 3072 rows the panel kernel can hold in
+    registers (they stream their columns from memory), the next ones use the 12-slot variant, the last ones the
+    8-slot one; all three against the oracle's QR."""
+    rows, cols, n = 3200, 384, 2
+    grads = [W.gen_grad(69, i, rows, cols)[0] for i in range(n)]
+    states = [W.gen_soap_state(69, i, rows, cols) for i in range(n)]
+    hp = canz.SoapHparams(lr=0.003, eps=1e-8, step=20, refresh=True, out_mode=canz.OUT_DELTA)
+    dev = SoapDevice(canz, rows, cols, grads, states)
+    run(canz, [dev], hp)
+    check(dev, grads, states, None, hp, "soap 3200x384")
+
+
 def test_step_under_graph_capture_replays(canz):
     """A step without refresh captured in a HIP graph: three replays with eager work in between, each compared
     with the eager result of the same step from the same state."""
