@@ -323,6 +323,40 @@ def test_refresh_of_a_long_side(canz):
     check(dev, grads, states, None, hp, "soap 3200x384")
 
 
+def test_config4_share_in_one_call(canz):
+    """The share bench.py --optimizer soap --config 4 runs, in its launch configuration: four 25600 x 5120 matrices in
+    one call, one launch batch, max_precond_dim 10000 (the long side keeps no basis), a refresh step.  The first 64
+    panels of the 5120-sided QR are longer than the panel kernel can hold in registers.  Matrix 0 is compared with the
+    oracle in full (state, update, refreshed basis); the bases of the others are checked to be orthonormal, and every
+    output to be finite and distinct from matrix 0's."""
+    import torch
+    rows, cols, n = 25600, 5120, 4
+    log("soap config 4: inputs")
+    grads = [W.gen_grad(4, i, rows, cols)[0] for i in range(n)]
+    states = []
+    for i in range(n):
+        st = {"mom": W.gen_normal_f32(4, i, 11, rows, cols, 0.02),
+              "var": np.mean(np.square(W.gen_normal_f32(4, i, 12, 2 * rows, cols, 0.02)).reshape(2, rows, cols), axis=0),
+              "left": np.zeros((1, 1), np.float32), "q_left": np.zeros((1, 1), np.float32),      # not passed: no basis
+              "right": W.gen_spd_f32(4, i, 14, cols, 0.02 * 0.02 * rows), "q_right": W.gen_orthogonal_f32(4, i, 16, cols)}
+        states.append(st)
+    hp = canz.SoapHparams(lr=0.003, eps=1e-8, step=10, refresh=True, out_mode=canz.OUT_DELTA, max_precond_dim=10000)
+    dev = SoapDevice(canz, rows, cols, grads, states, max_precond_dim=10000)
+    assert not dev.use_left and dev.use_right
+    log("soap config 4: device step")
+    run(canz, [dev], hp)
+    for i in range(1, n):
+        q = dev.t["q_right"][i]
+        orth = float((q.T @ q - torch.eye(cols, device="cuda")).abs().max())
+        assert orth <= TOL_ORTH, "basis of matrix %d: Q^T Q - I = %.3g" % (i, orth)
+        assert bool(torch.isfinite(dev.out_t[i]).all()) and not torch.equal(dev.out_t[i], dev.out_t[0])
+    log("soap config 4: oracle on matrix 0 (fp64)")
+    one = SoapDevice.__new__(SoapDevice)
+    one.__dict__.update(dev.__dict__)
+    one.n = 1
+    check(one, grads[:1], states[:1], None, hp, "soap 25600x5120, right side only")
+
+
 def test_step_under_graph_capture_replays(canz):
     """A step without refresh captured in a HIP graph: three replays with eager work in between, each compared
     with the eager result of the same step from the same state."""
