@@ -357,21 +357,23 @@ def test_config4_share_in_one_call(canz):
     check(one, grads[:1], states[:1], None, hp, "soap 25600x5120, right side only")
 
 
-def test_step_under_graph_capture_replays(canz):
-    """A step without refresh captured in a HIP graph: three replays with eager work in between, each compared
-    with the eager result of the same step from the same state."""
+@pytest.mark.parametrize("refresh", [False, True], ids=["plain", "refresh"])
+def test_step_under_graph_capture_replays(canz, refresh):
+    """A step (plain, and with the basis refresh: a few hundred more kernels, one of them the fill of Q^T, no memset)
+    captured in a HIP graph: three replays with eager work in between, each compared bit for bit with the eager
+    result of the same step from the same state."""
     import torch
     rows, cols, n = 200, 136, 2
     grads = [W.gen_grad(68, i, rows, cols)[0] for i in range(n)]
     states = [W.gen_soap_state(68, i, rows, cols) for i in range(n)]
-    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=3, out_mode=canz.OUT_DELTA)
+    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=3, out_mode=canz.OUT_DELTA, refresh=refresh)
     eager = SoapDevice(canz, rows, cols, grads, states)
     run(canz, [eager], hp)
     dev = SoapDevice(canz, rows, cols, grads, states)
     groups = [dev.group()]
     nbytes = canz.canz_soap_workspace_bytes(groups, hp)
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-    saved = {k: [t.clone() for t in dev.t[k]] for k in ("mom", "var", "left", "right")}
+    saved = {k: [t.clone() for t in dev.t[k]] for k in STATE_KEYS}
     stream = torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.stream(stream):
