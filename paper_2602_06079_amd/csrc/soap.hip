@@ -155,23 +155,25 @@ __global__ __launch_bounds__(NTH) void k_soap_store_q(PtrTable q, const float* _
 }
 
 // One panel of the Householder QR factorisation: columns j0 .. j0 + 31 of the matrix whose
-// column c is row c of wk (row length dp).  One workgroup of 16 wavefronts per matrix.
-//   vall row j0 + c  <- reflector v_c (zero before row j0 + c, 1 there)
-//   ybuf [dp][32]    <- Y  = V T^T, rows klo .. dp - 1   (H_0 ... H_31 = I - V T V^T, so
-//   y2   [dp][32]    <- Y2 = V T                          H^T A = A - Y (V^T A) and H A = A - Y2 (V^T A))
-// and the panel's later columns are updated in place as each reflector is found.  Columns at or
-// beyond d (padding) and columns that are already zero below the diagonal get tau = 0 (H = I).
+// column c is row c of wk (row length dp).  One workgroup of 16 wavefronts per matrix, two kernels.
+// The first finds the reflectors:
+//   vall row j0 + c  <- reflector v_c (zero before row j0 + c, 1 there),   tau[c] <- tau_c
+// updating the panel's later columns as each reflector is found.  Columns at or beyond d (padding)
+// and columns that are already zero below the diagonal get tau = 0 (H = I).  The second
+// (k_qr_tfactor) accumulates V V^T (32 x 32, which T needs) on the matrix cores, each wavefront
+// taking every 16th block of 8 rows, sums over the wavefronts in a fixed order, forms T column by
+// column (H_0 ... H_31 = I - V T V^T), and writes
+//   ybuf [dp][32]    <- Y  = V T^T, rows klo .. dp - 1   (H^T A = A - Y (V^T A))
+//   y2   [dp][32]    <- Y2 = V T                          (H A = A - Y2 (V^T A)).
 //
 // Column c2 of the panel belongs to wavefront (c2 - 1) mod 16 for the whole kernel: it alone reads and
 // writes that column, so the columns need no synchronisation between wavefronts.  What the others
-// need of step c is the reflector v_c, which its owner leaves in LDS (for rows up to VMAX; in the
-// reflector array otherwise) together with tau_c.  Per step: every wavefront applies H_c to its own later
-// columns; barrier; the owner of column c + 1, which has just updated it and (up to 3072 rows) still
-// holds it in registers, turns it into v_(c+1); barrier.  With v in LDS the barriers only have to
-// order LDS traffic, so they do not wait for the column stores in flight.
-// A second kernel accumulates V V^T (32 x 32, which T needs) on the matrix cores, each wavefront
-// taking every 16th block of 8 rows, sums over the wavefronts in a fixed order, forms T column by
-// column, and Y, Y2 row by row.
+// need of step c is the reflector v_c, which its owner leaves in LDS (for up to VMAX rows; in the
+// reflector array otherwise) together with tau_c.  Per step: every wavefront applies H_c to its own
+// later columns; barrier; the owner of column c + 1 turns it into v_(c+1); barrier.  With v in LDS the
+// barriers only have to order LDS traffic, so they do not wait for the stores in flight.
+// Up to 3072 remaining rows the columns stay in registers for the whole kernel (k_qr_panel_regs);
+// k_qr_panel_long, for longer panels, streams them from memory (L2) on every step.
 struct QrPanel {
   float* wk;
   float* vall;
@@ -184,13 +186,33 @@ struct QrPanel {
 };
 
 constexpr int VMAX = 12288;   // rows of a reflector kept in LDS
-constexpr int XR = 12;        // float4 per lane of the next column kept in registers (3072 rows)
-constexpr int QUN = 4;        // loads in flight per lane and operand in the streaming loops
+constexpr int QUN = 8;        // loads in flight per lane in the streaming loops
 constexpr int TLD = QB + 4;   // row length of the T factor in LDS (rows 16-byte aligned)
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-__global__ __launch_bounds__(QTH) void k_qr_panel(QrPanel a) {
+// tau and the scale of v for a column with diagonal element al and sum of squares ss below it
+__device__ __forceinline__ void reflector_of(bool live, float ss, float al, float& tau, float& scale) {
+  tau = 0.f, scale = 0.f;
+  if (live && ss > 0.f) {
+    const float nrm = sqrtf(__builtin_fmaf(al, al, ss));
+    const float beta = al >= 0.f ? -nrm : nrm;
+    tau = (beta - al) / beta;
+    scale = 1.f / (al - beta);
+  }
+}
+// elements 4 q .. 4 q + 3 of v_c from those of the column
+__device__ __forceinline__ f32x4 v_of(const f32x4& x, int q, int c, float scale) {
+  f32x4 o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int r = 4 * q + e;
+    o[e] = r < c ? 0.f : (r == c ? 1.f : x[e] * scale);
+  }
+  return o;
+}
+
+__global__ __launch_bounds__(QTH) void k_qr_panel_long(QrPanel a) {
   __shared__ f32x4 s_v4[VMAX / 4];
   __shared__ float s_tau[QB];
   const int b = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -199,7 +221,6 @@ __global__ __launch_bounds__(QTH) void k_qr_panel(QrPanel a) {
   const int len = static_cast<int>(dp) - j0;     // rows j0 .. dp - 1, a multiple of 32
   const int nvec = len / 4;
   const bool vlds = len <= VMAX;
-  const bool in_regs = nvec <= 64 * XR;
   float* wk = a.wk + static_cast<int64_t>(b) * a.s_wk;
   float* vrows = a.vall + static_cast<int64_t>(b) * a.s_vall;
   auto col = [&](int c) { return reinterpret_cast<f32x4*>(wk + static_cast<int64_t>(j0 + c) * dp + j0); };
@@ -210,28 +231,18 @@ __global__ __launch_bounds__(QTH) void k_qr_panel(QrPanel a) {
     else
       __syncthreads();
   };
-  // tau and the scale of v for a column with diagonal element al and sum of squares ss below it
-  auto reflector = [&](int c, float ss, float al, float& tau, float& scale) {
-    tau = 0.f, scale = 0.f;
-    if (j0 + c < a.d && ss > 0.f) {
-      const float nrm = sqrtf(__builtin_fmaf(al, al, ss));
-      const float beta = al >= 0.f ? -nrm : nrm;
-      tau = (beta - al) / beta;
-      scale = 1.f / (al - beta);
+  // column c (in memory; this wavefront's own stores if it was updated) becomes v_c
+  auto make_v = [&](int c, float ss, float al) {
+    float tau, scale;
+    reflector_of(j0 + c < a.d, ss, al, tau, scale);
+    const f32x4* x = col(c);
+    f32x4* vg = vrow(c);
+    for (int q = lane; q < nvec; q += 64) {
+      const f32x4 o = v_of(x[q], q, c, scale);
+      if (vlds) s_v4[q] = o;
+      vg[q] = o;
     }
-  };
-  auto v_of = [&](const f32x4& x, int q, int c, float scale) {
-    f32x4 o;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int r = 4 * q + e;
-      o[e] = r < c ? 0.f : (r == c ? 1.f : x[e] * scale);
-    }
-    return o;
-  };
-  auto put_v = [&](int c, int q, const f32x4& o) {
-    if (vlds) s_v4[q] = o;
-    vrow(c)[q] = o;
+    if (lane == 0) s_tau[c] = tau;
   };
 
   if (wave == 0) {   // column 0: its head, then v_0
@@ -245,11 +256,7 @@ __global__ __launch_bounds__(QTH) void k_qr_panel(QrPanel a) {
         if (4 * q + e == 0) al = v[e];
       }
     }
-    ss = wave_sum(ss), al = wave_sum(al);
-    float tau, scale;
-    reflector(0, ss, al, tau, scale);
-    for (int q = lane; q < nvec; q += 64) put_v(0, q, v_of(x[q], q, 0, scale));
-    if (lane == 0) s_tau[0] = tau;
+    make_v(0, wave_sum(ss), wave_sum(al));
   }
   barrier();
 
@@ -257,83 +264,51 @@ __global__ __launch_bounds__(QTH) void k_qr_panel(QrPanel a) {
     const float tau = s_tau[c];
     const f32x4* vg = vrow(c);
     auto ldv = [&](int q) { return vlds ? s_v4[q] : vg[q]; };
-    f32x4 keep[XR];
     float ss2 = 0.f, al2 = 0.f;
     for (int c2 = wave + 1; c2 < QB; c2 += QWAVES) {
       if (c2 <= c) continue;
-      const bool next = c2 == c + 1;
-      if (tau == 0.f && !next) continue;           // H_c = I: nothing to apply
+      const bool next = c2 == c + 1;            // this wavefront also takes the head of the next column
+      if (tau == 0.f && !next) continue;        // H_c = I: nothing to apply
       f32x4* x = col(c2);
-      if (next && in_regs) {
+      float f = 0.f;
+      if (tau != 0.f) {
         float dot = 0.f;
-#pragma unroll
-        for (int sl = 0; sl < XR; ++sl) {
-          const int q = lane + 64 * sl;
-          if (q < nvec) {
-            keep[sl] = x[q];
-            const f32x4 y = ldv(q);
-            dot += (keep[sl][0] * y[0] + keep[sl][1] * y[1]) + (keep[sl][2] * y[2] + keep[sl][3] * y[3]);
-          }
-        }
-        const float f = tau * wave_sum(dot);
-#pragma unroll
-        for (int sl = 0; sl < XR; ++sl) {
-          const int q = lane + 64 * sl;
-          if (q < nvec) {
-            if (tau != 0.f) {
-              const f32x4 y = ldv(q);
-#pragma unroll
-              for (int e = 0; e < 4; ++e) keep[sl][e] = __builtin_fmaf(-f, y[e], keep[sl][e]);
-              x[q] = keep[sl];
-            }
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int r = 4 * q + e;
-              if (r > c2) ss2 += keep[sl][e] * keep[sl][e];
-              if (r == c2) al2 = keep[sl][e];
-            }
-          }
-        }
-      } else {
-        float f = 0.f;
-        if (tau != 0.f) {
-          float dot = 0.f;
-          for (int q0 = lane; q0 < nvec; q0 += 64 * QUN) {
-            f32x4 xv[QUN];
-#pragma unroll
-            for (int u = 0; u < QUN; ++u) xv[u] = x[min(q0 + 64 * u, nvec - 1)];   // in bounds; surplus loads unused
-#pragma unroll
-            for (int u = 0; u < QUN; ++u) {
-              const int q = q0 + 64 * u;
-              if (q < nvec) {
-                const f32x4 y = ldv(q);
-                dot += (xv[u][0] * y[0] + xv[u][1] * y[1]) + (xv[u][2] * y[2] + xv[u][3] * y[3]);
-              }
-            }
-          }
-          f = tau * wave_sum(dot);
-        }
         for (int q0 = lane; q0 < nvec; q0 += 64 * QUN) {
           f32x4 xv[QUN];
 #pragma unroll
-          for (int u = 0; u < QUN; ++u) xv[u] = x[min(q0 + 64 * u, nvec - 1)];
+          for (int u = 0; u < QUN; ++u) xv[u] = x[min(q0 + 64 * u, nvec - 1)];   // in bounds; surplus loads unused
 #pragma unroll
           for (int u = 0; u < QUN; ++u) {
             const int q = q0 + 64 * u;
             if (q < nvec) {
-              if (tau != 0.f) {
-                const f32x4 y = ldv(q);
+              const f32x4 y = ldv(q);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) xv[u][e] = __builtin_fmaf(-f, y[e], xv[u][e]);
-                x[q] = xv[u];
-              }
-              if (next) {
+              for (int e = 0; e < 4; ++e) dot = __builtin_fmaf(xv[u][e], y[e], dot);
+            }
+          }
+        }
+        f = tau * wave_sum(dot);
+      }
+      for (int q0 = lane; q0 < nvec; q0 += 64 * QUN) {
+        f32x4 xv[QUN];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                  const int r = 4 * q + e;
-                  if (r > c2) ss2 += xv[u][e] * xv[u][e];
-                  if (r == c2) al2 = xv[u][e];
-                }
+        for (int u = 0; u < QUN; ++u) xv[u] = x[min(q0 + 64 * u, nvec - 1)];
+#pragma unroll
+        for (int u = 0; u < QUN; ++u) {
+          const int q = q0 + 64 * u;
+          if (q < nvec) {
+            if (tau != 0.f) {
+              const f32x4 y = ldv(q);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) xv[u][e] = __builtin_fmaf(-f, y[e], xv[u][e]);
+              x[q] = xv[u];
+            }
+            if (next) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const int r = 4 * q + e;
+                if (r > c2) ss2 += xv[u][e] * xv[u][e];
+                if (r == c2) al2 = xv[u][e];
               }
             }
           }
@@ -341,22 +316,7 @@ __global__ __launch_bounds__(QTH) void k_qr_panel(QrPanel a) {
       }
     }
     barrier();   // every wavefront has finished with v_c
-    if (c + 1 < QB && wave == c % QWAVES) {   // the owner of column c + 1 makes v_(c+1)
-      ss2 = wave_sum(ss2), al2 = wave_sum(al2);   // one lane holds the diagonal element, the others 0
-      float tau2, scale2;
-      reflector(c + 1, ss2, al2, tau2, scale2);
-      if (in_regs) {
-#pragma unroll
-        for (int sl = 0; sl < XR; ++sl) {
-          const int q = lane + 64 * sl;
-          if (q < nvec) put_v(c + 1, q, v_of(keep[sl], q, c + 1, scale2));
-        }
-      } else {
-        const f32x4* x = col(c + 1);               // this wavefront's own stores
-        for (int q = lane; q < nvec; q += 64) put_v(c + 1, q, v_of(x[q], q, c + 1, scale2));
-      }
-      if (lane == 0) s_tau[c + 1] = tau2;
-    }
+    if (c + 1 < QB && wave == c % QWAVES) make_v(c + 1, wave_sum(ss2), wave_sum(al2));   // al2: one lane holds it
     barrier();   // v_(c+1) and tau_(c+1) are in place
   }
   if (t < QB) (a.tau + static_cast<int64_t>(b) * QB)[t] = s_tau[t];
@@ -417,7 +377,7 @@ __device__ __forceinline__ void apply_reflector(f32x4 (&ka)[XS], f32x4 (&kb)[XS]
   }
 }
 
-// The same first half for panels of at most 256 XS remaining rows (XS = 8: 2048, XS = 12: 3072): every
+// The first kernel of a panel with at most 256 XS remaining rows (XS = 8: 2048, XS = 12: 3072): every
 // wavefront loads its two columns (wave + 1 and wave + 17) into registers once and keeps them there; a step
 // reads v_c from LDS, and the owner of column c + 1 writes v_(c+1) to LDS and to the reflector array.  The
 // columns are never written back: what the factorisation leaves in them is R, which nothing uses.
@@ -462,24 +422,14 @@ __global__ __launch_bounds__(QTH) void k_qr_panel_regs(QrPanel a) {
   };
   // column c (in k), whose head is (ss, al), becomes the reflector v_c: to LDS, to the reflector array, tau to LDS
   auto make_v = [&](const f32x4 (&k)[XS], int c, float ss, float al) {
-    float tau = 0.f, scale = 0.f;
-    if (j0 + c < a.d && ss > 0.f) {
-      const float nrm = sqrtf(__builtin_fmaf(al, al, ss));
-      const float beta = al >= 0.f ? -nrm : nrm;
-      tau = (beta - al) / beta;
-      scale = 1.f / (al - beta);
-    }
+    float tau, scale;
+    reflector_of(j0 + c < a.d, ss, al, tau, scale);
     f32x4* vg = reinterpret_cast<f32x4*>(vrows + static_cast<int64_t>(j0 + c) * dp + j0);
 #pragma unroll
     for (int sl = 0; sl < XS; ++sl) {
       const int q = lane + 64 * sl;
       if (q < nvec) {
-        f32x4 o;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = 4 * q + e;
-          o[e] = r < c ? 0.f : (r == c ? 1.f : k[sl][e] * scale);
-        }
+        const f32x4 o = v_of(k[sl], q, c, scale);
         s_v4[q] = o;
         vg[q] = o;
       }
@@ -529,7 +479,7 @@ __global__ __launch_bounds__(QTH) void k_qr_panel_regs(QrPanel a) {
   if (t < QB) (a.tau + static_cast<int64_t>(b) * QB)[t] = s_tau[t];
 }
 
-// Second half of a panel: T from the reflectors and their tau, then Y and Y2 (see k_qr_panel).
+// Second kernel of a panel: T from the reflectors and their tau, then Y and Y2 (see above).
 __global__ __launch_bounds__(QTH) void k_qr_tfactor(QrPanel a) {
   __shared__ float s_part[8 * 1024];
   __shared__ float s_g[QB][QB + 1];
@@ -776,7 +726,7 @@ int refresh_side(void* const* q_tab, int first, int nb, int64_t d, int64_t dp, c
     else if (dp - j0 <= 64 * 4 * 12)
       hipLaunchKernelGGL(k_qr_panel_regs<12>, dim3(nb), dim3(QTH), 0, st, a);
     else
-      hipLaunchKernelGGL(k_qr_panel, dim3(nb), dim3(QTH), 0, st, a);
+      hipLaunchKernelGGL(k_qr_panel_long, dim3(nb), dim3(QTH), 0, st, a);
     hipLaunchKernelGGL(k_qr_tfactor, dim3(nb), dim3(QTH), 0, st, a);
     prof_mark(st, CANZ_KERNEL_SOAP_PANEL, false);
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "panel kernel: %s", hipGetErrorString(e));
