@@ -277,6 +277,37 @@ def test_rank_deficient_refresh(canz):
     check(dev, grads, states, None, hp, "soap rank-deficient", basis_kw={"q_left": {"unique_cols": cols, "tol_q": 1e-3}})
 
 
+def test_zero_gradient_and_empty_state(canz):
+    """G = 0 from an empty state with a refresh: no update, every moment and statistic stays zero, and the QR of the
+    zero matrix leaves every reflector switched off (tau = 0), so the refreshed bases are the identity."""
+    rows, cols, n = 136, 72, 2
+    grads = [np.zeros((rows, cols), np.uint16) for _ in range(n)]
+    states = [W.gen_soap_state(70, i, rows, cols, identity_bases=False) for i in range(n)]
+    for st in states:
+        for k in ("mom", "var", "left", "right"):
+            st[k][:] = 0
+    params = [W.gen_param(70, i, rows, cols) for i in range(n)]
+    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=1, refresh=True)
+    dev = SoapDevice(canz, rows, cols, grads, states, outs=params)
+    run(canz, [dev], hp)
+    for i in range(n):
+        assert np.array_equal(dev.out_host(i), widen(params[i]))
+        for k in ("mom", "var", "left", "right"):
+            assert not dev.state_host(k, i).any(), k
+        assert np.array_equal(dev.state_host("q_left", i), np.eye(rows)) and np.array_equal(dev.state_host("q_right", i), np.eye(cols))
+
+
+def test_first_refresh_from_identity_bases(canz):
+    """The usual start: identity bases, a few steps of statistics, then the first refresh (the QR of S itself)."""
+    rows, cols, n = 264, 200, 2
+    states = [W.gen_soap_state(71, i, rows, cols, identity_bases=True) for i in range(n)]
+    grads = [W.gen_grad(71, i, rows, cols)[0] for i in range(n)]
+    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=10, refresh=True, out_mode=canz.OUT_DELTA)
+    dev = SoapDevice(canz, rows, cols, grads, states)
+    run(canz, [dev], hp)
+    check(dev, grads, states, None, hp, "soap first refresh from identity")
+
+
 def test_two_groups_in_one_call_and_batches_are_independent(canz):
     """Two shape classes in one call; each matrix's results are bit-identical to a call with that matrix alone."""
     import torch
