@@ -354,6 +354,41 @@ def test_refresh_of_a_long_side(canz):
     check(dev, grads, states, None, hp, "soap 3200x384")
 
 
+def test_config2_share_in_one_call(canz):
+    """The share bench.py --optimizer soap runs by default, in its launch configuration: Algorithm 1 with W = SOAP
+    FLOPs on the 0.6B-shaped set, the most loaded rank's 15 matrices of 3072 x 1024 as two micro-groups (8 + 7) in one
+    call, a refresh step.  One matrix of each group is compared with the oracle in full; the others' bases are checked
+    to be orthonormal and their outputs to be finite and different from one another."""
+    import torch
+    s = W.matrix_set(2)
+    _, owner, load = canz.canz_partition_alpha(s["rows"], s["cols"], s["bucket_off"], s["n_ranks"], 1.0,
+                                               cost_kind=canz.COST_SOAP_FLOPS)
+    rank = int(np.argmax(load))
+    groups = canz.canz_microgroup_plan(s["rows"], s["cols"], s["dtype"], owner, rank, max_mats=8)
+    assert [len(g) for g in groups] == [8, 7] and {(s["rows"][p], s["cols"][p]) for g in groups for p in g} == {(3072, 1024)}
+    rows, cols = 3072, 1024
+    hp = canz.SoapHparams(lr=0.003, eps=1e-8, step=10, refresh=True, out_mode=canz.OUT_DELTA)
+    devs, inputs = [], []
+    for g in groups:
+        log("soap config 2: inputs of a group of %d" % len(g))
+        grads = [W.gen_grad(2, p, rows, cols)[0] for p in g]
+        states = [W.gen_soap_state(2, p, rows, cols, identity_bases=(k > 0)) for k, p in enumerate(g)]
+        devs.append(SoapDevice(canz, rows, cols, grads, states))
+        inputs.append((grads, states))
+    run(canz, devs, hp)
+    for dev, (grads, states) in zip(devs, inputs):
+        for i in range(1, dev.n):
+            for key, d in (("q_left", rows), ("q_right", cols)):
+                q = dev.t[key][i]
+                orth = float((q.T @ q - torch.eye(d, device="cuda")).abs().max())
+                assert orth <= TOL_ORTH, "%s of matrix %d: Q^T Q - I = %.3g" % (key, i, orth)
+            assert bool(torch.isfinite(dev.out_t[i]).all()) and not torch.equal(dev.out_t[i], dev.out_t[i - 1])
+        one = SoapDevice.__new__(SoapDevice)
+        one.__dict__.update(dev.__dict__)
+        one.n = 1
+        check(one, grads[:1], states[:1], None, hp, "soap config 2 share, group of %d, matrix 0" % dev.n)
+
+
 def test_config4_share_in_one_call(canz):
     """The share bench.py --optimizer soap --config 4 runs, in its launch configuration: four 25600 x 5120 matrices in
     one call, one launch batch, max_precond_dim 10000 (the long side keeps no basis), a refresh step.  The first 64
