@@ -158,10 +158,12 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
   if (nk > 1) fetch(1, 1);
   stash(0, 0);
   __syncthreads();
-  for (int kt = 0; kt < nk; kt += 2) {
+  int kt = 0;
+  for (; kt + 1 < nk; kt += 2) {   // pairs of stages without a test between them: the two halves schedule as one body
     stage(kt, 0, 0, 1);
-    if (kt + 1 < nk) stage(kt + 1, 1, 1, 0);
+    stage(kt + 1, 1, 1, 0);
   }
+  if (kt < nk) stage(kt, 0, 0, 1);   // odd stage count (k = 32 (2 j + 1)): only the products of a QR panel
   if (!FOLD) {
 #pragma unroll
     for (int i = 0; i < NI; ++i)
@@ -201,6 +203,14 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
       } else {  // SE_STAT
         float* S = static_cast<float*>(stat.p[b]);
         const int d = static_cast<int>(g.d);
+        // all old values are requested before the first store, so that the 16 read-modify-writes overlap
+        // instead of running as a chain of dependent memory round trips
+        float old[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = row0 + 8 * (r >> 2) + (r & 3);
+          old[r] = g.beta != 0.f && row < d && col < d ? S[static_cast<int64_t>(row) * d + col] : 0.f;
+        }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int row = row0 + 8 * (r >> 2) + (r & 3);
@@ -208,13 +218,14 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
           if (row < d && col < d) {
             const int64_t at = static_cast<int64_t>(row) * d + col;
             val = g.gscale * v[r];
-            if (g.beta != 0.f) val += g.beta * S[at];
+            if (g.beta != 0.f) val += g.beta * old[r];
             S[at] = val;
             if (mirror) S[static_cast<int64_t>(col) * d + row] = val;
             if (row == col) val += g.eps;
           }
           v[r] = val;
         }
+        if (g.c == nullptr) continue;   // the padded copy is only wanted when something reads it
         put16(g.c + cb, g.ldc, row0, col, v, mirror);
       }
     }

@@ -856,7 +856,7 @@ int run_batch(const canz_soap_group& g, int first, int nb, const canz_soap_hpara
     for (int i = 0; i < nb; ++i) tab.p[i] = stat_tab[first + i];
     ShGemm q{};
     q.M = dp, q.N = dp, q.K = kp, q.ldp = kp, q.ldq = kp, q.sp = 2 * plane, q.sq = 2 * plane;
-    q.P = side, q.Q = side, q.c = stat, q.d = d, q.beta = hp.beta2, q.gscale = 1.f - hp.beta2, q.eps = 0.f;
+    q.P = side, q.Q = side, q.c = hp.refresh ? stat : nullptr, q.d = d, q.beta = hp.beta2, q.gscale = 1.f - hp.beta2, q.eps = 0.f;
     CANZ_HIP(CANZ_KERNEL_SOAP_STAT, (launch_gemm<SE_STAT, true>(q, nb, tab, s, o, st)), "statistics kernel");
     if (!hp.refresh) return CANZ_OK;
     return refresh_side(q_tab, first, nb, d, dp, stat, qt_old, ws, c, s, o, st);
