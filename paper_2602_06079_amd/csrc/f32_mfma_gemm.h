@@ -64,8 +64,8 @@ __device__ __forceinline__ void put16(float* C, int64_t ld, int row0, int col, c
 
 // BN = 128: 128 x 128 tiles, each wavefront a 64 x 64 quarter.  BN = 32 (for products whose N is 32, the
 // width of a QR panel): 128 x 32 tiles, each wavefront a 32 x 32 block of rows.
-template <int EPI, bool SYM, int BN = SB>
-__global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape s, OutSpec o) {
+template <int EPI, bool SYM, int BN>
+__device__ __forceinline__ void sh_gemm_body(const ShGemm& g, const PtrTable& stat, const Shape& s, const OutSpec& o) {
   static_assert(BN == SB || (BN == 32 && !SYM), "tile widths: 128, or 32 for plain products");
   constexpr int NI = BN == SB ? 2 : 1;   // 32 x 32 MFMA tiles per wavefront, along M and along N
   constexpr int QX = BN / 32;            // 32-row groups of the Q tile
@@ -233,6 +233,20 @@ __global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape 
 }
 
 template <int EPI, bool SYM, int BN = SB>
+__global__ __launch_bounds__(NTH) void k_sh_gemm(ShGemm g, PtrTable stat, Shape s, OutSpec o) {
+  sh_gemm_body<EPI, SYM, BN>(g, stat, s, o);
+}
+// The statistics variant carries a second set of accumulators; left to itself the register allocator takes
+// more than half of a SIMD's registers for it, which leaves one block per CU and nothing to cover its
+// barriers and epilogue with (MFMA pipe 40 % busy).  Held to two wavefronts per SIMD it fits without spills.
+// The other variants are left alone: under the same limit they lose their AGPR accumulators and 5 % of their rate.
+template <int EPI, bool SYM, int BN = SB>
+__global__ __launch_bounds__(NTH) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_sh_gemm_2w(ShGemm g, PtrTable stat, Shape s,
+                                                                                             OutSpec o) {
+  sh_gemm_body<EPI, SYM, BN>(g, stat, s, o);
+}
+
+template <int EPI, bool SYM, int BN = SB>
 hipError_t launch_gemm(ShGemm g, int nb, const PtrTable& stat, const Shape& s, const OutSpec& o, hipStream_t st) {
   if (g.M < SB || g.N < BN || g.K < SK || g.M % SB || g.N % BN || g.K % SK || (SYM && g.M != g.N)) return hipErrorInvalidValue;
   if (g.ldc == 0) g.ldc = g.N, g.sc = g.M * g.N;
@@ -240,7 +254,10 @@ hipError_t launch_gemm(ShGemm g, int nb, const PtrTable& stat, const Shape& s, c
   if (g.qdiv == 0) g.qdiv = 1;
   const int64_t tm = g.M / SB, tn = g.N / BN;
   const int64_t blocks = (SYM ? tm * (tm + 1) / 2 : tm * tn) * nb;
-  hipLaunchKernelGGL((k_sh_gemm<EPI, SYM, BN>), dim3(static_cast<unsigned>(blocks)), dim3(NTH), 0, st, g, stat, s, o);
+  if constexpr (EPI == SE_STAT)
+    hipLaunchKernelGGL((k_sh_gemm_2w<EPI, SYM, BN>), dim3(static_cast<unsigned>(blocks)), dim3(NTH), 0, st, g, stat, s, o);
+  else
+    hipLaunchKernelGGL((k_sh_gemm<EPI, SYM, BN>), dim3(static_cast<unsigned>(blocks)), dim3(NTH), 0, st, g, stat, s, o);
   return hipGetLastError();
 }
 
