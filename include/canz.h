@@ -254,10 +254,12 @@ int canz_muon_step(const canz_group* g, int32_t n_groups, const canz_muon_hparam
  * beta = 1 gives the running sums of the original algorithm (initialise L and R to eps0 I for
  * its L_0 = eps0 I, or to zero and pass eps).  The inverse fourth roots are computed in fp32
  * by root_iters rounds of a matmul-only coupled Newton iteration
- * (T = (5 I - M) / 4; X <- X T; M <- T^4 M; from M = z A, X = z^(1/4) I, z = 5 / (2 ||A||_F)),
+ * (T = (5 I - M) / 4; X <- X T; M <- T^4 M; from M = z A, X = z^(1/4) I, z = 5 / (2 b) with
+ * b = ||A|| ||A'^4||^(1/4), A' = A / ||A||, Frobenius norms: an upper bound of the largest eigenvalue
+ * that is at most d^(1/8) above it, for two products before the first round),
  * which converges to A^(-1/4) for symmetric positive definite A = S + eps I once the
- * smallest eigenvalue of M has grown to 1: about log(cond(A)) / log(2.44) + 5 rounds (25 rounds
- * cover cond(A) <= 10^6).  eps must be large enough that A is positive definite in fp32:
+ * smallest eigenvalue of M has grown to 1: about log(d^(1/8) cond(A) / 2.5) / log(2.44) + 4 rounds
+ * (22 rounds cover cond(A) <= 10^6 up to d = 32768; 25 is the default).  eps must be large enough that A is positive definite in fp32:
  * eps >= 10^-6 lambda_max(S) is safe; below that the iteration may diverge (NaN output).
  * Because the statistics are held in fp32, the update's relative error against exact arithmetic
  * grows like 1.3e-8 lambda_max(S) / eps: below 5e-3 for eps >= 10^-5 lambda_max(S).
@@ -280,7 +282,7 @@ typedef struct {
 
 typedef struct {
   float beta, lr, weight_decay, eps;
-  int32_t root_iters;       /* >= 1; 25 is the default of the cost model CANZ_COST_SHAMPOO_FLOPS */
+  int32_t root_iters;       /* >= 1; 25 is the default (also that of the cost model CANZ_COST_SHAMPOO_FLOPS) */
   int32_t out_mode;         /* CANZ_OUT_* */
 } canz_shampoo_hparams;
 

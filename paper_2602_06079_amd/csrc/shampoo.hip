@@ -14,7 +14,8 @@
 // same accumulators, which halves their work and keeps the iterates symmetric bit for bit.
 //
 // Inverse fourth root (coupled Newton iteration for the inverse p-th root, p = 4): from
-// M = z A, X = z^(1/4) I with z = 5 / (2 ||A||_F), repeat T = (5 I - M) / 4, X <- X T,
+// M = z A, X = z^(1/4) I with z = 5 / (2 b), b an upper bound of the largest eigenvalue (see k_sh_init),
+// repeat T = (5 I - M) / 4, X <- X T,
 // M <- T^4 M; M -> I and X -> A^(-1/4).  Four products per round: X T, T T, T^2 T^2, T^4 M (the
 // last one also writes the next T).  The round count is fixed by the caller: no test of
 // convergence is read back, so the step never synchronises and can be captured in a graph.
@@ -56,20 +57,40 @@ __global__ __launch_bounds__(NTH) void k_sh_sumsq(const float* __restrict__ a, i
   if (t == 0) partial[b * NPART + p] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
 }
 
-// Start of the root iteration: z = 5 / (2 ||A||_F); M = z A; T = 5/4 I - 1/4 M; X = z^(1/4) I.
-__global__ __launch_bounds__(NTH) void k_sh_init(const float* __restrict__ a, const float* __restrict__ partial,
+// Start of the root iteration.  The iteration needs M = z A with eigenvalues in (0, 5); the closer the largest
+// comes to 5/2 the fewer rounds the smallest needs to grow to 1.  ||A||_F bounds the largest eigenvalue of A,
+// but loosely (by sqrt(d) for a flat spectrum: three and a half rounds at d = 3072); ||A'^4||_F^(1/4) with
+// A' = A / ||A||_F is a bound too, at most d^(1/8) above it, for two products.
+//   k_sh_prescale:  A' = A / ||A||_F
+//   k_sh_init:      z' = 5 / (2 ||A'^4||_F^(1/4));  M = z' A';  T = 5/4 I - 1/4 M;  X = (z' / ||A||_F)^(1/4) I
+__device__ __forceinline__ double sum_partials(const float* partial, int b) {
+  double sum = 0.0;
+  for (int i = 0; i < NPART; ++i) sum += static_cast<double>(partial[b * NPART + i]);
+  return sum;
+}
+
+__global__ __launch_bounds__(NTH) void k_sh_prescale(const float* __restrict__ a, const float* __restrict__ partial,
+                                                      int64_t elems, float* __restrict__ m) {
+  const int b = blockIdx.y;
+  const float nrm = static_cast<float>(sqrt(sum_partials(partial, b)));
+  const float inv = nrm > 0.f ? 1.f / nrm : 0.f;
+  const int64_t off = static_cast<int64_t>(b) * elems;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * NTH + threadIdx.x; i < elems; i += static_cast<int64_t>(gridDim.x) * NTH)
+    m[off + i] = inv * a[off + i];
+}
+
+__global__ __launch_bounds__(NTH) void k_sh_init(const float* __restrict__ partial, const float* __restrict__ partial4,
                                                   int64_t dp, float* __restrict__ x, float* __restrict__ m,
                                                   float* __restrict__ tt) {
   const int b = blockIdx.y;
-  double sum = 0.0;
-  for (int i = 0; i < NPART; ++i) sum += static_cast<double>(partial[b * NPART + i]);
-  const float nrm = static_cast<float>(sqrt(sum));
-  const float z = nrm > 0.f ? 2.5f / nrm : 1.f;
-  const float x0 = sqrtf(sqrtf(z));
+  const float nrm = static_cast<float>(sqrt(sum_partials(partial, b)));
+  const float bound = static_cast<float>(pow(sum_partials(partial4, b), 0.125));   // ||A'^4||_F^(1/4) >= lambda_max(A')
+  const float z = bound > 0.f ? 2.5f / bound : 1.f;
+  const float x0 = nrm > 0.f ? sqrtf(sqrtf(z / nrm)) : 1.f;
   const int64_t elems = dp * dp, off = static_cast<int64_t>(b) * elems;
   for (int64_t i = static_cast<int64_t>(blockIdx.x) * NTH + threadIdx.x; i < elems; i += static_cast<int64_t>(gridDim.x) * NTH) {
     const bool diag = (i / dp) == (i % dp);
-    const float mv = z * a[off + i];
+    const float mv = z * m[off + i];
     m[off + i] = mv;
     tt[off + i] = (diag ? 1.25f : 0.f) - 0.25f * mv;
     x[off + i] = diag ? x0 : 0.f;
@@ -77,7 +98,7 @@ __global__ __launch_bounds__(NTH) void k_sh_init(const float* __restrict__ a, co
 }
 
 struct Carve {   // float offsets into the workspace of one launch batch
-  size_t gs, gt, tmp, lroot, rroot, a, x[2], m[2], t, t2, t4, partial, total_bytes;
+  size_t gs, gt, tmp, lroot, rroot, a, x[2], m[2], t, t2, t4, partial, partial4, total_bytes;
 };
 
 Carve carve(int64_t rows, int64_t cols, int nb) {
@@ -96,6 +117,7 @@ Carve carve(int64_t rows, int64_t cols, int nb) {
   c.m[0] = take(nb * dm * dm), c.m[1] = take(nb * dm * dm);
   c.t = take(nb * dm * dm), c.t2 = take(nb * dm * dm), c.t4 = take(nb * dm * dm);
   c.partial = take(static_cast<size_t>(nb) * NPART);
+  c.partial4 = take(static_cast<size_t>(nb) * NPART);
   c.total_bytes = off * sizeof(float);
   return c;
 }
@@ -178,23 +200,30 @@ int run_batch(const canz_shampoo_group& g, int first, int nb, const canz_shampoo
     for (int i = 0; i < nb; ++i) stat.p[i] = stat_tab[first + i];
     const int64_t dd = dp * dp;
     float *a = ws + c.a, *x[2] = {ws + c.x[0], ws + c.x[1]}, *m[2] = {ws + c.m[0], ws + c.m[1]};
-    float *tt = ws + c.t, *t2 = ws + c.t2, *t4 = ws + c.t4, *partial = ws + c.partial;
+    float *tt = ws + c.t, *t2 = ws + c.t2, *t4 = ws + c.t4, *partial = ws + c.partial, *partial4 = ws + c.partial4;
     ShGemm q{};
     q.M = dp, q.N = dp, q.K = kp, q.ldp = kp, q.ldq = kp, q.sp = dp * kp, q.sq = dp * kp;
     q.P = side, q.Q = side, q.c = a, q.d = d, q.beta = hp.beta, q.gscale = 1.f, q.eps = hp.eps;
     CANZ_HIP(CANZ_KERNEL_SH_STAT, (launch_gemm<SE_STAT, true>(q, nb, stat, s, o, st)), "statistics kernel");
-    prof_mark(st, CANZ_KERNEL_SH_INIT, true);
-    hipLaunchKernelGGL(k_sh_sumsq, dim3(NPART, nb), dim3(NTH), 0, st, a, dd, partial);
-    const unsigned init_blocks = static_cast<unsigned>(std::min<int64_t>(4096, (dd + NTH - 1) / NTH));
-    hipLaunchKernelGGL(k_sh_init, dim3(init_blocks, nb), dim3(NTH), 0, st, a, partial, dp, x[0], m[0], tt);
-    prof_mark(st, CANZ_KERNEL_SH_INIT, false);
-    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "root start: %s", hipGetErrorString(e));
     auto prod = [&](const float* P, const float* Q, float* C) {
       ShGemm r{};
       r.M = dp, r.N = dp, r.K = dp, r.ldp = dp, r.ldq = dp, r.sp = dd, r.sq = dd;
       r.P = P, r.Q = Q, r.c = C;
       return r;
     };
+    const unsigned init_blocks = static_cast<unsigned>(std::min<int64_t>(4096, (dd + NTH - 1) / NTH));
+    prof_mark(st, CANZ_KERNEL_SH_INIT, true);
+    hipLaunchKernelGGL(k_sh_sumsq, dim3(NPART, nb), dim3(NTH), 0, st, a, dd, partial);
+    hipLaunchKernelGGL(k_sh_prescale, dim3(init_blocks, nb), dim3(NTH), 0, st, a, partial, dd, m[0]);
+    prof_mark(st, CANZ_KERNEL_SH_INIT, false);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "root start: %s", hipGetErrorString(e));
+    CANZ_HIP(CANZ_KERNEL_SH_ROOT, (launch_gemm<SE_PLAIN, true>(prod(m[0], m[0], t2), nb, none, s, o, st)), "root start (A A)");
+    CANZ_HIP(CANZ_KERNEL_SH_ROOT, (launch_gemm<SE_PLAIN, true>(prod(t2, t2, t4), nb, none, s, o, st)), "root start (A2 A2)");
+    prof_mark(st, CANZ_KERNEL_SH_INIT, true);
+    hipLaunchKernelGGL(k_sh_sumsq, dim3(NPART, nb), dim3(NTH), 0, st, t4, dd, partial4);
+    hipLaunchKernelGGL(k_sh_init, dim3(init_blocks, nb), dim3(NTH), 0, st, partial, partial4, dp, x[0], m[0], tt);
+    prof_mark(st, CANZ_KERNEL_SH_INIT, false);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "root start: %s", hipGetErrorString(e));
     int cur = 0;
     for (int it = 0; it < hp.root_iters; ++it) {
       const bool last = it + 1 == hp.root_iters;

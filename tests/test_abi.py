@@ -114,8 +114,8 @@ def test_shampoo_argument_errors_and_workspace_without_device(canz):
     canz.canz_shampoo_step([], hp, 0, 0, 0)
     # workspace: fp32 working matrices padded to multiples of 128; rows 256, cols 512, one matrix:
     # G in two orientations and L^(-1/4) G (3 x 256 x 512), the two roots (256^2 + 512^2), eight
-    # 512 x 512 matrices of the root iteration, 64 partial sums
-    want = 4 * (3 * 256 * 512 + 256 * 256 + 512 * 512 + 8 * 512 * 512 + 64)
+    # 512 x 512 matrices of the root iteration, twice 64 partial sums
+    want = 4 * (3 * 256 * 512 + 256 * 256 + 512 * 512 + 8 * 512 * 512 + 128)
     assert canz.canz_shampoo_workspace_bytes([G(rows=256, cols=512, n_mats=1)], hp) == want
     assert canz.canz_shampoo_workspace_bytes([G(rows=200, cols=500, n_mats=1)], hp) == want
     assert ctypes.sizeof(canz._ShGroup) == 16 + 16 + 32 and ctypes.sizeof(canz._ShHparams) == 24

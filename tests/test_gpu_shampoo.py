@@ -192,6 +192,30 @@ def test_zero_gradient_and_empty_group(canz):
     canz.canz_shampoo_step([empty], hp, None, 0, torch.cuda.current_stream().cuda_stream)
 
 
+def test_round_count_for_condition_1e6(canz):
+    """22 rounds are what the header promises for cond(S + eps I) = 1e6: at that condition number the update after 22
+    rounds must agree with the update after 40 (both at the fp32 floor of the iteration), and 12 rounds must not (so
+    the case does need its rounds).  L starts with eigenvalues from 1 down to 1e-6 in a random basis; the gradient is
+    small against them and has components along all of them, the smallest amplified 31-fold by the root."""
+    rows, cols = 256, 320
+    q = W.gen_orthogonal_f32(46, 0, 3, rows).astype(np.float64)
+    left = ((q * np.logspace(0, -6, rows)) @ q.T).astype(np.float32)
+    left = np.triu(left) + np.triu(left, 1).T
+    right = np.eye(cols, dtype=np.float32)
+    g = W.gen_grad(46, 0, rows, cols, std=1e-5, dtype=W.DT_F32)[0]
+    outs = {}
+    for rounds in (12, 22, 40):
+        hp = canz.ShampooHparams(lr=1.0, eps=1e-7, root_iters=rounds, out_mode=canz.OUT_DELTA)
+        dev = ShampooDevice(canz, rows, cols, [g], [left.copy()], [right.copy()])
+        run(canz, [dev], hp)
+        outs[rounds] = dev.out_host(0)
+        assert np.isfinite(outs[rounds]).all()
+    late = rel_fro(outs[22], outs[40])
+    early = rel_fro(outs[12], outs[40])
+    log("shampoo cond 1e6: 22 vs 40 rounds %.3g, 12 vs 40 rounds %.3g" % (late, early))
+    assert late <= 5e-3 and early >= 0.05
+
+
 def test_8b_shaped_class_1024x4096(canz):
     """The k / v projection shape of the Qwen3-8B-shaped set: a 1024 x 1024 and a 4096 x 4096 root per matrix."""
     rows, cols, n = 1024, 4096, 2
