@@ -291,8 +291,12 @@ def main_soap(args, canz, W, np, torch):
     f = args.refresh_every
     limit = args.max_precond_dim
 
+    keep_rot = not args.rotate_momentum_every_step
+
     def hparams(t):
-        return canz.SoapHparams(beta1=0.95, beta2=0.95, lr=3e-3, eps=1e-8, step=t, refresh=(t % f == 0), max_precond_dim=limit)
+        # the rotated momentum is valid from the second step on (the first one rotates M and leaves M' behind)
+        return canz.SoapHparams(beta1=0.95, beta2=0.95, lr=3e-3, eps=1e-8, step=t, refresh=(t % f == 0), max_precond_dim=limit,
+                                mom_rot_valid=keep_rot and t > 1)
 
     gen = torch.Generator(device="cuda")
     gen.manual_seed(W.SEED_BASE + cfg)
@@ -308,9 +312,11 @@ def main_soap(args, canz, W, np, torch):
         qls = [torch.eye(rows, device="cuda") for _ in g] if use_l else []
         qrs = [torch.eye(cols, device="cuda") for _ in g] if use_r else []
         outs = [torch.randn(rows, cols, device="cuda", generator=gen) * 0.02 for _ in g]
-        keep.append((grads, moms, vars_, lefts, rights, qls, qrs, outs))
+        rots = [torch.zeros(rows, cols, device="cuda") for _ in g] if keep_rot else []
+        keep.append((grads, moms, vars_, lefts, rights, qls, qrs, outs, rots))
         dgroups.append(canz.SoapGroup(rows=rows, cols=cols, grad=grads, mom=moms, var=vars_, left=lefts, right=rights,
-                                      qleft=qls, qright=qrs, out=outs, grad_dtype=canz.DT_BF16, out_dtype=canz.DT_F32))
+                                      qleft=qls, qright=qrs, out=outs, mom_rot=rots, grad_dtype=canz.DT_BF16,
+                                      out_dtype=canz.DT_F32))
     ws_bytes = max(canz.canz_soap_workspace_bytes(dgroups, hparams(1)), canz.canz_soap_workspace_bytes(dgroups, hparams(f)))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
@@ -359,8 +365,10 @@ def main_soap(args, canz, W, np, torch):
         use_l, use_r = r <= limit, c <= limit
         per_rot = (2.0 * r * r * c if use_l else 0.0) + (2.0 * r * c * c if use_r else 0.0)
         per_rot_iss = (2.0 * pad(r) * pad(r) * pad(c) if use_l else 0.0) + (2.0 * pad(r) * pad(c) * pad(c) if use_r else 0.0)
-        alg["soap_rotate"] += 3 * n * per_rot * args.steps          # G and M in, the direction back
-        iss["soap_rotate"] += 3 * n * per_rot_iss * args.steps
+        # G (and M, unless its rotated image is kept) in, the direction back; M again after a refresh if it is kept
+        n_rot = (2 * args.steps + n_refresh) if keep_rot else 3 * args.steps
+        alg["soap_rotate"] += n_rot * n * per_rot
+        iss["soap_rotate"] += n_rot * n * per_rot_iss
         for d, k, used in ((r, c, use_l), (c, r, use_r)):
             if used:
                 a, i = sym(d, k)
@@ -419,9 +427,10 @@ def main_soap(args, canz, W, np, torch):
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic", "launch": "eager",
         "config": {"workload": "soap step, config %d %s partitioned by SOAP FLOPs: rank %d of %d (alpha=1), %d matrices %s in %d "
-                               "micro-groups, basis refresh every %d steps (%d of the %d timed steps), max_precond_dim %d" %
+                               "micro-groups, basis refresh every %d steps (%d of the %d timed steps), max_precond_dim %d, %s" %
                                (cfg, s["name"], rank, R, n_share, sorted({(s["rows"][p], s["cols"][p]) for g in groups for p in g}),
-                                len(groups), f, n_refresh_timed, args.steps, limit),
+                                len(groups), f, n_refresh_timed, args.steps, limit,
+                                "rotated momentum kept between steps" if keep_rot else "momentum rotated on every step"),
                    "elements": sum(s["rows"][p] * s["cols"][p] for g in groups for p in g)},
         "plain_step_ms": plain_ms, "refresh_ms": refresh_ms,
         "tflops_algorithmic": total_alg / (ms_per_step * args.steps * 1e-3) / 1e12,
@@ -444,6 +453,8 @@ def main():
                          "config 2, the 0.6B shapes)")
     ap.add_argument("--refresh-every", type=int, default=10, help="soap: basis refresh on every n-th step")
     ap.add_argument("--max-precond-dim", type=int, default=10000, help="soap: a longer side keeps no basis")
+    ap.add_argument("--rotate-momentum-every-step", action="store_true",
+                    help="soap: do not keep the rotated momentum between steps (three rotations per step instead of two)")
     ap.add_argument("--precision", choices=["bf16", "f32"], default="bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tp-schedule", type=int, default=0, metavar="MB",

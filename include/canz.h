@@ -320,6 +320,12 @@ int canz_shampoo_step(const canz_shampoo_group* g, int32_t n_groups, const canz_
  *   L <- beta2 L + (1 - beta2) G G^T,   R <- beta2 R + (1 - beta2) G^T G
  *   if refresh:  Q_L <- orthogonal factor of the QR decomposition of L Q_L,  Q_R likewise of R Q_R
  *                (one round of orthogonal iteration towards the eigenvectors; V is not rotated)
+ * Between two refreshes the bases stand still, so M' obeys the momentum recurrence itself,
+ * M' <- beta1 M' + (1 - beta1) G', and need not be rotated anew: a caller that passes mom_rot saves one
+ * of the three rotations of a step.  With mom_rot_valid = 0 the step rotates M as above and leaves M'
+ * in mom_rot; with mom_rot_valid = 1 it takes M' from mom_rot and updates it in place; a refresh step
+ * leaves it rotated into the new bases.  So mom_rot is valid after every step, and a caller passes 0
+ * only on the first step and after changing M or a basis itself.  M stays the state in the original space.
  * A side longer than max_precond_dim keeps no statistic and no basis (its Q is the identity and
  * its tables may be NULL); at least one side must be within the limit.  Everything is fp32.
  * The caller owns all state and decides when to refresh (every f-th step) and how the bases
@@ -347,6 +353,7 @@ typedef struct {
   void* const* qleft;       /* [n_mats] */
   void* const* qright;      /* [n_mats] */
   void* const* out;         /* [n_mats] parameters, or [n_mats*tp] Delta W fragments */
+  void* const* mom_rot;     /* [n_mats] rows x cols, or NULL: the rotated momentum M' kept between steps */
 } canz_soap_group;
 
 typedef struct {
@@ -356,6 +363,7 @@ typedef struct {
   int32_t refresh;          /* 1: refresh the bases at the end of this step */
   int32_t max_precond_dim;  /* >= 1 */
   int32_t out_mode;         /* CANZ_OUT_* */
+  int32_t mom_rot_valid;    /* 1: mom_rot holds Q_L^T M Q_R of the M and the bases passed in */
 } canz_soap_hparams;
 
 /*

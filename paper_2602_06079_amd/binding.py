@@ -70,13 +70,14 @@ class _SoapGroup(C.Structure):
                 ("grad_dtype", C.c_int32), ("out_dtype", C.c_int32),
                 ("grad", C.POINTER(C.c_void_p)), ("mom", C.POINTER(C.c_void_p)), ("var", C.POINTER(C.c_void_p)),
                 ("left", C.POINTER(C.c_void_p)), ("right", C.POINTER(C.c_void_p)),
-                ("qleft", C.POINTER(C.c_void_p)), ("qright", C.POINTER(C.c_void_p)), ("out", C.POINTER(C.c_void_p))]
+                ("qleft", C.POINTER(C.c_void_p)), ("qright", C.POINTER(C.c_void_p)), ("out", C.POINTER(C.c_void_p)),
+                ("mom_rot", C.POINTER(C.c_void_p))]
 
 
 class _SoapHparams(C.Structure):
     _fields_ = [("beta1", C.c_float), ("beta2", C.c_float), ("lr", C.c_float), ("weight_decay", C.c_float),
                 ("eps", C.c_float), ("step", C.c_int32), ("bias_correction", C.c_int32), ("refresh", C.c_int32),
-                ("max_precond_dim", C.c_int32), ("out_mode", C.c_int32)]
+                ("max_precond_dim", C.c_int32), ("out_mode", C.c_int32), ("mom_rot_valid", C.c_int32)]
 
 
 def _load():
@@ -359,11 +360,12 @@ class SoapHparams:
     refresh: bool = False
     max_precond_dim: int = 10000
     out_mode: int = OUT_PARAM
+    mom_rot_valid: bool = False
 
     def _c(self) -> _SoapHparams:
         return _SoapHparams(self.beta1, self.beta2, self.lr, self.weight_decay, self.eps, int(self.step),
                             int(bool(self.bias_correction)), int(bool(self.refresh)), int(self.max_precond_dim),
-                            int(self.out_mode))
+                            int(self.out_mode), int(bool(self.mom_rot_valid)))
 
 
 @dataclass
@@ -379,6 +381,7 @@ class SoapGroup:
     qleft: Sequence = field(default_factory=list)   # n_mats, fp32 rows x rows, columns are the basis vectors
     qright: Sequence = field(default_factory=list)  # n_mats, fp32 cols x cols
     out: Sequence = field(default_factory=list)     # n_mats (params) or n_mats * tp (delta fragments)
+    mom_rot: Sequence = field(default_factory=list) # n_mats, fp32 rows x cols: the rotated momentum, or empty
     tp: int = 1
     grad_dtype: int = DT_BF16
     out_dtype: int = DT_F32
@@ -391,7 +394,7 @@ def _marshal_soap(groups: Sequence[SoapGroup]):
     for i, g in enumerate(groups):
         n_mats = len(g.mom) if g.n_mats < 0 else g.n_mats
         tabs = []
-        for seq in (g.grad, g.mom, g.var, g.left, g.right, g.qleft, g.qright, g.out):
+        for seq in (g.grad, g.mom, g.var, g.left, g.right, g.qleft, g.qright, g.out, g.mom_rot):
             t = (C.c_void_p * max(len(seq), 1))(*[_addr(x) for x in seq])
             keep.append(t)
             tabs.append(C.cast(t, C.POINTER(C.c_void_p)) if len(seq) else None)

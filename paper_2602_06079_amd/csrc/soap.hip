@@ -89,11 +89,13 @@ __global__ __launch_bounds__(NTH) void k_soap_load(Shape s, PtrTable grad, int g
   }
 }
 
-// Adam in the rotated space.  rot [nb][2][rp][cp] holds G' and M'; V (dense, caller's) is updated
-// in place; N' = (c1 M') / (sqrt(c2 V) + eps) goes to np [nb][rp][cp], or transposed to
-// [nb][cp][rp]; zero outside rows x cols.
-__global__ __launch_bounds__(NTH) void k_soap_adam(Shape s, PtrTable var, const float* __restrict__ rot, int64_t rp,
-                                                    int64_t cp, float beta2, float c1, float c2, float eps, int transposed,
+// Adam in the rotated space.  rot [nb][2][rp][cp] holds G' and (unless `incremental`) M'; V (dense,
+// caller's) is updated in place; N' = (c1 M') / (sqrt(c2 V) + eps) goes to np [nb][rp][cp], or
+// transposed to [nb][cp][rp]; zero outside rows x cols.  If the caller keeps the rotated momentum
+// (`keep`, dense, mrot): incremental: M' = beta1 mrot + (1 - beta1) G'; either way mrot <- M'.
+__global__ __launch_bounds__(NTH) void k_soap_adam(Shape s, PtrTable var, PtrTable mrot, bool keep, bool incremental,
+                                                    const float* __restrict__ rot, int64_t rp, int64_t cp, float beta1,
+                                                    float beta2, float c1, float c2, float eps, int transposed,
                                                     float* __restrict__ np) {
   __shared__ float tile[64][65];
   const int b = blockIdx.z, r0 = blockIdx.y * 64, c0 = blockIdx.x * 64, t = threadIdx.x;
@@ -108,7 +110,10 @@ __global__ __launch_bounds__(NTH) void k_soap_adam(Shape s, PtrTable var, const 
     float n = 0.f;
     if (row < s.rows && col < s.cols) {
       const int64_t at = static_cast<int64_t>(row) * cp + col, av = static_cast<int64_t>(row) * s.cols + col;
-      const float g = gr[at], m = gr[plane + at];
+      const float g = gr[at];
+      float* mr = static_cast<float*>(mrot.p[b]);
+      const float m = incremental ? __builtin_fmaf(beta1, mr[av], (1.f - beta1) * g) : gr[plane + at];
+      if (keep) mr[av] = m;
       const float vn = __builtin_fmaf(beta2, v[av], (1.f - beta2) * (g * g));
       v[av] = vn;
       n = (c1 * m) / (sqrtf(c2 * vn) + eps);
@@ -124,6 +129,19 @@ __global__ __launch_bounds__(NTH) void k_soap_adam(Shape s, PtrTable var, const 
   for (int e = 0; e < 16; ++e) {
     const int idx = e * NTH + t, r = idx >> 6, c = idx & 63;
     out[static_cast<int64_t>(c0 + r) * rp + r0 + c] = tile[c][r];
+  }
+}
+
+// dense rows x cols matrices of the caller <- the padded working copies src[b * stride] (row length cp)
+__global__ __launch_bounds__(NTH) void k_soap_unpad(Shape s, PtrTable dst, const float* __restrict__ src, int64_t stride,
+                                                     int64_t cp) {
+  const int b = blockIdx.z, r0 = blockIdx.y * 64, c0 = blockIdx.x * 64, t = threadIdx.x;
+  const float* from = src + static_cast<int64_t>(b) * stride;
+  float* to = static_cast<float*>(dst.p[b]);
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    const int idx = e * NTH + t, row = r0 + (idx >> 6), col = c0 + (idx & 63);
+    if (row < s.rows && col < s.cols) to[static_cast<int64_t>(row) * s.cols + col] = from[static_cast<int64_t>(row) * cp + col];
   }
 }
 
@@ -661,7 +679,8 @@ int check_group(const canz_soap_group& g, int idx, bool need_ptrs, const canz_so
   for (int i = 0; i < g.n_mats * g.tp; ++i)
     if (bad(g.grad[i])) return fail(CANZ_EINVAL, "group %d: grad[%d] null or not 16-byte aligned", idx, i);
   for (int i = 0; i < g.n_mats; ++i) {
-    if (bad(g.mom[i]) || bad(g.var[i])) return fail(CANZ_EINVAL, "group %d: moment %d null or not 16-byte aligned", idx, i);
+    if (bad(g.mom[i]) || bad(g.var[i]) || (g.mom_rot && bad(g.mom_rot[i])))
+      return fail(CANZ_EINVAL, "group %d: moment %d null or not 16-byte aligned", idx, i);
     if (u.left && (bad(g.left[i]) || bad(g.qleft[i])))
       return fail(CANZ_EINVAL, "group %d: left state %d null or not 16-byte aligned", idx, i);
     if (u.right && (bad(g.right[i]) || bad(g.qright[i])))
@@ -794,35 +813,48 @@ int run_batch(const canz_soap_group& g, int first, int nb, const canz_soap_hpara
   prof_mark(st, CANZ_KERNEL_SOAP_LOAD, false);
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "load kernels: %s", hipGetErrorString(e));
 
-  // rotation into the bases: G' and M' as problems 2 b and 2 b + 1 of one launch
-  if (u.left && u.right) {
-    ShGemm a{};   // t1 = (X Q_R)^T: [cp][rp]
-    a.M = cp, a.N = rp, a.K = cp, a.ldp = cp, a.ldq = cp, a.sp = cp * cp, a.pdiv = 2, a.sq = plane;
-    a.P = qrt, a.Q = gm, a.c = t1;
-    CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, (launch_gemm<SE_PLAIN, false>(a, 2 * nb, none, s, o, st)), "rotation (right)");
-    ShGemm bq{};  // rot = Q_L^T (X Q_R): [rp][cp]
-    bq.M = rp, bq.N = cp, bq.K = rp, bq.ldp = rp, bq.ldq = rp, bq.sp = rp * rp, bq.pdiv = 2, bq.sq = plane;
-    bq.P = qlt, bq.Q = t1, bq.c = rot;
-    CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, (launch_gemm<SE_PLAIN, false>(bq, 2 * nb, none, s, o, st)), "rotation (left)");
-  } else if (u.left) {
-    ShGemm bq{};  // rot = Q_L^T X with X^T as the second operand
-    bq.M = rp, bq.N = cp, bq.K = rp, bq.ldp = rp, bq.ldq = rp, bq.sp = rp * rp, bq.pdiv = 2, bq.sq = plane;
-    bq.P = qlt, bq.Q = gmt, bq.c = rot;
-    CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, (launch_gemm<SE_PLAIN, false>(bq, 2 * nb, none, s, o, st)), "rotation (left)");
-  } else {
-    ShGemm a{};   // rot = X Q_R
-    a.M = rp, a.N = cp, a.K = cp, a.ldp = cp, a.ldq = cp, a.sp = plane, a.sq = cp * cp, a.qdiv = 2;
-    a.P = gm, a.Q = qrt, a.c = rot;
-    CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, (launch_gemm<SE_PLAIN, false>(a, 2 * nb, none, s, o, st)), "rotation (right)");
-  }
+  // rotation into the bases of `per` planes of each matrix's (G, M) pair, from plane `p0` on: problem p is
+  // plane p0 + p % per of matrix p / per; consecutive problems of a matrix share the basis operand
+  auto rotate_in = [&](int p0, int per) -> int {
+    const int64_t step_ = per == 2 ? plane : 2 * plane, at = p0 * plane;
+    const int count = per * nb;
+    if (u.left && u.right) {
+      ShGemm a{};   // t1 = (X Q_R)^T: [cp][rp]
+      a.M = cp, a.N = rp, a.K = cp, a.ldp = cp, a.ldq = cp, a.sp = cp * cp, a.pdiv = per, a.sq = step_;
+      a.P = qrt, a.Q = gm + at, a.c = t1 + at, a.ldc = rp, a.sc = step_;
+      CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, (launch_gemm<SE_PLAIN, false>(a, count, none, s, o, st)), "rotation (right)");
+      ShGemm bq{};  // rot = Q_L^T (X Q_R): [rp][cp]
+      bq.M = rp, bq.N = cp, bq.K = rp, bq.ldp = rp, bq.ldq = rp, bq.sp = rp * rp, bq.pdiv = per, bq.sq = step_;
+      bq.P = qlt, bq.Q = t1 + at, bq.c = rot + at, bq.ldc = cp, bq.sc = step_;
+      CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, (launch_gemm<SE_PLAIN, false>(bq, count, none, s, o, st)), "rotation (left)");
+    } else if (u.left) {
+      ShGemm bq{};  // rot = Q_L^T X with X^T as the second operand
+      bq.M = rp, bq.N = cp, bq.K = rp, bq.ldp = rp, bq.ldq = rp, bq.sp = rp * rp, bq.pdiv = per, bq.sq = step_;
+      bq.P = qlt, bq.Q = gmt + at, bq.c = rot + at, bq.ldc = cp, bq.sc = step_;
+      CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, (launch_gemm<SE_PLAIN, false>(bq, count, none, s, o, st)), "rotation (left)");
+    } else {
+      ShGemm a{};   // rot = X Q_R
+      a.M = rp, a.N = cp, a.K = cp, a.ldp = cp, a.ldq = cp, a.sp = step_, a.sq = cp * cp, a.qdiv = per;
+      a.P = gm + at, a.Q = qrt, a.c = rot + at, a.ldc = cp, a.sc = step_;
+      CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, (launch_gemm<SE_PLAIN, false>(a, count, none, s, o, st)), "rotation (right)");
+    }
+    return CANZ_OK;
+  };
+  // With a valid rotated momentum from the caller only G is rotated (M' follows its own recurrence in the rotated
+  // space, which is the same linear map as long as the bases stand still); otherwise G and M.
+  const bool incremental = g.mom_rot != nullptr && hp.mom_rot_valid != 0;
+  if (int rc = rotate_in(0, incremental ? 1 : 2)) return rc;
+  PtrTable mrot{};
+  if (g.mom_rot)
+    for (int i = 0; i < nb; ++i) mrot.p[i] = g.mom_rot[first + i];
 
   {
     const double c1 = hp.bias_correction ? 1.0 / (1.0 - std::pow(static_cast<double>(hp.beta1), hp.step)) : 1.0;
     const double c2 = hp.bias_correction ? 1.0 / (1.0 - std::pow(static_cast<double>(hp.beta2), hp.step)) : 1.0;
     const int transposed = u.left && !u.right;
     prof_mark(st, CANZ_KERNEL_SOAP_ADAM, true);
-    hipLaunchKernelGGL(k_soap_adam, tiles, dim3(NTH), 0, st, s, var, rot, rp, cp, hp.beta2, static_cast<float>(c1),
-                       static_cast<float>(c2), hp.eps, transposed, np);
+    hipLaunchKernelGGL(k_soap_adam, tiles, dim3(NTH), 0, st, s, var, mrot, g.mom_rot != nullptr, incremental, rot, rp, cp,
+                       hp.beta1, hp.beta2, static_cast<float>(c1), static_cast<float>(c2), hp.eps, transposed, np);
     prof_mark(st, CANZ_KERNEL_SOAP_ADAM, false);
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "adam kernel: %s", hipGetErrorString(e));
   }
@@ -865,6 +897,18 @@ int run_batch(const canz_soap_group& g, int first, int nb, const canz_soap_hpara
     if (int rc = one_side(g.left, g.qleft, g.rows, rp, cp, gm, qlt)) return rc;
   if (u.right)
     if (int rc = one_side(g.right, g.qright, g.cols, cp, rp, gmt, qrt)) return rc;
+  if (hp.refresh && g.mom_rot) {
+    // the caller's rotated momentum follows the new bases: M' = Q_L^T M Q_R once more, with the M of this step
+    prof_mark(st, CANZ_KERNEL_SOAP_LOAD, true);
+    if (u.left) load_basis(g.qleft, g.rows, rp, ql, qlt);
+    if (u.right) load_basis(g.qright, g.cols, cp, qr, qrt);
+    prof_mark(st, CANZ_KERNEL_SOAP_LOAD, false);
+    if (int rc = rotate_in(1, 1)) return rc;
+    prof_mark(st, CANZ_KERNEL_SOAP_ADAM, true);
+    hipLaunchKernelGGL(k_soap_unpad, tiles, dim3(NTH), 0, st, s, mrot, rot + plane, 2 * plane, cp);
+    prof_mark(st, CANZ_KERNEL_SOAP_ADAM, false);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "momentum re-rotation: %s", hipGetErrorString(e));
+  }
   return CANZ_OK;
 }
 

@@ -162,4 +162,4 @@ def test_soap_argument_errors_and_workspace_without_device(canz):
     assert canz.canz_soap_workspace_bytes(one, canz.SoapHparams(refresh=True)) == fresh
     # one-sided: no half-rotated images, no basis of the long side, the statistic of the short side only
     assert canz.canz_soap_workspace_bytes(one, canz.SoapHparams(max_precond_dim=256)) == 4 * (7 * plane + 3 * 256 * 256)
-    assert ctypes.sizeof(canz._SoapGroup) == 16 + 16 + 64 and ctypes.sizeof(canz._SoapHparams) == 40
+    assert ctypes.sizeof(canz._SoapGroup) == 16 + 16 + 72 and ctypes.sizeof(canz._SoapHparams) == 44

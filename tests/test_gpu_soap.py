@@ -31,6 +31,7 @@ pytestmark = pytest.mark.gpu
 
 TOL_MOM, TOL_STAT, TOL_VAR, TOL_UPDATE = 1e-6, 1e-5, 5e-6, 2e-5
 TOL_ORTH, TOL_TRI, TOL_Q = 5e-6, 5e-6, 1e-4
+TOL_MOM_ROT = 5e-6
 STATE_KEYS = ("mom", "var", "left", "right", "q_left", "q_right")
 
 
@@ -45,9 +46,11 @@ class SoapDevice:
     states: per matrix a dict of fp32 host arrays (STATE_KEYS); outs: parameter arrays, or None
     for Delta W fragments."""
 
-    def __init__(self, canz, rows, cols, grads, states, outs=None, tp=1, out_np_dtype=np.float32, max_precond_dim=10000):
+    def __init__(self, canz, rows, cols, grads, states, outs=None, tp=1, out_np_dtype=np.float32, max_precond_dim=10000,
+                 mom_rot=None):
         import torch
         self.canz, self.rows, self.cols, self.tp, self.n = canz, rows, cols, tp, len(states)
+        self.mom_rot_t = [] if mom_rot is None else [to_device(m) for m in mom_rot]     # the caller-held rotated momentum
         self.use_left, self.use_right = rows <= max_precond_dim, cols <= max_precond_dim
         self.t = {k: [to_device(st[k]) for st in states] for k in STATE_KEYS}
         if not self.use_left:
@@ -77,8 +80,8 @@ class SoapDevice:
     def group(self):
         return self.canz.SoapGroup(rows=self.rows, cols=self.cols, grad=self.grad_t, mom=self.t["mom"], var=self.t["var"],
                                    left=self.t["left"], right=self.t["right"], qleft=self.t["q_left"],
-                                   qright=self.t["q_right"], out=self.out_t, tp=self.tp, grad_dtype=self.grad_dtype,
-                                   out_dtype=self.out_dtype)
+                                   qright=self.t["q_right"], out=self.out_t, mom_rot=self.mom_rot_t, tp=self.tp,
+                                   grad_dtype=self.grad_dtype, out_dtype=self.out_dtype)
 
     def out_host(self, i):
         if not self.delta:
@@ -152,6 +155,13 @@ def check(dev, grads, states, params, hp, label, tol_update=TOL_UPDATE, basis_kw
                 worst["orth"], worst["tri"], worst["q"] = max(worst["orth"], orth), max(worst["tri"], tri), max(worst["q"], diff)
             else:
                 assert np.array_equal(got_q, widen(states[i][q_key])), "%s: basis changed without a refresh" % label
+        if dev.mom_rot_t:
+            # the rotated momentum the device leaves: M of this step in the bases it returns (its own, whose columns
+            # may differ in sign from the oracle's)
+            ql = dev.state_host("q_left", i) if dev.use_left else None
+            qr = dev.state_host("q_right", i) if dev.use_right else None
+            er = rel_fro(to_host64(dev.mom_rot_t[i]), SO.rotate_in(ref["mom"], ql, qr))
+            assert er <= TOL_MOM_ROT, "%s: rotated momentum of matrix %d: %.3g" % (label, i, er)
         got = dev.out_host(i)
         assert np.isfinite(got).all()
         want = ref["delta"] if params is None else ref["param"]
@@ -213,20 +223,25 @@ def test_first_step_from_empty_state_is_adam_in_the_given_bases(canz):
         check(dev, grads, states, None, hp, "soap first step, %s bases" % ("identity" if identity else "random"))
 
 
-def test_trajectory_with_refreshes(canz):
+@pytest.mark.parametrize("keep_rot", [False, True], ids=["rotate-every-step", "rotated-momentum-kept"])
+def test_trajectory_with_refreshes(canz, keep_rot):
     """Six steps, refresh on every second one; the oracle carries its own state and, after a refresh, takes the
     device's bases (they agree to TOL_Q up to column signs; the comparison of the following steps is then on the
-    same bases instead of on two bases that differ by rounding)."""
+    same bases instead of on two bases that differ by rounding).  With the rotated momentum kept by the caller the
+    first step rotates M and every later one lets M' follow its own recurrence, across the refreshes; the oracle
+    rotates M on every step."""
     rows, cols, n = 160, 288, 2
     states = [W.gen_soap_state(63, i, rows, cols) for i in range(n)]
     params = [W.gen_param(63, i, rows, cols) for i in range(n)]
     grads = [W.gen_grad(63, i, rows, cols, step=0)[0] for i in range(n)]
-    dev = SoapDevice(canz, rows, cols, grads, states, outs=params)
+    dev = SoapDevice(canz, rows, cols, grads, states, outs=params,
+                     mom_rot=[np.full((rows, cols), np.nan, np.float32) for _ in range(n)] if keep_rot else None)
     for step in range(1, 7):
         if step > 1:
             grads = [W.gen_grad(63, i, rows, cols, step=step - 1)[0] for i in range(n)]
             dev.set_grads(grads)
-        hp = canz.SoapHparams(lr=0.02, weight_decay=0.01, eps=1e-8, beta1=0.9, beta2=0.95, step=step + 4, refresh=step % 2 == 0)
+        hp = canz.SoapHparams(lr=0.02, weight_decay=0.01, eps=1e-8, beta1=0.9, beta2=0.95, step=step + 4, refresh=step % 2 == 0,
+                              mom_rot_valid=keep_rot and step > 1)
         run(canz, [dev], hp)
         check(dev, grads, states, params, hp, "soap trajectory step %d" % step)
         # next step starts from what the device holds (fp32), on both sides
@@ -244,17 +259,23 @@ def test_tp_fragments_fp32_gradients_bf16_delta(canz):
     check(dev, grads, states, None, hp, "soap tp=4 bf16 delta", tol_update=2 ** -8)     # bf16 storage of Delta W
 
 
+@pytest.mark.parametrize("keep_rot", [False, True], ids=["rotate", "kept"])
 @pytest.mark.parametrize("shape,limit", [((300, 100), 128), ((100, 300), 128), ((300, 100), 100), ((100, 300), 100)],
                          ids=lambda v: str(v).replace(" ", ""))
-def test_one_sided_above_the_limit(canz, shape, limit):
-    """The side longer than max_precond_dim has no statistic and no basis: its tables are not passed at all."""
+def test_one_sided_above_the_limit(canz, shape, limit, keep_rot):
+    """The side longer than max_precond_dim has no statistic and no basis: its tables are not passed at all.  With the
+    rotated momentum kept, the caller hands in a valid M' (the rotation of its M, computed here in fp64)."""
     rows, cols = shape
     n = 2
     grads = [W.gen_grad(65, i, rows, cols)[0] for i in range(n)]
     states = [W.gen_soap_state(65, i, rows, cols) for i in range(n)]
     params = [W.gen_param(65, i, rows, cols) for i in range(n)]
-    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=5, refresh=True, max_precond_dim=limit)
-    dev = SoapDevice(canz, rows, cols, grads, states, outs=params, max_precond_dim=limit)
+    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=5, refresh=True, max_precond_dim=limit, mom_rot_valid=keep_rot)
+    rot = None
+    if keep_rot:
+        rot = [SO.rotate_in(widen(st["mom"]), widen(st["q_left"]) if rows <= limit else None,
+                            widen(st["q_right"]) if cols <= limit else None).astype(np.float32) for st in states]
+    dev = SoapDevice(canz, rows, cols, grads, states, outs=params, max_precond_dim=limit, mom_rot=rot)
     assert dev.use_left != dev.use_right
     run(canz, [dev], hp)
     check(dev, grads, states, params, hp, "soap one-sided %dx%d limit %d" % (rows, cols, limit))
