@@ -388,13 +388,15 @@ def test_config2_share_in_one_call(canz):
     groups = canz.canz_microgroup_plan(s["rows"], s["cols"], s["dtype"], owner, rank, max_mats=8)
     assert [len(g) for g in groups] == [8, 7] and {(s["rows"][p], s["cols"][p]) for g in groups for p in g} == {(3072, 1024)}
     rows, cols = 3072, 1024
-    hp = canz.SoapHparams(lr=0.003, eps=1e-8, step=10, refresh=True, out_mode=canz.OUT_DELTA)
+    hp = canz.SoapHparams(lr=0.003, eps=1e-8, step=10, refresh=True, out_mode=canz.OUT_DELTA, mom_rot_valid=True)
     devs, inputs = [], []
     for g in groups:
         log("soap config 2: inputs of a group of %d" % len(g))
         grads = [W.gen_grad(2, p, rows, cols)[0] for p in g]
         states = [W.gen_soap_state(2, p, rows, cols, identity_bases=(k > 0)) for k, p in enumerate(g)]
-        devs.append(SoapDevice(canz, rows, cols, grads, states))
+        # the caller keeps the rotated momentum, as the benchmark does: a valid M' for every matrix
+        rot = [SO.rotate_in(widen(st["mom"]), widen(st["q_left"]), widen(st["q_right"])).astype(np.float32) for st in states]
+        devs.append(SoapDevice(canz, rows, cols, grads, states, mom_rot=rot))
         inputs.append((grads, states))
     run(canz, devs, hp)
     for dev, (grads, states) in zip(devs, inputs):
@@ -414,8 +416,8 @@ def test_config4_share_in_one_call(canz):
     """The share bench.py --optimizer soap --config 4 runs, in its launch configuration: four 25600 x 5120 matrices in
     one call, one launch batch, max_precond_dim 10000 (the long side keeps no basis), a refresh step.  The first 64
     panels of the 5120-sided QR are longer than the panel kernel can hold in registers.  Matrix 0 is compared with the
-    oracle in full (state, update, refreshed basis); the bases of the others are checked to be orthonormal, and every
-    output to be finite and distinct from matrix 0's."""
+    oracle in full (state, update, refreshed basis, re-rotated momentum); the bases of the others are checked to be
+    orthonormal, and every output to be finite and distinct from matrix 0's.  The caller keeps the rotated momentum."""
     import torch
     rows, cols, n = 25600, 5120, 4
     log("soap config 4: inputs")
@@ -427,8 +429,10 @@ def test_config4_share_in_one_call(canz):
               "left": np.zeros((1, 1), np.float32), "q_left": np.zeros((1, 1), np.float32),      # not passed: no basis
               "right": W.gen_spd_f32(4, i, 14, cols, 0.02 * 0.02 * rows), "q_right": W.gen_orthogonal_f32(4, i, 16, cols)}
         states.append(st)
-    hp = canz.SoapHparams(lr=0.003, eps=1e-8, step=10, refresh=True, out_mode=canz.OUT_DELTA, max_precond_dim=10000)
-    dev = SoapDevice(canz, rows, cols, grads, states, max_precond_dim=10000)
+    hp = canz.SoapHparams(lr=0.003, eps=1e-8, step=10, refresh=True, out_mode=canz.OUT_DELTA, max_precond_dim=10000,
+                          mom_rot_valid=True)
+    rot = [SO.rotate_in(widen(st["mom"]), None, widen(st["q_right"])).astype(np.float32) for st in states]
+    dev = SoapDevice(canz, rows, cols, grads, states, max_precond_dim=10000, mom_rot=rot)
     assert not dev.use_left and dev.use_right
     log("soap config 4: device step")
     run(canz, [dev], hp)
