@@ -12,19 +12,19 @@
 // runs right side first with its result written transposed, (G Q_R)^T = Q_R^T-rows times G-rows,
 // so that the left side finds its second operand contiguous along k; the rotation back runs
 // the same way round.  G and M travel through the rotation as two problems of one launch that
-// share the basis operand.
+// share the basis operand; with a rotated momentum kept by the caller (mom_rot) only G is rotated
+// and M' follows M' <- beta1 M' + (1 - beta1) G' in the Adam kernel.
 //
 // QR refresh: blocked Householder factorisation with panels of 32 columns, on the transposed
-// matrix (a column of S = L Q is a contiguous row of the working copy).  One workgroup per
-// matrix factors a panel in place (each wavefront owns whole columns of the panel, so the only
-// block-wide synchronisation is two barriers per column); the trailing columns are updated,
-// and afterwards the orthogonal factor is accumulated from the last panel to the first, with
-// the compact WY form H = I - V T V^T through three products per panel:
-//   Y = V [T^T | T]   (one small product against the panel's stored T),
+// matrix (a column of S = L Q is a contiguous row of the working copy).  Per panel: one workgroup
+// per matrix finds the 32 reflectors (each wavefront owns whole columns of the panel, so the only
+// block-wide synchronisation is two barriers per column), a second kernel forms the compact WY
+// factors H = I - V T V^T, Y = V T^T, Y2 = V T, and two products update the trailing columns:
 //   W = (columns) V,  (columns) -= W Y^T.
-// Tile boundaries of these products are rounded down to multiples of 128; the extra rows and
-// columns they touch either hold zeros in V (no effect) or are columns the factorisation has
-// finished with (R is never needed: only Q is).
+// Afterwards the orthogonal factor is accumulated from the last panel to the first with the same
+// two products (and Y2).  Tile boundaries of these products are rounded down to multiples of 128;
+// the extra rows and columns they touch either hold zeros in V (no effect) or are columns the
+// factorisation has finished with (R is never needed: only Q is).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
