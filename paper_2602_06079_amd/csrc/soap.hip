@@ -179,7 +179,7 @@ __global__ __launch_bounds__(NTH) void k_soap_store_q(PtrTable q, const float* _
 // updating the panel's later columns as each reflector is found.  Columns at or beyond d (padding)
 // and columns that are already zero below the diagonal get tau = 0 (H = I).  The second
 // (k_qr_tfactor) accumulates V V^T (32 x 32, which T needs) on the matrix cores, each wavefront
-// taking every 16th block of 8 rows, sums over the wavefronts in a fixed order, forms T column by
+// taking every 16th group of 32 rows, sums over the wavefronts in a fixed order, forms T column by
 // column (H_0 ... H_31 = I - V T V^T), and writes
 //   ybuf [dp][32]    <- Y  = V T^T, rows klo .. dp - 1   (H^T A = A - Y (V^T A))
 //   y2   [dp][32]    <- Y2 = V T                          (H A = A - Y2 (V^T A)).
@@ -517,16 +517,15 @@ __global__ __launch_bounds__(QTH) void k_qr_tfactor(QrPanel a) {
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     const float* vbase = vrows + static_cast<int64_t>(j0 + (lane & 31)) * dp + j0 + 4 * (lane >> 5);
     const int nblk = len / 8;
-    for (int kb0 = wave; kb0 < nblk; kb0 += QWAVES * QUN) {
-      f32x4 x[QUN];
+    // a wavefront takes four consecutive blocks at a time (32 rows x 32 k: one whole 128-byte line per row)
+    for (int kb0 = 4 * wave; kb0 < nblk; kb0 += 4 * QWAVES) {   // nblk is a multiple of 4
+      f32x4 x[4];
 #pragma unroll
-      for (int u = 0; u < QUN; ++u) x[u] = *reinterpret_cast<const f32x4*>(vbase + 8 * min(kb0 + QWAVES * u, nblk - 1));
+      for (int u = 0; u < 4; ++u) x[u] = *reinterpret_cast<const f32x4*>(vbase + 8 * (kb0 + u));
 #pragma unroll
-      for (int u = 0; u < QUN; ++u)
-        if (kb0 + QWAVES * u < nblk) {
+      for (int u = 0; u < 4; ++u)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[u][e], x[u][e], acc, 0, 0, 0);
-        }
+        for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[u][e], x[u][e], acc, 0, 0, 0);
     }
     // sum over the wavefronts in a fixed order, eight at a time through LDS
     float* scratch = s_part;
