@@ -327,7 +327,8 @@ int canz_shampoo_step(const canz_shampoo_group* g, int32_t n_groups, const canz_
  * leaves it rotated into the new bases.  So mom_rot is valid after every step, and a caller passes 0
  * only on the first step and after changing M or a basis itself.  M stays the state in the original space.
  * A side longer than max_precond_dim keeps no statistic and no basis (its Q is the identity and
- * its tables may be NULL); at least one side must be within the limit.  Everything is fp32.
+ * its tables may be NULL); at least one side must be within the limit, and a side with a basis may
+ * have at most 12288 rows or columns (the cited implementation's default limit is 10000).  Everything is fp32.
  * The caller owns all state and decides when to refresh (every f-th step) and how the bases
  * start (identity, or eigenvectors of the first statistics computed elsewhere).  The QR step is
  * a blocked Householder factorisation: the basis it writes is orthonormal to fp32 rounding and
@@ -380,7 +381,7 @@ int canz_soap_workspace_bytes(const canz_soap_group* g, int32_t n_groups, const 
  * (no allocation, copy, memset or synchronisation), completion in stream order.
  * Errors: CANZ_EINVAL (null pointers, n_mats < 0, tp outside 1..8, betas outside [0, 1), eps < 0,
  * step < 1, max_precond_dim < 1), CANZ_ESHAPE (cols not divisible by tp, fragment width not a
- * multiple of 8, an extent above 32768), CANZ_EWORKSPACE, CANZ_EUNSUPPORTED (dtype / mode enums,
+ * multiple of 8, an extent above 32768, a side with a basis above 12288), CANZ_EWORKSPACE, CANZ_EUNSUPPORTED (dtype / mode enums,
  * both extents above max_precond_dim), CANZ_EHIP.
  */
 int canz_soap_step(const canz_soap_group* g, int32_t n_groups, const canz_soap_hparams* hp,

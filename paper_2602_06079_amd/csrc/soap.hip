@@ -186,8 +186,8 @@ __global__ __launch_bounds__(NTH) void k_soap_store_q(PtrTable q, const float* _
 //
 // Column c2 of the panel belongs to wavefront (c2 - 1) mod 16 for the whole kernel: it alone reads and
 // writes that column, so the columns need no synchronisation between wavefronts.  What the others
-// need of step c is the reflector v_c, which its owner leaves in LDS (for up to VMAX rows; in the
-// reflector array otherwise) together with tau_c.  Per step: every wavefront applies H_c to its own
+// need of step c is the reflector v_c, which its owner leaves in LDS (a basis has at most VMAX rows)
+// together with tau_c.  Per step: every wavefront applies H_c to its own
 // later columns; barrier; the owner of column c + 1 turns it into v_(c+1); barrier.  With v in LDS the
 // barriers only have to order LDS traffic, so they do not wait for the stores in flight.
 // Up to 3072 remaining rows the columns stay in registers for the whole kernel (k_qr_panel_regs);
@@ -203,7 +203,7 @@ struct QrPanel {
   int j0, klo;
 };
 
-constexpr int VMAX = 12288;   // rows of a reflector kept in LDS
+constexpr int VMAX = 12288;   // rows of a reflector kept in LDS: the largest extent a side with a basis may have
 constexpr int QUN = 8;        // loads in flight per lane in the streaming loops
 constexpr int TLD = QB + 4;   // row length of the T factor in LDS (rows 16-byte aligned)
 
@@ -238,17 +238,10 @@ __global__ __launch_bounds__(QTH) void k_qr_panel_long(QrPanel a) {
   const int j0 = a.j0;
   const int len = static_cast<int>(dp) - j0;     // rows j0 .. dp - 1, a multiple of 32
   const int nvec = len / 4;
-  const bool vlds = len <= VMAX;
   float* wk = a.wk + static_cast<int64_t>(b) * a.s_wk;
   float* vrows = a.vall + static_cast<int64_t>(b) * a.s_vall;
   auto col = [&](int c) { return reinterpret_cast<f32x4*>(wk + static_cast<int64_t>(j0 + c) * dp + j0); };
   auto vrow = [&](int c) { return reinterpret_cast<f32x4*>(vrows + static_cast<int64_t>(j0 + c) * dp + j0); };
-  auto barrier = [&]() {
-    if (vlds)
-      lds_barrier();
-    else
-      __syncthreads();
-  };
   // column c (in memory; this wavefront's own stores if it was updated) becomes v_c
   auto make_v = [&](int c, float ss, float al) {
     float tau, scale;
@@ -257,7 +250,7 @@ __global__ __launch_bounds__(QTH) void k_qr_panel_long(QrPanel a) {
     f32x4* vg = vrow(c);
     for (int q = lane; q < nvec; q += 64) {
       const f32x4 o = v_of(x[q], q, c, scale);
-      if (vlds) s_v4[q] = o;
+      s_v4[q] = o;
       vg[q] = o;
     }
     if (lane == 0) s_tau[c] = tau;
@@ -276,12 +269,11 @@ __global__ __launch_bounds__(QTH) void k_qr_panel_long(QrPanel a) {
     }
     make_v(0, wave_sum(ss), wave_sum(al));
   }
-  barrier();
+  lds_barrier();
 
   for (int c = 0; c < QB; ++c) {
     const float tau = s_tau[c];
-    const f32x4* vg = vrow(c);
-    auto ldv = [&](int q) { return vlds ? s_v4[q] : vg[q]; };
+    auto ldv = [&](int q) { return s_v4[q]; };
     float ss2 = 0.f, al2 = 0.f;
     for (int c2 = wave + 1; c2 < QB; c2 += QWAVES) {
       if (c2 <= c) continue;
@@ -333,9 +325,9 @@ __global__ __launch_bounds__(QTH) void k_qr_panel_long(QrPanel a) {
         }
       }
     }
-    barrier();   // every wavefront has finished with v_c
+    lds_barrier();   // every wavefront has finished with v_c
     if (c + 1 < QB && wave == c % QWAVES) make_v(c + 1, wave_sum(ss2), wave_sum(al2));   // al2: one lane holds it
-    barrier();   // v_(c+1) and tau_(c+1) are in place
+    lds_barrier();   // v_(c+1) and tau_(c+1) are in place
   }
   if (t < QB) (a.tau + static_cast<int64_t>(b) * QB)[t] = s_tau[t];
 }
@@ -661,6 +653,8 @@ int check_group(const canz_soap_group& g, int idx, bool need_ptrs, const canz_so
   if (g.rows > MAX_EXTENT || g.cols > MAX_EXTENT)
     return fail(CANZ_ESHAPE, "group %d: extent above %lld", idx, static_cast<long long>(MAX_EXTENT));
   const Sides u = sides(g, hp);
+  if ((u.left && g.rows > VMAX) || (u.right && g.cols > VMAX))
+    return fail(CANZ_ESHAPE, "group %d: a side with a basis may have at most %d rows or columns (lower max_precond_dim)", idx, VMAX);
   if (!u.left && !u.right)
     return fail(CANZ_EUNSUPPORTED, "group %d: both extents exceed max_precond_dim (plain Adam is not part of this library)", idx);
   if (g.tp < 1 || g.tp > MAX_TP) return fail(CANZ_EINVAL, "group %d: tp must be in 1..%d", idx, MAX_TP);

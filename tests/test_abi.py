@@ -145,6 +145,8 @@ def test_soap_argument_errors_and_workspace_without_device(canz):
     assert code([G(**ok)], canz.SoapHparams(max_precond_dim=0)) == canz.EINVAL
     assert code([G(**ok)], canz.SoapHparams(out_mode=3)) == canz.EUNSUPPORTED
     assert code([G(**ok)], canz.SoapHparams(max_precond_dim=255)) == canz.EUNSUPPORTED     # neither side has a basis
+    assert code([G(**{**ok, "rows": 12289})], canz.SoapHparams(max_precond_dim=20000)) == canz.ESHAPE   # too long for a basis
+    assert canz.canz_soap_workspace_bytes([G(rows=12289, cols=512, n_mats=1)], hp) > 0                   # fine one-sided
     assert "max_precond_dim" in canz.canz_last_error()
     assert code([G(**ok)], hp, ws=0) == canz.EWORKSPACE
     assert code([G(**ok)], hp, ws_bytes=1024) == canz.EWORKSPACE
