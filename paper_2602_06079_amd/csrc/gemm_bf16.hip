@@ -1002,6 +1002,7 @@ int cu_count() {
 // small kernel when they would leave at least half of the chip idle for a whole tile time -
 // which includes launches with no full round at all.
 constexpr int64_t SMALL_MAX_K = 4096;
+constexpr int64_t SMALL_ALL_MAX_K = 2048;   // polynomial products up to this k and under two rounds: small tiles only
 
 template <int EPI>
 int64_t tile_count(const GemmDims& d) {
@@ -1013,7 +1014,11 @@ int64_t tile_count(const GemmDims& d) {
 template <int EPI>
 int64_t large_share(int64_t tiles, int64_t cus, int64_t longest_k) {
   const int64_t left = tiles % cus;
-  if (longest_k > SMALL_MAX_K || left == 0 || 2 * left > cus) return tiles;
+  if (longest_k > SMALL_MAX_K) return tiles;
+  // a polynomial product (k = m, the shortest k range of the step) of less than two rounds runs faster on small
+  // tiles throughout: 59.6 -> 52.4 us on 26 matrices of 1024 x 1024; the same rule costs the Gram product 7 %
+  if (EPI == EPI_POLY && tiles < 2 * cus && longest_k <= SMALL_ALL_MAX_K) return 0;
+  if (left == 0 || 2 * left > cus) return tiles;
   return tiles - left;
 }
 
