@@ -157,6 +157,7 @@ def main_shampoo(args, canz, W, np, torch):
         (cfg, s["name"], rank, n_share, len(groups), plan_ms, float(load.max()) / mean))
     # 22 rounds: what covers a condition number of 1e6 at these extents (25, the library default, covers 1e7)
     hp = canz.ShampooHparams(beta=0.9, eps=1e-2, lr=0.02, root_iters=22)
+    every = max(1, args.roots_every)       # 1: the roots on every step, as published
     gen = torch.Generator(device="cuda")
     gen.manual_seed(W.SEED_BASE + cfg)
     dgroups, keep = [], []
@@ -166,23 +167,31 @@ def main_shampoo(args, canz, W, np, torch):
         lefts = [torch.zeros(rows, rows, device="cuda") for _ in g]
         rights = [torch.zeros(cols, cols, device="cuda") for _ in g]
         outs = [torch.randn(rows, cols, device="cuda", generator=gen) * 0.02 for _ in g]
-        keep.append((grads, lefts, rights, outs))
-        dgroups.append(canz.ShampooGroup(rows=rows, cols=cols, grad=grads, left=lefts, right=rights, out=outs,
-                                         grad_dtype=canz.DT_BF16, out_dtype=canz.DT_F32))
+        lroots = [torch.zeros(rows, rows, device="cuda") for _ in g] if every > 1 else []
+        rroots = [torch.zeros(cols, cols, device="cuda") for _ in g] if every > 1 else []
+        keep.append((grads, lefts, rights, outs, lroots, rroots))
+        dgroups.append(canz.ShampooGroup(rows=rows, cols=cols, grad=grads, left=lefts, right=rights, out=outs, lroot=lroots,
+                                         rroot=rroots, grad_dtype=canz.DT_BF16, out_dtype=canz.DT_F32))
     ws_bytes = canz.canz_shampoo_workspace_bytes(dgroups, hp)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
 
-    def step():
-        canz.canz_shampoo_step(dgroups, hp, ws, ws_bytes, stream)
+    hp_keep = canz.ShampooHparams(beta=0.9, eps=1e-2, lr=0.02, root_iters=22, keep_roots=True)
+    t_now = [0]
+
+    def step():   # step t computes the roots if t = 1 (mod every), else it keeps the last ones
+        t_now[0] += 1
+        canz.canz_shampoo_step(dgroups, hp if (t_now[0] - 1) % every == 0 else hp_keep, ws, ws_bytes, stream)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     canz.canz_profile_enable(n_share * (12 + 8 * hp.root_iters) + 8)
+    t_now[0] = 0                           # a step with the roots: the longest there is
     step()
     torch.cuda.synchronize()
     launches_per_step = sum(n for _ms, n in canz.canz_profile_collect().values())
+    t_now[0] = args.warmup
     canz.canz_profile_enable(launches_per_step * args.steps + 8)
     torch.cuda.synchronize()
     t_start = time.perf_counter()
@@ -205,6 +214,8 @@ def main_shampoo(args, canz, W, np, torch):
 
     alg = dict(sh_stat=0.0, sh_root=0.0, sh_apply=0.0)
     iss = dict(sh_stat=0.0, sh_root=0.0, sh_apply=0.0)
+    # share of the timed steps that computed the roots
+    root_share = sum(1 for t in range(args.warmup + 1, args.warmup + args.steps + 1) if (t - 1) % every == 0) / args.steps
     for g in groups:
         r, c = s["rows"][g[0]], s["cols"][g[0]]
         n = len(g)
@@ -213,8 +224,8 @@ def main_shampoo(args, canz, W, np, torch):
             alg["sh_stat"] += n * a
             iss["sh_stat"] += n * i
             a, i = sym(d, d)
-            alg["sh_root"] += n * a * (4 * hp.root_iters - 3 + 2)      # + A'A' and A'^2 A'^2 for the starting bound
-            iss["sh_root"] += n * i * (4 * hp.root_iters - 3 + 2)
+            alg["sh_root"] += n * a * (4 * hp.root_iters - 3 + 2) * root_share      # + A'A' and A'^2 A'^2 for the starting bound
+            iss["sh_root"] += n * i * (4 * hp.root_iters - 3 + 2) * root_share
         alg["sh_apply"] += n * (2.0 * r * r * c + 2.0 * r * c * c)
         iss["sh_apply"] += n * (2.0 * pad(r) * pad(r) * pad(c) + 2.0 * pad(r) * pad(c) * pad(c))
     kernels = {}
@@ -258,9 +269,9 @@ def main_shampoo(args, canz, W, np, torch):
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic", "launch": "eager",
         "config": {"workload": "shampoo step, config %d %s partitioned by Shampoo FLOPs: rank %d of %d (alpha=1), %d matrices %s "
-                               "in %d micro-groups, %d root rounds" %
+                               "in %d micro-groups, %d root rounds, roots %s" %
                                (cfg, s["name"], rank, R, n_share, sorted({(s["rows"][p], s["cols"][p]) for g in groups for p in g}),
-                                len(groups), hp.root_iters),
+                                len(groups), hp.root_iters, "on every step" if every == 1 else "on every %d-th step" % every),
                    "elements": sum(s["rows"][p] * s["cols"][p] for g in groups for p in g)},
         "tflops_algorithmic": total_alg / (ms_per_step * 1e-3) / 1e12, "tflops_issued": total_iss / (ms_per_step * 1e-3) / 1e12,
         "frac_mfma_peak_issued": total_iss / (ms_per_step * 1e-3) / 1e12 / peak,
@@ -452,6 +463,8 @@ def main():
                          "canz_soap_step on the share Algorithm 1 assigns under that operator's FLOPs cost (default set: "
                          "config 2, the 0.6B shapes)")
     ap.add_argument("--refresh-every", type=int, default=10, help="soap: basis refresh on every n-th step")
+    ap.add_argument("--roots-every", type=int, default=1,
+                    help="shampoo: inverse roots on every n-th step, kept in between (default 1: on every step, as published)")
     ap.add_argument("--max-precond-dim", type=int, default=10000, help="soap: a longer side keeps no basis")
     ap.add_argument("--rotate-momentum-every-step", action="store_true",
                     help="soap: do not keep the rotated momentum between steps (three rotations per step instead of two)")

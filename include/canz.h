@@ -267,6 +267,10 @@ int canz_muon_step(const canz_group* g, int32_t n_groups, const canz_muon_hparam
  * One micro-group: n_mats matrices of identical shape and dtypes; grad / out / tp as in
  * canz_group; left[i] (rows x rows) and right[i] (cols x cols) are fp32, dense, row-major,
  * device, 16-byte aligned, updated in place (they stay exactly symmetric).
+ * Practical Shampoo recomputes the roots only every n-th step.  A caller that passes lroot / rroot
+ * (same layout as left / right) gets the roots of a step with keep_roots = 0 written there, and a
+ * step with keep_roots = 1 takes them from there instead of computing them: about 2 % of the cost
+ * of a full step.
  */
 typedef struct {
   int64_t rows, cols;
@@ -278,12 +282,17 @@ typedef struct {
   void* const* left;        /* [n_mats] */
   void* const* right;       /* [n_mats] */
   void* const* out;         /* [n_mats] parameters, or [n_mats*tp] Delta W fragments */
+  void* const* lroot;       /* [n_mats] rows x rows, or NULL: (L + eps I)^(-1/4) kept between steps */
+  void* const* rroot;       /* [n_mats] cols x cols, or NULL (both tables or neither) */
 } canz_shampoo_group;
 
 typedef struct {
   float beta, lr, weight_decay, eps;
   int32_t root_iters;       /* >= 1; 25 is the default (also that of the cost model CANZ_COST_SHAMPOO_FLOPS) */
   int32_t out_mode;         /* CANZ_OUT_* */
+  int32_t keep_roots;       /* 0: the roots are computed on every step (the algorithm as published);
+                               1: the step uses the roots in lroot / rroot as they are (the statistics are
+                               still updated): the amortised variant that recomputes them every n-th step */
 } canz_shampoo_hparams;
 
 /*
@@ -299,7 +308,8 @@ int canz_shampoo_workspace_bytes(const canz_shampoo_group* g, int32_t n_groups,
  * Same conventions as canz_muon_step: host tables of device pointers read during the call,
  * caller-owned 256-byte aligned workspace whose contents are scratch, kernel launches only
  * (no allocation, copy, memset or synchronisation), completion in stream order.
- * Errors: CANZ_EINVAL (null pointers, n_mats < 0, tp outside 1..8, root_iters < 1, eps < 0),
+ * Errors: CANZ_EINVAL (null pointers, n_mats < 0, tp outside 1..8, root_iters < 1, eps < 0, one root table
+ * without the other, keep_roots without the tables),
  * CANZ_ESHAPE (cols not divisible by tp, fragment width not a multiple of 8, an extent above
  * 32768), CANZ_EWORKSPACE, CANZ_EUNSUPPORTED (dtype / mode enums), CANZ_EHIP.
  */

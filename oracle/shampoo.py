@@ -16,6 +16,8 @@ paper cites for it (Gupta, Koren and Singer 2018), for one matrix:
    the symmetric eigendecomposition:  (S + eps I)^(-1/4) = V diag((lambda_i + eps)^(-1/4)) V^T;
 4. preconditioned gradient  O = (L + eps I)^(-1/4) G (R + eps I)^(-1/4);
 5. P <- P (1 - lr wd) - lr O   or   Delta W = - lr O  cut into column fragments.
+Practical variants recompute the roots of step 3 only every n-th step and use the last ones in between
+(the statistics of step 2 are still updated): shampoo_step takes such kept roots as an input.
 
 Inputs are the exact values the device sees, widened to fp64; numpy's matmul and
 numpy.linalg.eigh are the library steps.  The device reaches step 3 through a matmul-only
@@ -58,12 +60,15 @@ def statistics(grad: np.ndarray, left: np.ndarray, right: np.ndarray, beta: floa
     return new_left, new_right
 
 
-def shampoo_step(grad, left, right, hp: Hparams, param=None):
+def shampoo_step(grad, left, right, hp: Hparams, param=None, kept_roots=None):
     """One Shampoo step for one matrix.
 
     grad   rows x cols array, or a list of tp column fragments
     left   rows x rows statistic before the step;  right  cols x cols likewise
     param  rows x cols parameter (optional)
+    kept_roots  (left root, right root) from an earlier step: the amortised variant, in which the
+           statistics are updated on every step and the roots only on some; None: the roots of the
+           new statistics, as published
 
     Returns a dict with 'left', 'right' (statistics after the step), 'left_root',
     'right_root' (the inverse fourth roots), 'precond' (O), 'delta' (-lr O) and, if
@@ -71,8 +76,12 @@ def shampoo_step(grad, left, right, hp: Hparams, param=None):
     """
     g = gather_columns(grad) if isinstance(grad, (list, tuple)) else np.asarray(grad, dtype=np.float64)
     new_left, new_right = statistics(g, left, right, hp.beta)
-    left_root = inverse_fourth_root(new_left, hp.eps)
-    right_root = inverse_fourth_root(new_right, hp.eps)
+    if kept_roots is None:
+        left_root = inverse_fourth_root(new_left, hp.eps)
+        right_root = inverse_fourth_root(new_right, hp.eps)
+    else:
+        left_root = np.asarray(kept_roots[0], dtype=np.float64)
+        right_root = np.asarray(kept_roots[1], dtype=np.float64)
     precond = left_root @ g @ right_root
     delta = -hp.lr * precond
     out = {"left": new_left, "right": new_right, "left_root": left_root, "right_root": right_root,

@@ -57,12 +57,12 @@ class _ShGroup(C.Structure):
     _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("n_mats", C.c_int32), ("tp", C.c_int32),
                 ("grad_dtype", C.c_int32), ("out_dtype", C.c_int32),
                 ("grad", C.POINTER(C.c_void_p)), ("left", C.POINTER(C.c_void_p)), ("right", C.POINTER(C.c_void_p)),
-                ("out", C.POINTER(C.c_void_p))]
+                ("out", C.POINTER(C.c_void_p)), ("lroot", C.POINTER(C.c_void_p)), ("rroot", C.POINTER(C.c_void_p))]
 
 
 class _ShHparams(C.Structure):
     _fields_ = [("beta", C.c_float), ("lr", C.c_float), ("weight_decay", C.c_float), ("eps", C.c_float),
-                ("root_iters", C.c_int32), ("out_mode", C.c_int32)]
+                ("root_iters", C.c_int32), ("out_mode", C.c_int32), ("keep_roots", C.c_int32)]
 
 
 class _SoapGroup(C.Structure):
@@ -298,9 +298,11 @@ class ShampooHparams:
     eps: float = 1e-6
     root_iters: int = 25
     out_mode: int = OUT_PARAM
+    keep_roots: bool = False
 
     def _c(self) -> _ShHparams:
-        return _ShHparams(self.beta, self.lr, self.weight_decay, self.eps, int(self.root_iters), int(self.out_mode))
+        return _ShHparams(self.beta, self.lr, self.weight_decay, self.eps, int(self.root_iters), int(self.out_mode),
+                          int(bool(self.keep_roots)))
 
 
 @dataclass
@@ -312,6 +314,8 @@ class ShampooGroup:
     left: Sequence = field(default_factory=list)    # n_mats, fp32 rows x rows
     right: Sequence = field(default_factory=list)   # n_mats, fp32 cols x cols
     out: Sequence = field(default_factory=list)     # n_mats (params) or n_mats * tp (delta fragments)
+    lroot: Sequence = field(default_factory=list)   # n_mats, fp32 rows x rows: the kept inverse fourth roots, or empty
+    rroot: Sequence = field(default_factory=list)   # n_mats, fp32 cols x cols
     tp: int = 1
     grad_dtype: int = DT_BF16
     out_dtype: int = DT_F32
@@ -324,7 +328,7 @@ def _marshal_shampoo(groups: Sequence[ShampooGroup]):
     for i, g in enumerate(groups):
         n_mats = len(g.left) if g.n_mats < 0 else g.n_mats
         tabs = []
-        for seq in (g.grad, g.left, g.right, g.out):
+        for seq in (g.grad, g.left, g.right, g.out, g.lroot, g.rroot):
             t = (C.c_void_p * max(len(seq), 1))(*[_addr(x) for x in seq])
             keep.append(t)
             tabs.append(C.cast(t, C.POINTER(C.c_void_p)) if len(seq) else None)

@@ -292,5 +292,18 @@ static __global__ __launch_bounds__(NTH) void k_sh_load(Shape s, PtrTable grad, 
   }
 }
 
+// dense rows x cols matrices of the caller <- the padded working copies src[b * stride] (row length cp)
+static __global__ __launch_bounds__(NTH) void k_unpad(Shape s, PtrTable dst, const float* __restrict__ src, int64_t stride,
+                                                     int64_t cp) {
+  const int b = blockIdx.z, r0 = blockIdx.y * 64, c0 = blockIdx.x * 64, t = threadIdx.x;
+  const float* from = src + static_cast<int64_t>(b) * stride;
+  float* to = static_cast<float*>(dst.p[b]);
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    const int idx = e * NTH + t, row = r0 + (idx >> 6), col = c0 + (idx & 63);
+    if (row < s.rows && col < s.cols) to[static_cast<int64_t>(row) * s.cols + col] = from[static_cast<int64_t>(row) * cp + col];
+  }
+}
+
 }  // namespace f32mfma
 }  // namespace canz

@@ -11,7 +11,8 @@
 // the load kernel), and every matrix of the root iteration is a polynomial in the symmetric
 // A = S + eps I, hence symmetric itself, so "times Q" and "times Q^T" coincide.  Symmetric
 // products compute only the tiles on or above the diagonal and write the mirror tile from the
-// same accumulators, which halves their work and keeps the iterates symmetric bit for bit.
+// same accumulators, which halves their work and keeps the iterates symmetric (bit for bit across
+// tiles; inside a diagonal tile the two halves are rounded separately and agree to an ulp or two).
 //
 // Inverse fourth root (coupled Newton iteration for the inverse p-th root, p = 4): from
 // M = z A, X = z^(1/4) I with z = 5 / (2 b), b an upper bound of the largest eigenvalue (see k_sh_init),
@@ -137,7 +138,7 @@ int check_hparams(const canz_shampoo_hparams* hp) {
   return CANZ_OK;
 }
 
-int check_group(const canz_shampoo_group& g, int idx, bool need_ptrs, int out_mode) {
+int check_group(const canz_shampoo_group& g, int idx, bool need_ptrs, int out_mode, bool keep_roots) {
   if (g.n_mats < 0) return fail(CANZ_EINVAL, "group %d: n_mats < 0", idx);
   if (g.rows < 1 || g.cols < 1) return fail(CANZ_EINVAL, "group %d: empty shape", idx);
   if (g.rows > MAX_EXTENT || g.cols > MAX_EXTENT)
@@ -151,13 +152,15 @@ int check_group(const canz_shampoo_group& g, int idx, bool need_ptrs, int out_mo
     return fail(CANZ_EUNSUPPORTED, "group %d: unknown out_dtype", idx);
   if (!need_ptrs || g.n_mats == 0) return CANZ_OK;
   if (!g.grad || !g.left || !g.right || !g.out) return fail(CANZ_EINVAL, "group %d: null pointer table", idx);
+  if ((g.lroot == nullptr) != (g.rroot == nullptr)) return fail(CANZ_EINVAL, "group %d: one root table without the other", idx);
+  if (keep_roots && !g.lroot) return fail(CANZ_EINVAL, "group %d: keep_roots needs the root tables", idx);
   const int n_out = out_mode == CANZ_OUT_DELTA ? g.n_mats * g.tp : g.n_mats;
   auto bad = [](const void* p) { return p == nullptr || (reinterpret_cast<uintptr_t>(p) & 15u) != 0; };
   for (int i = 0; i < g.n_mats * g.tp; ++i)
     if (bad(g.grad[i])) return fail(CANZ_EINVAL, "group %d: grad[%d] null or not 16-byte aligned", idx, i);
   for (int i = 0; i < g.n_mats; ++i)
-    if (bad(g.left[i]) || bad(g.right[i]))
-      return fail(CANZ_EINVAL, "group %d: statistic %d null or not 16-byte aligned", idx, i);
+    if (bad(g.left[i]) || bad(g.right[i]) || (g.lroot && (bad(g.lroot[i]) || bad(g.rroot[i]))))
+      return fail(CANZ_EINVAL, "group %d: statistic or root %d null or not 16-byte aligned", idx, i);
   for (int i = 0; i < n_out; ++i)
     if (bad(g.out[i])) return fail(CANZ_EINVAL, "group %d: out[%d] null or not 16-byte aligned", idx, i);
   return CANZ_OK;
@@ -195,16 +198,29 @@ int run_batch(const canz_shampoo_group& g, int first, int nb, const canz_shampoo
 
   // one side: statistic (d x d, in the caller's buffers) from the operand `side` [dp][kp], then
   // its inverse fourth root into `root`
-  auto one_side = [&](void* const* stat_tab, int64_t d, int64_t dp, int64_t kp, const float* side, float* root) -> int {
-    PtrTable stat{};
+  auto one_side = [&](void* const* stat_tab, void* const* root_tab, int64_t d, int64_t dp, int64_t kp, const float* side,
+                      float* root) -> int {
+    PtrTable stat{}, kept{};
     for (int i = 0; i < nb; ++i) stat.p[i] = stat_tab[first + i];
+    if (root_tab)
+      for (int i = 0; i < nb; ++i) kept.p[i] = root_tab[first + i];
+    Shape sq{};   // the d x d matrices of this side, for the padded load and the dense store of a kept root
+    sq.rows = d, sq.cols = d, sq.tp = 1, sq.wfrag = d;
+    const dim3 sq_tiles(static_cast<unsigned>(dp / 64), static_cast<unsigned>(dp / 64), static_cast<unsigned>(nb));
     const int64_t dd = dp * dp;
     float *a = ws + c.a, *x[2] = {ws + c.x[0], ws + c.x[1]}, *m[2] = {ws + c.m[0], ws + c.m[1]};
     float *tt = ws + c.t, *t2 = ws + c.t2, *t4 = ws + c.t4, *partial = ws + c.partial, *partial4 = ws + c.partial4;
     ShGemm q{};
     q.M = dp, q.N = dp, q.K = kp, q.ldp = kp, q.ldq = kp, q.sp = dp * kp, q.sq = dp * kp;
-    q.P = side, q.Q = side, q.c = a, q.d = d, q.beta = hp.beta, q.gscale = 1.f, q.eps = hp.eps;
+    q.P = side, q.Q = side, q.c = hp.keep_roots ? nullptr : a, q.d = d, q.beta = hp.beta, q.gscale = 1.f, q.eps = hp.eps;
     CANZ_HIP(CANZ_KERNEL_SH_STAT, (launch_gemm<SE_STAT, true>(q, nb, stat, s, o, st)), "statistics kernel");
+    if (hp.keep_roots) {   // the caller's root, padded (its transposed image, which equals it, goes to a free buffer)
+      prof_mark(st, CANZ_KERNEL_SH_LOAD, true);
+      hipLaunchKernelGGL(k_sh_load, sq_tiles, dim3(NTH), 0, st, sq, kept, static_cast<int>(CANZ_DT_F32), dp, dp, root, x[0]);
+      prof_mark(st, CANZ_KERNEL_SH_LOAD, false);
+      if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "root load: %s", hipGetErrorString(e));
+      return CANZ_OK;
+    }
     auto prod = [&](const float* P, const float* Q, float* C) {
       ShGemm r{};
       r.M = dp, r.N = dp, r.K = dp, r.ldp = dp, r.ldq = dp, r.sp = dd, r.sq = dd;
@@ -237,11 +253,17 @@ int run_batch(const canz_shampoo_group& g, int first, int nb, const canz_shampoo
       CANZ_HIP(CANZ_KERNEL_SH_ROOT, (launch_gemm<SE_MT, true>(r, nb, none, s, o, st)), "root kernel (T4 M)");
       cur ^= 1;
     }
+    if (root_tab) {
+      prof_mark(st, CANZ_KERNEL_SH_LOAD, true);
+      hipLaunchKernelGGL(k_unpad, sq_tiles, dim3(NTH), 0, st, sq, kept, root, dd, dp);
+      prof_mark(st, CANZ_KERNEL_SH_LOAD, false);
+      if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "root store: %s", hipGetErrorString(e));
+    }
     return CANZ_OK;
   };
   float *lroot = ws + c.lroot, *rroot = ws + c.rroot;
-  if (int rc = one_side(g.left, g.rows, rp, cp, gs, lroot)) return rc;
-  if (int rc = one_side(g.right, g.cols, cp, rp, gt, rroot)) return rc;
+  if (int rc = one_side(g.left, g.lroot, g.rows, rp, cp, gs, lroot)) return rc;
+  if (int rc = one_side(g.right, g.rroot, g.cols, cp, rp, gt, rroot)) return rc;
 
   // O = (L^(-1/4) G) R^(-1/4): P = L root, Q = G^T gives rows x cols; then P = that, Q = R root
   ShGemm a1{};
@@ -266,7 +288,7 @@ extern "C" int canz_shampoo_workspace_bytes(const canz_shampoo_group* g, int32_t
   if (int rc = check_hparams(hp)) return rc;
   size_t need = ALIGN;
   for (int i = 0; i < n_groups; ++i) {
-    if (int rc = check_group(g[i], i, false, hp->out_mode)) return rc;
+    if (int rc = check_group(g[i], i, false, hp->out_mode, hp->keep_roots != 0)) return rc;
     if (g[i].n_mats == 0) continue;
     need = std::max(need, carve(g[i].rows, g[i].cols, std::min(g[i].n_mats, batch_cap(g[i]))).total_bytes);
   }
@@ -281,7 +303,7 @@ extern "C" int canz_shampoo_step(const canz_shampoo_group* g, int32_t n_groups, 
   if (int rc = canz_shampoo_workspace_bytes(g, n_groups, hp, &need)) return rc;
   bool any = false;
   for (int i = 0; i < n_groups; ++i) {
-    if (int rc = check_group(g[i], i, true, hp->out_mode)) return rc;
+    if (int rc = check_group(g[i], i, true, hp->out_mode, hp->keep_roots != 0)) return rc;
     any = any || g[i].n_mats > 0;
   }
   if (!any) return CANZ_OK;

@@ -132,19 +132,6 @@ __global__ __launch_bounds__(NTH) void k_soap_adam(Shape s, PtrTable var, PtrTab
   }
 }
 
-// dense rows x cols matrices of the caller <- the padded working copies src[b * stride] (row length cp)
-__global__ __launch_bounds__(NTH) void k_soap_unpad(Shape s, PtrTable dst, const float* __restrict__ src, int64_t stride,
-                                                     int64_t cp) {
-  const int b = blockIdx.z, r0 = blockIdx.y * 64, c0 = blockIdx.x * 64, t = threadIdx.x;
-  const float* from = src + static_cast<int64_t>(b) * stride;
-  float* to = static_cast<float*>(dst.p[b]);
-#pragma unroll
-  for (int e = 0; e < 16; ++e) {
-    const int idx = e * NTH + t, row = r0 + (idx >> 6), col = c0 + (idx & 63);
-    if (row < s.rows && col < s.cols) to[static_cast<int64_t>(row) * s.cols + col] = from[static_cast<int64_t>(row) * cp + col];
-  }
-}
-
 // a[b][i] = (identity ? (row == col) : 0) for the [rows][ld] matrices of a batch
 __global__ __launch_bounds__(NTH) void k_soap_fill(float* __restrict__ a, int64_t elems, int64_t ld, int identity) {
   float* ab = a + static_cast<int64_t>(blockIdx.y) * elems;
@@ -898,7 +885,7 @@ int run_batch(const canz_soap_group& g, int first, int nb, const canz_soap_hpara
     prof_mark(st, CANZ_KERNEL_SOAP_LOAD, false);
     if (int rc = rotate_in(1, 1)) return rc;
     prof_mark(st, CANZ_KERNEL_SOAP_ADAM, true);
-    hipLaunchKernelGGL(k_soap_unpad, tiles, dim3(NTH), 0, st, s, mrot, rot + plane, 2 * plane, cp);
+    hipLaunchKernelGGL(k_unpad, tiles, dim3(NTH), 0, st, s, mrot, rot + plane, 2 * plane, cp);
     prof_mark(st, CANZ_KERNEL_SOAP_ADAM, false);
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "momentum re-rotation: %s", hipGetErrorString(e));
   }

@@ -118,7 +118,9 @@ def test_shampoo_argument_errors_and_workspace_without_device(canz):
     want = 4 * (3 * 256 * 512 + 256 * 256 + 512 * 512 + 8 * 512 * 512 + 128)
     assert canz.canz_shampoo_workspace_bytes([G(rows=256, cols=512, n_mats=1)], hp) == want
     assert canz.canz_shampoo_workspace_bytes([G(rows=200, cols=500, n_mats=1)], hp) == want
-    assert ctypes.sizeof(canz._ShGroup) == 16 + 16 + 32 and ctypes.sizeof(canz._ShHparams) == 24
+    assert ctypes.sizeof(canz._ShGroup) == 16 + 16 + 48 and ctypes.sizeof(canz._ShHparams) == 28
+    assert code([G(**{**ok, "lroot": [20480]})], hp) == canz.EINVAL                              # one root table without the other
+    assert code([G(**ok)], canz.ShampooHparams(keep_roots=True)) == canz.EINVAL                  # nothing to keep them in
 
 
 def test_soap_argument_errors_and_workspace_without_device(canz):

@@ -32,9 +32,12 @@ class ShampooDevice:
     """One micro-group on the device.  grads: per matrix a host array or a list of tp fragments;
     lefts / rights: fp32 host arrays; outs: parameter arrays, or None for Delta W fragments."""
 
-    def __init__(self, canz, rows, cols, grads, lefts, rights, outs=None, tp=1, out_np_dtype=np.float32):
+    def __init__(self, canz, rows, cols, grads, lefts, rights, outs=None, tp=1, out_np_dtype=np.float32, keep_roots=False):
         import torch
         self.canz, self.rows, self.cols, self.tp, self.n = canz, rows, cols, tp, len(lefts)
+        # caller-held inverse roots (NaN until a full step writes them)
+        self.lroot_t = [to_device(np.full((rows, rows), np.nan, np.float32)) for _ in lefts] if keep_roots else []
+        self.rroot_t = [to_device(np.full((cols, cols), np.nan, np.float32)) for _ in lefts] if keep_roots else []
         first = grads[0][0] if isinstance(grads[0], (list, tuple)) else grads[0]
         self.grad_dtype = W.DT_BF16 if first.dtype == np.uint16 else W.DT_F32
         self.grad_t = []
@@ -56,8 +59,8 @@ class ShampooDevice:
 
     def group(self):
         return self.canz.ShampooGroup(rows=self.rows, cols=self.cols, grad=self.grad_t, left=self.left_t,
-                                      right=self.right_t, out=self.out_t, tp=self.tp, grad_dtype=self.grad_dtype,
-                                      out_dtype=self.out_dtype)
+                                      right=self.right_t, out=self.out_t, lroot=self.lroot_t, rroot=self.rroot_t, tp=self.tp,
+                                      grad_dtype=self.grad_dtype, out_dtype=self.out_dtype)
 
     def out_host(self, i):
         if not self.delta:
@@ -134,6 +137,41 @@ def test_two_steps_with_decay_and_fp32_gradients(canz):
         dev.grad_t[i].copy_(to_device(g2[i]))
     run(canz, [dev], hp)
     check(dev, g2, l1, r1, None, hp, "shampoo step 2")
+
+
+def test_kept_roots_between_steps(canz):
+    """The amortised variant: a full step leaves its roots with the caller (compared with the oracle's roots), the next
+    step takes them from there while its statistics move on; the oracle gets the device's kept roots as they are."""
+    rows, cols, n = 200, 328, 2
+    g1 = [W.gen_grad(47, i, rows, cols)[0] for i in range(n)]
+    l0 = [np.eye(rows, dtype=np.float32) * np.float32(0.02) for _ in range(n)]
+    r0 = [np.eye(cols, dtype=np.float32) * np.float32(0.01) for _ in range(n)]
+    hp = canz.ShampooHparams(beta=0.9, lr=0.1, eps=1e-3, out_mode=canz.OUT_DELTA)
+    dev = ShampooDevice(canz, rows, cols, g1, l0, r0, keep_roots=True)
+    run(canz, [dev], hp)
+    check(dev, g1, l0, r0, None, hp, "shampoo full step with roots kept")
+    ohp = oracle_hparams(hp)
+    for i in range(n):
+        ref = SH.shampoo_step(widen(g1[i]), widen(l0[i]), widen(r0[i]), ohp)
+        for got, want in ((dev.lroot_t[i], ref["left_root"]), (dev.rroot_t[i], ref["right_root"])):
+            got = to_host64(got)
+            assert rel_fro(got, want) <= 1e-4 and np.abs(got - got.T).max() <= 1e-5 * np.abs(got).max()
+    l1 = [dev.left_t[i].cpu().numpy() for i in range(n)]
+    r1 = [dev.right_t[i].cpu().numpy() for i in range(n)]
+    kept = [(to_host64(dev.lroot_t[i]), to_host64(dev.rroot_t[i])) for i in range(n)]
+    g2 = [W.gen_grad(47, i, rows, cols, step=1)[0] for i in range(n)]
+    for i in range(n):
+        dev.grad_t[i].copy_(to_device(g2[i]))
+    hp2 = canz.ShampooHparams(beta=0.9, lr=0.1, eps=1e-3, out_mode=canz.OUT_DELTA, keep_roots=True)
+    run(canz, [dev], hp2)
+    worst = 0.0
+    for i in range(n):
+        ref = SH.shampoo_step(widen(g2[i]), widen(l1[i]), widen(r1[i]), ohp, kept_roots=kept[i])
+        assert rel_fro(to_host64(dev.left_t[i]), ref["left"]) <= TOL_STAT and rel_fro(to_host64(dev.right_t[i]), ref["right"]) <= TOL_STAT
+        assert np.array_equal(to_host64(dev.lroot_t[i]), kept[i][0]), "a step with keep_roots must not touch the roots"
+        worst = max(worst, rel_fro(dev.out_host(i), ref["delta"]))
+    log("shampoo step on kept roots: worst Delta W error %.3g (tol 1e-5: two fp32 products)" % worst)
+    assert worst <= 1e-5
 
 
 def test_tp_fragments_equal_the_whole_matrix(canz):

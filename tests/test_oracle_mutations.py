@@ -141,6 +141,11 @@ SHAMPOO_MUTANTS = [
      "left_root = inverse_fourth_root(np.asarray(left, dtype=np.float64), hp.eps)"),
     ("fragments gathered along rows", "return np.concatenate([np.asarray(f, dtype=np.float64) for f in fragments], axis=1)",
      "return np.concatenate([np.asarray(f, dtype=np.float64) for f in fragments], axis=0).reshape(fragments[0].shape[0], -1)"),
+    ("kept roots ignored", "if kept_roots is None:", "if True:"),
+    ("kept roots swapped", "left_root = np.asarray(kept_roots[0], dtype=np.float64)",
+     "left_root = np.asarray(kept_roots[0] if np.shape(kept_roots[0]) != np.shape(kept_roots[1]) else kept_roots[1], dtype=np.float64)"),
+    ("kept right root transposed", "right_root = np.asarray(kept_roots[1], dtype=np.float64)",
+     "right_root = np.asarray(kept_roots[1], dtype=np.float64).T"),
 ]
 
 SHAMPOO_COST_MUTANTS = [

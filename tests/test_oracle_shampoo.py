@@ -143,6 +143,26 @@ def test_parameter_update_and_fragments():
     assert np.allclose(whole["precond"], whole["left_root"] @ g @ whole["right_root"], rtol=1e-13, atol=1e-14)
 
 
+@pytest.mark.parametrize("shape", [(4, 6), (5, 5)])
+def test_kept_roots_replace_the_roots_of_the_new_statistics(shape):
+    """With kept roots the step is O = A G B for the matrices handed in (not their roots, not their transposes), while
+    the statistics still move; identity roots give O = G; the roots a full step returns, kept, reproduce that step."""
+    rows, cols = shape
+    g = _gauss(21, rows, cols, 1.0)
+    a, b = _gauss(22, rows, rows, 1.0), _gauss(23, cols, cols, 1.0)          # not symmetric on purpose
+    hp = SH.Hparams(lr=1.0, eps=1e-3, beta=0.5)
+    l0, r0 = np.eye(rows), np.eye(cols)
+    out = SH.shampoo_step(g, l0, r0, hp, kept_roots=(a, b))
+    want = np.array([[sum(a[i, k] * g[k, m] * b[m, j] for k in range(rows) for m in range(cols)) for j in range(cols)]
+                     for i in range(rows)])
+    assert np.allclose(out["precond"], want, rtol=1e-13, atol=1e-13)
+    full = SH.shampoo_step(g, l0, r0, hp)
+    assert np.array_equal(out["left"], full["left"]) and np.array_equal(out["right"], full["right"])
+    assert np.array_equal(SH.shampoo_step(g, l0, r0, hp, kept_roots=(np.eye(rows), np.eye(cols)))["precond"], g)
+    again = SH.shampoo_step(g, l0, r0, hp, kept_roots=(full["left_root"], full["right_root"]))
+    assert np.array_equal(again["delta"], full["delta"])
+
+
 def test_shampoo_cost_model_by_hand():
     """W(p) for the planner: r = 2, c = 3, 25 root rounds: 4*4*3 + 4*9*2 + 200*(8 + 27) = 7120 FLOPs;
     in the planner's units of 2^20 FLOPs a 4096 x 4096 matrix costs
