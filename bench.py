@@ -307,7 +307,7 @@ def main_soap(args, canz, W, np, torch):
     def hparams(t):
         # the rotated momentum is valid from the second step on (the first one rotates M and leaves M' behind)
         return canz.SoapHparams(beta1=0.95, beta2=0.95, lr=3e-3, eps=1e-8, step=t, refresh=(t % f == 0), max_precond_dim=limit,
-                                mom_rot_valid=keep_rot and t > 1)
+                                mom_rot_valid=keep_rot and t > 1, bf16_rotations=args.bf16_rotations)
 
     gen = torch.Generator(device="cuda")
     gen.manual_seed(W.SEED_BASE + cfg)
@@ -362,11 +362,13 @@ def main_soap(args, canz, W, np, torch):
     canz.canz_profile_disable()
     n_refresh = sum(1 for t in range(first_profiled, first_profiled + args.steps) if t % f == 0)
 
-    def pad(x):
-        return (x + 127) // 128 * 128
+    def pad(x, to=128):
+        return (x + to - 1) // to * to
 
     def sym(d, k):
-        return d * (d + 1) * k, (pad(d) // 128) * (pad(d) // 128 + 1) // 2 * 128 * 128 * 2 * pad(k)
+        # the statistic is symmetric (d (d + 1) k FLOPs); from bf16 gradients, as here, it is computed as the whole
+        # square by the bf16 kernels, on operands padded to 256
+        return d * (d + 1) * k, 2 * pad(d, 256) * pad(d, 256) * pad(k, 256)
 
     alg = dict(soap_rotate=0.0, soap_stat=0.0, soap_qr=0.0)
     iss = dict(soap_rotate=0.0, soap_stat=0.0)
@@ -375,7 +377,8 @@ def main_soap(args, canz, W, np, torch):
         n = len(g)
         use_l, use_r = r <= limit, c <= limit
         per_rot = (2.0 * r * r * c if use_l else 0.0) + (2.0 * r * c * c if use_r else 0.0)
-        per_rot_iss = (2.0 * pad(r) * pad(r) * pad(c) if use_l else 0.0) + (2.0 * pad(r) * pad(c) * pad(c) if use_r else 0.0)
+        pr, pc = (pad(r, 256), pad(c, 256)) if args.bf16_rotations else (pad(r), pad(c))   # the bf16 kernels' tiles are 256 wide
+        per_rot_iss = (2.0 * pr * pr * pc if use_l else 0.0) + (2.0 * pr * pc * pc if use_r else 0.0)
         # G (and M, unless its rotated image is kept) in, the direction back; M again after a refresh if it is kept
         n_rot = (2 * args.steps + n_refresh) if keep_rot else 3 * args.steps
         alg["soap_rotate"] += n_rot * n * per_rot
@@ -396,13 +399,14 @@ def main_soap(args, canz, W, np, torch):
                 kernels[k]["tflops_issued"] = iss[k] / (ms * 1e-3) / 1e12
     refresh_ms = sum(kernels[k]["ms_per_step"] * args.steps for k in ("soap_qr", "soap_panel") if k in kernels) / max(n_refresh, 1)
     plain_ms = sum(v["ms_per_step"] for k, v in kernels.items() if k not in ("soap_qr", "soap_panel"))
-    dom = "soap_rotate"
-    peak = 157.3
+    # the dominant kernel: the rotations, unless they run on the bf16 matrix cores and the fp32 statistics take longer
+    dom = max(("soap_rotate", "soap_stat"), key=lambda k: kernels[k]["ms_per_step"])
+    peak = 2500.0 if (dom == "soap_stat" or args.bf16_rotations) else 157.3
     launches = kernels[dom]["launches_per_step"] * args.steps
     per_launch = alg[dom] / launches
     achieved = per_launch / (kernels[dom]["avg_ms"] * 1e-3) / 1e12
     issued = iss[dom] / launches / (kernels[dom]["avg_ms"] * 1e-3) / 1e12
-    roofline = dict(bound="mfma", kernel="k_sh_gemm (%s)" % dom, achieved=achieved, peak=peak, unit="TFLOP/s",
+    roofline = dict(bound="mfma", kernel="%s (%s)" % ("k_gemm_nt_bf16" if peak > 1000 else "k_sh_gemm", dom), achieved=achieved, peak=peak, unit="TFLOP/s",
                     frac=achieved / peak, traffic=None, achieved_issued=issued, frac_issued=issued / peak,
                     flops_per_launch=per_launch, avg_launch_ms=kernels[dom]["avg_ms"])
     cpu = None
@@ -436,7 +440,7 @@ def main_soap(args, canz, W, np, torch):
         "metric": "optimizer_step_latency_ms", "value": ms_per_step, "unit": "ms",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic", "launch": "eager",
+        "dtype": "f32 (rotations on bf16 operands)" if args.bf16_rotations else "f32", "data": "synthetic", "launch": "eager",
         "config": {"workload": "soap step, config %d %s partitioned by SOAP FLOPs: rank %d of %d (alpha=1), %d matrices %s in %d "
                                "micro-groups, basis refresh every %d steps (%d of the %d timed steps), max_precond_dim %d, %s" %
                                (cfg, s["name"], rank, R, n_share, sorted({(s["rows"][p], s["cols"][p]) for g in groups for p in g}),
@@ -468,6 +472,8 @@ def main():
     ap.add_argument("--max-precond-dim", type=int, default=10000, help="soap: a longer side keeps no basis")
     ap.add_argument("--rotate-momentum-every-step", action="store_true",
                     help="soap: do not keep the rotated momentum between steps (three rotations per step instead of two)")
+    ap.add_argument("--bf16-rotations", action="store_true",
+                    help="soap: the rotation products on bf16 operands with fp32 accumulation (state, statistics, refresh stay fp32)")
     ap.add_argument("--precision", choices=["bf16", "f32"], default="bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tp-schedule", type=int, default=0, metavar="MB",

@@ -338,7 +338,11 @@ int canz_shampoo_step(const canz_shampoo_group* g, int32_t n_groups, const canz_
  * only on the first step and after changing M or a basis itself.  M stays the state in the original space.
  * A side longer than max_precond_dim keeps no statistic and no basis (its Q is the identity and
  * its tables may be NULL); at least one side must be within the limit, and a side with a basis may
- * have at most 12288 rows or columns (the cited implementation's default limit is 10000).  Everything is fp32.
+ * have at most 12288 rows or columns (the cited implementation's default limit is 10000).  Everything is fp32,
+ * unless bf16_rotations is set: then the products that rotate G (and M) into the bases and N' back take their
+ * operands (G, M, the bases, N' and the intermediate of a two-sided rotation) rounded to bf16 and accumulate in
+ * fp32, about four times faster and with a relative error of the update near 1e-2 (each rounding is 2^-9
+ * relative); momentum, second moment, statistics, the refresh and mom_rot's re-rotation after it stay in fp32.
  * The caller owns all state and decides when to refresh (every f-th step) and how the bases
  * start (identity, or eigenvectors of the first statistics computed elsewhere).  The QR step is
  * a blocked Householder factorisation: the basis it writes is orthonormal to fp32 rounding and
@@ -375,6 +379,7 @@ typedef struct {
   int32_t max_precond_dim;  /* >= 1 */
   int32_t out_mode;         /* CANZ_OUT_* */
   int32_t mom_rot_valid;    /* 1: mom_rot holds Q_L^T M Q_R of the M and the bases passed in */
+  int32_t bf16_rotations;   /* 0: everything in fp32; 1: the rotations of steps 3 and 6 on bf16 operands */
 } canz_soap_hparams;
 
 /*

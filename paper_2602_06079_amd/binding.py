@@ -77,7 +77,8 @@ class _SoapGroup(C.Structure):
 class _SoapHparams(C.Structure):
     _fields_ = [("beta1", C.c_float), ("beta2", C.c_float), ("lr", C.c_float), ("weight_decay", C.c_float),
                 ("eps", C.c_float), ("step", C.c_int32), ("bias_correction", C.c_int32), ("refresh", C.c_int32),
-                ("max_precond_dim", C.c_int32), ("out_mode", C.c_int32), ("mom_rot_valid", C.c_int32)]
+                ("max_precond_dim", C.c_int32), ("out_mode", C.c_int32), ("mom_rot_valid", C.c_int32),
+                ("bf16_rotations", C.c_int32)]
 
 
 def _load():
@@ -365,11 +366,12 @@ class SoapHparams:
     max_precond_dim: int = 10000
     out_mode: int = OUT_PARAM
     mom_rot_valid: bool = False
+    bf16_rotations: bool = False
 
     def _c(self) -> _SoapHparams:
         return _SoapHparams(self.beta1, self.beta2, self.lr, self.weight_decay, self.eps, int(self.step),
                             int(bool(self.bias_correction)), int(bool(self.refresh)), int(self.max_precond_dim),
-                            int(self.out_mode), int(bool(self.mom_rot_valid)))
+                            int(self.out_mode), int(bool(self.mom_rot_valid)), int(bool(self.bf16_rotations)))
 
 
 @dataclass

@@ -36,6 +36,7 @@
 #include "device_util.h"
 #include "f32_mfma_gemm.h"
 #include "kernels.h"
+#include "panel_layout.h"
 
 namespace canz {
 namespace {
@@ -49,17 +50,41 @@ constexpr int QB = 32;            // panel width of the QR factorisation
 constexpr int QTH = 1024;         // threads of the panel kernel: 16 wavefronts
 constexpr int QWAVES = QTH / 64;
 
+// Where k_soap_load leaves its results: fp32 working copies and / or bf16 images in the panel layout
+// (panel_layout.h; padded to multiples of 256, operands of the bf16 MFMA kernels), each in both orientations.
+struct LoadOut {
+  float *gm, *gmt;               // fp32: gm [nb][2][rp][cp] (G, then M) and gmt [nb][2][cp][rp]
+  bool g32, m32;                 // which of their two planes are wanted
+  __bf16 *gp, *gpt, *mp, *mpt;   // bf16 panels: G [nb][rp2][cp2], G^T [nb][cp2][rp2], M, M^T; nullptr: not wanted
+  int64_t rp2, cp2;
+};
+
+// one 64 x 64 fp32 tile in LDS -> the 8-element chunks of its bf16 panel image, straight (dst rows = tile rows) or
+// transposed (dst rows = tile columns); (r0, c0): the tile's place in the matrix, kc: row length of the image
+__device__ __forceinline__ void tile_to_panels(const float (*tile)[65], __bf16* __restrict__ dst, int64_t r0, int64_t c0,
+                                               int64_t kc, bool transposed, int t) {
+  const int cv = (t & 7) * 8;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const int rl = (t >> 3) + half * 32;
+    bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = static_cast<__bf16>(transposed ? tile[cv + e][rl] : tile[rl][cv + e]);
+    *reinterpret_cast<bf16x8*>(dst + (transposed ? panel_chunk_off(c0 + rl, r0 + cv, kc) : panel_chunk_off(r0 + rl, c0 + cv, kc))) = o;
+  }
+}
+
 // G (bf16 or fp32, whole or tp column fragments) and the momentum M <- beta1 M + (1 - beta1) G
-// (fp32, dense, in the caller's buffer) -> fp32 working copies of both, in both orientations,
-// zero outside rows x cols: gm [nb][2][rp][cp] (G, then M) and gmt [nb][2][cp][rp].
+// (fp32, dense, in the caller's buffer) -> working copies of both as `w` asks, zero outside rows x cols.
+// One block per 64 x 64 tile of the padded matrix (padded to 256 if a bf16 image is wanted, else to 128).
 __global__ __launch_bounds__(NTH) void k_soap_load(Shape s, PtrTable grad, int grad_dtype, PtrTable mom, float beta1,
-                                                    int64_t rp, int64_t cp, float* __restrict__ gm, float* __restrict__ gmt) {
+                                                    int64_t rp, int64_t cp, LoadOut w) {
   __shared__ float tg[64][65], tm[64][65];
   const int b = blockIdx.z, r0 = blockIdx.y * 64, c0 = blockIdx.x * 64, t = threadIdx.x;
   const int wf = static_cast<int>(s.wfrag);
   const int64_t plane = rp * cp;
-  float* gs = gm + static_cast<int64_t>(b) * 2 * plane;
-  float* gt = gmt + static_cast<int64_t>(b) * 2 * plane;
+  float* gs = w.gm + static_cast<int64_t>(b) * 2 * plane;
+  float* gt = w.gmt + static_cast<int64_t>(b) * 2 * plane;
   float* m = static_cast<float*>(mom.p[b]);
 #pragma unroll
   for (int e = 0; e < 16; ++e) {
@@ -75,18 +100,29 @@ __global__ __launch_bounds__(NTH) void k_soap_load(Shape s, PtrTable grad, int g
       mv = __builtin_fmaf(beta1, m[am], (1.f - beta1) * g);
       m[am] = mv;
     }
-    gs[static_cast<int64_t>(row) * cp + col] = g;
-    gs[plane + static_cast<int64_t>(row) * cp + col] = mv;
+    if (row < rp && col < cp) {
+      if (w.g32) gs[static_cast<int64_t>(row) * cp + col] = g;
+      if (w.m32) gs[plane + static_cast<int64_t>(row) * cp + col] = mv;
+    }
     tg[r][c] = g;
     tm[r][c] = mv;
   }
   __syncthreads();
+  if (w.g32 || w.m32) {
 #pragma unroll
-  for (int e = 0; e < 16; ++e) {
-    const int idx = e * NTH + t, r = idx >> 6, c = idx & 63;  // r: column of G, c: row of G
-    gt[static_cast<int64_t>(c0 + r) * rp + r0 + c] = tg[c][r];
-    gt[plane + static_cast<int64_t>(c0 + r) * rp + r0 + c] = tm[c][r];
+    for (int e = 0; e < 16; ++e) {
+      const int idx = e * NTH + t, r = idx >> 6, c = idx & 63;  // r: column of G, c: row of G
+      if (c0 + r < cp && r0 + c < rp) {
+        if (w.g32) gt[static_cast<int64_t>(c0 + r) * rp + r0 + c] = tg[c][r];
+        if (w.m32) gt[plane + static_cast<int64_t>(c0 + r) * rp + r0 + c] = tm[c][r];
+      }
+    }
   }
+  const int64_t p2 = static_cast<int64_t>(b) * w.rp2 * w.cp2;
+  if (w.gp) tile_to_panels(tg, w.gp + p2, r0, c0, w.cp2, false, t);
+  if (w.gpt) tile_to_panels(tg, w.gpt + p2, r0, c0, w.rp2, true, t);
+  if (w.mp) tile_to_panels(tm, w.mp + p2, r0, c0, w.cp2, false, t);
+  if (w.mpt) tile_to_panels(tm, w.mpt + p2, r0, c0, w.rp2, true, t);
 }
 
 // Adam in the rotated space.  rot [nb][2][rp][cp] holds G' and (unless `incremental`) M'; V (dense,
@@ -130,6 +166,96 @@ __global__ __launch_bounds__(NTH) void k_soap_adam(Shape s, PtrTable var, PtrTab
     const int idx = e * NTH + t, r = idx >> 6, c = idx & 63;
     out[static_cast<int64_t>(c0 + r) * rp + r0 + c] = tile[c][r];
   }
+}
+
+// The caller's basis Q (d x d, dense fp32) -> padded working copies in both orientations, zero outside d x d: fp32
+// [dp][dp] (if `f32`) and / or bf16 panels [dp2][dp2] (if given).  One block per 64 x 64 tile of the larger padding.
+__global__ __launch_bounds__(NTH) void k_soap_load_basis(PtrTable q, int64_t d, int64_t dp, bool f32, float* __restrict__ straight,
+                                                          float* __restrict__ transposed, int64_t dp2, __bf16* __restrict__ sp,
+                                                          __bf16* __restrict__ tp) {
+  __shared__ float tile[64][65];
+  const int b = blockIdx.z, r0 = blockIdx.y * 64, c0 = blockIdx.x * 64, t = threadIdx.x;
+  const float* src = static_cast<const float*>(q.p[b]);
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    const int idx = e * NTH + t, r = idx >> 6, c = idx & 63;
+    const int64_t row = r0 + r, col = c0 + c;
+    const float val = row < d && col < d ? src[row * d + col] : 0.f;
+    if (f32 && row < dp && col < dp) straight[(b * dp + row) * dp + col] = val;
+    tile[r][c] = val;
+  }
+  __syncthreads();
+  if (f32) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int idx = e * NTH + t, r = idx >> 6, c = idx & 63;  // r: column of Q, c: row of Q
+      if (c0 + r < dp && r0 + c < dp) transposed[(b * dp + c0 + r) * dp + r0 + c] = tile[c][r];
+    }
+  }
+  if (sp) tile_to_panels(tile, sp + b * dp2 * dp2, r0, c0, dp2, false, t);
+  if (tp) tile_to_panels(tile, tp + b * dp2 * dp2, r0, c0, dp2, true, t);
+}
+
+inline int64_t pad256(int64_t x) { return (x + PAD - 1) / PAD * PAD; }
+
+// Adam in the rotated space on bf16 panels: G' (and, unless `incremental`, M') [rp2][cp2] panels in, N' panels
+// out, straight [rp2][cp2] and / or transposed [cp2][rp2], zero outside rows x cols; V and the kept rotated
+// momentum are the caller's dense fp32 arrays as in k_soap_adam.  One block per 64 x 64 tile: the panel chunks
+// (8 consecutive elements of a row) go through LDS so that the dense fp32 arrays are read and written with one
+// row of 64 elements per wavefront, whatever the row length of the caller's matrix.
+__global__ __launch_bounds__(NTH) void k_soap_adam_bf16(Shape s, PtrTable var, PtrTable mrot, bool keep, bool incremental,
+                                                         const __bf16* __restrict__ grot, const __bf16* __restrict__ mrot_p,
+                                                         int64_t rp2, int64_t cp2, float beta1, float beta2, float c1,
+                                                         float c2, float eps, __bf16* __restrict__ n_straight,
+                                                         __bf16* __restrict__ n_transposed) {
+  __shared__ float tg[64][65], tm[64][65];
+  const int b = blockIdx.z, r0 = blockIdx.y * 64, c0 = blockIdx.x * 64, t = threadIdx.x;
+  const int64_t plane = rp2 * cp2;
+  const __bf16* gp = grot + static_cast<int64_t>(b) * plane;
+  float* v = static_cast<float*>(var.p[b]);
+  float* mr = static_cast<float*>(mrot.p[b]);
+  const int cv = (t & 7) * 8;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const int rl = (t >> 3) + half * 32;
+    const int64_t at = panel_chunk_off(r0 + rl, c0 + cv, cp2);
+    const bf16x8 g8 = *reinterpret_cast<const bf16x8*>(gp + at);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) tg[rl][cv + e] = static_cast<float>(g8[e]);
+    if (!incremental) {
+      const bf16x8 m8 = *reinterpret_cast<const bf16x8*>(mrot_p + static_cast<int64_t>(b) * plane + at);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) tm[rl][cv + e] = static_cast<float>(m8[e]);
+    }
+  }
+  __syncthreads();
+  float vo[16], mo[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {   // all old values first: one memory latency for the tile
+    const int idx = e * NTH + t, row = r0 + (idx >> 6), col = c0 + (idx & 63);
+    const bool in = row < s.rows && col < s.cols;
+    const int64_t av = static_cast<int64_t>(row) * s.cols + col;
+    vo[e] = in ? v[av] : 0.f;
+    mo[e] = in && incremental ? mr[av] : 0.f;
+  }
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    const int idx = e * NTH + t, r = idx >> 6, c = idx & 63, row = r0 + r, col = c0 + c;
+    float n = 0.f;
+    if (row < s.rows && col < s.cols) {
+      const int64_t av = static_cast<int64_t>(row) * s.cols + col;
+      const float g = tg[r][c];
+      const float m = incremental ? __builtin_fmaf(beta1, mo[e], (1.f - beta1) * g) : tm[r][c];
+      if (keep) mr[av] = m;
+      const float vn = __builtin_fmaf(beta2, vo[e], (1.f - beta2) * (g * g));
+      v[av] = vn;
+      n = (c1 * m) / (sqrtf(c2 * vn) + eps);
+    }
+    tg[r][c] = n;   // the element this thread read
+  }
+  __syncthreads();
+  if (n_straight) tile_to_panels(tg, n_straight + static_cast<int64_t>(b) * plane, r0, c0, cp2, false, t);
+  if (n_transposed) tile_to_panels(tg, n_transposed + static_cast<int64_t>(b) * plane, r0, c0, rp2, true, t);
 }
 
 // a[b][i] = (identity ? (row == col) : 0) for the [rows][ld] matrices of a batch
@@ -575,6 +701,8 @@ __global__ __launch_bounds__(QTH) void k_qr_tfactor(QrPanel a) {
 
 struct Carve {   // float offsets into the workspace of one launch batch
   size_t gm, gmt, t1, rot, np, yt, ql, qlt, qr, qrt, stat, wk, vall, y2, ybuf, tau, wt, qt, total_bytes;
+  // bf16 rotations (offsets in floats as well; each array holds bf16 panels padded to 256)
+  size_t gp, gpt, mp, mpt, as_g, at_g, as_m, at_m, rg, rgt, rm, rmt, npn, npt, ys, yst, qlp, qltp, qrp, qrtp;
 };
 
 struct Sides {
@@ -583,8 +711,12 @@ struct Sides {
 Sides sides(const canz_soap_group& g, const canz_soap_hparams& hp) {
   return {g.rows <= hp.max_precond_dim, g.cols <= hp.max_precond_dim};
 }
+// Gradients that arrive as bf16 are exact operands of the bf16 matrix cores: the products of G G^T and G^T G are
+// exact in fp32 and are accumulated in fp32, so the statistics lose nothing against the fp32 kernel and take
+// a fraction of its time.
+bool bf16_statistics(const canz_soap_group& g) { return g.grad_dtype == CANZ_DT_BF16; }
 
-Carve carve(int64_t rows, int64_t cols, int nb, Sides u, bool refresh) {
+Carve carve(int64_t rows, int64_t cols, int nb, Sides u, bool refresh, bool bf16, bool stat16) {
   const size_t rp = pad128(rows), cp = pad128(cols);
   const size_t dm = std::max(u.left ? rp : 0, u.right ? cp : 0);
   Carve c{};
@@ -612,12 +744,24 @@ Carve carve(int64_t rows, int64_t cols, int nb, Sides u, bool refresh) {
     c.wt = take(nb * dm * QB);
     c.qt = take(nb * dm * dm);
   }
+  const size_t rp2 = pad256(rows), cp2 = pad256(cols), p2 = nb * rp2 * cp2 / 2;   // floats that hold a batch of panels
+  if (bf16 || stat16) c.gp = take(bf16 || u.left ? p2 : 0), c.gpt = take(bf16 || u.right ? p2 : 0);
+  if (bf16) {
+    const bool both = u.left && u.right;
+    c.mp = take(p2), c.mpt = take(p2);
+    c.as_g = take(u.right ? p2 : 0), c.at_g = take(u.right ? p2 : 0), c.as_m = take(u.right ? p2 : 0), c.at_m = take(u.right ? p2 : 0);
+    c.rg = take(u.left ? p2 : 0), c.rgt = take(u.left ? p2 : 0), c.rm = take(u.left ? p2 : 0), c.rmt = take(u.left ? p2 : 0);
+    c.npn = take(p2), c.npt = take(p2);
+    c.ys = take(both ? p2 : 0), c.yst = take(both ? p2 : 0);
+    c.qlp = take(u.left ? nb * rp2 * rp2 / 2 : 0), c.qltp = take(u.left ? nb * rp2 * rp2 / 2 : 0);
+    c.qrp = take(u.right ? nb * cp2 * cp2 / 2 : 0), c.qrtp = take(u.right ? nb * cp2 * cp2 / 2 : 0);
+  }
   c.total_bytes = off * sizeof(float);
   return c;
 }
 
 int batch_cap(const canz_soap_group& g, const canz_soap_hparams& hp) {
-  const size_t one = carve(g.rows, g.cols, 1, sides(g, hp), hp.refresh != 0).total_bytes;
+  const size_t one = carve(g.rows, g.cols, 1, sides(g, hp), hp.refresh != 0, hp.bf16_rotations != 0, bf16_statistics(g)).total_bytes;
   const int64_t by_bytes = std::max<int64_t>(1, static_cast<int64_t>(BATCH_BYTES / one));
   return static_cast<int>(std::min<int64_t>(MAX_PTRS / g.tp, by_bytes));
 }
@@ -754,7 +898,9 @@ int refresh_side(void* const* q_tab, int first, int nb, int64_t d, int64_t dp, c
 int run_batch(const canz_soap_group& g, int first, int nb, const canz_soap_hparams& hp, float* ws, hipStream_t st) {
   const int64_t rp = pad128(g.rows), cp = pad128(g.cols), plane = rp * cp;
   const Sides u = sides(g, hp);
-  const Carve c = carve(g.rows, g.cols, nb, u, hp.refresh != 0);
+  const bool bf16 = hp.bf16_rotations != 0;
+  const bool stat16 = bf16_statistics(g);
+  const Carve c = carve(g.rows, g.cols, nb, u, hp.refresh != 0, bf16, stat16);
   Shape s{};
   s.rows = g.rows, s.cols = g.cols;
   s.m = std::min(g.rows, g.cols), s.n = std::max(g.rows, g.cols);
@@ -777,19 +923,45 @@ int run_batch(const canz_soap_group& g, int first, int nb, const canz_soap_hpara
   float *ql = ws + c.ql, *qlt = ws + c.qlt, *qr = ws + c.qr, *qrt = ws + c.qrt, *stat = ws + c.stat;
   const dim3 tiles(static_cast<unsigned>(cp / 64), static_cast<unsigned>(rp / 64), static_cast<unsigned>(nb));
 
+  // With a valid rotated momentum from the caller only G is rotated (M' follows its own recurrence in the rotated
+  // space, which is the same linear map as long as the bases stand still); otherwise G and M.
+  const bool incremental = g.mom_rot != nullptr && hp.mom_rot_valid != 0;
+  // bf16 images in the panel layout (padded to 256): operands of the bf16 rotations and of the statistics
+  const int64_t rp2 = pad256(g.rows), cp2 = pad256(g.cols), p2 = rp2 * cp2;
+  const SplitWs no_split{nullptr, 0};
+  auto pan = [&](size_t at) { return reinterpret_cast<__bf16*>(ws + at); };
+
   prof_mark(st, CANZ_KERNEL_SOAP_LOAD, true);
-  hipLaunchKernelGGL(k_soap_load, tiles, dim3(NTH), 0, st, s, grad, g.grad_dtype, mom, hp.beta1, rp, cp, gm, gmt);
-  // the bases: padded copies in both orientations (q [d][d] dense -> q, q^T, zero outside d x d)
-  auto load_basis = [&](void* const* tab, int64_t d, int64_t dp, float* straight, float* transposed) {
-    Shape sq{};
-    sq.rows = d, sq.cols = d, sq.tp = 1, sq.wfrag = d;
+  {
+    // fp32 copies: G for the fp32 rotations and the fp32 statistics, M for the fp32 rotations and for the
+    // re-rotation of a kept M' after a refresh; bf16 images: G for the bf16 rotations and statistics, M for the
+    // bf16 rotations of a step that rotates it
+    LoadOut w{};
+    w.gm = gm, w.gmt = gmt;
+    w.g32 = !bf16 || !stat16;
+    w.m32 = !bf16 || (hp.refresh && g.mom_rot != nullptr);
+    w.rp2 = rp2, w.cp2 = cp2;
+    if (bf16 || (stat16 && u.left)) w.gp = pan(c.gp);
+    if (bf16 || (stat16 && u.right)) w.gpt = pan(c.gpt);
+    if (bf16 && !incremental) w.mp = pan(c.mp), w.mpt = pan(c.mpt);
+    const bool images = w.gp || w.gpt;
+    const dim3 grid(static_cast<unsigned>((images ? cp2 : cp) / 64), static_cast<unsigned>((images ? rp2 : rp) / 64),
+                    static_cast<unsigned>(nb));
+    hipLaunchKernelGGL(k_soap_load, grid, dim3(NTH), 0, st, s, grad, g.grad_dtype, mom, hp.beta1, rp, cp, w);
+  }
+  // the bases: padded copies in both orientations, zero outside d x d: fp32 for the fp32 rotations and for the
+  // refresh (which multiplies the new statistic with the old basis), bf16 images for the bf16 rotations
+  auto load_basis = [&](void* const* tab, int64_t d, int64_t dp, float* straight, float* transposed, bool f32, int64_t dp2,
+                        __bf16* sp, __bf16* tp) {
     PtrTable q{};
     for (int i = 0; i < nb; ++i) q.p[i] = tab[first + i];
-    hipLaunchKernelGGL(k_sh_load, dim3(static_cast<unsigned>(dp / 64), static_cast<unsigned>(dp / 64), static_cast<unsigned>(nb)),
-                       dim3(NTH), 0, st, sq, q, static_cast<int>(CANZ_DT_F32), dp, dp, straight, transposed);
+    const unsigned side = static_cast<unsigned>((sp ? dp2 : dp) / 64);
+    hipLaunchKernelGGL(k_soap_load_basis, dim3(side, side, static_cast<unsigned>(nb)), dim3(NTH), 0, st, q, d, dp, f32, straight,
+                       transposed, dp2, sp, tp);
   };
-  if (u.left) load_basis(g.qleft, g.rows, rp, ql, qlt);
-  if (u.right) load_basis(g.qright, g.cols, cp, qr, qrt);
+  const bool basis32 = !bf16 || hp.refresh;
+  if (u.left) load_basis(g.qleft, g.rows, rp, ql, qlt, basis32, rp2, bf16 ? pan(c.qlp) : nullptr, bf16 ? pan(c.qltp) : nullptr);
+  if (u.right) load_basis(g.qright, g.cols, cp, qr, qrt, basis32, cp2, bf16 ? pan(c.qrp) : nullptr, bf16 ? pan(c.qrtp) : nullptr);
   prof_mark(st, CANZ_KERNEL_SOAP_LOAD, false);
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "load kernels: %s", hipGetErrorString(e));
 
@@ -820,68 +992,135 @@ int run_batch(const canz_soap_group& g, int first, int nb, const canz_soap_hpara
     }
     return CANZ_OK;
   };
-  // With a valid rotated momentum from the caller only G is rotated (M' follows its own recurrence in the rotated
-  // space, which is the same linear map as long as the bases stand still); otherwise G and M.
-  const bool incremental = g.mom_rot != nullptr && hp.mom_rot_valid != 0;
-  if (int rc = rotate_in(0, incremental ? 1 : 2)) return rc;
   PtrTable mrot{};
   if (g.mom_rot)
     for (int i = 0; i < nb; ++i) mrot.p[i] = g.mom_rot[first + i];
+  const double c1 = hp.bias_correction ? 1.0 / (1.0 - std::pow(static_cast<double>(hp.beta1), hp.step)) : 1.0;
+  const double c2 = hp.bias_correction ? 1.0 / (1.0 - std::pow(static_cast<double>(hp.beta2), hp.step)) : 1.0;
 
-  {
-    const double c1 = hp.bias_correction ? 1.0 / (1.0 - std::pow(static_cast<double>(hp.beta1), hp.step)) : 1.0;
-    const double c2 = hp.bias_correction ? 1.0 / (1.0 - std::pow(static_cast<double>(hp.beta2), hp.step)) : 1.0;
-    const int transposed = u.left && !u.right;
+  if (bf16) {
+    // The rotations on the bf16 matrix cores (fp32 accumulation): the bases, G (and M on a step that rotates it) and
+    // N' are rounded to bf16 once each, the intermediate of a two-sided rotation once more; momentum, second
+    // moment, the statistics' accumulation and the refresh stay in fp32.  The products reuse the update kernel of the
+    // Muon step (it writes its result in both orientations, which is what the next product wants as its second
+    // operand) and its last product (which writes the parameter update).
+    const GemmDims right_dims{cp2, rp2, cp2, cp2, cp2, cp2 * cp2, p2, nb};   // (basis rows) x (matrix rows), k over columns
+    const GemmDims left_dims{rp2, cp2, rp2, rp2, rp2, rp2 * rp2, p2, nb};    // (basis rows) x (matrix columns), k over rows
+    // X' = Q_L^T X Q_R for X given as straight and transposed panels; the result as straight panels
+    auto rotate_in16 = [&](const __bf16* xs, const __bf16* xt, size_t as_, size_t at_, size_t r_, size_t rt_,
+                           const __bf16** result) -> int {
+      if (u.right)   // as = (X Q_R)^T [cp2][rp2], at = X Q_R [rp2][cp2]
+        CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, launch_update_bf16(right_dims, pan(c.qrtp), xs, pan(as_), pan(at_), nullptr, no_split, st),
+                 "rotation (right, bf16)");
+      if (u.left)    // r = Q_L^T (.) [rp2][cp2] from the transposed image of what the right side left (or of X)
+        CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE,
+                 launch_update_bf16(left_dims, pan(c.qltp), u.right ? pan(as_) : xt, pan(r_), pan(rt_), nullptr, no_split, st),
+                 "rotation (left, bf16)");
+      *result = u.left ? pan(r_) : pan(at_);
+      return CANZ_OK;
+    };
+    const __bf16 *g_rot = nullptr, *m_rot = nullptr;
+    if (int rc = rotate_in16(pan(c.gp), pan(c.gpt), c.as_g, c.at_g, c.rg, c.rgt, &g_rot)) return rc;
+    if (!incremental)
+      if (int rc = rotate_in16(pan(c.mp), pan(c.mpt), c.as_m, c.at_m, c.rm, c.rmt, &m_rot)) return rc;
+    const bool want_t = u.left && !u.right;   // the left side alone takes N'^T as its second operand
+    const dim3 tiles2(static_cast<unsigned>(cp2 / 64), static_cast<unsigned>(rp2 / 64), static_cast<unsigned>(nb));
     prof_mark(st, CANZ_KERNEL_SOAP_ADAM, true);
-    hipLaunchKernelGGL(k_soap_adam, tiles, dim3(NTH), 0, st, s, var, mrot, g.mom_rot != nullptr, incremental, rot, rp, cp,
-                       hp.beta1, hp.beta2, static_cast<float>(c1), static_cast<float>(c2), hp.eps, transposed, np);
+    hipLaunchKernelGGL(k_soap_adam_bf16, tiles2, dim3(NTH), 0, st, s, var, mrot, g.mom_rot != nullptr, incremental, g_rot, m_rot,
+                       rp2, cp2, hp.beta1, hp.beta2, static_cast<float>(c1), static_cast<float>(c2), hp.eps,
+                       want_t ? nullptr : pan(c.npn), want_t ? pan(c.npt) : nullptr);
     prof_mark(st, CANZ_KERNEL_SOAP_ADAM, false);
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "adam kernel: %s", hipGetErrorString(e));
-  }
-
-  // rotation back, the last product writes the update
-  if (u.left && u.right) {
-    ShGemm cq{};  // yt = (N' Q_R^T)^T: [cp][rp]
-    cq.M = cp, cq.N = rp, cq.K = cp, cq.ldp = cp, cq.ldq = cp, cq.sp = cp * cp, cq.sq = plane;
-    cq.P = qr, cq.Q = np, cq.c = yt;
-    CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, (launch_gemm<SE_PLAIN, false>(cq, nb, none, s, o, st)), "back rotation (right)");
-    ShGemm dq{};
-    dq.M = rp, dq.N = cp, dq.K = rp, dq.ldp = rp, dq.ldq = rp, dq.sp = rp * rp, dq.sq = plane;
-    dq.P = ql, dq.Q = yt;
-    CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, (launch_gemm<SE_OUT, false>(dq, nb, none, s, o, st)), "back rotation (left)");
-  } else if (u.left) {
-    ShGemm dq{};  // np holds N'^T
-    dq.M = rp, dq.N = cp, dq.K = rp, dq.ldp = rp, dq.ldq = rp, dq.sp = rp * rp, dq.sq = plane;
-    dq.P = ql, dq.Q = np;
-    CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, (launch_gemm<SE_OUT, false>(dq, nb, none, s, o, st)), "back rotation (left)");
+    if (u.left && u.right) {
+      // ys = (N' Q_R^T)^T [cp2][rp2]; then Q_L times it, into the caller's buffers
+      CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, launch_update_bf16(right_dims, pan(c.qrp), pan(c.npn), pan(c.ys), pan(c.yst), nullptr, no_split, st),
+               "back rotation (right, bf16)");
+      CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, launch_final_bf16(left_dims, pan(c.qlp), pan(c.ys), nullptr, no_split, s, o, st),
+               "back rotation (left, bf16)");
+    } else if (u.left) {
+      CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, launch_final_bf16(left_dims, pan(c.qlp), pan(c.npt), nullptr, no_split, s, o, st),
+               "back rotation (left, bf16)");
+    } else {
+      const GemmDims d{rp2, cp2, cp2, cp2, cp2, p2, cp2 * cp2, nb};   // N' [rp2][cp2] times Q_R^T
+      CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, launch_final_bf16(d, pan(c.npn), pan(c.qrp), nullptr, no_split, s, o, st),
+               "back rotation (right, bf16)");
+    }
   } else {
-    ShGemm cq{};
-    cq.M = rp, cq.N = cp, cq.K = cp, cq.ldp = cp, cq.ldq = cp, cq.sp = plane, cq.sq = cp * cp;
-    cq.P = np, cq.Q = qr;
-    CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, (launch_gemm<SE_OUT, false>(cq, nb, none, s, o, st)), "back rotation (right)");
+    if (int rc = rotate_in(0, incremental ? 1 : 2)) return rc;
+
+    {
+      const int transposed = u.left && !u.right;
+      prof_mark(st, CANZ_KERNEL_SOAP_ADAM, true);
+      hipLaunchKernelGGL(k_soap_adam, tiles, dim3(NTH), 0, st, s, var, mrot, g.mom_rot != nullptr, incremental, rot, rp, cp,
+                         hp.beta1, hp.beta2, static_cast<float>(c1), static_cast<float>(c2), hp.eps, transposed, np);
+      prof_mark(st, CANZ_KERNEL_SOAP_ADAM, false);
+      if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "adam kernel: %s", hipGetErrorString(e));
+    }
+
+    // rotation back, the last product writes the update
+    if (u.left && u.right) {
+      ShGemm cq{};  // yt = (N' Q_R^T)^T: [cp][rp]
+      cq.M = cp, cq.N = rp, cq.K = cp, cq.ldp = cp, cq.ldq = cp, cq.sp = cp * cp, cq.sq = plane;
+      cq.P = qr, cq.Q = np, cq.c = yt;
+      CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, (launch_gemm<SE_PLAIN, false>(cq, nb, none, s, o, st)), "back rotation (right)");
+      ShGemm dq{};
+      dq.M = rp, dq.N = cp, dq.K = rp, dq.ldp = rp, dq.ldq = rp, dq.sp = rp * rp, dq.sq = plane;
+      dq.P = ql, dq.Q = yt;
+      CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, (launch_gemm<SE_OUT, false>(dq, nb, none, s, o, st)), "back rotation (left)");
+    } else if (u.left) {
+      ShGemm dq{};  // np holds N'^T
+      dq.M = rp, dq.N = cp, dq.K = rp, dq.ldp = rp, dq.ldq = rp, dq.sp = rp * rp, dq.sq = plane;
+      dq.P = ql, dq.Q = np;
+      CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, (launch_gemm<SE_OUT, false>(dq, nb, none, s, o, st)), "back rotation (left)");
+    } else {
+      ShGemm cq{};
+      cq.M = rp, cq.N = cp, cq.K = cp, cq.ldp = cp, cq.ldq = cp, cq.sp = plane, cq.sq = cp * cp;
+      cq.P = np, cq.Q = qr;
+      CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, (launch_gemm<SE_OUT, false>(cq, nb, none, s, o, st)), "back rotation (right)");
+    }
+
   }
 
   // statistics (and, on a refresh step, the new basis) side by side
   auto one_side = [&](void* const* stat_tab, void* const* q_tab, int64_t d, int64_t dp, int64_t kp, const float* side,
-                      const float* qt_old) -> int {
+                      const float* qt_old, const __bf16* side16, int64_t d2, int64_t k2) -> int {
     PtrTable tab{};
     for (int i = 0; i < nb; ++i) tab.p[i] = stat_tab[first + i];
-    ShGemm q{};
-    q.M = dp, q.N = dp, q.K = kp, q.ldp = kp, q.ldq = kp, q.sp = 2 * plane, q.sq = 2 * plane;
-    q.P = side, q.Q = side, q.c = hp.refresh ? stat : nullptr, q.d = d, q.beta = hp.beta2, q.gscale = 1.f - hp.beta2, q.eps = 0.f;
-    CANZ_HIP(CANZ_KERNEL_SOAP_STAT, (launch_gemm<SE_STAT, true>(q, nb, tab, s, o, st)), "statistics kernel");
+    if (stat16) {
+      // S <- beta2 S + (1 - beta2) X X^T as the "last product" of the bf16 kernels: it updates the caller's dense
+      // fp32 array in place as old * decay + factor * product
+      Shape sq{};
+      sq.rows = d, sq.cols = d, sq.m = d, sq.n = d, sq.mp = d2, sq.np = d2, sq.tp = 1, sq.wfrag = d;
+      OutSpec so{};
+      so.out = tab, so.out_dtype = CANZ_DT_F32, so.out_mode = CANZ_OUT_PARAM, so.decay = hp.beta2, so.neg_lr_scale = 1.f - hp.beta2;
+      const GemmDims sd{d2, d2, k2, k2, k2, d2 * k2, d2 * k2, nb};
+      CANZ_HIP(CANZ_KERNEL_SOAP_STAT, launch_final_bf16(sd, side16, side16, nullptr, no_split, sq, so, st),
+               "statistics kernel (bf16 operands)");
+      if (hp.refresh) {   // the padded copy the refresh multiplies the basis with (its transposed image lands in wk, unused)
+        prof_mark(st, CANZ_KERNEL_SOAP_STAT, true);
+        hipLaunchKernelGGL(k_sh_load, dim3(static_cast<unsigned>(dp / 64), static_cast<unsigned>(dp / 64), static_cast<unsigned>(nb)),
+                           dim3(NTH), 0, st, sq, tab, static_cast<int>(CANZ_DT_F32), dp, dp, stat, ws + c.wk);
+        prof_mark(st, CANZ_KERNEL_SOAP_STAT, false);
+        if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "statistic copy: %s", hipGetErrorString(e));
+      }
+    } else {
+      ShGemm q{};
+      q.M = dp, q.N = dp, q.K = kp, q.ldp = kp, q.ldq = kp, q.sp = 2 * plane, q.sq = 2 * plane;
+      q.P = side, q.Q = side, q.c = hp.refresh ? stat : nullptr, q.d = d, q.beta = hp.beta2, q.gscale = 1.f - hp.beta2, q.eps = 0.f;
+      CANZ_HIP(CANZ_KERNEL_SOAP_STAT, (launch_gemm<SE_STAT, true>(q, nb, tab, s, o, st)), "statistics kernel");
+    }
     if (!hp.refresh) return CANZ_OK;
     return refresh_side(q_tab, first, nb, d, dp, stat, qt_old, ws, c, s, o, st);
   };
   if (u.left)
-    if (int rc = one_side(g.left, g.qleft, g.rows, rp, cp, gm, qlt)) return rc;
+    if (int rc = one_side(g.left, g.qleft, g.rows, rp, cp, gm, qlt, pan(c.gp), rp2, cp2)) return rc;
   if (u.right)
-    if (int rc = one_side(g.right, g.qright, g.cols, cp, rp, gmt, qrt)) return rc;
+    if (int rc = one_side(g.right, g.qright, g.cols, cp, rp, gmt, qrt, pan(c.gpt), cp2, rp2)) return rc;
   if (hp.refresh && g.mom_rot) {
     // the caller's rotated momentum follows the new bases: M' = Q_L^T M Q_R once more, with the M of this step
     prof_mark(st, CANZ_KERNEL_SOAP_LOAD, true);
-    if (u.left) load_basis(g.qleft, g.rows, rp, ql, qlt);
-    if (u.right) load_basis(g.qright, g.cols, cp, qr, qrt);
+    if (u.left) load_basis(g.qleft, g.rows, rp, ql, qlt, true, rp2, nullptr, nullptr);
+    if (u.right) load_basis(g.qright, g.cols, cp, qr, qrt, true, cp2, nullptr, nullptr);
     prof_mark(st, CANZ_KERNEL_SOAP_LOAD, false);
     if (int rc = rotate_in(1, 1)) return rc;
     prof_mark(st, CANZ_KERNEL_SOAP_ADAM, true);
@@ -906,7 +1145,7 @@ extern "C" int canz_soap_workspace_bytes(const canz_soap_group* g, int32_t n_gro
     if (int rc = check_group(g[i], i, false, *hp)) return rc;
     if (g[i].n_mats == 0) continue;
     need = std::max(need, carve(g[i].rows, g[i].cols, std::min(g[i].n_mats, batch_cap(g[i], *hp)), sides(g[i], *hp),
-                                hp->refresh != 0).total_bytes);
+                                hp->refresh != 0, hp->bf16_rotations != 0, bf16_statistics(g[i])).total_bytes);
   }
   *bytes_out = need;
   return CANZ_OK;

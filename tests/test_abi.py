@@ -160,10 +160,20 @@ def test_soap_argument_errors_and_workspace_without_device(canz):
     plane, sq = 256 * 512, 512 * 512
     plain = 4 * (10 * plane + 2 * 256 * 256 + 2 * sq + sq)
     fresh = plain + 4 * (4 * sq + 2 * 512 * 32 + 64)
-    one = [G(rows=256, cols=512, n_mats=1)]
+    one = [G(rows=256, cols=512, n_mats=1, grad_dtype=canz.DT_F32)]
     assert canz.canz_soap_workspace_bytes(one, hp) == plain
-    assert canz.canz_soap_workspace_bytes([G(rows=200, cols=500, n_mats=1)], hp) == plain
+    assert canz.canz_soap_workspace_bytes([G(rows=200, cols=500, n_mats=1, grad_dtype=canz.DT_F32)], hp) == plain
     assert canz.canz_soap_workspace_bytes(one, canz.SoapHparams(refresh=True)) == fresh
     # one-sided: no half-rotated images, no basis of the long side, the statistic of the short side only
-    assert canz.canz_soap_workspace_bytes(one, canz.SoapHparams(max_precond_dim=256)) == 4 * (7 * plane + 3 * 256 * 256)
-    assert ctypes.sizeof(canz._SoapGroup) == 16 + 16 + 72 and ctypes.sizeof(canz._SoapHparams) == 44
+    one_sided = 4 * (7 * plane + 3 * 256 * 256)
+    assert canz.canz_soap_workspace_bytes(one, canz.SoapHparams(max_precond_dim=256)) == one_sided
+    # bf16 gradients: their bf16 image padded to 256, one orientation per side with a statistic
+    one16 = [G(rows=256, cols=512, n_mats=1, grad_dtype=canz.DT_BF16)]
+    assert canz.canz_soap_workspace_bytes(one16, hp) == plain + 2 * 2 * plane
+    assert canz.canz_soap_workspace_bytes(one16, canz.SoapHparams(max_precond_dim=256)) == one_sided + 2 * plane
+    # bf16 rotations add bf16 images padded to 256: sixteen planes (G, M, their half-rotated and rotated images, N', its
+    # half-rotated image, each in two orientations) and the bases in two orientations
+    want16 = plain + 2 * (16 * plane + 2 * 256 * 256 + 2 * sq)
+    assert canz.canz_soap_workspace_bytes(one, canz.SoapHparams(bf16_rotations=True)) == want16
+    assert canz.canz_soap_workspace_bytes(one16, canz.SoapHparams(bf16_rotations=True)) == want16
+    assert ctypes.sizeof(canz._SoapGroup) == 16 + 16 + 72 and ctypes.sizeof(canz._SoapHparams) == 48
