@@ -77,6 +77,9 @@ __device__ __forceinline__ void tile_to_panels(const float (*tile)[65], __bf16* 
 // G (bf16 or fp32, whole or tp column fragments) and the momentum M <- beta1 M + (1 - beta1) G
 // (fp32, dense, in the caller's buffer) -> working copies of both as `w` asks, zero outside rows x cols.
 // One block per 64 x 64 tile of the padded matrix (padded to 256 if a bf16 image is wanted, else to 128).
+// VEC: cols and cols / tp are multiples of 8, so a lane's 8 consecutive elements lie in one fragment and every
+// access of the caller's arrays is a 16-byte vector.
+template <bool VEC>
 __global__ __launch_bounds__(NTH) void k_soap_load(Shape s, PtrTable grad, int grad_dtype, PtrTable mom, float beta1,
                                                     int64_t rp, int64_t cp, LoadOut w) {
   __shared__ float tg[64][65], tm[64][65];
@@ -86,6 +89,56 @@ __global__ __launch_bounds__(NTH) void k_soap_load(Shape s, PtrTable grad, int g
   float* gs = w.gm + static_cast<int64_t>(b) * 2 * plane;
   float* gt = w.gmt + static_cast<int64_t>(b) * 2 * plane;
   float* m = static_cast<float*>(mom.p[b]);
+  if (VEC) {
+    const int cv = (t & 7) * 8;
+    f32x4 gv[2][2], mv[2][2];
+    bool live[2];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {   // all loads first: the tables may alias as far as the compiler knows
+      const int row = r0 + (t >> 3) + half * 32, col = c0 + cv;
+      live[half] = row < s.rows && col < s.cols;
+      gv[half][0] = gv[half][1] = mv[half][0] = mv[half][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (!live[half]) continue;
+      const int f = col / wf;
+      const int64_t at = static_cast<int64_t>(row) * wf + (col - f * wf);
+      if (grad_dtype == CANZ_DT_BF16) {
+        const bf16x8 g8 = *reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(grad.p[b * s.tp + f]) + at);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) gv[half][0][e] = static_cast<float>(g8[e]), gv[half][1][e] = static_cast<float>(g8[4 + e]);
+      } else {
+        const f32x4* g4 = reinterpret_cast<const f32x4*>(static_cast<const float*>(grad.p[b * s.tp + f]) + at);
+        gv[half][0] = g4[0], gv[half][1] = g4[1];
+      }
+      const f32x4* m4 = reinterpret_cast<const f32x4*>(m + static_cast<int64_t>(row) * s.cols + col);
+      mv[half][0] = m4[0], mv[half][1] = m4[1];
+    }
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int rl = (t >> 3) + half * 32, row = r0 + rl, col = c0 + cv;
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          mv[half][q][e] = live[half] ? __builtin_fmaf(beta1, mv[half][q][e], (1.f - beta1) * gv[half][q][e]) : 0.f;
+          tg[rl][cv + 4 * q + e] = gv[half][q][e];
+          tm[rl][cv + 4 * q + e] = mv[half][q][e];
+        }
+      if (live[half]) {
+        f32x4* m4 = reinterpret_cast<f32x4*>(m + static_cast<int64_t>(row) * s.cols + col);
+        m4[0] = mv[half][0], m4[1] = mv[half][1];
+      }
+      if (row < rp && col < cp) {
+        if (w.g32) {
+          f32x4* o = reinterpret_cast<f32x4*>(gs + static_cast<int64_t>(row) * cp + col);
+          o[0] = gv[half][0], o[1] = gv[half][1];
+        }
+        if (w.m32) {
+          f32x4* o = reinterpret_cast<f32x4*>(gs + plane + static_cast<int64_t>(row) * cp + col);
+          o[0] = mv[half][0], o[1] = mv[half][1];
+        }
+      }
+    }
+  } else {
 #pragma unroll
   for (int e = 0; e < 16; ++e) {
     const int idx = e * NTH + t, r = idx >> 6, c = idx & 63;
@@ -106,6 +159,7 @@ __global__ __launch_bounds__(NTH) void k_soap_load(Shape s, PtrTable grad, int g
     }
     tg[r][c] = g;
     tm[r][c] = mv;
+  }
   }
   __syncthreads();
   if (w.g32 || w.m32) {
@@ -933,21 +987,24 @@ int run_batch(const canz_soap_group& g, int first, int nb, const canz_soap_hpara
 
   prof_mark(st, CANZ_KERNEL_SOAP_LOAD, true);
   {
-    // fp32 copies: G for the fp32 rotations and the fp32 statistics, M for the fp32 rotations and for the
-    // re-rotation of a kept M' after a refresh; bf16 images: G for the bf16 rotations and statistics, M for the
-    // bf16 rotations of a step that rotates it
+    // fp32 copies: G for the fp32 rotations and the fp32 statistics, M for the fp32 rotations; bf16 images: G for the
+    // bf16 rotations and statistics, M for the bf16 rotations of a step that rotates it (also the re-rotation of a
+    // kept M' after a refresh)
     LoadOut w{};
     w.gm = gm, w.gmt = gmt;
     w.g32 = !bf16 || !stat16;
-    w.m32 = !bf16 || (hp.refresh && g.mom_rot != nullptr);
+    w.m32 = !bf16;
     w.rp2 = rp2, w.cp2 = cp2;
     if (bf16 || (stat16 && u.left)) w.gp = pan(c.gp);
     if (bf16 || (stat16 && u.right)) w.gpt = pan(c.gpt);
-    if (bf16 && !incremental) w.mp = pan(c.mp), w.mpt = pan(c.mpt);
+    if (bf16 && (!incremental || (hp.refresh && g.mom_rot != nullptr))) w.mp = pan(c.mp), w.mpt = pan(c.mpt);
     const bool images = w.gp || w.gpt;
     const dim3 grid(static_cast<unsigned>((images ? cp2 : cp) / 64), static_cast<unsigned>((images ? rp2 : rp) / 64),
                     static_cast<unsigned>(nb));
-    hipLaunchKernelGGL(k_soap_load, grid, dim3(NTH), 0, st, s, grad, g.grad_dtype, mom, hp.beta1, rp, cp, w);
+    if (g.cols % 8 == 0 && s.wfrag % 8 == 0)
+      hipLaunchKernelGGL(k_soap_load<true>, grid, dim3(NTH), 0, st, s, grad, g.grad_dtype, mom, hp.beta1, rp, cp, w);
+    else
+      hipLaunchKernelGGL(k_soap_load<false>, grid, dim3(NTH), 0, st, s, grad, g.grad_dtype, mom, hp.beta1, rp, cp, w);
   }
   // the bases: padded copies in both orientations, zero outside d x d: fp32 for the fp32 rotations and for the
   // refresh (which multiplies the new statistic with the old basis), bf16 images for the bf16 rotations
@@ -955,7 +1012,7 @@ int run_batch(const canz_soap_group& g, int first, int nb, const canz_soap_hpara
                         __bf16* sp, __bf16* tp) {
     PtrTable q{};
     for (int i = 0; i < nb; ++i) q.p[i] = tab[first + i];
-    const unsigned side = static_cast<unsigned>((sp ? dp2 : dp) / 64);
+    const unsigned side = static_cast<unsigned>((sp || tp ? dp2 : dp) / 64);
     hipLaunchKernelGGL(k_soap_load_basis, dim3(side, side, static_cast<unsigned>(nb)), dim3(NTH), 0, st, q, d, dp, f32, straight,
                        transposed, dp2, sp, tp);
   };
@@ -998,14 +1055,15 @@ int run_batch(const canz_soap_group& g, int first, int nb, const canz_soap_hpara
   const double c1 = hp.bias_correction ? 1.0 / (1.0 - std::pow(static_cast<double>(hp.beta1), hp.step)) : 1.0;
   const double c2 = hp.bias_correction ? 1.0 / (1.0 - std::pow(static_cast<double>(hp.beta2), hp.step)) : 1.0;
 
+  // shapes of the bf16 rotation products (first operand: a basis)
+  const GemmDims right_dims{cp2, rp2, cp2, cp2, cp2, cp2 * cp2, p2, nb};   // (basis rows) x (matrix rows), k over columns
+  const GemmDims left_dims{rp2, cp2, rp2, rp2, rp2, rp2 * rp2, p2, nb};    // (basis rows) x (matrix columns), k over rows
   if (bf16) {
     // The rotations on the bf16 matrix cores (fp32 accumulation): the bases, G (and M on a step that rotates it) and
     // N' are rounded to bf16 once each, the intermediate of a two-sided rotation once more; momentum, second
     // moment, the statistics' accumulation and the refresh stay in fp32.  The products reuse the update kernel of the
     // Muon step (it writes its result in both orientations, which is what the next product wants as its second
     // operand) and its last product (which writes the parameter update).
-    const GemmDims right_dims{cp2, rp2, cp2, cp2, cp2, cp2 * cp2, p2, nb};   // (basis rows) x (matrix rows), k over columns
-    const GemmDims left_dims{rp2, cp2, rp2, rp2, rp2, rp2 * rp2, p2, nb};    // (basis rows) x (matrix columns), k over rows
     // X' = Q_L^T X Q_R for X given as straight and transposed panels; the result as straight panels
     auto rotate_in16 = [&](const __bf16* xs, const __bf16* xt, size_t as_, size_t at_, size_t r_, size_t rt_,
                            const __bf16** result) -> int {
@@ -1116,8 +1174,34 @@ int run_batch(const canz_soap_group& g, int first, int nb, const canz_soap_hpara
     if (int rc = one_side(g.left, g.qleft, g.rows, rp, cp, gm, qlt, pan(c.gp), rp2, cp2)) return rc;
   if (u.right)
     if (int rc = one_side(g.right, g.qright, g.cols, cp, rp, gmt, qrt, pan(c.gpt), cp2, rp2)) return rc;
-  if (hp.refresh && g.mom_rot) {
-    // the caller's rotated momentum follows the new bases: M' = Q_L^T M Q_R once more, with the M of this step
+  if (hp.refresh && g.mom_rot && bf16) {
+    // the caller's rotated momentum follows the new bases, M' = Q_L^T M Q_R once more with the M of this step: bf16
+    // operands as for every rotation of this mode; the last product leaves its fp32 sums in the caller's array
+    prof_mark(st, CANZ_KERNEL_SOAP_LOAD, true);
+    if (u.left) load_basis(g.qleft, g.rows, rp, ql, qlt, false, rp2, nullptr, pan(c.qltp));
+    if (u.right) load_basis(g.qright, g.cols, cp, qr, qrt, false, cp2, nullptr, pan(c.qrtp));
+    prof_mark(st, CANZ_KERNEL_SOAP_LOAD, false);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "basis load: %s", hipGetErrorString(e));
+    Shape whole = s;
+    whole.tp = 1, whole.wfrag = g.cols;
+    OutSpec mo{};
+    mo.out = mrot, mo.out_dtype = CANZ_DT_F32, mo.out_mode = CANZ_OUT_DELTA, mo.decay = 1.f, mo.neg_lr_scale = 1.f;
+    if (u.left && u.right) {
+      CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE,
+               launch_update_bf16(right_dims, pan(c.qrtp), pan(c.mp), pan(c.as_m), pan(c.at_m), nullptr, no_split, st),
+               "momentum re-rotation (right, bf16)");
+      CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, launch_final_bf16(left_dims, pan(c.qltp), pan(c.as_m), nullptr, no_split, whole, mo, st),
+               "momentum re-rotation (left, bf16)");
+    } else if (u.left) {
+      CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, launch_final_bf16(left_dims, pan(c.qltp), pan(c.mpt), nullptr, no_split, whole, mo, st),
+               "momentum re-rotation (left, bf16)");
+    } else {
+      const GemmDims d{rp2, cp2, cp2, cp2, cp2, p2, cp2 * cp2, nb};   // M [rp2][cp2] times (Q_R^T)^T
+      CANZ_HIP(CANZ_KERNEL_SOAP_ROTATE, launch_final_bf16(d, pan(c.mp), pan(c.qrtp), nullptr, no_split, whole, mo, st),
+               "momentum re-rotation (right, bf16)");
+    }
+  } else if (hp.refresh && g.mom_rot) {
+    // the same in fp32
     prof_mark(st, CANZ_KERNEL_SOAP_LOAD, true);
     if (u.left) load_basis(g.qleft, g.rows, rp, ql, qlt, true, rp2, nullptr, nullptr);
     if (u.right) load_basis(g.qright, g.cols, cp, qr, qrt, true, cp2, nullptr, nullptr);
