@@ -352,6 +352,10 @@ int canz_shampoo_step(const canz_shampoo_group* g, int32_t n_groups, const canz_
  * its columns are fixed up to sign (which the step does not depend on); where L Q_L is rank
  * deficient the trailing columns are some orthonormal completion.
  *
+ * Consecutive groups of one call that agree in shape, tp, dtypes and in which tables they pass run as one
+ * group (a matrix's result does not depend on what shares its launch; a refresh fills the chip better the
+ * more matrices it holds).
+ *
  * One micro-group: n_mats matrices of identical shape and dtypes; grad / out / tp as in
  * canz_group; all state is fp32, dense, row-major, device, 16-byte aligned, updated in place:
  * mom[i], var[i] rows x cols; left[i], qleft[i] rows x rows; right[i], qright[i] cols x cols

@@ -30,6 +30,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <vector>
 
 #include "canz.h"
 #include "canz_internal.h"
@@ -1215,6 +1216,67 @@ int run_batch(const canz_soap_group& g, int first, int nb, const canz_soap_hpara
   return CANZ_OK;
 }
 
+// Consecutive groups of a call that agree in shape, tp, dtypes and in which tables they pass run as one group: every
+// matrix is computed on its own whatever shares its launch, a refresh keeps only one workgroup per matrix busy in
+// its panel kernel, and its products are small - the more matrices share a launch, the better the chip is filled.
+struct MergedGroup {
+  canz_soap_group g{};
+  std::vector<const void*> grad;
+  std::vector<void*> tab[8];   // mom, var, left, right, qleft, qright, out, mom_rot
+};
+
+void* const* const* tables_of(const canz_soap_group& g, void* const* (&out)[8]) {
+  out[0] = g.mom, out[1] = g.var, out[2] = g.left, out[3] = g.right, out[4] = g.qleft, out[5] = g.qright, out[6] = g.out,
+  out[7] = g.mom_rot;
+  return out;
+}
+
+bool mergeable(const canz_soap_group& a, const canz_soap_group& b) {
+  if (a.rows != b.rows || a.cols != b.cols || a.tp != b.tp || a.grad_dtype != b.grad_dtype || a.out_dtype != b.out_dtype) return false;
+  if ((a.grad == nullptr) != (b.grad == nullptr)) return false;
+  void* const* ta[8];
+  void* const* tb[8];
+  tables_of(a, ta), tables_of(b, tb);
+  for (int k = 0; k < 8; ++k)
+    if ((ta[k] == nullptr) != (tb[k] == nullptr)) return false;
+  return true;
+}
+
+std::vector<MergedGroup> merge_groups(const canz_soap_group* g, int n_groups, const canz_soap_hparams& hp) {
+  std::vector<MergedGroup> all;
+  const auto append = [&](MergedGroup& m, const canz_soap_group& x) {
+    void* const* t[8];
+    tables_of(x, t);
+    const int per_out = hp.out_mode == CANZ_OUT_DELTA ? x.tp : 1;
+    if (x.grad) m.grad.insert(m.grad.end(), x.grad, x.grad + static_cast<size_t>(x.n_mats) * x.tp);
+    for (int k = 0; k < 8; ++k)
+      if (t[k]) m.tab[k].insert(m.tab[k].end(), t[k], t[k] + static_cast<size_t>(x.n_mats) * (k == 6 ? per_out : 1));
+    m.g.n_mats += x.n_mats;
+  };
+  for (int i = 0; i < n_groups; ++i) {
+    if (g[i].n_mats == 0) continue;
+    if (all.empty() || !mergeable(all.back().g, g[i])) {
+      all.emplace_back();
+      all.back().g = g[i];
+      all.back().g.n_mats = 0;
+    }
+    append(all.back(), g[i]);
+  }
+  for (MergedGroup& m : all) {   // the tables now stand still: point the group at them
+    canz_soap_group& x = m.g;
+    if (x.grad) x.grad = m.grad.data();
+    if (x.mom) x.mom = m.tab[0].data();
+    if (x.var) x.var = m.tab[1].data();
+    if (x.left) x.left = m.tab[2].data();
+    if (x.right) x.right = m.tab[3].data();
+    if (x.qleft) x.qleft = m.tab[4].data();
+    if (x.qright) x.qright = m.tab[5].data();
+    if (x.out) x.out = m.tab[6].data();
+    if (x.mom_rot) x.mom_rot = m.tab[7].data();
+  }
+  return all;
+}
+
 }  // namespace
 }  // namespace canz
 
@@ -1225,12 +1287,11 @@ extern "C" int canz_soap_workspace_bytes(const canz_soap_group* g, int32_t n_gro
   if (n_groups < 0 || (n_groups > 0 && !g)) return fail(CANZ_EINVAL, "bad group array");
   if (int rc = check_hparams(hp)) return rc;
   size_t need = ALIGN;
-  for (int i = 0; i < n_groups; ++i) {
+  for (int i = 0; i < n_groups; ++i)
     if (int rc = check_group(g[i], i, false, *hp)) return rc;
-    if (g[i].n_mats == 0) continue;
-    need = std::max(need, carve(g[i].rows, g[i].cols, std::min(g[i].n_mats, batch_cap(g[i], *hp)), sides(g[i], *hp),
-                                hp->refresh != 0, hp->bf16_rotations != 0, bf16_statistics(g[i])).total_bytes);
-  }
+  for (const MergedGroup& m : merge_groups(g, n_groups, *hp))
+    need = std::max(need, carve(m.g.rows, m.g.cols, std::min(m.g.n_mats, batch_cap(m.g, *hp)), sides(m.g, *hp), hp->refresh != 0,
+                                hp->bf16_rotations != 0, bf16_statistics(m.g)).total_bytes);
   *bytes_out = need;
   return CANZ_OK;
 }
@@ -1251,10 +1312,10 @@ extern "C" int canz_soap_step(const canz_soap_group* g, int32_t n_groups, const 
   if (workspace_bytes < need)
     return fail(CANZ_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  for (int i = 0; i < n_groups; ++i) {
-    const int cap = batch_cap(g[i], *hp);
-    for (int first = 0; first < g[i].n_mats; first += cap)
-      if (int rc = run_batch(g[i], first, std::min(cap, g[i].n_mats - first), *hp, static_cast<float*>(workspace), st)) return rc;
+  for (const MergedGroup& m : merge_groups(g, n_groups, *hp)) {
+    const int cap = batch_cap(m.g, *hp);
+    for (int first = 0; first < m.g.n_mats; first += cap)
+      if (int rc = run_batch(m.g, first, std::min(cap, m.g.n_mats - first), *hp, static_cast<float*>(workspace), st)) return rc;
   }
   return CANZ_OK;
 }
