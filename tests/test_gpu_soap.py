@@ -351,6 +351,39 @@ def test_two_groups_in_one_call_and_batches_are_independent(canz):
         assert torch.equal(d.out_t[1], a.out_t[0])
 
 
+@pytest.mark.parametrize("bf16_rot", [False, True], ids=["fp32", "bf16-rotations"])
+def test_like_shaped_groups_of_a_call_are_merged_and_unchanged(canz, bf16_rot):
+    """Three groups in one call, the first two of one shape (the library runs them as one launch batch), the third of
+    another; every matrix's state, output and kept rotated momentum are bit-identical to a call with its own group alone."""
+    import torch
+    shapes = [(264, 136), (264, 136), (136, 264)]
+    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=4, refresh=True, bf16_rotations=bf16_rot)
+
+    def build():
+        out = []
+        for gi, (rows, cols) in enumerate(shapes):
+            n = 2 + gi
+            grads = [W.gen_grad(84, 10 * gi + i, rows, cols)[0] for i in range(n)]
+            states = [W.gen_soap_state(84, 10 * gi + i, rows, cols) for i in range(n)]
+            params = [W.gen_param(84, 10 * gi + i, rows, cols) for i in range(n)]
+            rot = [np.full((rows, cols), np.nan, np.float32) for _ in range(n)]
+            out.append((SoapDevice(canz, rows, cols, grads, states, outs=params, mom_rot=rot), grads, states, params))
+        return out
+
+    together, apart = build(), build()
+    run(canz, [d for d, _, _, _ in together], hp)
+    for d, _, _, _ in apart:
+        run(canz, [d], hp)
+    for (d, grads, states, params), (a, _, _, _) in zip(together, apart):
+        for key in STATE_KEYS:
+            for i in range(d.n):
+                assert torch.equal(d.t[key][i], a.t[key][i]), "%s of matrix %d differs between one call and three" % (key, i)
+        for i in range(d.n):
+            assert torch.equal(d.out_t[i], a.out_t[i]) and torch.equal(d.mom_rot_t[i], a.mom_rot_t[i])
+        if not bf16_rot:
+            check(d, grads, states, params, hp, "soap merged groups %dx%d" % (d.rows, d.cols))
+
+
 def test_config2_shape_with_refresh(canz):
     """Four 2048 x 1024 matrices (the 0.6B-shaped share's shape): state and update of every matrix against the oracle,
     refreshed bases of the first one against the oracle's QR, properties on all."""
