@@ -4,4 +4,4 @@
 ``paper_2602_06079_amd.workloads`` holds the seeded synthetic inputs.  Importing
 the package loads nothing native; the binding raises if the library is missing.
 """
-__version__ = "0.3.0"
+__version__ = "0.4.0"

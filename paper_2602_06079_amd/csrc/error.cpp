@@ -19,4 +19,4 @@ int fail(int code, const char* fmt, ...) {
 }  // namespace canz
 
 extern "C" const char* canz_last_error(void) { return g_msg; }
-extern "C" const char* canz_version(void) { return "0.3.0"; }
+extern "C" const char* canz_version(void) { return "0.4.0"; }

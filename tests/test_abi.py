@@ -21,7 +21,7 @@ def test_header_functions_are_exported(canz):
     lib = ctypes.CDLL(canz.LIB_PATH)
     for n in names:
         assert getattr(lib, n) is not None
-    assert canz.canz_version() == "0.3.0"
+    assert canz.canz_version() == "0.4.0"
 
 
 def test_struct_layouts_match_header(canz):
