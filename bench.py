@@ -365,10 +365,14 @@ def main_soap(args, canz, W, np, torch):
     def pad(x, to=128):
         return (x + to - 1) // to * to
 
-    def sym(d, k):
-        # the statistic is symmetric (d (d + 1) k FLOPs); from bf16 gradients, as here, it is computed as the whole
-        # square by the bf16 kernels, on operands padded to 256
-        return d * (d + 1) * k, 2 * pad(d, 256) * pad(d, 256) * pad(k, 256)
+    def sym(d, k, n):
+        # the statistic is symmetric (d (d + 1) k FLOPs); from bf16 gradients, as here, the bf16 kernels compute its
+        # 256 x 256 tiles on operands padded to 256: those on and above the diagonal where the sums are long (the
+        # library's rule, restated here for the count), else the whole square
+        t = pad(d, 256) // 256
+        saved_us = t * (t - 1) // 2 * n / 256.0 * (pad(k, 256) // 32) * 0.65
+        tiles = t * (t + 1) // 2 if saved_us > 1.5 * (15.0 + d * d * n * 4.0 / 4.0e6) else t * t
+        return d * (d + 1) * k, tiles * 256 * 256 * 2 * pad(k, 256)
 
     alg = dict(soap_rotate=0.0, soap_stat=0.0, soap_qr=0.0)
     iss = dict(soap_rotate=0.0, soap_stat=0.0)
@@ -385,7 +389,8 @@ def main_soap(args, canz, W, np, torch):
         iss["soap_rotate"] += n_rot * n * per_rot_iss
         for d, k, used in ((r, c, use_l), (c, r, use_r)):
             if used:
-                a, i = sym(d, k)
+                # like-shaped consecutive groups run as one launch batch
+                a, i = sym(d, k, sum(len(h) for h in groups if (s["rows"][h[0]], s["cols"][h[0]]) == (r, c)))
                 alg["soap_stat"] += n * a * args.steps
                 iss["soap_stat"] += n * i * args.steps
                 alg["soap_qr"] += n * (2.0 + 4.0 / 3.0 + 4.0 / 3.0) * d ** 3 * n_refresh

@@ -53,7 +53,11 @@ constexpr int GROUP_M = 4;       // tile rows per raster band
 constexpr int N_XCD = 8;
 static_assert(BM == PANEL_ROWS && BK == PANEL_K, "tile = panel");
 
-enum { EPI_GRAM = 0, EPI_POLY = 1, EPI_UPDATE = 2, EPI_FINAL = 3 };
+enum { EPI_GRAM = 0, EPI_POLY = 1, EPI_UPDATE = 2, EPI_FINAL = 3, EPI_FINAL_SYM = 4 };
+// EPI_FINAL_SYM: the last-product epilogue (the caller's dense buffers) over the tiles on and above the diagonal of a
+// symmetric result only; the caller mirrors them into the lower triangle afterwards.
+constexpr bool epi_symmetric(int epi) { return epi == EPI_GRAM || epi == EPI_POLY || epi == EPI_FINAL_SYM; }
+constexpr bool epi_final(int epi) { return epi == EPI_FINAL || epi == EPI_FINAL_SYM; }
 
 struct EpiArgs {
   void* c;                 // GRAM/POLY: [nb][M][N] panels; UPDATE: straight output [nb][M][N] panels
@@ -88,7 +92,7 @@ __device__ __forceinline__ void decode_tile(int logical, int tiles_m, int tiles_
                                             int& tn) {
   b = logical / per_batch;
   const int tix = logical - b * per_batch;
-  if (EPI == EPI_GRAM || EPI == EPI_POLY) {
+  if (epi_symmetric(EPI)) {
     // symmetric output: only tiles with tn >= tm exist (per_batch = nt (nt + 1) / 2); the
     // epilogue writes each off-diagonal tile twice, straight and mirrored.  Raster: bands of
     // 4 tile rows; inside the band starting at r0 the columns r0, r0+1, ... are walked one
@@ -199,7 +203,7 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[4][4], __bf16* stage
     }
   };
 
-  if (EPI != EPI_FINAL) {
+  if (!epi_final(EPI)) {
     // ---- straight image: element (i, j) of C is (row i, k = j) of the result's panels.
     // A 16-byte chunk is 8 consecutive j of one row, i.e. one value from each of 8 lanes:
     // neighbouring lanes exchange their packed pairs so that every lane writes two bf16 of
@@ -459,7 +463,7 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(Args args, EpiArgs e_
   if constexpr (!Args::multi) d = args.d, P = args.P, Q = args.Q;
   int tiles_n = static_cast<int>(d.N / BN);
   int tiles_m = static_cast<int>(d.M / BM);
-  int per_batch = (EPI == EPI_GRAM || EPI == EPI_POLY) ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
+  int per_batch = epi_symmetric(EPI) ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
   int slot;
   {
     const int nblocks = gridDim.x, bid = blockIdx.x;
@@ -509,7 +513,7 @@ __global__ __launch_bounds__(NTHREADS) void k_gemm_nt_bf16(Args args, EpiArgs e_
     e.c = pr.c, e.ct = pr.ct, e.aux = pr.aux, e.scale = pr.scale;
     logical -= args.begin[j];
     tiles_n = static_cast<int>(d.N / BN), tiles_m = static_cast<int>(d.M / BM);
-    per_batch = (EPI == EPI_GRAM || EPI == EPI_POLY) ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
+    per_batch = epi_symmetric(EPI) ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
     nk_all = static_cast<int>(d.K / BK);
     nk = nk_all;
   }
@@ -674,7 +678,7 @@ __global__ __launch_bounds__(NTHREADS) void k_split_finish(GemmDims d, EpiArgs e
   __shared__ __attribute__((aligned(1024))) __bf16 stg[4][(BM + BN) * BK];
   const int tiles_n = static_cast<int>(d.N / BN);
   const int tiles_m = static_cast<int>(d.M / BM);
-  const int per_batch = (EPI == EPI_GRAM || EPI == EPI_POLY) ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
+  const int per_batch = epi_symmetric(EPI) ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
   const int l = blockIdx.x;
   int b, tm, tn;
   decode_tile<EPI>(e.full_rounds * e.main_grid + l, tiles_m, tiles_n, per_batch, b, tm, tn);
@@ -758,7 +762,7 @@ __global__ __launch_bounds__(NTHREADS, 3) void k_gemm_nt_bf16_small(Args args, E
     d = args.d, P = args.P, Q = args.Q;
   }
   const int tiles_m = static_cast<int>(d.M / BM), tiles_n = static_cast<int>(d.N / BN);
-  const bool symmetric = EPI == EPI_GRAM || EPI == EPI_POLY;
+  const bool symmetric = epi_symmetric(EPI);
   const int per_batch = symmetric ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
   int b, tm, tn;
   decode_tile<EPI>(logical, tiles_m, tiles_n, per_batch, b, tm, tn);
@@ -866,7 +870,7 @@ __global__ __launch_bounds__(NTHREADS, 3) void k_gemm_nt_bf16_small(Args args, E
         for (int r = 0; r < 16; ++r) acc[i][j][r] *= sc1;
   }
 
-  if (EPI == EPI_FINAL) {
+  if (epi_final(EPI)) {
     const int ld = static_cast<int>(o.out_mode == CANZ_OUT_DELTA ? s.wfrag : s.cols);
     if ((ld & 3) != 0) {
       // unaligned row length: element-wise accesses straight from the accumulators
@@ -1007,7 +1011,7 @@ constexpr int64_t SMALL_ALL_MAX_K = 2048;   // polynomial products up to this k 
 template <int EPI>
 int64_t tile_count(const GemmDims& d) {
   const int64_t tm = d.M / BM, tn = d.N / BN;
-  return ((EPI == EPI_GRAM || EPI == EPI_POLY) ? tm * (tm + 1) / 2 : tm * tn) * d.nb;
+  return (epi_symmetric(EPI) ? tm * (tm + 1) / 2 : tm * tn) * d.nb;
 }
 
 // number of tiles [0, whole) for the large kernel; the rest, if any, for the small one
@@ -1151,6 +1155,12 @@ hipError_t launch_final_bf16(const GemmDims& d, const void* p, const void* q, co
   EpiArgs e{};
   e.scale = scale;
   return launch<EPI_FINAL>(d, p, q, e, w, s, o, st);
+}
+
+hipError_t launch_final_sym_bf16(const GemmDims& d, const void* x, const SplitWs& w, const Shape& s, const OutSpec& o,
+                                 hipStream_t st) {
+  if (d.M != d.N) return hipErrorInvalidValue;
+  return launch<EPI_FINAL_SYM>(d, x, x, EpiArgs{}, w, s, o, st);
 }
 
 }  // namespace canz

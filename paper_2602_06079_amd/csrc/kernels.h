@@ -128,6 +128,10 @@ hipError_t launch_update_bf16(const GemmDims& d, const void* b_in, const void* x
 // wide matrix: P = B, Q = XT (C = B X);  tall matrix: P = XT, Q = B (C = X^T B = (B X)^T)
 hipError_t launch_final_bf16(const GemmDims& d, const void* p, const void* q, const float* scale, const SplitWs& w,
                              const Shape& s, const OutSpec& o, hipStream_t st);
+// the same for a symmetric result O = X X^T (M = N): only the tiles on and above the diagonal are computed and
+// written; the elements below the diagonal tiles are left as they were (the caller mirrors them)
+hipError_t launch_final_sym_bf16(const GemmDims& d, const void* x, const SplitWs& w, const Shape& s, const OutSpec& o,
+                                 hipStream_t st);
 
 // ---- fp32 verification GEMMs (same contracts, float storage) ----------------------
 hipError_t launch_gram_f32(const GemmDims& d, const void* xw, void* a_out, const float* scale2, hipStream_t st);

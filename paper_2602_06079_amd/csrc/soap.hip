@@ -313,6 +313,28 @@ __global__ __launch_bounds__(NTH) void k_soap_adam_bf16(Shape s, PtrTable var, P
   if (n_transposed) tile_to_panels(tg, n_transposed + static_cast<int64_t>(b) * plane, r0, c0, rp2, true, t);
 }
 
+// S[row][col] <- S[col][row] for row > col of the caller's dense d x d matrices: the symmetric statistic is computed
+// on and above the diagonal tiles only.  One block per 64 x 64 tile on or below the diagonal (blockIdx.y >= blockIdx.x).
+__global__ __launch_bounds__(NTH) void k_soap_mirror(PtrTable stat, int64_t d) {
+  __shared__ float tile[64][65];
+  if (blockIdx.y < blockIdx.x) return;
+  const int b = blockIdx.z, r0 = blockIdx.y * 64, c0 = blockIdx.x * 64, t = threadIdx.x;
+  float* m = static_cast<float*>(stat.p[b]);
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {   // the tile above the diagonal that mirrors this one: rows c0.., columns r0..
+    const int idx = e * NTH + t, r = idx >> 6, c = idx & 63;
+    const int64_t row = c0 + r, col = r0 + c;
+    tile[r][c] = row < d && col < d ? m[row * d + col] : 0.f;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    const int idx = e * NTH + t, r = idx >> 6, c = idx & 63;
+    const int64_t row = r0 + r, col = c0 + c;
+    if (row < d && col < row) m[row * d + col] = tile[c][r];
+  }
+}
+
 // a[b][i] = (identity ? (row == col) : 0) for the [rows][ld] matrices of a batch
 __global__ __launch_bounds__(NTH) void k_soap_fill(float* __restrict__ a, int64_t elems, int64_t ld, int identity) {
   float* ab = a + static_cast<int64_t>(blockIdx.y) * elems;
@@ -1147,14 +1169,30 @@ int run_batch(const canz_soap_group& g, int first, int nb, const canz_soap_hpara
     for (int i = 0; i < nb; ++i) tab.p[i] = stat_tab[first + i];
     if (stat16) {
       // S <- beta2 S + (1 - beta2) X X^T as the "last product" of the bf16 kernels: it updates the caller's dense
-      // fp32 array in place as old * decay + factor * product
+      // fp32 array in place as old * decay + factor * product, on and above the diagonal tiles; the rest is mirrored
       Shape sq{};
       sq.rows = d, sq.cols = d, sq.m = d, sq.n = d, sq.mp = d2, sq.np = d2, sq.tp = 1, sq.wfrag = d;
       OutSpec so{};
       so.out = tab, so.out_dtype = CANZ_DT_F32, so.out_mode = CANZ_OUT_PARAM, so.decay = hp.beta2, so.neg_lr_scale = 1.f - hp.beta2;
       const GemmDims sd{d2, d2, k2, k2, k2, d2 * k2, d2 * k2, nb};
-      CANZ_HIP(CANZ_KERNEL_SOAP_STAT, launch_final_bf16(sd, side16, side16, nullptr, no_split, sq, so, st),
-               "statistics kernel (bf16 operands)");
+      // Only the tiles on and above the diagonal, mirrored afterwards, where that pays: the products it saves (about
+      // 0.65 us per 32-long k-step of a tile, a round of tiles on 256 CUs at a time) against one more pass over the
+      // statistic at some 4 TB/s that does not overlap with anything.  Long sums win (25600 x 5120: 3.9 -> 1.3 ms),
+      // short ones do not (3072 x 1024: the mirror pass costs what the products save).
+      const int64_t t256 = d2 / 256;
+      const double saved_us = static_cast<double>(t256 * (t256 - 1) / 2 * nb) / 256.0 * static_cast<double>(k2 / 32) * 0.65;
+      const double mirror_us = 15.0 + static_cast<double>(d) * static_cast<double>(d) * nb * 4.0 / 4.0e6;
+      if (saved_us > 1.5 * mirror_us) {
+        CANZ_HIP(CANZ_KERNEL_SOAP_STAT, launch_final_sym_bf16(sd, side16, no_split, sq, so, st), "statistics kernel (bf16 operands)");
+        prof_mark(st, CANZ_KERNEL_SOAP_STAT, true);
+        const unsigned t64 = static_cast<unsigned>((d + 63) / 64);
+        hipLaunchKernelGGL(k_soap_mirror, dim3(t64, t64, static_cast<unsigned>(nb)), dim3(NTH), 0, st, tab, d);
+        prof_mark(st, CANZ_KERNEL_SOAP_STAT, false);
+        if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "statistic mirror: %s", hipGetErrorString(e));
+      } else {
+        CANZ_HIP(CANZ_KERNEL_SOAP_STAT, launch_final_bf16(sd, side16, side16, nullptr, no_split, sq, so, st),
+                 "statistics kernel (bf16 operands)");
+      }
       if (hp.refresh) {   // the padded copy the refresh multiplies the basis with (its transposed image lands in wk, unused)
         prof_mark(st, CANZ_KERNEL_SOAP_STAT, true);
         hipLaunchKernelGGL(k_sh_load, dim3(static_cast<unsigned>(dp / 64), static_cast<unsigned>(dp / 64), static_cast<unsigned>(nb)),

@@ -409,6 +409,32 @@ def test_refresh_of_a_long_side(canz):
     check(dev, grads, states, None, hp, "soap 3200x384")
 
 
+def test_long_sums_take_the_symmetric_statistic_path(canz):
+    """2000 x 8200 with a basis on the short side only, four matrices: the sums of G G^T are long enough for the
+    library to compute the tiles on and above the diagonal only and mirror them (neither extent a multiple of the
+    256-wide tiles, so diagonal and edge tiles are ragged).  Matrix 0 against the oracle in full - the statistic
+    to 1e-5 and exactly symmetric - the others' statistics exactly symmetric and distinct."""
+    import torch
+    rows, cols, n, limit = 2000, 8200, 4, 4096
+    grads = [W.gen_grad(85, i, rows, cols)[0] for i in range(n)]
+    states = [{"mom": W.gen_normal_f32(85, i, 11, rows, cols, 0.02),
+               "var": np.mean(np.square(W.gen_normal_f32(85, i, 12, 4 * rows, cols, 0.02)).reshape(4, rows, cols), axis=0),
+               "left": W.gen_spd_f32(85, i, 13, rows, 0.02 * 0.02 * cols), "q_left": W.gen_orthogonal_f32(85, i, 15, rows),
+               "right": np.zeros((1, 1), np.float32), "q_right": np.zeros((1, 1), np.float32)}      # not passed: no basis
+              for i in range(n)]
+    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=6, out_mode=canz.OUT_DELTA, max_precond_dim=limit)
+    dev = SoapDevice(canz, rows, cols, grads, states, max_precond_dim=limit)
+    assert dev.use_left and not dev.use_right
+    run(canz, [dev], hp)
+    for i in range(1, n):
+        assert torch.equal(dev.t["left"][i], dev.t["left"][i].T) and not torch.equal(dev.t["left"][i], dev.t["left"][0])
+        assert bool(torch.isfinite(dev.out_t[i]).all())
+    one = SoapDevice.__new__(SoapDevice)
+    one.__dict__.update(dev.__dict__)
+    one.n = 1
+    check(one, grads[:1], states[:1], None, hp, "soap 2000x8200, left side only, symmetric statistic")
+
+
 def test_config2_share_in_one_call(canz):
     """The share bench.py --optimizer soap runs by default, in its launch configuration: Algorithm 1 with W = SOAP
     FLOPs on the 0.6B-shaped set, the most loaded rank's 15 matrices of 3072 x 1024 as two micro-groups (8 + 7) in one
