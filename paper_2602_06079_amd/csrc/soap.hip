@@ -6,7 +6,10 @@
 //   P <- P (1 - lr wd) - lr N  (or Delta W = -lr N);
 //   L <- beta2 L + (1 - beta2) G G^T,  R <- beta2 R + (1 - beta2) G^T G;
 //   on a refresh step  Q_L <- orthogonal factor of QR(L Q_L),  Q_R likewise.
-// Everything is fp32 on v_mfma_f32_32x32x2_f32 (the products) and plain vector code.
+// State and sums are fp32; the products run on v_mfma_f32_32x32x2_f32, with two exceptions on the bf16 matrix
+// cores (the kernels of the Muon step, operands in its panel layout): the statistics of gradients that arrive as
+// bf16 (their own values are the operands, every product is exact in fp32, the sums stay fp32), and, if the caller
+// asks for it (bf16_rotations), the rotations with the bases, M and N' rounded to bf16.
 //
 // The products all take the form C[i][j] = sum_k P[i][k] Q[j][k].  The rotation into the basis
 // runs right side first with its result written transposed, (G Q_R)^T = Q_R^T-rows times G-rows,
