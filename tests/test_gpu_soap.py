@@ -224,13 +224,16 @@ def test_first_step_from_empty_state_is_adam_in_the_given_bases(canz):
         check(dev, grads, states, None, hp, "soap first step, %s bases" % ("identity" if identity else "random"))
 
 
+@pytest.mark.parametrize("bf16_rot", [False, True], ids=["fp32", "bf16-rotations"])
 @pytest.mark.parametrize("keep_rot", [False, True], ids=["rotate-every-step", "rotated-momentum-kept"])
-def test_trajectory_with_refreshes(canz, keep_rot):
+def test_trajectory_with_refreshes(canz, keep_rot, bf16_rot):
     """Six steps, refresh on every second one; the oracle carries its own state and, after a refresh, takes the
     device's bases (they agree to TOL_Q up to column signs; the comparison of the following steps is then on the
     same bases instead of on two bases that differ by rounding).  With the rotated momentum kept by the caller the
     first step rotates M and every later one lets M' follow its own recurrence, across the refreshes; the oracle
-    rotates M on every step."""
+    rotates M on every step.  With the rotations on bf16 operands every step is held to that mode's tolerances (the
+    oracle restarts from the device's state, so the comparison is per step; the kept M' carries its rounding from
+    step to step, decaying with beta1)."""
     rows, cols, n = 160, 288, 2
     states = [W.gen_soap_state(63, i, rows, cols) for i in range(n)]
     params = [W.gen_param(63, i, rows, cols) for i in range(n)]
@@ -242,9 +245,10 @@ def test_trajectory_with_refreshes(canz, keep_rot):
             grads = [W.gen_grad(63, i, rows, cols, step=step - 1)[0] for i in range(n)]
             dev.set_grads(grads)
         hp = canz.SoapHparams(lr=0.02, weight_decay=0.01, eps=1e-8, beta1=0.9, beta2=0.95, step=step + 4, refresh=step % 2 == 0,
-                              mom_rot_valid=keep_rot and step > 1)
+                              mom_rot_valid=keep_rot and step > 1, bf16_rotations=bf16_rot)
         run(canz, [dev], hp)
-        check(dev, grads, states, params, hp, "soap trajectory step %d" % step)
+        tols = dict(tol_update=TOL16_UPDATE, tol_var=TOL16_VAR, tol_mom_rot=TOL16_MOM_ROT_WHOLE) if bf16_rot else {}
+        check(dev, grads, states, params, hp, "soap trajectory step %d%s" % (step, ", bf16 rotations" if bf16_rot else ""), **tols)
         # next step starts from what the device holds (fp32), on both sides
         states = [{k: dev.t[k][i].cpu().numpy() for k in STATE_KEYS} for i in range(n)]
         params = [dev.out_t[i].cpu().numpy() for i in range(n)]
@@ -596,8 +600,9 @@ def test_bf16_rotations_config2_shape(canz):
           tol_mom_rot=TOL16_MOM_ROT)
 
 
+@pytest.mark.parametrize("bf16_rot", [False, True], ids=["fp32", "bf16-rotations"])
 @pytest.mark.parametrize("refresh", [False, True], ids=["plain", "refresh"])
-def test_step_under_graph_capture_replays(canz, refresh):
+def test_step_under_graph_capture_replays(canz, refresh, bf16_rot):
     """A step (plain, and with the basis refresh: a few hundred more kernels, one of them the fill of Q^T, no memset)
     captured in a HIP graph: three replays with eager work in between, each compared bit for bit with the eager
     result of the same step from the same state."""
@@ -605,7 +610,7 @@ def test_step_under_graph_capture_replays(canz, refresh):
     rows, cols, n = 200, 136, 2
     grads = [W.gen_grad(68, i, rows, cols)[0] for i in range(n)]
     states = [W.gen_soap_state(68, i, rows, cols) for i in range(n)]
-    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=3, out_mode=canz.OUT_DELTA, refresh=refresh)
+    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=3, out_mode=canz.OUT_DELTA, refresh=refresh, bf16_rotations=bf16_rot)
     eager = SoapDevice(canz, rows, cols, grads, states)
     run(canz, [eager], hp)
     dev = SoapDevice(canz, rows, cols, grads, states)
