@@ -341,8 +341,9 @@ int canz_shampoo_step(const canz_shampoo_group* g, int32_t n_groups, const canz_
  * have at most 12288 rows or columns (the cited implementation's default limit is 10000).  Everything is fp32,
  * unless bf16_rotations is set: then the products that rotate G (and M) into the bases and N' back take their
  * operands (G, M, the bases, N' and the intermediate of a two-sided rotation) rounded to bf16 and accumulate in
- * fp32, about four times faster and with a relative error of the update near 1e-2 (each rounding is 2^-9
- * relative); that includes the re-rotation of mom_rot after a refresh, whose last product still leaves its fp32
+ * fp32, about four times faster and with a relative error of the update near 5e-3 for a state with history (each
+ * rounding is 2^-9 relative; on a first step from V = 0 the direction is nearly the sign of G', which the
+ * rounding flips where |G'| is below it: about 7e-2 there); that includes the re-rotation of mom_rot after a refresh, whose last product still leaves its fp32
  * sums in mom_rot.  Momentum, second moment, the statistics' sums and the refresh stay in fp32.  Independently
  * of this switch, gradients that arrive as bf16 have their statistics G G^T and G^T G computed on the bf16 matrix
  * cores: their values are the exact operands, each product is exact in fp32 and the sums are kept in fp32.

@@ -562,6 +562,36 @@ def test_bf16_rotations_refresh_tp_fragments(canz):
           tol_mom_rot=TOL16_MOM_ROT_WHOLE)
 
 
+def test_bf16_rotations_first_step_and_zero_gradient(canz):
+    """The two degenerate inputs in the bf16 mode.  A first step from M = V = 0 is N' = g' / (|g'| sqrt(c) + eps): where
+    |g'| is below the rounding the rotation adds (some 3e-3 of the typical size) the value is wrong by up to its own
+    size, however the rotation is rounded, so the error of the update is that share of the elements (measured 0.074
+    at eps = 1e-3 of the gradient scale, tolerance 0.15; V, which is (1 - beta2) g'^2 with no history to dilute
+    the rounding, 4.7e-3) - a property of the step, stated in the header.  A zero
+    gradient from an empty state leaves everything zero."""
+    rows, cols, n = 200, 136, 2
+    grads = [W.gen_grad(86, i, rows, cols)[0] for i in range(n)]
+    states = [W.gen_soap_state(86, i, rows, cols) for i in range(n)]
+    for st in states:
+        for k in ("mom", "var", "left", "right"):
+            st[k][:] = 0
+    hp = canz.SoapHparams(lr=0.01, eps=2e-5, step=1, out_mode=canz.OUT_DELTA, bf16_rotations=True)
+    dev = SoapDevice(canz, rows, cols, grads, states)
+    run(canz, [dev], hp)
+    check(dev, grads, states, None, hp, "soap bf16 rotations, first step", tol_update=0.15, tol_var=TOL16_VAR * 20)
+    zero = [np.zeros((rows, cols), np.uint16) for _ in range(n)]
+    params = [W.gen_param(86, i, rows, cols) for i in range(n)]
+    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=1, refresh=True, bf16_rotations=True)
+    dev = SoapDevice(canz, rows, cols, zero, states, outs=params, mom_rot=[np.full((rows, cols), np.nan, np.float32) for _ in range(n)])
+    run(canz, [dev], hp)
+    for i in range(n):
+        assert np.array_equal(dev.out_host(i), widen(params[i]))
+        for k in ("mom", "var", "left", "right"):
+            assert not dev.state_host(k, i).any(), k
+        assert not to_host64(dev.mom_rot_t[i]).any()
+        assert np.array_equal(dev.state_host("q_left", i), np.eye(rows)) and np.array_equal(dev.state_host("q_right", i), np.eye(cols))
+
+
 @pytest.mark.parametrize("shape,limit", [((264, 200), 10000), ((300, 100), 128), ((100, 300), 128)], ids=lambda v: str(v).replace(" ", ""))
 def test_bf16_rotations_refresh_with_kept_rotated_momentum(canz, shape, limit):
     """A refresh step of the steady state (the caller's M' is valid on entry), two-sided and one-sided: bf16 gradients, so
