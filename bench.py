@@ -295,6 +295,12 @@ def main_soap(args, canz, W, np, torch):
     rank = int(np.argmax(load))
     groups = canz.canz_microgroup_plan(s["rows"], s["cols"], s["dtype"], owner, rank, max_mats=8)
     plan_ms = (time.perf_counter() - t0) * 1e3
+    if args.share:
+        # a share given by hand instead of the planner's: N matrices of one shape (e.g. a one-sided case)
+        r_, c_, n_ = (int(v) for v in args.share.lower().split("x"))
+        s = dict(s, rows=list(s["rows"]) + [r_] * n_, cols=list(s["cols"]) + [c_] * n_)
+        first = len(s["rows"]) - n_
+        groups = [list(range(first + i, min(first + i + 8, first + n_))) for i in range(0, n_, 8)]
     mean = float(load.sum()) / len(load)
     n_share = sum(len(g) for g in groups)
     log("soap on config %d (%s): rank %d owns %d matrices in %d groups; planner %.2f ms, R_LB(FLOPs) %.3f" %
@@ -446,9 +452,9 @@ def main_soap(args, canz, W, np, torch):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32 (rotations on bf16 operands)" if args.bf16_rotations else "f32", "data": "synthetic", "launch": "eager",
-        "config": {"workload": "soap step, config %d %s partitioned by SOAP FLOPs: rank %d of %d (alpha=1), %d matrices %s in %d "
+        "config": {"workload": ("soap step, share given by hand (--share %s; the planner figures below are of config %d %s, rank %d of %d): " % (args.share, cfg, s["name"], rank, R) if args.share else "soap step, config %d %s partitioned by SOAP FLOPs: rank %d of %d (alpha=1), " % (cfg, s["name"], rank, R)) + "%d matrices %s in %d "
                                "micro-groups, basis refresh every %d steps (%d of the %d timed steps), max_precond_dim %d, %s" %
-                               (cfg, s["name"], rank, R, n_share, sorted({(s["rows"][p], s["cols"][p]) for g in groups for p in g}),
+                               (n_share, sorted({(s["rows"][p], s["cols"][p]) for g in groups for p in g}),
                                 len(groups), f, n_refresh_timed, args.steps, limit,
                                 "rotated momentum kept between steps" if keep_rot else "momentum rotated on every step"),
                    "elements": sum(s["rows"][p] * s["cols"][p] for g in groups for p in g)},
@@ -477,6 +483,8 @@ def main():
     ap.add_argument("--max-precond-dim", type=int, default=10000, help="soap: a longer side keeps no basis")
     ap.add_argument("--rotate-momentum-every-step", action="store_true",
                     help="soap: do not keep the rotated momentum between steps (three rotations per step instead of two)")
+    ap.add_argument("--share", default="", metavar="RxCxN",
+                    help="soap: run N matrices of R x C instead of the share the planner assigns (e.g. 25600x5120x4)")
     ap.add_argument("--bf16-rotations", action="store_true",
                     help="soap: the rotation products on bf16 operands with fp32 accumulation (state, statistics, refresh stay fp32)")
     ap.add_argument("--precision", choices=["bf16", "f32"], default="bf16")

@@ -40,6 +40,7 @@ enum {
 };
 
 enum { CANZ_COST_NUMEL = 0, CANZ_COST_NS_FLOPS = 1, CANZ_COST_SHAMPOO_FLOPS = 2, CANZ_COST_SOAP_FLOPS = 3 };
+#define CANZ_SOAP_COST_MAX_PRECOND_DIM 10000 /* the limit CANZ_COST_SOAP_FLOPS assumes for canz_soap_hparams.max_precond_dim */
 enum { CANZ_DT_F32 = 0, CANZ_DT_BF16 = 1 };
 enum { CANZ_SCALE_NONE = 0, CANZ_SCALE_ASPECT = 1, CANZ_SCALE_RMS = 2 };
 enum { CANZ_PREC_BF16 = 0, CANZ_PREC_F32 = 1 };
@@ -70,7 +71,9 @@ const char* canz_version(void);
  *                          25 root iterations, (4 r c (r + c) + 200 (r^3 + c^3)) / 2^20 rounded
  *                          down (the cost follows the operator, App. D.5),
  *                          CANZ_COST_SOAP_FLOPS the FLOPs of canz_soap_step with a refresh every 10th
- *                          step, ((120 r c (r + c) + 7 (r^3 + c^3)) / 15) / 2^20, both divisions
+ *                          step and max_precond_dim = CANZ_SOAP_COST_MAX_PRECOND_DIM: with s1 and s3 the
+ *                          sums of d and d^3 over the sides d (of r, c) within that limit, the only
+ *                          ones that keep a basis, ((120 r c s1 + 7 s3) / 15) / 2^20, both divisions
  *                          rounded down
  *   bucket_off   [n_buckets+1] non-decreasing, bucket_off[0] = 0, last = n_mats
  *   alpha        blend factor in [0, 1]: 1 = fill deficits, 0 = even split per bucket

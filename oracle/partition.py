@@ -50,14 +50,20 @@ def shampoo_flops(rows: int, cols: int, root_iters: int = 25) -> int:
     return 4 * r * r * c + 4 * c * c * r + 8 * root_iters * (r ** 3 + c ** 3)
 
 
-def soap_flops(rows: int, cols: int, refresh_every: int = 10) -> int:
-    """FLOPs of one SOAP step on a rows x cols matrix, averaged over a refresh period: per step the
-    rotation of G and of M into the bases, the rotation of the direction back and the two statistics,
-    four times 2 r^2 c + 2 r c^2; per refresh and side of extent d the product S Q (2 d^3), the
-    Householder QR (4/3 d^3) and the accumulation of its orthogonal factor (4/3 d^3).  Rounded down.
+SOAP_COST_MAX_PRECOND_DIM = 10000   # the limit the cost model assumes: the cited implementation's default
+
+
+def soap_flops(rows: int, cols: int, refresh_every: int = 10, max_precond_dim: int = SOAP_COST_MAX_PRECOND_DIM) -> int:
+    """FLOPs of one SOAP step on a rows x cols matrix, averaged over a refresh period.  The cost follows the
+    operator (App. D.5), and the operator keeps no basis on a side longer than max_precond_dim: only a side of
+    extent d within the limit costs, per step, its share of the rotation of G and of M into the bases, of the
+    rotation of the direction back and its statistic, four times 2 r c d; and per refresh the product S Q
+    (2 d^3), the Householder QR (4/3 d^3) and the accumulation of its orthogonal factor (4/3 d^3).
+    Rounded down.  A matrix with both sides above the limit costs nothing here (the step does not take it).
     """
     r, c = int(rows), int(cols)
-    return (3 * refresh_every * 8 * r * c * (r + c) + 14 * (r ** 3 + c ** 3)) // (3 * refresh_every)
+    sides = [d for d in (r, c) if d <= max_precond_dim]
+    return (3 * refresh_every * 8 * r * c * sum(sides) + 14 * sum(d ** 3 for d in sides)) // (3 * refresh_every)
 
 
 def param_cost(rows, cols, cost_kind: int = COST_NUMEL, ns_steps: int = 5):

@@ -25,8 +25,9 @@ def _shampoo_flops(rows, cols, root_iters=25):
     return 4 * rows * cols * (rows + cols) + 8 * root_iters * (rows ** 3 + cols ** 3)
 
 
-def _soap_flops(rows, cols, refresh_every=10):
-    return 8 * rows * cols * (rows + cols) + 14 * (rows ** 3 + cols ** 3) / (3 * refresh_every)
+def _soap_flops(rows, cols, refresh_every=10, max_precond_dim=10000):
+    sides = [d for d in (rows, cols) if d <= max_precond_dim]      # a longer side keeps no basis and costs nothing
+    return 8 * rows * cols * sum(sides) + 14 * sum(d ** 3 for d in sides) / (3 * refresh_every)
 
 
 def _ratio(v):

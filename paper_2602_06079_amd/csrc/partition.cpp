@@ -25,10 +25,13 @@ int64_t checked_cost(int64_t rows, int64_t cols, int cost_kind) {
   } else if (cost_kind == CANZ_COST_NS_FLOPS) {
     w = 5 * (4 * m * m * n + 2 * m * m * m);
   } else if (cost_kind == CANZ_COST_SOAP_FLOPS) {
-    // SOAP step: rotations of G and M into the bases, the rotation back and the statistics, 8 r c (r + c);
-    // a refresh every 10th step (product 2 d^3, QR 4/3 d^3, accumulation of Q 4/3 d^3 per side):
-    // 7/15 (r^3 + c^3) per step; counted in units of 2^20 FLOPs
-    w = ((120 * m * n * (m + n) + 7 * (m * m * m + n * n * n)) / 15) >> 20;
+    // SOAP step, per side of extent d that keeps a basis (d within the limit the model assumes): its share of the
+    // rotations of G and M into the bases, of the rotation back and its statistic, 8 r c d; a refresh every 10th
+    // step (product 2 d^3, QR 4/3 d^3, accumulation of Q 4/3 d^3): 7/15 d^3 per step; in units of 2^20 FLOPs
+    const __int128 lim = CANZ_SOAP_COST_MAX_PRECOND_DIM;
+    const __int128 s1 = (m <= lim ? m : 0) + (n <= lim ? n : 0);
+    const __int128 s3 = (m <= lim ? m * m * m : 0) + (n <= lim ? n * n * n : 0);
+    w = ((120 * m * n * s1 + 7 * s3) / 15) >> 20;
   } else {
     // Shampoo step: statistics and preconditioning products 4 (r^2 c + c^2 r), two inverse roots
     // of 25 rounds x 4 products each: 200 (r^3 + c^3); counted in units of 2^20 FLOPs

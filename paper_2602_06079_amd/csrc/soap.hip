@@ -374,8 +374,17 @@ __global__ __launch_bounds__(NTH) void k_soap_store_q(PtrTable q, const float* _
 // (k_qr_tfactor) accumulates V V^T (32 x 32, which T needs) on the matrix cores, each wavefront
 // taking every 16th group of 32 rows, sums over the wavefronts in a fixed order, forms T column by
 // column (H_0 ... H_31 = I - V T V^T), and writes
-//   ybuf [dp][32]    <- Y  = V T^T, rows klo .. dp - 1   (H^T A = A - Y (V^T A))
-//   y2   [dp][32]    <- Y2 = V T                          (H A = A - Y2 (V^T A)).
+//   ybuf [dp][128]   <- Y  = V T^T, rows klo .. dp - 1   (H^T A = A - Y (V^T A))
+//   y2   [dp][128]   <- Y2 = V T                          (H A = A - Y2 (V^T A)),
+// both into the 32 columns `ycol`.. of a strip that holds the four panels of a block of 128 columns side by side.
+//
+// Blocks.  The four panels of a block are applied to the rows beyond the block in one go: with W_raw = X [V_0 .. V_3]
+// (X: the rows to update), the W of panel b applied after panels a < b is W_b = W_raw,b - sum_{a<b} W_a C_ab,
+// C_ab = Y_a^T V_b = T_a (V_a^T V_b), i.e. W = W_raw U with U = (I + C)^(-1), C strictly block upper triangular; then
+// X -= W [Y_0 .. Y_3]^T.  When the orthogonal factor is accumulated the panels are applied last to first with Y2:
+// W = W_raw U2, U2 = (I + C2)^(-1), C2_ab = Y2_a^T V_b = T_a^T (V_a^T V_b) for a > b.  k_qr_tfactor of panel `pos`
+// of a block also forms V_a^T V_pos for the earlier panels a of the block and writes the blocks C_a,pos and
+// C2_pos,a (it reads T_a from tbuf, where every panel leaves its T); k_qr_block_u turns them into U^T and U2^T.
 //
 // Column c2 of the panel belongs to wavefront (c2 - 1) mod 16 for the whole kernel: it alone reads and
 // writes that column, so the columns need no synchronisation between wavefronts.  What the others
@@ -385,15 +394,19 @@ __global__ __launch_bounds__(NTH) void k_soap_store_q(PtrTable q, const float* _
 // barriers only have to order LDS traffic, so they do not wait for the stores in flight.
 // Up to 3072 remaining rows the columns stay in registers for the whole kernel (k_qr_panel_regs);
 // k_qr_panel_long, for longer panels, streams them from memory (L2) on every step.
+constexpr int QBLK = 128;   // columns of a block: four panels
 struct QrPanel {
   float* wk;
   float* vall;
-  float* ybuf;
-  float* y2;
+  float* ybuf;     // this block's Y strip  [dp][128]
+  float* y2;       // this block's Y2 strip [dp][128]
   float* tau;      // [nb][32] handed from the first kernel of a panel to the second
+  float* tbuf;     // [nb][dp / 32][32][32]: T of every panel
+  float* cbuf;     // [nb][2][128][128]: C (blocks above the diagonal) and C2 (below) of the block under way
   int64_t dp, d;
-  int64_t s_wk, s_vall, s_y, s_y2;   // batch strides
+  int64_t s_wk, s_vall, s_y, s_y2, s_t;   // batch strides
   int j0, klo;
+  int ycol;        // 32 * (position of the panel in its block)
 };
 
 constexpr int VMAX = 12288;   // rows of a reflector kept in LDS: the largest extent a side with a basis may have
@@ -694,23 +707,34 @@ __global__ __launch_bounds__(QTH) void k_qr_tfactor(QrPanel a) {
   const int len = static_cast<int>(dp) - j0;
   const float* vrows = a.vall + static_cast<int64_t>(b) * a.s_vall;
   if (t < QB) s_tau[t] = (a.tau + static_cast<int64_t>(b) * QB)[t];
+  // The products of a whole block run over the rows of the reflectors from the block's first column on: this panel's
+  // reflectors are zero there, which the panel kernel (it writes them from column j0 on) has not stored.
+  for (int e = t; e < QB * a.ycol; e += QTH) {
+    const int r = e / a.ycol, q = e - r * a.ycol;
+    (a.vall + static_cast<int64_t>(b) * a.s_vall)[static_cast<int64_t>(j0 + r) * dp + (j0 - a.ycol) + q] = 0.f;
+  }
 
-  // V V^T on the matrix cores: lane l supplies rows l % 32 at k and k + 4 (l / 32), four k per load
-  {
+  // s_g <- U^T V on the matrix cores, V this panel's reflectors, U those of the panel that starts at row `ju` (this
+  // panel itself for V V^T), summed over the rows j0 .. dp - 1 (V is zero before): lane l supplies rows l % 32 at k
+  // and k + 4 (l / 32), four k per load
+  auto gram = [&](int ju) {
     f32x16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     const float* vbase = vrows + static_cast<int64_t>(j0 + (lane & 31)) * dp + j0 + 4 * (lane >> 5);
+    const float* ubase = vrows + static_cast<int64_t>(ju + (lane & 31)) * dp + j0 + 4 * (lane >> 5);
     const int nblk = len / 8;
     // a wavefront takes four consecutive blocks at a time (32 rows x 32 k: one whole 128-byte line per row)
     for (int kb0 = 4 * wave; kb0 < nblk; kb0 += 4 * QWAVES) {   // nblk is a multiple of 4
-      f32x4 x[4];
+      f32x4 x[4], u4[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) x[u] = *reinterpret_cast<const f32x4*>(vbase + 8 * (kb0 + u));
 #pragma unroll
+      for (int u = 0; u < 4; ++u) u4[u] = *reinterpret_cast<const f32x4*>(ubase + 8 * (kb0 + u));
+#pragma unroll
       for (int u = 0; u < 4; ++u)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[u][e], x[u][e], acc, 0, 0, 0);
+        for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(u4[u][e], x[u][e], acc, 0, 0, 0);
     }
     // sum over the wavefronts in a fixed order, eight at a time through LDS
     float* scratch = s_part;
@@ -727,8 +751,9 @@ __global__ __launch_bounds__(QTH) void k_qr_tfactor(QrPanel a) {
     }
     const int r = t >> 6, l = t & 63;   // thread t holds accumulator register r of lane l
     s_g[8 * (r >> 2) + (r & 3) + 4 * (l >> 5)][l & 31] = total;
-  }
-  __syncthreads();
+    __syncthreads();
+  };
+  gram(j0);
 
   // T, forward and column by column: T[c][c] = tau_c, T[0:c, c] = -tau_c T[0:c, 0:c] (V^T v_c)
   // (thread i keeps row i of T in registers; its entries left of the diagonal are zero, so the sums may start at 0)
@@ -747,6 +772,27 @@ __global__ __launch_bounds__(QTH) void k_qr_tfactor(QrPanel a) {
     }
   }
   __syncthreads();
+  {   // T for the later panels of the block
+    float* tb = a.tbuf + static_cast<int64_t>(b) * a.s_t + static_cast<int64_t>(j0 / QB) * QB * QB;
+    tb[t] = s_t[t >> 5][t & 31];
+  }
+  // the blocks of C and C2 that pair this panel with the earlier ones of its block
+  for (int pa = 0; pa < a.ycol / QB; ++pa) {
+    const int ja = j0 - a.ycol + pa * QB;
+    __syncthreads();               // s_g is free again
+    gram(ja);                      // s_g[i][j] = (V_a^T V)[i][j]
+    const float* ta = a.tbuf + static_cast<int64_t>(b) * a.s_t + static_cast<int64_t>(ja / QB) * QB * QB;
+    const int i = t >> 5, j = t & 31;
+    float c = 0.f, c2 = 0.f;
+#pragma unroll 8
+    for (int l = 0; l < QB; ++l) {
+      c = __builtin_fmaf(ta[i * QB + l], s_g[l][j], c);     // C_a,pos = T_a (V_a^T V)
+      c2 = __builtin_fmaf(s_t[l][i], s_g[j][l], c2);        // C2_pos,a = T^T (V^T V_a) = T^T (V_a^T V)^T
+    }
+    float* cb = a.cbuf + static_cast<int64_t>(b) * 2 * QBLK * QBLK;
+    cb[(pa * QB + i) * QBLK + a.ycol + j] = c;
+    cb[QBLK * QBLK + (a.ycol + i) * QBLK + pa * QB + j] = c2;
+  }
 
   // Y = V T^T and Y2 = V T on the matrix cores, 32 rows per wavefront and turn; blocks of rows before j0
   // (down to the tile boundary klo) are zero.  Lane l supplies V[r0 + l % 32][k] and T[l % 32][k] resp.
@@ -772,15 +818,49 @@ __global__ __launch_bounds__(QTH) void k_qr_tfactor(QrPanel a) {
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int64_t at = (r0 + 8 * (r >> 2) + (r & 3) + 4 * (lane >> 5)) * QB + (lane & 31);
+      const int64_t at = (r0 + 8 * (r >> 2) + (r & 3) + 4 * (lane >> 5)) * QBLK + a.ycol + (lane & 31);
       ybuf[at] = ay[r];
       y2[at] = ay2[r];
     }
   }
 }
 
+// U^T and U2^T of one block of four panels from the blocks of C (above the diagonal) and C2 (below) that the panels'
+// T kernels left in cbuf: U = (I + C)^(-1) by U_ab = -C_ab - sum_{a<c<b} C_ac U_cb, U2 = (I + C2)^(-1) by
+// U2_ab = -C2_ab - sum_{b<c<a} C2_ac U2_cb; identity blocks on the diagonal, zero on the other side.  One workgroup
+// of 1024 threads per matrix; thread (i, j) computes element (i, j) of every 32 x 32 block.
+__global__ __launch_bounds__(QTH) void k_qr_block_u(const float* __restrict__ cbuf, float* __restrict__ ut, float* __restrict__ u2t,
+                                                    int64_t s_u2) {
+  __shared__ float s_c[QBLK][QBLK + 1], s_u[QBLK][QBLK + 1];
+  const int b = blockIdx.x, t = threadIdx.x, i = t >> 5, j = t & 31;
+  for (int lower = 0; lower < 2; ++lower) {
+    const float* c = cbuf + (static_cast<int64_t>(b) * 2 + lower) * QBLK * QBLK;
+    for (int e = t; e < QBLK * QBLK; e += QTH) {
+      const int r = e >> 7, q = e & 127;
+      const bool live = lower ? (r >> 5) > (q >> 5) : (r >> 5) < (q >> 5);
+      s_c[r][q] = live ? c[e] : 0.f;
+      s_u[r][q] = r == q ? 1.f : 0.f;
+    }
+    __syncthreads();
+    for (int k = 1; k < 4; ++k) {          // blocks at distance k from the diagonal
+      for (int lo = 0; lo + k < 4; ++lo) {
+        const int ba = lower ? lo + k : lo, bb = lower ? lo : lo + k;   // block row, block column
+        float acc = s_c[ba * QB + i][bb * QB + j];
+        for (int bc = lo + 1; bc < lo + k; ++bc)
+#pragma unroll 8
+          for (int l = 0; l < QB; ++l) acc = __builtin_fmaf(s_c[ba * QB + i][bc * QB + l], s_u[bc * QB + l][bb * QB + j], acc);
+        s_u[ba * QB + i][bb * QB + j] = -acc;
+      }
+      __syncthreads();
+    }
+    float* out = lower ? u2t + static_cast<int64_t>(b) * s_u2 : ut + static_cast<int64_t>(b) * QBLK * QBLK;
+    for (int e = t; e < QBLK * QBLK; e += QTH) out[e] = s_u[e & 127][e >> 7];   // transposed
+    __syncthreads();
+  }
+}
+
 struct Carve {   // float offsets into the workspace of one launch batch
-  size_t gm, gmt, t1, rot, np, yt, ql, qlt, qr, qrt, stat, wk, vall, y2, ybuf, tau, wt, qt, total_bytes;
+  size_t gm, gmt, t1, rot, np, yt, ql, qlt, qr, qrt, stat, wk, vall, y2, ybuf, tau, wt, qt, tb, cb, ub, u2, total_bytes;
   // bf16 rotations (offsets in floats as well; each array holds bf16 panels padded to 256)
   size_t gp, gpt, mp, mpt, as_g, at_g, as_m, at_m, rg, rgt, rm, rmt, npn, npt, ys, yst, qlp, qltp, qrp, qrtp;
 };
@@ -818,11 +898,15 @@ Carve carve(int64_t rows, int64_t cols, int nb, Sides u, bool refresh, bool bf16
   if (refresh) {
     c.wk = take(nb * dm * dm);
     c.vall = take(nb * dm * dm);
-    c.y2 = take(nb * dm * dm);         // dm / 32 panels of [dm][32]
-    c.ybuf = take(nb * dm * QB);
+    c.y2 = take(nb * dm * dm);         // dm / 128 blocks of [dm][128]
+    c.ybuf = take(nb * dm * QBLK);     // the Y strip of the block under way
     c.tau = take(nb * QB);
-    c.wt = take(nb * dm * QB);
+    c.wt = take(2 * nb * dm * QBLK);   // W_raw and W of a block
     c.qt = take(nb * dm * dm);
+    c.tb = take(nb * dm * QB);         // T of every panel
+    c.cb = take(2 * nb * QBLK * QBLK); // C and C2 of the block under way
+    c.ub = take(nb * QBLK * QBLK);     // U^T of the block under way
+    c.u2 = take(nb * dm * QBLK);       // U2^T of every block
   }
   const size_t rp2 = pad256(rows), cp2 = pad256(cols), p2 = nb * rp2 * cp2 / 2;   // floats that hold a batch of panels
   if (bf16 || stat16) c.gp = take(bf16 || u.left ? p2 : 0), c.gpt = take(bf16 || u.right ? p2 : 0);
@@ -920,49 +1004,96 @@ int refresh_side(void* const* q_tab, int first, int nb, int64_t d, int64_t dp, c
   p0.P = qt_old, p0.Q = stat, p0.c = wk;
   CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_PLAIN, false>(p0, nb, none, s, o, st)), "refresh product");
 
-  // W = (rows lo.. of m) V_panel over the rows j0.. of the reflectors: wt[j][0..31]
-  auto w_product = [&](const float* m, int64_t lo, int64_t j0) {
+  // Blocks of 128 columns = four panels; all of a block's columns are rows of one 128-row tile of the working copy.
+  // Inside the block every panel is applied to that tile alone (rank 32); to the rows beyond it the whole block is
+  // applied at once (rank 128), which moves the trailing matrix through memory once per block instead of once per
+  // panel.  A last block with fewer than four panels has no rows beyond it.
+  float *ycat = ws + c.ybuf, *wraw = ws + c.wt, *wfix = ws + c.wt + static_cast<size_t>(nb) * dp * QBLK;
+  float *tb = ws + c.tb, *cb = ws + c.cb, *ub = ws + c.ub, *u2 = ws + c.u2;
+  const int64_t s_strip = dp * QBLK, s_t = dp * QB, s_u2 = dp * QBLK;
+  // W = (rows lo .. lo + rows - 1 of m) [V of `width` columns from column j0 on], over the rows j0.. of the reflectors
+  auto w_product = [&](const float* m, int64_t lo, int64_t rows_, int64_t j0, int64_t width, float* w_out) {
     ShGemm w{};
-    w.M = dp - lo, w.N = QB, w.K = dp - j0, w.ldp = dp, w.ldq = dp, w.sp = dd, w.sq = s_vall;
+    w.M = rows_, w.N = width, w.K = dp - j0, w.ldp = dp, w.ldq = dp, w.sp = dd, w.sq = s_vall;
     w.P = m + lo * dp + j0, w.Q = vall + j0 * dp + j0;
-    w.c = wt + lo * QB, w.ldc = QB, w.sc = s_y;
+    w.c = w_out + lo * QBLK, w.ldc = QBLK, w.sc = s_strip;
     return w;
   };
-  // (rows lo.., columns klo.. of m) -= W Y^T with Y given as [dp][32] rows
-  auto sub_product = [&](float* m, int64_t lo, int64_t klo, const float* y, int64_t sy) {
+  // (rows lo .. lo + rows - 1, columns klo.. of m) -= W Y^T: W and Y are the columns ycol .. ycol + width - 1 of their strips
+  auto sub_product = [&](float* m, int64_t lo, int64_t rows_, int64_t klo, const float* w_in, const float* y, int64_t sy,
+                         int64_t ycol, int64_t width) {
     ShGemm u{};
-    u.M = dp - lo, u.N = dp - klo, u.K = QB, u.ldp = QB, u.ldq = QB, u.sp = s_y, u.sq = sy;
-    u.P = wt + lo * QB, u.Q = y + klo * QB;
+    u.M = rows_, u.N = dp - klo, u.K = width, u.ldp = QBLK, u.ldq = QBLK, u.sp = s_strip, u.sq = sy;
+    u.P = w_in + lo * QBLK + ycol, u.Q = y + klo * QBLK + ycol;
     u.c = m + lo * dp + klo, u.ldc = dp, u.sc = dd;
     return u;
   };
+  // W = W_raw U for a whole block: wfix = wraw (rows lo..) times the transposed factor ut [128][128]
+  auto fix_product = [&](int64_t lo, int64_t rows_, const float* ut, int64_t s_ut) {
+    ShGemm f{};
+    f.M = rows_, f.N = QBLK, f.K = QBLK, f.ldp = QBLK, f.ldq = QBLK, f.sp = s_strip, f.sq = s_ut;
+    f.P = wraw + lo * QBLK, f.Q = ut;
+    f.c = wfix + lo * QBLK, f.ldc = QBLK, f.sc = s_strip;
+    return f;
+  };
+  // one panel with the rank-32 products: W into its 32 columns of wraw, then the update
+  auto apply_panel = [&](float* m, int64_t lo, int64_t rows_, int64_t klo, int64_t j0, const float* y, int64_t sy, const char* what) -> int {
+    const int64_t ycol = j0 % QBLK;
+    ShGemm w = w_product(m, lo, rows_, j0, QB, wraw);
+    w.c += ycol;
+    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_PLAIN, false, QB>(w, nb, none, s, o, st)), what);
+    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_SUB, false>(sub_product(m, lo, rows_, klo, wraw, y, sy, ycol, QB), nb, none, s, o, st)), what);
+    return CANZ_OK;
+  };
+  // a whole block with the rank-128 products
+  auto apply_block = [&](float* m, int64_t lo, int64_t klo, int64_t jb, const float* y, int64_t sy, const float* ut, int64_t s_ut,
+                         const char* what) -> int {
+    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_PLAIN, false>(w_product(m, lo, dp - lo, jb, QBLK, wraw), nb, none, s, o, st)), what);
+    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_PLAIN, false>(fix_product(lo, dp - lo, ut, s_ut), nb, none, s, o, st)), what);
+    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_SUB, false>(sub_product(m, lo, dp - lo, klo, wfix, y, sy, 0, QBLK), nb, none, s, o, st)), what);
+    return CANZ_OK;
+  };
 
-  for (int64_t j0 = 0; j0 < d; j0 += QB) {
-    const int64_t jlo = floor128(j0 + QB), klo = floor128(j0);
-    QrPanel a{};
-    a.wk = wk, a.vall = vall, a.ybuf = ybuf, a.y2 = y2 + (j0 / QB) * dp * QB, a.tau = ws + c.tau;
-    a.dp = dp, a.d = d, a.s_wk = dd, a.s_vall = s_vall, a.s_y = s_y, a.s_y2 = dd;
-    a.j0 = static_cast<int>(j0), a.klo = static_cast<int>(klo);
+  for (int64_t jb = 0; jb < d; jb += QBLK) {            // factorisation, block by block
+    float* y2blk = y2 + (jb / QBLK) * dp * QBLK;
+    const int64_t panels = std::min<int64_t>(4, (d - jb + QB - 1) / QB);
+    for (int64_t pp = 0; pp < panels; ++pp) {
+      const int64_t j0 = jb + pp * QB;
+      QrPanel a{};
+      a.wk = wk, a.vall = vall, a.ybuf = ycat, a.y2 = y2blk, a.tau = ws + c.tau, a.tbuf = tb, a.cbuf = cb;
+      a.dp = dp, a.d = d, a.s_wk = dd, a.s_vall = s_vall, a.s_y = s_strip, a.s_y2 = dd, a.s_t = s_t;
+      a.j0 = static_cast<int>(j0), a.klo = static_cast<int>(jb), a.ycol = static_cast<int>(pp * QB);
+      prof_mark(st, CANZ_KERNEL_SOAP_PANEL, true);
+      if (dp - j0 <= 64 * 4 * 8)
+        hipLaunchKernelGGL(k_qr_panel_regs<8>, dim3(nb), dim3(QTH), 0, st, a);
+      else if (dp - j0 <= 64 * 4 * 12)
+        hipLaunchKernelGGL(k_qr_panel_regs<12>, dim3(nb), dim3(QTH), 0, st, a);
+      else
+        hipLaunchKernelGGL(k_qr_panel_long, dim3(nb), dim3(QTH), 0, st, a);
+      hipLaunchKernelGGL(k_qr_tfactor, dim3(nb), dim3(QTH), 0, st, a);
+      prof_mark(st, CANZ_KERNEL_SOAP_PANEL, false);
+      if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "panel kernel: %s", hipGetErrorString(e));
+      if (pp + 1 < panels)   // the later panels of the block: the block's own 128 rows
+        if (int rc = apply_panel(wk, jb, QBLK, jb, j0, ycat, s_strip, "QR (panel update)")) return rc;
+    }
+    if (jb + QBLK >= dp) break;   // no columns after this block
     prof_mark(st, CANZ_KERNEL_SOAP_PANEL, true);
-    if (dp - j0 <= 64 * 4 * 8)
-      hipLaunchKernelGGL(k_qr_panel_regs<8>, dim3(nb), dim3(QTH), 0, st, a);
-    else if (dp - j0 <= 64 * 4 * 12)
-      hipLaunchKernelGGL(k_qr_panel_regs<12>, dim3(nb), dim3(QTH), 0, st, a);
-    else
-      hipLaunchKernelGGL(k_qr_panel_long, dim3(nb), dim3(QTH), 0, st, a);
-    hipLaunchKernelGGL(k_qr_tfactor, dim3(nb), dim3(QTH), 0, st, a);
+    hipLaunchKernelGGL(k_qr_block_u, dim3(nb), dim3(QTH), 0, st, cb, ub, u2 + (jb / QBLK) * QBLK * QBLK, s_u2);
     prof_mark(st, CANZ_KERNEL_SOAP_PANEL, false);
-    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "panel kernel: %s", hipGetErrorString(e));
-    if (jlo >= dp) continue;   // no columns after this panel
-    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_PLAIN, false, QB>(w_product(wk, jlo, j0), nb, none, s, o, st)), "QR (W)");
-    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_SUB, false>(sub_product(wk, jlo, klo, ybuf, s_y), nb, none, s, o, st)), "QR (update)");
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "block kernel: %s", hipGetErrorString(e));
+    if (int rc = apply_block(wk, jb + QBLK, jb, jb, ycat, s_strip, ub, QBLK * QBLK, "QR (block update)")) return rc;
   }
-  // Q = H(0) H(1) ... applied to the identity from the last panel to the first
-  for (int64_t j0 = (d - 1) / QB * QB; j0 >= 0; j0 -= QB) {
-    const int64_t lo = floor128(j0);
-    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_PLAIN, false, QB>(w_product(qt, lo, j0), nb, none, s, o, st)), "Q (W)");
-    CANZ_HIP(CANZ_KERNEL_SOAP_QR, (launch_gemm<SE_SUB, false>(sub_product(qt, lo, lo, y2 + (j0 / QB) * dp * QB, dd), nb, none, s, o, st)),
-             "Q (update)");
+  // Q = H(0) H(1) ... applied to the identity from the last block to the first; a last block without all four panels
+  // (it has no U2) panel by panel
+  for (int64_t jb = (d - 1) / QBLK * QBLK; jb >= 0; jb -= QBLK) {
+    const float* y2blk = y2 + (jb / QBLK) * dp * QBLK;
+    const int64_t panels = std::min<int64_t>(4, (d - jb + QB - 1) / QB);
+    if (panels == 4 && jb + QBLK < dp) {
+      if (int rc = apply_block(qt, jb, jb, jb, y2blk, dd, u2 + (jb / QBLK) * QBLK * QBLK, s_u2, "Q (block update)")) return rc;
+    } else {
+      for (int64_t pp = panels - 1; pp >= 0; --pp)
+        if (int rc = apply_panel(qt, jb, dp - jb, jb, jb + pp * QB, y2blk, dd, "Q (panel update)")) return rc;
+    }
   }
   PtrTable q{};
   for (int i = 0; i < nb; ++i) q.p[i] = q_tab[first + i];

@@ -156,10 +156,11 @@ def test_soap_argument_errors_and_workspace_without_device(canz):
     # workspace in floats, rows 256, cols 512, one matrix, both sides: G and M in two orientations, the half-rotated
     # and the rotated pair (4 x 2 planes), N' and its half-rotated image (2 planes), the bases in two orientations,
     # one padded statistic of the larger side; a refresh step adds four square matrices of that side (working copy,
-    # reflectors, the panels' Y2 = V T, Q^T), two strips of 32 columns (one panel's Y, W) and 32 tau (one 256-byte unit)
+    # reflectors, the panels' Y2 = V T, Q^T), strips of 128 columns (one block's Y, W twice, U2^T of every block) and of 32
+    # (T of every panel), 32 tau (one 256-byte unit) and three 128 x 128 matrices (C, C2, U^T of one block)
     plane, sq = 256 * 512, 512 * 512
     plain = 4 * (10 * plane + 2 * 256 * 256 + 2 * sq + sq)
-    fresh = plain + 4 * (4 * sq + 2 * 512 * 32 + 64)
+    fresh = plain + 4 * (4 * sq + (128 + 2 * 128 + 32 + 128) * 512 + 64 + 3 * 128 * 128)
     one = [G(rows=256, cols=512, n_mats=1, grad_dtype=canz.DT_F32)]
     assert canz.canz_soap_workspace_bytes(one, hp) == plain
     assert canz.canz_soap_workspace_bytes([G(rows=200, cols=500, n_mats=1, grad_dtype=canz.DT_F32)], hp) == plain

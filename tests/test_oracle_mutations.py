@@ -196,8 +196,12 @@ SOAP_MUTANTS = [
 
 
 SOAP_COST_MUTANTS = [
-    ("refresh not spread over the period", "+ 14 * (r ** 3 + c ** 3)) // (3 * refresh_every)", "+ 14 * (r ** 3 + c ** 3) * refresh_every) // (3 * refresh_every)"),
-    ("three rotations instead of four products", "3 * refresh_every * 8 * r * c * (r + c)", "3 * refresh_every * 6 * r * c * (r + c)"),
+    ("refresh not spread over the period", "+ 14 * sum(d ** 3 for d in sides)) // (3 * refresh_every)",
+     "+ 14 * sum(d ** 3 for d in sides) * refresh_every) // (3 * refresh_every)"),
+    ("three rotations instead of four products", "3 * refresh_every * 8 * r * c * sum(sides)", "3 * refresh_every * 6 * r * c * sum(sides)"),
+    ("side above the limit still counted", "sides = [d for d in (r, c) if d <= max_precond_dim]", "sides = [r, c]"),
+    ("limit itself excluded", "sides = [d for d in (r, c) if d <= max_precond_dim]", "sides = [d for d in (r, c) if d < max_precond_dim]"),
+    ("model's limit off by a factor", "SOAP_COST_MAX_PRECOND_DIM = 10000", "SOAP_COST_MAX_PRECOND_DIM = 100000"),
     ("cost units not scaled", "return [soap_flops(int(r), int(c)) >> 20", "return [soap_flops(int(r), int(c))"),
 ]
 

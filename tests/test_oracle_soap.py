@@ -266,3 +266,12 @@ def test_soap_cost_model_by_hand():
     assert OP.soap_flops(2, 3, refresh_every=1) == 240 + 163
     assert OP.param_cost([4096], [4096], OP.COST_SOAP_FLOPS) == [1109742]
     assert OP.param_cost([2], [3], OP.COST_SOAP_FLOPS) == [0]
+    # A side above the limit keeps no basis and costs nothing: limit 2 leaves the side of extent 2 of a 2 x 3 matrix,
+    # 4 * 2 * 2 * 3 * 2 = 96 per step and 14/3 * 8 = 37.33 per refresh, floor(96 + 3.73) = 99; the limit itself is
+    # within; nothing is left of a matrix with both sides above it.
+    assert OP.soap_flops(2, 3, max_precond_dim=2) == 99 and OP.soap_flops(3, 2, max_precond_dim=2) == 99
+    assert OP.soap_flops(2, 3, max_precond_dim=3) == 256 and OP.soap_flops(2, 3, max_precond_dim=1) == 0
+    # the model's own limit is 10000: a 25600 x 5120 matrix counts its 5120-long side only,
+    # floor((8 * 25600 * 5120 * 5120 + 14/30 * 5120^3) / 2^20) = floor(5120000 + 59733.33) = 5179733
+    assert OP.param_cost([25600, 5120], [5120, 25600], OP.COST_SOAP_FLOPS) == [5179733, 5179733]
+    assert OP.param_cost([10000], [10001], OP.COST_SOAP_FLOPS) == [(8 * 10000 * 10001 * 10000 + 14 * 10000 ** 3 // 30) >> 20]
