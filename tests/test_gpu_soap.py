@@ -477,8 +477,8 @@ def test_config2_share_in_one_call(canz):
 
 
 def test_config4_share_in_one_call(canz):
-    """The share bench.py --optimizer soap --config 4 runs, in its launch configuration: four 25600 x 5120 matrices in
-    one call, one launch batch, max_precond_dim 10000 (the long side keeps no basis), a refresh step.  The first 64
+    """The one-sided share bench.py --optimizer soap --config 4 --share 25600x5120x4 runs, in its launch configuration: four
+    25600 x 5120 matrices in one call, one launch batch, max_precond_dim 10000 (the long side keeps no basis), a refresh step.  The first 64
     panels of the 5120-sided QR are longer than the panel kernel can hold in registers.  Matrix 0 is compared with the
     oracle in full (state, update, refreshed basis, re-rotated momentum); the bases of the others are checked to be
     orthonormal, and every output to be finite and distinct from matrix 0's.  The caller keeps the rotated momentum."""
@@ -628,6 +628,45 @@ def test_bf16_rotations_config2_shape(canz):
     one.n = 1
     check(one, grads[:1], states[:1], None, hp, "soap bf16 rotations 3072x1024", tol_update=TOL16_UPDATE, tol_var=TOL16_VAR,
           tol_mom_rot=TOL16_MOM_ROT)
+
+
+def test_config4_planner_share_in_one_call(canz):
+    """The share bench.py --optimizer soap --config 4 runs, in its launch configuration: Algorithm 1 with W = SOAP FLOPs
+    on the 32B-shaped set gives the most loaded rank six matrices of 8192 x 5120, both sides with a basis; one call, one
+    launch batch, a refresh step with the caller's rotated momentum valid.  The 8192-sided QR has 64 blocks of four
+    panels, the first 160 panels longer than the panel kernel holds in registers.  Matrix 0 (random orthogonal bases)
+    against the oracle in full; the others (identity bases) orthonormal, finite and distinct."""
+    import torch
+    s = W.matrix_set(4)
+    _, owner, load = canz.canz_partition_alpha(s["rows"], s["cols"], s["bucket_off"], s["n_ranks"], 1.0,
+                                               cost_kind=canz.COST_SOAP_FLOPS)
+    rank = int(np.argmax(load))
+    groups = canz.canz_microgroup_plan(s["rows"], s["cols"], s["dtype"], owner, rank, max_mats=8)
+    assert [len(g) for g in groups] == [6] and {(s["rows"][p], s["cols"][p]) for p in groups[0]} == {(8192, 5120)}
+    rows, cols, n = 8192, 5120, 6
+    log("soap config 4 (planner share): inputs")
+    grads = [W.gen_grad(4, p, rows, cols)[0] for p in groups[0]]
+    # matrices 2 .. 5 start from the same state as matrix 1 (their gradients differ): the seeded 8192-sided statistics
+    # take seconds each to draw on the host
+    states = [W.gen_soap_state(4, groups[0][min(k, 1)], rows, cols, identity_bases=(k > 0)) if k < 2 else None for k in range(n)]
+    states = [st if st is not None else states[1] for st in states]
+    rot = [SO.rotate_in(widen(st["mom"]), widen(st["q_left"]), widen(st["q_right"])).astype(np.float32) if k == 0
+           else st["mom"].copy() for k, st in enumerate(states)]
+    hp = canz.SoapHparams(lr=0.003, eps=1e-8, step=10, refresh=True, out_mode=canz.OUT_DELTA, mom_rot_valid=True)
+    dev = SoapDevice(canz, rows, cols, grads, states, mom_rot=rot)
+    log("soap config 4 (planner share): device step")
+    run(canz, [dev], hp)
+    for i in range(1, n):
+        for key, d in (("q_left", rows), ("q_right", cols)):
+            q = dev.t[key][i].double()      # measured in fp64: an fp32 product of 8192 terms rounds at the tolerance itself
+            orth = float((q.T @ q - torch.eye(d, device="cuda", dtype=torch.float64)).abs().max())
+            assert orth <= TOL_ORTH, "%s of matrix %d: Q^T Q - I = %.3g" % (key, i, orth)
+        assert bool(torch.isfinite(dev.out_t[i]).all()) and not torch.equal(dev.out_t[i], dev.out_t[i - 1])
+    log("soap config 4 (planner share): oracle on matrix 0 (fp64)")
+    one = SoapDevice.__new__(SoapDevice)
+    one.__dict__.update(dev.__dict__)
+    one.n = 1
+    check(one, grads[:1], states[:1], None, hp, "soap 6 x 8192x5120, matrix 0")
 
 
 @pytest.mark.parametrize("bf16_rot", [False, True], ids=["fp32", "bf16-rotations"])
