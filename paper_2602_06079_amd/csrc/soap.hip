@@ -393,7 +393,7 @@ __global__ __launch_bounds__(NTH) void k_soap_store_q(PtrTable q, const float* _
 // later columns; barrier; the owner of column c + 1 turns it into v_(c+1); barrier.  With v in LDS the
 // barriers only have to order LDS traffic, so they do not wait for the stores in flight.
 // Up to 3072 remaining rows the columns stay in registers for the whole kernel (k_qr_panel_regs);
-// k_qr_panel_long, for longer panels, streams them from memory (L2) on every step.
+// k_qr_panel_hybrid, for longer panels, keeps the first 2048 rows there and streams the rest from memory (L2) on every step.
 constexpr int QBLK = 128;   // columns of a block: four panels
 struct QrPanel {
   float* wk;
@@ -410,7 +410,6 @@ struct QrPanel {
 };
 
 constexpr int VMAX = 12288;   // rows of a reflector kept in LDS: the largest extent a side with a basis may have
-constexpr int QUN = 8;        // loads in flight per lane in the streaming loops
 constexpr int TLD = QB + 4;   // row length of the T factor in LDS (rows 16-byte aligned)
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
@@ -434,108 +433,6 @@ __device__ __forceinline__ f32x4 v_of(const f32x4& x, int q, int c, float scale)
     o[e] = r < c ? 0.f : (r == c ? 1.f : x[e] * scale);
   }
   return o;
-}
-
-__global__ __launch_bounds__(QTH) void k_qr_panel_long(QrPanel a) {
-  __shared__ f32x4 s_v4[VMAX / 4];
-  __shared__ float s_tau[QB];
-  const int b = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int64_t dp = a.dp;
-  const int j0 = a.j0;
-  const int len = static_cast<int>(dp) - j0;     // rows j0 .. dp - 1, a multiple of 32
-  const int nvec = len / 4;
-  float* wk = a.wk + static_cast<int64_t>(b) * a.s_wk;
-  float* vrows = a.vall + static_cast<int64_t>(b) * a.s_vall;
-  auto col = [&](int c) { return reinterpret_cast<f32x4*>(wk + static_cast<int64_t>(j0 + c) * dp + j0); };
-  auto vrow = [&](int c) { return reinterpret_cast<f32x4*>(vrows + static_cast<int64_t>(j0 + c) * dp + j0); };
-  // column c (in memory; this wavefront's own stores if it was updated) becomes v_c
-  auto make_v = [&](int c, float ss, float al) {
-    float tau, scale;
-    reflector_of(j0 + c < a.d, ss, al, tau, scale);
-    const f32x4* x = col(c);
-    f32x4* vg = vrow(c);
-    for (int q = lane; q < nvec; q += 64) {
-      const f32x4 o = v_of(x[q], q, c, scale);
-      s_v4[q] = o;
-      vg[q] = o;
-    }
-    if (lane == 0) s_tau[c] = tau;
-  };
-
-  if (wave == 0) {   // column 0: its head, then v_0
-    const f32x4* x = col(0);
-    float ss = 0.f, al = 0.f;
-    for (int q = lane; q < nvec; q += 64) {
-      const f32x4 v = x[q];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        if (4 * q + e > 0) ss += v[e] * v[e];
-        if (4 * q + e == 0) al = v[e];
-      }
-    }
-    make_v(0, wave_sum(ss), wave_sum(al));
-  }
-  lds_barrier();
-
-  for (int c = 0; c < QB; ++c) {
-    const float tau = s_tau[c];
-    auto ldv = [&](int q) { return s_v4[q]; };
-    float ss2 = 0.f, al2 = 0.f;
-    for (int c2 = wave + 1; c2 < QB; c2 += QWAVES) {
-      if (c2 <= c) continue;
-      const bool next = c2 == c + 1;            // this wavefront also takes the head of the next column
-      if (tau == 0.f && !next) continue;        // H_c = I: nothing to apply
-      f32x4* x = col(c2);
-      float f = 0.f;
-      if (tau != 0.f) {
-        float dot = 0.f;
-        for (int q0 = lane; q0 < nvec; q0 += 64 * QUN) {
-          f32x4 xv[QUN];
-#pragma unroll
-          for (int u = 0; u < QUN; ++u) xv[u] = x[min(q0 + 64 * u, nvec - 1)];   // in bounds; surplus loads unused
-#pragma unroll
-          for (int u = 0; u < QUN; ++u) {
-            const int q = q0 + 64 * u;
-            if (q < nvec) {
-              const f32x4 y = ldv(q);
-#pragma unroll
-              for (int e = 0; e < 4; ++e) dot = __builtin_fmaf(xv[u][e], y[e], dot);
-            }
-          }
-        }
-        f = tau * wave_sum(dot);
-      }
-      for (int q0 = lane; q0 < nvec; q0 += 64 * QUN) {
-        f32x4 xv[QUN];
-#pragma unroll
-        for (int u = 0; u < QUN; ++u) xv[u] = x[min(q0 + 64 * u, nvec - 1)];
-#pragma unroll
-        for (int u = 0; u < QUN; ++u) {
-          const int q = q0 + 64 * u;
-          if (q < nvec) {
-            if (tau != 0.f) {
-              const f32x4 y = ldv(q);
-#pragma unroll
-              for (int e = 0; e < 4; ++e) xv[u][e] = __builtin_fmaf(-f, y[e], xv[u][e]);
-              x[q] = xv[u];
-            }
-            if (next) {
-#pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                const int r = 4 * q + e;
-                if (r > c2) ss2 += xv[u][e] * xv[u][e];
-                if (r == c2) al2 = xv[u][e];
-              }
-            }
-          }
-        }
-      }
-    }
-    lds_barrier();   // every wavefront has finished with v_c
-    if (c + 1 < QB && wave == c % QWAVES) make_v(c + 1, wave_sum(ss2), wave_sum(al2));   // al2: one lane holds it
-    lds_barrier();   // v_(c+1) and tau_(c+1) are in place
-  }
-  if (t < QB) (a.tau + static_cast<int64_t>(b) * QB)[t] = s_tau[t];
 }
 
 // Sum over the 64 lanes through the data-parallel-primitive lanes of the vector ALU (no LDS crossbar
@@ -673,6 +570,163 @@ __global__ __launch_bounds__(QTH) void k_qr_panel_regs(QrPanel a) {
         apply_reflector<XS, true, false>(ka, kb, s_v4, nvec, lane, tau);
       else if (do_b)
         apply_reflector<XS, false, true>(ka, kb, s_v4, nvec, lane, tau);
+    }
+    // the owner of column c + 1 takes its head while the others are still busy with their columns
+    const bool owner = c + 1 < QB && wave == c % QWAVES;
+    float ss = 0.f, al = 0.f;
+    if (owner) {
+      if (c + 1 == ca)
+        head(ka, c + 1, ss, al);
+      else
+        head(kb, c + 1, ss, al);
+    }
+    lds_barrier();   // every wavefront has finished with v_c
+    if (owner) {
+      if (c + 1 == ca)
+        make_v(ka, c + 1, ss, al);
+      else
+        make_v(kb, c + 1, ss, al);
+    }
+    lds_barrier();   // v_(c+1) and tau_(c+1) are in place
+  }
+  if (t < QB) (a.tau + static_cast<int64_t>(b) * QB)[t] = s_tau[t];
+}
+
+// The first kernel of a panel with more remaining rows than the registers hold: as k_qr_panel_regs, every wavefront
+// keeps the first 256 XS rows of its two columns in registers for the whole kernel; the rows beyond are streamed
+// from the working copy on every step (read for the dot product, read and written for the update: the wavefront's
+// own stores, which it reads back itself).  v_c is in LDS at full length.
+template <int XS>
+__global__ __launch_bounds__(QTH) void k_qr_panel_hybrid(QrPanel a) {
+  __shared__ f32x4 s_v4[VMAX / 4];
+  __shared__ float s_tau[QB];
+  constexpr int NR = 64 * XS;   // float4 of a column kept in registers
+  constexpr int TU = 2;         // loads in flight per lane in the streaming loops
+  const int b = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int64_t dp = a.dp;
+  const int j0 = a.j0;
+  const int nvec = (static_cast<int>(dp) - j0) / 4;   // > NR
+  float* wk = a.wk + static_cast<int64_t>(b) * a.s_wk;
+  float* vrows = a.vall + static_cast<int64_t>(b) * a.s_vall;
+  auto col = [&](int c) { return reinterpret_cast<f32x4*>(wk + static_cast<int64_t>(j0 + c) * dp + j0); };
+  const int ca = wave + 1, cb = wave + 1 + QWAVES;    // this wavefront's columns (cb only if < 32)
+  f32x4 ka[XS], kb[XS];
+
+  auto load_col = [&](f32x4 (&k)[XS], int c) {
+    const f32x4* x = col(c);
+#pragma unroll
+    for (int sl = 0; sl < XS; ++sl) k[sl] = x[lane + 64 * sl];
+  };
+  // sum of squares below row c and the element at row c (c < 32: it lies in the registers), over the wavefront
+  auto head = [&](const f32x4 (&k)[XS], int c, float& ss, float& al) {
+    ss = 0.f, al = 0.f;
+#pragma unroll
+    for (int sl = 0; sl < XS; ++sl) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int r = 4 * (lane + 64 * sl) + e;
+        if (r > c) ss += k[sl][e] * k[sl][e];
+        if (r == c) al = k[sl][e];
+      }
+    }
+    const f32x4* x = col(c);
+    for (int q0 = NR + lane; q0 < nvec; q0 += 64 * TU) {
+      f32x4 xv[TU];
+#pragma unroll
+      for (int u = 0; u < TU; ++u) xv[u] = x[min(q0 + 64 * u, nvec - 1)];   // in bounds; surplus loads unused
+#pragma unroll
+      for (int u = 0; u < TU; ++u)
+        if (q0 + 64 * u < nvec)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) ss += xv[u][e] * xv[u][e];
+    }
+    ss = wave_sum_dpp(ss), al = wave_sum_dpp(al);
+  };
+  // column c, whose head is (ss, al), becomes the reflector v_c: to LDS, to the reflector array, tau to LDS
+  auto make_v = [&](const f32x4 (&k)[XS], int c, float ss, float al) {
+    float tau, scale;
+    reflector_of(j0 + c < a.d, ss, al, tau, scale);
+    f32x4* vg = reinterpret_cast<f32x4*>(vrows + static_cast<int64_t>(j0 + c) * dp + j0);
+#pragma unroll
+    for (int sl = 0; sl < XS; ++sl) {
+      const int q = lane + 64 * sl;
+      const f32x4 o = v_of(k[sl], q, c, scale);
+      s_v4[q] = o;
+      vg[q] = o;
+    }
+    const f32x4* x = col(c);
+    for (int q = NR + lane; q < nvec; q += 64) {
+      f32x4 o = x[q];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] *= scale;
+      s_v4[q] = o;
+      vg[q] = o;
+    }
+    if (lane == 0) s_tau[c] = tau;
+  };
+  // H_c applied to column c2, held in k and, beyond the registers, in memory
+  auto apply = [&](f32x4 (&k)[XS], int c2, float tau) {
+    f32x4* x = col(c2);
+    float dot = 0.f;
+#pragma unroll
+    for (int sl = 0; sl < XS; ++sl) {
+      const f32x4 y = s_v4[lane + 64 * sl];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) dot = __builtin_fmaf(k[sl][e], y[e], dot);
+    }
+    for (int q0 = NR + lane; q0 < nvec; q0 += 64 * TU) {
+      f32x4 xv[TU];
+#pragma unroll
+      for (int u = 0; u < TU; ++u) xv[u] = x[min(q0 + 64 * u, nvec - 1)];
+#pragma unroll
+      for (int u = 0; u < TU; ++u) {
+        const int q = q0 + 64 * u;
+        if (q < nvec) {
+          const f32x4 y = s_v4[q];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) dot = __builtin_fmaf(xv[u][e], y[e], dot);
+        }
+      }
+    }
+    const float f = tau * wave_sum_dpp(dot);
+#pragma unroll
+    for (int sl = 0; sl < XS; ++sl) {
+      const f32x4 y = s_v4[lane + 64 * sl];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) k[sl][e] = __builtin_fmaf(-f, y[e], k[sl][e]);
+    }
+    for (int q0 = NR + lane; q0 < nvec; q0 += 64 * TU) {
+      f32x4 xv[TU];
+#pragma unroll
+      for (int u = 0; u < TU; ++u) xv[u] = x[min(q0 + 64 * u, nvec - 1)];
+#pragma unroll
+      for (int u = 0; u < TU; ++u) {
+        const int q = q0 + 64 * u;
+        if (q < nvec) {
+          const f32x4 y = s_v4[q];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) xv[u][e] = __builtin_fmaf(-f, y[e], xv[u][e]);
+          x[q] = xv[u];
+        }
+      }
+    }
+  };
+
+  if (wave == 0) {
+    float ss, al;
+    load_col(ka, 0);
+    head(ka, 0, ss, al);
+    make_v(ka, 0, ss, al);
+  }
+  load_col(ka, ca);
+  if (cb < QB) load_col(kb, cb);
+  lds_barrier();
+
+  for (int c = 0; c < QB; ++c) {
+    const float tau = s_tau[c];
+    if (tau != 0.f) {   // columns that have become reflectors are left alone
+      if (ca > c) apply(ka, ca, tau);
+      if (cb < QB && cb > c) apply(kb, cb, tau);
     }
     // the owner of column c + 1 takes its head while the others are still busy with their columns
     const bool owner = c + 1 < QB && wave == c % QWAVES;
@@ -1069,7 +1123,7 @@ int refresh_side(void* const* q_tab, int first, int nb, int64_t d, int64_t dp, c
       else if (dp - j0 <= 64 * 4 * 12)
         hipLaunchKernelGGL(k_qr_panel_regs<12>, dim3(nb), dim3(QTH), 0, st, a);
       else
-        hipLaunchKernelGGL(k_qr_panel_long, dim3(nb), dim3(QTH), 0, st, a);
+        hipLaunchKernelGGL(k_qr_panel_hybrid<8>, dim3(nb), dim3(QTH), 0, st, a);
       hipLaunchKernelGGL(k_qr_tfactor, dim3(nb), dim3(QTH), 0, st, a);
       prof_mark(st, CANZ_KERNEL_SOAP_PANEL, false);
       if (hipError_t e = hipGetLastError(); e != hipSuccess) return fail(CANZ_EHIP, "panel kernel: %s", hipGetErrorString(e));

@@ -402,7 +402,7 @@ def test_config2_shape_with_refresh(canz):
 
 def test_refresh_of_a_long_side(canz):
     """3200 rows: the first panels of the left side are longer than the 3072 rows the panel kernel can hold in
-    registers (they stream their columns from memory), the next ones use the 12-slot variant, the last ones the
+    registers (they stream the rows beyond the first 2048 from memory), the next ones use the 12-slot variant, the last ones the
     8-slot one; all three against the oracle's QR."""
     rows, cols, n = 3200, 384, 2
     grads = [W.gen_grad(69, i, rows, cols)[0] for i in range(n)]
