@@ -274,6 +274,7 @@ int canz_muon_step(const canz_group* g, int32_t n_groups, const canz_muon_hparam
  * (same layout as left / right) gets the roots of a step with keep_roots = 0 written there, and a
  * step with keep_roots = 1 takes them from there instead of computing them: about 2 % of the cost
  * of a full step.
+ * Consecutive groups of one call that agree in shape, tp, dtypes and in which tables they pass run as one group.
  */
 typedef struct {
   int64_t rows, cols;

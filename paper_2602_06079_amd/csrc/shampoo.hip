@@ -277,6 +277,61 @@ int run_batch(const canz_shampoo_group& g, int first, int nb, const canz_shampoo
   return CANZ_OK;
 }
 
+// Consecutive groups of a call that agree in shape, tp, dtypes and in which tables they pass run as one group: every
+// matrix is computed on its own whatever shares its launch, and the products of small matrices fill the chip only
+// when many of them share one.
+struct MergedGroup {
+  canz_shampoo_group g{};
+  std::vector<const void*> grad;
+  std::vector<void*> tab[5];   // left, right, out, lroot, rroot
+};
+
+void tables_of(const canz_shampoo_group& g, void* const* (&out)[5]) {
+  out[0] = g.left, out[1] = g.right, out[2] = g.out, out[3] = g.lroot, out[4] = g.rroot;
+}
+
+bool mergeable(const canz_shampoo_group& a, const canz_shampoo_group& b) {
+  if (a.rows != b.rows || a.cols != b.cols || a.tp != b.tp || a.grad_dtype != b.grad_dtype || a.out_dtype != b.out_dtype) return false;
+  if ((a.grad == nullptr) != (b.grad == nullptr)) return false;
+  void* const* ta[5];
+  void* const* tb[5];
+  tables_of(a, ta), tables_of(b, tb);
+  for (int k = 0; k < 5; ++k)
+    if ((ta[k] == nullptr) != (tb[k] == nullptr)) return false;
+  return true;
+}
+
+std::vector<MergedGroup> merge_groups(const canz_shampoo_group* g, int n_groups, int out_mode) {
+  std::vector<MergedGroup> all;
+  for (int i = 0; i < n_groups; ++i) {
+    const canz_shampoo_group& x = g[i];
+    if (x.n_mats == 0) continue;
+    if (all.empty() || !mergeable(all.back().g, x)) {
+      all.emplace_back();
+      all.back().g = x;
+      all.back().g.n_mats = 0;
+    }
+    MergedGroup& m = all.back();
+    void* const* t[5];
+    tables_of(x, t);
+    const int per_out = out_mode == CANZ_OUT_DELTA ? x.tp : 1;
+    if (x.grad) m.grad.insert(m.grad.end(), x.grad, x.grad + static_cast<size_t>(x.n_mats) * x.tp);
+    for (int k = 0; k < 5; ++k)
+      if (t[k]) m.tab[k].insert(m.tab[k].end(), t[k], t[k] + static_cast<size_t>(x.n_mats) * (k == 2 ? per_out : 1));
+    m.g.n_mats += x.n_mats;
+  }
+  for (MergedGroup& m : all) {   // the tables now stand still: point the group at them
+    canz_shampoo_group& x = m.g;
+    if (x.grad) x.grad = m.grad.data();
+    if (x.left) x.left = m.tab[0].data();
+    if (x.right) x.right = m.tab[1].data();
+    if (x.out) x.out = m.tab[2].data();
+    if (x.lroot) x.lroot = m.tab[3].data();
+    if (x.rroot) x.rroot = m.tab[4].data();
+  }
+  return all;
+}
+
 }  // namespace
 }  // namespace canz
 
@@ -287,11 +342,10 @@ extern "C" int canz_shampoo_workspace_bytes(const canz_shampoo_group* g, int32_t
   if (n_groups < 0 || (n_groups > 0 && !g)) return fail(CANZ_EINVAL, "bad group array");
   if (int rc = check_hparams(hp)) return rc;
   size_t need = ALIGN;
-  for (int i = 0; i < n_groups; ++i) {
+  for (int i = 0; i < n_groups; ++i)
     if (int rc = check_group(g[i], i, false, hp->out_mode, hp->keep_roots != 0)) return rc;
-    if (g[i].n_mats == 0) continue;
-    need = std::max(need, carve(g[i].rows, g[i].cols, std::min(g[i].n_mats, batch_cap(g[i]))).total_bytes);
-  }
+  for (const MergedGroup& m : merge_groups(g, n_groups, hp->out_mode))
+    need = std::max(need, carve(m.g.rows, m.g.cols, std::min(m.g.n_mats, batch_cap(m.g))).total_bytes);
   *bytes_out = need;
   return CANZ_OK;
 }
@@ -312,10 +366,10 @@ extern "C" int canz_shampoo_step(const canz_shampoo_group* g, int32_t n_groups, 
   if (workspace_bytes < need)
     return fail(CANZ_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  for (int i = 0; i < n_groups; ++i) {
-    const int cap = batch_cap(g[i]);
-    for (int first = 0; first < g[i].n_mats; first += cap)
-      if (int rc = run_batch(g[i], first, std::min(cap, g[i].n_mats - first), *hp, static_cast<float*>(workspace), st)) return rc;
+  for (const MergedGroup& m : merge_groups(g, n_groups, hp->out_mode)) {
+    const int cap = batch_cap(m.g);
+    for (int first = 0; first < m.g.n_mats; first += cap)
+      if (int rc = run_batch(m.g, first, std::min(cap, m.g.n_mats - first), *hp, static_cast<float*>(workspace), st)) return rc;
   }
   return CANZ_OK;
 }

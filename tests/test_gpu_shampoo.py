@@ -214,6 +214,34 @@ def test_decaying_spectrum_and_batch_independence(canz):
     assert np.array_equal(solo.out_host(0), devs[0].out_host(1))
 
 
+def test_like_shaped_groups_of_a_call_are_merged_and_unchanged(canz):
+    """Three groups in one call, the first two of one shape (the library runs them as one launch batch), the third of
+    another, with caller-held roots: statistics, roots and parameters are bit-identical to one call per group."""
+    import torch
+    shapes = [(264, 136, 2), (264, 136, 3), (136, 264, 2)]
+    hp = canz.ShampooHparams(eps=1e-3)
+
+    def build():
+        out = []
+        for k, (rows, cols, n) in enumerate(shapes):
+            grads = [W.gen_grad(47, 10 * k + i, rows, cols)[0] for i in range(n)]
+            lefts = [np.zeros((rows, rows), np.float32) for _ in range(n)]
+            rights = [np.zeros((cols, cols), np.float32) for _ in range(n)]
+            params = [W.gen_param(47, 10 * k + i, rows, cols) for i in range(n)]
+            out.append((ShampooDevice(canz, rows, cols, grads, lefts, rights, outs=params, keep_roots=True), grads, lefts, rights, params))
+        return out
+
+    together, apart = build(), build()
+    run(canz, [d for d, *_ in together], hp)
+    for d, *_ in apart:
+        run(canz, [d], hp)
+    for (d, grads, lefts, rights, params), (a, *_) in zip(together, apart):
+        for i in range(d.n):
+            for got, want in ((d.left_t, a.left_t), (d.right_t, a.right_t), (d.lroot_t, a.lroot_t), (d.rroot_t, a.rroot_t), (d.out_t, a.out_t)):
+                assert torch.equal(got[i], want[i]), "matrix %d differs between one call and three" % i
+        check(d, grads, lefts, rights, params, hp, "shampoo merged groups %dx%d" % (d.rows, d.cols))
+
+
 def test_zero_gradient_and_empty_group(canz):
     """A zero gradient on empty statistics gives a zero update (A = eps I, no NaN); empty groups are skipped."""
     import torch
