@@ -194,9 +194,11 @@ def test_ragged_shapes_one_step(canz, shape):
     check(dev, grads, states, params, hp, "soap ragged %dx%d" % shape)
 
 
-@pytest.mark.parametrize("shape", [(300, 77), (77, 300), (256, 256), (520, 1032), (33, 160)], ids=lambda s: "%dx%d" % s)
+@pytest.mark.parametrize("shape", [(300, 77), (77, 300), (256, 256), (520, 1032), (33, 160), (1, 9), (129, 127), (255, 257), (384, 385)],
+                         ids=lambda s: "%dx%d" % s)
 def test_refresh_on_ragged_shapes(canz, shape):
-    """A refresh step: extents that are no multiple of the 32-wide panels or the 128-wide tiles."""
+    """A refresh step: extents that are no multiple of the 32-wide panels or the 128-wide tiles, and extents just below,
+    at and just above the boundaries of the blocks of four panels (128 columns) that the factorisation applies at once."""
     rows, cols = shape
     n = 2
     grads = [W.gen_grad(61, i, rows, cols)[0] for i in range(n)]
