@@ -110,6 +110,21 @@ def test_rank_latency_tool_on_config2(canz):
     assert worst["Alg. 1, alpha = 1, W = FLOPs"] <= static * 1.02
 
 
+def test_rank_latency_tool_for_soap_on_config2(canz):
+    """The same report for the SOAP step (the generalisation experiment of App. C in miniature): with the operator's
+    own FLOPs as W(p) the slowest rank is faster than under the static rule and than with W = numel (measured 15.1
+    against 22.3 and 17.2 ms)."""
+    from paper_2602_06079_amd import rank_latency
+    text = rank_latency.report((2,), steps=1, optimizer="soap")
+    rows = [l.split("|") for l in text.splitlines() if l.startswith("| 2 ")]
+    assert len(rows) == 3
+    worst = {r[2].strip(): float(r[4]) for r in rows}
+    log("SOAP, slowest rank, ms: %s" % worst)
+    assert all(v > 0 for v in worst.values())
+    assert worst["Alg. 1, alpha = 1, W = SOAP FLOPs"] <= 0.85 * worst["static, Eq. 1 per bucket"]
+    assert worst["Alg. 1, alpha = 1, W = SOAP FLOPs"] <= 1.02 * worst["Alg. 1, alpha = 1, W = numel"]
+
+
 def test_two_streams_with_separate_workspaces(canz):
     """Steps enqueued on two streams at once, each with its own workspace, give the same
     bits as the same steps run one after the other (the library keeps no state of a step
