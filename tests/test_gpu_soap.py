@@ -390,6 +390,22 @@ def test_like_shaped_groups_of_a_call_are_merged_and_unchanged(canz, bf16_rot):
             check(d, grads, states, params, hp, "soap merged groups %dx%d" % (d.rows, d.cols))
 
 
+def test_more_matrices_than_one_launch_batch_holds(canz):
+    """140 small matrices in two like-shaped groups of 70: the library merges them and cuts the 140 into launch batches
+    of 128 and 12 (a pointer table holds 128 buffers).  A refresh step; every matrix against the oracle."""
+    rows, cols, n = 40, 24, 70
+    hp = canz.SoapHparams(lr=0.01, eps=1e-8, step=10, refresh=True, out_mode=canz.OUT_DELTA)
+    devs, ins = [], []
+    for k in range(2):
+        grads = [W.gen_grad(87, 100 * k + i, rows, cols)[0] for i in range(n)]
+        states = [W.gen_soap_state(87, 100 * k + i, rows, cols) for i in range(n)]
+        devs.append(SoapDevice(canz, rows, cols, grads, states))
+        ins.append((grads, states))
+    run(canz, devs, hp)
+    for k, d in enumerate(devs):
+        check(d, ins[k][0], ins[k][1], None, hp, "soap 2 x 70 matrices of 40x24, group %d" % k)
+
+
 def test_config2_shape_with_refresh(canz):
     """Four 2048 x 1024 matrices (the 0.6B-shaped share's shape): state and update of every matrix against the oracle,
     refreshed bases of the first one against the oracle's QR, properties on all."""
